@@ -1,0 +1,250 @@
+"""Plain fp64 CPU oracle for the dAD hot path.  TEST INFRASTRUCTURE ONLY.
+
+This module is the reference the HIP library is checked against.  It is slow,
+written for readability, uses numpy in float64 throughout, and shares nothing
+with the GPU code: no kernels, headers, helpers, tables or constants.  Only the
+tests, the smoke check and the benchmark's CPU-baseline leg may import it; the
+product path never does.
+
+Notation follows the paper (arXiv 2102.09631): for one linear layer with input
+width h_in = h_{i-1} and output width h_out = h_i,
+
+    A     in R^{N x h_in}   input activations A_{i-1}, one row per sample/token
+    Delta in R^{N x h_out}  back-propagated errors Delta_i, one row per sample
+    M  =  A^T Delta         the layer's weight gradient (Section 3.1, Eq. 4)
+
+Pins (see tests/test_oracle_*.py):
+  mlp_factors          central finite differences of the loss
+  stack_factors        pooled-batch gradient of the MLP equals gradient of stack
+  full_grad            brute-force triple loop, N=1 outer product, linearity
+  block_spi*           three unrelated routes agree; exact truncated SVD when
+                       r >= rank(M); Eckart-Young bound and Pythagoras otherwise
+  sequential_spi       converges to numpy's truncated SVD on a planted spectrum
+No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F64 = np.float64
+
+# --------------------------------------------------------------------------
+# Tiny feed-forward network: forward pass and reverse-mode factors
+# --------------------------------------------------------------------------
+
+_ACT = {
+    "identity": (lambda z: z, lambda z: np.ones_like(z)),
+    "tanh": (np.tanh, lambda z: 1.0 - np.tanh(z) ** 2),
+    "sigmoid": (lambda z: 1.0 / (1.0 + np.exp(-z)),
+                lambda z: (1.0 / (1.0 + np.exp(-z))) * (1.0 - 1.0 / (1.0 + np.exp(-z)))),
+    "relu": (lambda z: np.maximum(z, 0.0), lambda z: (z > 0.0).astype(F64)),
+}
+
+
+def mlp_forward(Ws, Bs, acts, X):
+    """Section 3, Eq. 1: Z_i = A_{i-1} W_i + B_i, A_i = phi_i(Z_i), A_0 = X.
+
+    W_i has shape h_{i-1} x h_i (the shape Eq. 1 needs; the prose gives the
+    indices shifted by one).  Returns the lists [A_0..A_L] and [Z_1..Z_L].
+    """
+    A = [np.asarray(X, F64)]
+    Z = []
+    for W, B, a in zip(Ws, Bs, acts):
+        z = A[-1] @ np.asarray(W, F64) + np.asarray(B, F64)
+        Z.append(z)
+        A.append(_ACT[a][0](z))
+    return A, Z
+
+
+def mlp_loss(Ws, Bs, acts, X, Y, n_global=None):
+    """Squared-error loss  (1/n_global) * sum_samples 0.5*||a_L - y||^2.
+
+    The paper leaves the reduction open.  A normaliser shared by all sites
+    (the global sample count) is what keeps per-site gradients additive.
+    """
+    A, _ = mlp_forward(Ws, Bs, acts, X)
+    n_global = X.shape[0] if n_global is None else n_global
+    return 0.5 * np.sum((A[-1] - np.asarray(Y, F64)) ** 2) / n_global
+
+
+def mlp_factors(Ws, Bs, acts, X, Y, n_global=None):
+    """Section 3.1, Eq. 2-3: the auto-diff factor pairs of every layer.
+
+    Delta_L = dLoss/dA_L (.) phi'_L(Z_L)                       (Eq. 2)
+    Delta_i = (Delta_{i+1} W_{i+1}^T) (.) phi'_i(Z_i), i < L    (Eq. 3, with the
+              transpose that the shapes of Eq. 1 require)
+    Returns [(A_{i-1}, Delta_i) for i = 1..L]; Eq. 4 then gives
+    dLoss/dW_i = A_{i-1}^T Delta_i.
+    """
+    A, Z = mlp_forward(Ws, Bs, acts, X)
+    L = len(Ws)
+    n_global = X.shape[0] if n_global is None else n_global
+    deltas = [None] * L
+    deltas[L - 1] = (A[L] - np.asarray(Y, F64)) / n_global * _ACT[acts[L - 1]][1](Z[L - 1])
+    for i in range(L - 2, -1, -1):
+        deltas[i] = (deltas[i + 1] @ np.asarray(Ws[i + 1], F64).T) * _ACT[acts[i]][1](Z[i])
+    return [(A[i], deltas[i]) for i in range(L)]
+
+
+# --------------------------------------------------------------------------
+# dAD: stacking and the exact gradient
+# --------------------------------------------------------------------------
+
+def stack_factors(A_sites, D_sites):
+    """Section 3.2: concatenate the sites' factors along the batch dimension.
+
+    Also Algorithm 1 (the aggregator's vertcat of the rank-reduced pairs).
+    """
+    return (np.concatenate([np.asarray(a) for a in A_sites], axis=0),
+            np.concatenate([np.asarray(d) for d in D_sites], axis=0))
+
+
+def full_grad(A, Delta):
+    """Section 3.1, Eq. 4: M[p, q] = sum_n A[n, p] * Delta[n, q], in fp64."""
+    return np.asarray(A, F64).T @ np.asarray(Delta, F64)
+
+
+def rank_r_grad(Pt, Gt):
+    """Algorithm 1, local rebuild: sum_j p_j g_j^T with p_j = Pt[j], g_j = Gt[j].
+
+    Orientation h_in x h_out, that of Eq. 4.
+    """
+    return np.asarray(Pt, F64).T @ np.asarray(Gt, F64)
+
+
+# --------------------------------------------------------------------------
+# Rank-r compression: block form of the structured power iteration
+# --------------------------------------------------------------------------
+
+def _orth(Y):
+    """Orthonormal basis of span(Y) by Householder QR with diag(R) > 0."""
+    Q, R = np.linalg.qr(Y)
+    s = np.sign(np.diag(R))
+    s[s == 0] = 1.0
+    return Q * s
+
+
+def block_spi(A, Delta, G0t, n_iter):
+    """Algorithm 2 / Eq. 6 applied to all r start vectors at once (factored route).
+
+    Each iteration applies M^T M = Delta^T (A A^T) Delta to the current h_out x r
+    block without ever forming M, evaluated right to left, then replaces the
+    block by an orthonormal basis of its span (this takes the place of the
+    one-vector-at-a-time peeling of Eq. 7: it leaves the spanned subspace, and
+    therefore the rank-r gradient, unchanged in exact arithmetic).  Finally the
+    left factor P = A^T (Delta G) is formed; the singular values stay inside P
+    (footnote to Section 3.3.1), so nothing is divided.
+
+    G0t: r x h_out start matrix, row j = g_0^j.  Returns (Pt r x h_in, Gt r x h_out)
+    with Gt's rows orthonormal; the rank-r gradient is Pt^T Gt.
+    """
+    A = np.asarray(A, F64)
+    D = np.asarray(Delta, F64)
+    G = np.asarray(G0t, F64).T.copy()
+    if n_iter < 1:
+        raise ValueError("n_iter >= 1")
+    for _ in range(n_iter):
+        V = D @ G            # Delta g
+        U = A.T @ V
+        W = A @ U            # (A A^T)(Delta g) = C (Delta g)
+        Y = D.T @ W          # B (Delta g)
+        G = _orth(Y)
+    V = D @ G
+    P = A.T @ V
+    return P.T.copy(), G.T.copy()
+
+
+def block_spi_dense(A, Delta, G0t, n_iter):
+    """Same result by an unrelated route: iterate on the explicit gradient (Eq. 5).
+
+    Forms M, iterates Y <- M^T (M Y) with re-orthonormalisation, and projects M on
+    the span of the last iterate with a projector built from an SVD of that
+    iterate (rank-revealing, so a start block wider than rank(M) is handled).
+    Returns the h_in x h_out rank-r gradient M Pi.
+    """
+    M = full_grad(A, Delta)
+    Y = np.asarray(G0t, F64).T.copy()
+    for k in range(n_iter):
+        Y = M.T @ (M @ Y)
+        if k + 1 < n_iter:
+            Y = _orth(Y)
+    Uy, s, _ = np.linalg.svd(Y, full_matrices=False)
+    tol = s[0] * max(Y.shape) * np.finfo(F64).eps
+    Uy = Uy[:, s > tol]
+    return (M @ Uy) @ Uy.T
+
+
+def block_spi_precomputed(A, Delta, G0t, n_iter):
+    """Same result with the association order Algorithm 2 prints.
+
+    C = A A^T (N x N) and B = Delta^T C (h_out x N) are formed once; each
+    iteration is g <- B (Delta g) (Eq. 6).  Only sensible for small N.
+    """
+    A = np.asarray(A, F64)
+    D = np.asarray(Delta, F64)
+    C = A @ A.T
+    B = D.T @ C
+    G = np.asarray(G0t, F64).T.copy()
+    for _ in range(n_iter):
+        G = _orth(B @ (D @ G))
+    P = A.T @ (D @ G)
+    return P.T.copy(), G.T.copy()
+
+
+def sequential_spi(A, Delta, g0t, n_iter):
+    """Algorithm 2 one vector at a time, with peeling (Eq. 7).
+
+    Readings taken where the listing cannot be executed as printed: exactly r
+    components and n_iter applications each; the iterate is renormalised after
+    every application; the peeled term is sum_{i<j} sigma_i^2 g_i (g_i^T g), the
+    deflation of M^T M by the pairs already found (the printed Q (G^T g) mixes
+    vectors of length h_in and h_out).  sigma_j = sqrt(v^T C v), v = Delta g_j,
+    q_j = A^T v / sigma_j.  Returns (Q r x h_in with unit rows, sG r x h_out with
+    rows sigma_j g_j), so that Q^T sG approximates M.
+    """
+    A = np.asarray(A, F64)
+    D = np.asarray(Delta, F64)
+    C = A @ A.T
+    B = D.T @ C
+    g0t = np.asarray(g0t, F64)
+    r = g0t.shape[0]
+    Q = np.zeros((r, A.shape[1]))
+    sG = np.zeros((r, D.shape[1]))
+    gs, sig = [], []
+    for j in range(r):
+        g = g0t[j] / np.linalg.norm(g0t[j])
+        for _ in range(n_iter):
+            g_new = B @ (D @ g)
+            for gi, si in zip(gs, sig):
+                g_new = g_new - (si ** 2) * gi * (gi @ g)
+            g = g_new / np.linalg.norm(g_new)
+        v = D @ g
+        sigma = np.sqrt(v @ (C @ v))
+        Q[j] = (A.T @ v) / sigma
+        sG[j] = sigma * g
+        gs.append(g)
+        sig.append(sigma)
+    return Q, sG
+
+
+# --------------------------------------------------------------------------
+# Textbook results the iteration is checked against
+# --------------------------------------------------------------------------
+
+def truncated_svd(M, r):
+    """Best rank-r approximation of M in the Frobenius norm (Eckart-Young)."""
+    U, s, Vt = np.linalg.svd(np.asarray(M, F64), full_matrices=False)
+    return (U[:, :r] * s[:r]) @ Vt[:r]
+
+
+def eckart_young_residual(M, r):
+    """sqrt(sum_{j>r} sigma_j^2): no rank-r matrix is closer to M than this."""
+    s = np.linalg.svd(np.asarray(M, F64), compute_uv=False)
+    return float(np.sqrt(np.sum(s[r:] ** 2)))
+
+
+def rel_fro(X, ref):
+    """Relative Frobenius error ||X - ref||_F / ||ref||_F in fp64."""
+    X = np.asarray(X, F64)
+    ref = np.asarray(ref, F64)
+    return float(np.linalg.norm(X - ref) / np.linalg.norm(ref))

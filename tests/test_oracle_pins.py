@@ -1,0 +1,242 @@
+"""Pins for the fp64 CPU oracle: each check ties an oracle function to something
+other than itself (finite differences, brute force, numpy's SVD, closed forms,
+invariants of orthogonal projections).  CPU only.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from oracle import dad_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _tiny_mlp(rng, sizes=(5, 7, 6, 3), acts=("tanh", "sigmoid", "identity")):
+    Ws = [rng.standard_normal((sizes[i], sizes[i + 1])) * 0.7 for i in range(len(sizes) - 1)]
+    Bs = [rng.standard_normal(sizes[i + 1]) * 0.3 for i in range(len(sizes) - 1)]
+    return Ws, Bs, list(acts)
+
+
+# ---------------------------------------------------------------- Eq. 1-4 vs finite differences
+
+@pytest.mark.parametrize("acts", [("tanh", "sigmoid", "identity"), ("relu", "tanh", "tanh")])
+def test_factors_give_finite_difference_gradient(acts):
+    """Eq. 4 with the factors of Eq. 2-3 is the derivative of the loss (check 1)."""
+    rng = np.random.default_rng(7)
+    Ws, Bs, acts = _tiny_mlp(rng, acts=acts)
+    X = rng.standard_normal((9, 5))
+    Y = rng.standard_normal((9, 3))
+    factors = O.mlp_factors(Ws, Bs, acts, X, Y)
+    eps = 1e-6
+    for li, (A, D) in enumerate(factors):
+        G = O.full_grad(A, D)
+        assert G.shape == Ws[li].shape            # orientation h_{i-1} x h_i
+        fd = np.zeros_like(G)
+        for p in range(G.shape[0]):
+            for q in range(G.shape[1]):
+                Wp = [w.copy() for w in Ws]
+                Wm = [w.copy() for w in Ws]
+                Wp[li][p, q] += eps
+                Wm[li][p, q] -= eps
+                fd[p, q] = (O.mlp_loss(Wp, Bs, acts, X, Y) - O.mlp_loss(Wm, Bs, acts, X, Y)) / (2 * eps)
+        assert np.linalg.norm(G - fd) / np.linalg.norm(fd) < 1e-7
+
+
+def test_bias_gradient_is_column_sum_of_delta():
+    """A ones column appended to A turns the bias into a weight row: its gradient is 1^T Delta."""
+    rng = np.random.default_rng(8)
+    Ws, Bs, acts = _tiny_mlp(rng)
+    X = rng.standard_normal((4, 5))
+    Y = rng.standard_normal((4, 3))
+    A, D = O.mlp_factors(Ws, Bs, acts, X, Y)[1]
+    eps = 1e-6
+    fd = np.zeros(6)
+    for q in range(6):
+        Bp = [b.copy() for b in Bs]
+        Bm = [b.copy() for b in Bs]
+        Bp[1][q] += eps
+        Bm[1][q] -= eps
+        fd[q] = (O.mlp_loss(Ws, Bp, acts, X, Y) - O.mlp_loss(Ws, Bm, acts, X, Y)) / (2 * eps)
+    A1 = np.concatenate([A, np.ones((4, 1))], axis=1)
+    assert np.allclose(O.full_grad(A1, D)[-1], fd, rtol=1e-7, atol=1e-10)
+
+
+# ---------------------------------------------------------------- dAD exactness (linearity)
+
+def test_sites_sum_equals_stacked_equals_pooled():
+    """Section 3.2: stacking the sites' factors gives the exact pooled gradient (check 2)."""
+    rng = np.random.default_rng(11)
+    Ws, Bs, acts = _tiny_mlp(rng)
+    S, b = 3, 4
+    Xs = [rng.standard_normal((b, 5)) for _ in range(S)]
+    Ys = [rng.standard_normal((b, 3)) for _ in range(S)]
+    per_site = [O.mlp_factors(Ws, Bs, acts, Xs[s], Ys[s], n_global=S * b) for s in range(S)]
+    pooled = O.mlp_factors(Ws, Bs, acts, np.concatenate(Xs), np.concatenate(Ys))
+    for li in range(3):
+        A_st, D_st = O.stack_factors([per_site[s][li][0] for s in range(S)],
+                                     [per_site[s][li][1] for s in range(S)])
+        assert A_st.shape == (S * b, per_site[0][li][0].shape[1])
+        # rows of site s sit at [s*b, (s+1)*b)
+        assert np.array_equal(A_st[b:2 * b], per_site[1][li][0])
+        assert np.array_equal(D_st[2 * b:], per_site[2][li][1])
+        g_sum = sum(O.full_grad(*per_site[s][li]) for s in range(S))
+        g_stack = O.full_grad(A_st, D_st)
+        g_pool = O.full_grad(*pooled[li])
+        assert np.allclose(g_sum, g_stack, rtol=1e-13, atol=1e-15)
+        assert np.allclose(g_stack, g_pool, rtol=1e-13, atol=1e-15)
+
+
+def test_full_grad_brute_force_and_special_cases():
+    rng = np.random.default_rng(3)
+    A = rng.standard_normal((6, 4))
+    D = rng.standard_normal((6, 5))
+    ref = np.zeros((4, 5))
+    for p in range(4):
+        for q in range(5):
+            for n in range(6):
+                ref[p, q] += A[n, p] * D[n, q]
+    assert np.allclose(O.full_grad(A, D), ref, rtol=1e-14, atol=1e-15)
+    # one sample: a plain outer product
+    assert np.array_equal(O.full_grad(A[:1], D[:1]), np.outer(A[0], D[0]))
+    # hand-worked 2x2 example stored as a text fixture
+    with open(os.path.join(GOLDEN, "eq4_hand_example.json")) as f:
+        ex = json.load(f)
+    assert np.array_equal(O.full_grad(ex["A"], ex["Delta"]), np.array(ex["grad"], float))
+    assert np.array_equal(O.rank_r_grad(ex["A"], ex["Delta"]), np.array(ex["grad"], float))
+
+
+def test_gradient_rank_bounded_by_batch():
+    """Section 3.1: the gradient's rank cannot exceed the batch size."""
+    rng = np.random.default_rng(4)
+    A = rng.standard_normal((3, 12))
+    D = rng.standard_normal((3, 9))
+    assert np.linalg.matrix_rank(O.full_grad(A, D)) == 3
+
+
+# ---------------------------------------------------------------- structured power iteration
+
+def test_structured_iterate_equals_plain_iterate():
+    """Eq. 6 equals Eq. 5: B (Delta g) = M^T M g; sigma = sqrt(v^T C v) = ||A^T v||."""
+    rng = np.random.default_rng(5)
+    A = rng.standard_normal((7, 11))
+    D = rng.standard_normal((7, 13))
+    g = rng.standard_normal(13)
+    M = O.full_grad(A, D)
+    C = A @ A.T
+    B = D.T @ C
+    assert np.allclose(B @ (D @ g), M.T @ (M @ g), rtol=1e-12)
+    v = D @ g
+    assert np.isclose(np.sqrt(v @ C @ v), np.linalg.norm(A.T @ v), rtol=1e-13)
+    assert np.allclose(A.T @ v, M @ g, rtol=1e-12)
+
+
+@pytest.mark.parametrize("N,h_in,h_out,r,n", [(20, 33, 17, 5, 2), (64, 40, 50, 8, 3), (9, 30, 12, 4, 1)])
+def test_three_routes_agree(N, h_in, h_out, r, n):
+    rng = np.random.default_rng(N + r)
+    A = np.maximum(rng.standard_normal((N, h_in)), 0)
+    D = rng.standard_normal((N, h_out)) * 0.1
+    G0 = rng.standard_normal((r, h_out))
+    Pt, Gt = O.block_spi(A, D, G0, n)
+    assert Pt.shape == (r, h_in) and Gt.shape == (r, h_out)
+    Gh = O.rank_r_grad(Pt, Gt)
+    assert Gh.shape == (h_in, h_out)
+    dense = O.block_spi_dense(A, D, G0, n)
+    Pt2, Gt2 = O.block_spi_precomputed(A, D, G0, n)
+    assert O.rel_fro(Gh, dense) < 1e-11
+    assert O.rel_fro(O.rank_r_grad(Pt2, Gt2), dense) < 1e-11
+    assert np.allclose(Gt @ Gt.T, np.eye(r), atol=1e-12)
+
+
+def test_full_rank_budget_recovers_gradient_and_truncated_svd():
+    """r >= rank(M): the rank-r gradient is M itself and equals the truncated SVD (check 3a)."""
+    rng = np.random.default_rng(21)
+    # rank 3 through N = 3 samples
+    A = rng.standard_normal((3, 14))
+    D = rng.standard_normal((3, 10))
+    G0 = rng.standard_normal((4, 10))
+    M = O.full_grad(A, D)
+    Gh = O.rank_r_grad(*O.block_spi(A, D, G0, 2))
+    assert O.rel_fro(Gh, M) < 1e-12
+    assert O.rel_fro(Gh, O.truncated_svd(M, 4)) < 1e-12
+    assert O.rel_fro(O.block_spi_dense(A, D, G0, 2), M) < 1e-12
+    # rank 4 through duplicated rows, r equal to the rank
+    A4 = rng.standard_normal((4, 14))
+    D4 = rng.standard_normal((4, 10))
+    A = np.concatenate([A4, A4, A4])
+    D = np.concatenate([D4, D4, D4])
+    M = O.full_grad(A, D)
+    assert np.linalg.matrix_rank(M) == 4
+    Gh = O.rank_r_grad(*O.block_spi(A, D, G0, 2))
+    assert O.rel_fro(Gh, M) < 1e-11
+    assert O.rel_fro(Gh, O.truncated_svd(M, 4)) < 1e-11
+
+
+def test_low_rank_budget_obeys_eckart_young_and_pythagoras():
+    """r < rank(M): residual >= Eckart-Young bound, -> bound as n grows; projection identities (3b)."""
+    rng = np.random.default_rng(22)
+    N, h_in, h_out, r = 40, 30, 24, 5
+    A = np.maximum(rng.standard_normal((N, h_in)), 0)
+    D = rng.standard_normal((N, h_out)) * 0.03
+    G0 = rng.standard_normal((r, h_out))
+    M = O.full_grad(A, D)
+    bound = O.eckart_young_residual(M, r)
+    prev = np.inf
+    for n in (1, 2, 4, 8, 64):
+        Pt, Gt = O.block_spi(A, D, G0, n)
+        Gh = O.rank_r_grad(Pt, Gt)
+        res = np.linalg.norm(M - Gh)
+        assert res >= bound * (1 - 1e-12)
+        assert res <= prev * (1 + 1e-9)
+        prev = res
+        # orthogonal projection of M: ||M - Gh||^2 = ||M||^2 - ||Gh||^2
+        assert np.isclose(res ** 2, np.linalg.norm(M) ** 2 - np.linalg.norm(Gh) ** 2, rtol=1e-10)
+        assert np.allclose(Gt @ Gt.T, np.eye(r), atol=1e-12)
+        # P = M G exactly
+        assert np.allclose(Pt.T, M @ Gt.T, rtol=1e-10, atol=1e-14)
+    assert prev / bound < 1.05
+
+
+def test_converged_iteration_is_truncated_svd_and_sequential_route_agrees():
+    """With a spectral gap and many iterations both the block and the one-vector-at-a-time
+    (peeling, Eq. 7) routes reach numpy's truncated SVD."""
+    rng = np.random.default_rng(23)
+    N, h_in, h_out, r = 12, 40, 30, 4
+    A = rng.standard_normal((N, h_in))
+    D = rng.standard_normal((N, h_out)) * (0.5 ** np.arange(N))[:, None]
+    M = O.full_grad(A, D)
+    G0 = rng.standard_normal((r, h_out))
+    tsvd = O.truncated_svd(M, r)
+    assert O.rel_fro(O.rank_r_grad(*O.block_spi(A, D, G0, 60)), tsvd) < 1e-10
+    Q, sG = O.sequential_spi(A, D, G0, 200)
+    assert O.rel_fro(O.rank_r_grad(Q, sG), tsvd) < 1e-8
+    # unit left vectors, singular values carried by the right rows
+    assert np.allclose(np.linalg.norm(Q, axis=1), 1.0, atol=1e-12)
+    s = np.linalg.svd(M, compute_uv=False)
+    assert np.allclose(np.linalg.norm(sG, axis=1), s[:r], rtol=1e-8)
+
+
+def test_result_does_not_depend_on_basis_of_start_span():
+    """Only span(G0) matters: mixing the start rows by an invertible matrix leaves P G^T unchanged."""
+    rng = np.random.default_rng(24)
+    A = rng.standard_normal((25, 18))
+    D = rng.standard_normal((25, 16))
+    G0 = rng.standard_normal((3, 16))
+    T = rng.standard_normal((3, 3)) + 3 * np.eye(3)
+    a = O.rank_r_grad(*O.block_spi(A, D, G0, 2))
+    b = O.rank_r_grad(*O.block_spi(A, D, T @ G0, 2))
+    assert O.rel_fro(a, b) < 1e-11
+
+
+def test_stacked_rank_pairs_are_factors_again():
+    """Algorithm 1: sum_s P_s G_s^T equals the gradient of the stacked r-row pairs."""
+    rng = np.random.default_rng(25)
+    pairs = []
+    for s in range(3):
+        A = rng.standard_normal((10, 12))
+        D = rng.standard_normal((10, 9))
+        pairs.append(O.block_spi(A, D, rng.standard_normal((2, 9)), 2))
+    Pst, Gst = O.stack_factors([p for p, _ in pairs], [g for _, g in pairs])
+    assert Pst.shape == (6, 12) and Gst.shape == (6, 9)
+    assert np.allclose(O.full_grad(Pst, Gst), sum(O.rank_r_grad(p, g) for p, g in pairs), rtol=1e-12)
