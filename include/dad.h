@@ -1,0 +1,139 @@
+/*
+ * dad.h - C ABI of libdad: the single-GPU hot path of distributed
+ * auto-differentiation (dAD, arXiv 2102.09631) for AMD MI355X (gfx950).
+ *
+ * One linear layer with input width h_in = h_{i-1} and output width
+ * h_out = h_i contributes a factor pair, one row per sample or token
+ * (Section 3.3; Algorithm 2, INPUT):
+ *
+ *     A     N x h_in    input activations  A_{i-1}
+ *     Delta N x h_out   back-propagated errors  Delta_i
+ *
+ * whose product M = A^T Delta (h_in x h_out) is the layer's weight gradient
+ * (Section 3.1, Eq. 4).  The library stacks the pairs of S sites, compresses
+ * the implicit product to rank r without forming it, and rebuilds the gradient
+ * from either form.
+ *
+ * Conventions for every call
+ *   - All matrices are dense, row-major, with no padding between rows.
+ *   - Every pointer named "device" is a HIP device pointer on the current
+ *     device and is owned by the caller; the library allocates and frees no
+ *     device memory and keeps no state between calls.  Scratch space comes in
+ *     through `workspace` (size from the matching *_workspace_bytes query).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work and return; they do not synchronise.
+ *   - Argument errors are detected on the host and returned before anything
+ *     is enqueued (so they can be exercised without a GPU).  A numerical
+ *     breakdown found on the device is latched in the workspace and reported
+ *     by dad_poll_numeric_status.
+ *   - Device pointers must be 16-byte aligned.  Any N, h_in, h_out >= 1 is
+ *     accepted; shapes whose widths are multiples of the MFMA tile take the
+ *     fast kernels, others a slower guarded path with identical results up to
+ *     rounding order.
+ *   - Overlapping calls that share a workspace race; use one workspace per
+ *     stream.
+ */
+#ifndef DAD_H
+#define DAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Element type of the factor matrices.  Accumulation is always fp32. */
+typedef enum { DAD_F32 = 0, DAD_BF16 = 1 } dad_dtype;
+
+typedef enum {
+    DAD_OK = 0,
+    DAD_ERR_NULL = 1,      /* a required pointer is NULL                              */
+    DAD_ERR_SHAPE = 2,     /* a size is < 1, r > DAD_MAX_RANK or r > min(N,h_in,h_out) */
+    DAD_ERR_ALIGN = 3,     /* a device pointer is not 16-byte aligned                 */
+    DAD_ERR_WORKSPACE = 4, /* ws_bytes is smaller than the matching query returns     */
+    DAD_ERR_DTYPE = 5,     /* unknown dad_dtype                                       */
+    DAD_ERR_NUMERIC = 6,   /* orthonormalisation met a non-positive or NaN pivot      */
+    DAD_ERR_HIP = 7        /* a HIP runtime call failed (launch, copy, sync)          */
+} dad_status;
+
+#define DAD_MAX_RANK 64    /* largest r accepted by dad_compress_rank */
+#define DAD_MAX_SITES 4096 /* largest S accepted by dad_stack_factors */
+
+/* Human-readable name of a status code; static storage, never NULL. */
+const char* dad_status_string(dad_status s);
+
+/*
+ * dad_stack_factors - Section 3.2 (concatenate the sites' factors along the
+ * batch dimension) and Algorithm 1 (the aggregator's vertcat of the rank-r
+ * pairs): A_out = [A_1; ...; A_S], D_out = [Delta_1; ...; Delta_S].
+ *
+ *   S         number of sites, 1..DAD_MAX_SITES
+ *   A_sites   HOST array of S device pointers; A_sites[s] is rows[s] x h_in
+ *   D_sites   HOST array of S device pointers; D_sites[s] is rows[s] x h_out
+ *   rows      HOST array of S row counts, each >= 0 (an empty site is skipped)
+ *   dt        element type of all inputs and outputs (a bit-exact copy)
+ *   A_out     device, (sum rows) x h_in ;  D_out  device, (sum rows) x h_out
+ * Site s lands at row offset rows[0]+...+rows[s-1].  Outputs must not overlap
+ * inputs.  Returns DAD_ERR_SHAPE if S, h_in, h_out < 1 or any rows[s] < 0.
+ */
+dad_status dad_stack_factors(int S, const void* const* A_sites, const void* const* D_sites,
+                             const int64_t* rows, int64_t h_in, int64_t h_out, dad_dtype dt,
+                             void* A_out, void* D_out, void* stream);
+
+/* Bytes of device workspace dad_compress_rank needs for these sizes (0 on invalid sizes). */
+size_t dad_compress_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
+
+/*
+ * dad_compress_rank - Algorithm 2 (structured power iteration, Section 3.3.1,
+ * Eq. 5-6) applied to all r start vectors at once.  n_iter times the block
+ * G (h_out x r) is replaced by an orthonormal basis of
+ *     M^T M G = Delta^T ( A ( A^T ( Delta G ) ) ),
+ * evaluated right to left so that neither M nor A A^T is formed; the
+ * orthonormalisation (CholeskyQR2) stands in for the peeling of Eq. 7.  Then
+ * the left factor P = A^T (Delta G) is formed with the singular values left
+ * inside it (footnote to Section 3.3.1), so that  M ~ P G^T = M G G^T.
+ *
+ *   A, D      device, N x h_in and N x h_out, element type dt
+ *   r         target rank, 1 <= r <= min(N, h_in, h_out, DAD_MAX_RANK)
+ *   n_iter    number of applications of M^T M, >= 1
+ *   G0        device, r x h_out fp32: row j is the start vector g_0^j
+ *   Pt        device out, r x h_in  fp32: row j is the left vector p_j = M g_j
+ *   Gt        device out, r x h_out fp32: rows orthonormal
+ *   workspace device, ws_bytes >= dad_compress_workspace_bytes(...)
+ * Outputs have the factor layout (one row per component), so S such pairs can
+ * be stacked and compressed again (Algorithm 1).  For dt = DAD_BF16 the two
+ * N x r intermediates are rounded to bf16 between contractions; everything of
+ * size h x r or r x r stays fp32 (r x r factorisation in fp64).
+ * If the iterate loses rank (r > rank(M)) the outputs are unspecified and
+ * DAD_ERR_NUMERIC is latched for dad_poll_numeric_status.
+ */
+dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_in, int64_t h_out,
+                             dad_dtype dt, int r, int n_iter, const float* G0, float* Pt, float* Gt,
+                             void* workspace, size_t ws_bytes, void* stream);
+
+/* Bytes of device workspace dad_reconstruct_grad needs (may be 0 for small K; 0 on invalid sizes). */
+size_t dad_reconstruct_workspace_bytes(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
+
+/*
+ * dad_reconstruct_grad - Section 3.1, Eq. 4:  G = L^T R,  G[p][q] = sum_k L[k][p] R[k][q].
+ *   full gradient  : L = A (N x h_in), R = Delta (N x h_out), K = N, dt = factor type
+ *   rank-r gradient: L = Pt (r x h_in), R = Gt (r x h_out), K = r, dt = DAD_F32
+ *                    (Algorithm 1, the sites' local rebuild)
+ *   G         device out, h_in x h_out fp32, overwritten
+ *   workspace device, may be NULL when the query returns 0
+ */
+dad_status dad_reconstruct_grad(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out,
+                                dad_dtype dt, float* G, void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * Synchronises `stream`, reads the flag a previous dad_compress_rank latched in
+ * `workspace` and returns DAD_OK or DAD_ERR_NUMERIC (DAD_ERR_HIP if the sync or
+ * copy fails).  The flag is cleared at the start of every dad_compress_rank.
+ */
+dad_status dad_poll_numeric_status(const void* workspace, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DAD_H */

@@ -1,0 +1,172 @@
+"""ctypes binding of libdad's C ABI (include/dad.h).
+
+Argument marshalling only: torch supplies device memory and the current HIP
+stream; every step of the path runs inside the library's kernels.  There is no
+fallback: if libdad.so is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdad.so")
+
+DAD_F32, DAD_BF16 = 0, 1
+DAD_OK, DAD_ERR_NULL, DAD_ERR_SHAPE, DAD_ERR_ALIGN, DAD_ERR_WORKSPACE, DAD_ERR_DTYPE, DAD_ERR_NUMERIC, \
+    DAD_ERR_HIP = range(8)
+DAD_MAX_RANK = 64
+
+_lib = None
+
+
+class DadError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {lib().dad_status_string(status).decode()}")
+
+
+def lib() -> C.CDLL:
+    """Load libdad.so (built by paper_2102_09631_amd.build) and declare its prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2102_09631_amd.build` first "
+                           "(there is no fallback path)")
+    L = C.CDLL(LIB_PATH)
+    vp, i64, sz = C.c_void_p, C.c_int64, C.c_size_t
+    L.dad_status_string.restype = C.c_char_p
+    L.dad_status_string.argtypes = [C.c_int]
+    L.dad_stack_factors.restype = C.c_int
+    L.dad_stack_factors.argtypes = [C.c_int, C.POINTER(vp), C.POINTER(vp), C.POINTER(i64), i64, i64, C.c_int,
+                                    vp, vp, vp]
+    L.dad_compress_workspace_bytes.restype = sz
+    L.dad_compress_workspace_bytes.argtypes = [i64, i64, i64, C.c_int, C.c_int]
+    L.dad_compress_rank.restype = C.c_int
+    L.dad_compress_rank.argtypes = [vp, vp, i64, i64, i64, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, sz, vp]
+    L.dad_reconstruct_workspace_bytes.restype = sz
+    L.dad_reconstruct_workspace_bytes.argtypes = [i64, i64, i64, C.c_int]
+    L.dad_reconstruct_grad.restype = C.c_int
+    L.dad_reconstruct_grad.argtypes = [vp, vp, i64, i64, i64, C.c_int, vp, vp, sz, vp]
+    L.dad_poll_numeric_status.restype = C.c_int
+    L.dad_poll_numeric_status.argtypes = [vp, vp]
+    _lib = L
+    return L
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return DAD_F32
+    if t.dtype == torch.bfloat16:
+        return DAD_BF16
+    raise TypeError(f"factor dtype must be float32 or bfloat16, got {t.dtype}")
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(rc: int, where: str):
+    if rc != DAD_OK:
+        raise DadError(rc, where)
+
+
+def _dense2d(t: torch.Tensor, name: str):
+    if t.dim() != 2 or not t.is_contiguous() or not t.is_cuda:
+        raise ValueError(f"{name} must be a contiguous 2-D CUDA tensor")
+
+
+def stack_factors(A_sites, D_sites, A_out=None, D_out=None):
+    """dad_stack_factors: vertical concatenation of the sites' (A_s, Delta_s)."""
+    S = len(A_sites)
+    if S == 0 or len(D_sites) != S:
+        raise ValueError("need the same non-zero number of A and Delta blocks")
+    for a, d in zip(A_sites, D_sites):
+        _dense2d(a, "A_s")
+        _dense2d(d, "Delta_s")
+        if a.shape[0] != d.shape[0] or a.dtype != A_sites[0].dtype or d.dtype != a.dtype:
+            raise ValueError("site blocks disagree in rows or dtype")
+    h_in, h_out = A_sites[0].shape[1], D_sites[0].shape[1]
+    if any(a.shape[1] != h_in for a in A_sites) or any(d.shape[1] != h_out for d in D_sites):
+        raise ValueError("site blocks disagree in width")
+    rows = [int(a.shape[0]) for a in A_sites]
+    N = sum(rows)
+    dev, dt = A_sites[0].device, A_sites[0].dtype
+    if A_out is None:
+        A_out = torch.empty((N, h_in), dtype=dt, device=dev)
+    if D_out is None:
+        D_out = torch.empty((N, h_out), dtype=dt, device=dev)
+    pa = (C.c_void_p * S)(*[a.data_ptr() for a in A_sites])
+    pd = (C.c_void_p * S)(*[d.data_ptr() for d in D_sites])
+    pr = (C.c_int64 * S)(*rows)
+    _check(lib().dad_stack_factors(S, pa, pd, pr, h_in, h_out, _dt(A_sites[0]), A_out.data_ptr(), D_out.data_ptr(),
+                                   _stream()), "dad_stack_factors")
+    return A_out, D_out
+
+
+def compress_workspace_bytes(N, h_in, h_out, r, dtype) -> int:
+    return lib().dad_compress_workspace_bytes(N, h_in, h_out, r, DAD_BF16 if dtype == torch.bfloat16 else DAD_F32)
+
+
+def compress_rank(A, D, r, n_iter, G0, Pt=None, Gt=None, workspace=None, check=False):
+    """dad_compress_rank: (A, Delta, G0) -> (Pt r x h_in, Gt r x h_out), fp32.
+
+    `workspace` is a uint8 CUDA tensor of at least compress_workspace_bytes(...);
+    one is allocated when omitted.  With check=True the stream is synchronised
+    and a latched numerical breakdown raises DadError(DAD_ERR_NUMERIC).
+    """
+    _dense2d(A, "A")
+    _dense2d(D, "Delta")
+    _dense2d(G0, "G0")
+    N, h_in = A.shape
+    h_out = D.shape[1]
+    if D.shape[0] != N or D.dtype != A.dtype:
+        raise ValueError("A and Delta disagree in rows or dtype")
+    if G0.dtype != torch.float32 or tuple(G0.shape) != (r, h_out):
+        raise ValueError("G0 must be float32 of shape (r, h_out)")
+    dt = _dt(A)
+    if workspace is None:
+        nbytes = lib().dad_compress_workspace_bytes(N, h_in, h_out, r, dt)
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=A.device)
+    if Pt is None:
+        Pt = torch.empty((r, h_in), dtype=torch.float32, device=A.device)
+    if Gt is None:
+        Gt = torch.empty((r, h_out), dtype=torch.float32, device=A.device)
+    _check(lib().dad_compress_rank(A.data_ptr(), D.data_ptr(), N, h_in, h_out, dt, r, n_iter, G0.data_ptr(),
+                                   Pt.data_ptr(), Gt.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()),
+           "dad_compress_rank")
+    if check:
+        _check(lib().dad_poll_numeric_status(workspace.data_ptr(), _stream()), "dad_poll_numeric_status")
+    return Pt, Gt
+
+
+def reconstruct_workspace_bytes(K, h_in, h_out, dtype) -> int:
+    return lib().dad_reconstruct_workspace_bytes(K, h_in, h_out, DAD_BF16 if dtype == torch.bfloat16 else DAD_F32)
+
+
+def reconstruct_grad(L, R, G=None, workspace=None):
+    """dad_reconstruct_grad: G = L^T R (h_in x h_out fp32) from K-row factors."""
+    _dense2d(L, "L")
+    _dense2d(R, "R")
+    K, h_in = L.shape
+    h_out = R.shape[1]
+    if R.shape[0] != K or R.dtype != L.dtype:
+        raise ValueError("L and R disagree in rows or dtype")
+    dt = _dt(L)
+    if workspace is None:
+        nbytes = lib().dad_reconstruct_workspace_bytes(K, h_in, h_out, dt)
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=L.device) if nbytes else None
+    if G is None:
+        G = torch.empty((h_in, h_out), dtype=torch.float32, device=L.device)
+    _check(lib().dad_reconstruct_grad(L.data_ptr(), R.data_ptr(), K, h_in, h_out, dt, G.data_ptr(),
+                                      workspace.data_ptr() if workspace is not None else None,
+                                      workspace.numel() if workspace is not None else 0, _stream()),
+           "dad_reconstruct_grad")
+    return G
+
+
+def poll_numeric_status(workspace) -> int:
+    return lib().dad_poll_numeric_status(workspace.data_ptr(), _stream())

@@ -1,0 +1,201 @@
+// C ABI of libdad: argument checks on the host, then kernel launches on the caller's stream.
+#include "dad_internal.h"
+
+namespace dad {
+
+// implemented in the kernel translation units
+dad_status gen_thin_nn(const void*, const float*, void*, int64_t, int64_t, int, dad_dtype, hipStream_t);
+dad_status gen_thin_tn(const void*, const void*, float*, float*, SplitPlan, int64_t, int64_t, int, dad_dtype,
+                       hipStream_t);
+dad_status gen_rebuild(const void*, const void*, int64_t, int64_t, int64_t, dad_dtype, float*, float*, SplitPlan,
+                       hipStream_t);
+dad_status launch_stack(int, const void* const*, const void* const*, const int64_t*, int64_t, int64_t, dad_dtype,
+                        void*, void*, hipStream_t);
+int gram_blocks_for(int64_t h);
+
+static SplitPlan split_rows(int64_t rows, int64_t tiles, int64_t target_blocks, int64_t min_chunk, int64_t quantum) {
+    int64_t want = ceil_div(target_blocks, tiles);
+    int64_t max_splits = ceil_div(rows, min_chunk);
+    if (want > max_splits) want = max_splits;
+    if (want < 1) want = 1;
+    int64_t chunk = align_up((size_t)ceil_div(rows, want), (size_t)quantum);
+    SplitPlan sp;
+    sp.chunk = chunk;
+    sp.splits = (int)ceil_div(rows, chunk);
+    return sp;
+}
+
+CompressPlan plan_compress(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt) {
+    CompressPlan p;
+    p.fast = false;
+    p.tn_in = split_rows(N, ceil_div(h_in, 64), 2048, 256, 32);
+    p.tn_out = split_rows(N, ceil_div(h_out, 64), 2048, 256, 32);
+    p.gram_blocks = gram_blocks_for(h_out);
+    size_t o = 0;
+    p.off_flag = o;
+    o += 256;
+    p.off_V = o;
+    o += align_up((size_t)N * r * elem_size(dt), 256);
+    size_t part_in = (size_t)p.tn_in.splits * r * h_in * 4, part_out = (size_t)p.tn_out.splits * r * h_out * 4;
+    p.off_part = o;
+    o += align_up(part_in > part_out ? part_in : part_out, 256);
+    p.off_Ut = o;
+    o += align_up((size_t)r * h_in * 4, 256);
+    p.off_Yt = o;
+    o += align_up((size_t)r * h_out * 4, 256);
+    p.off_gram = o;
+    o += align_up((size_t)p.gram_blocks * r * r * 8, 256);
+    p.off_rinv = o;
+    o += align_up((size_t)r * r * 4, 256);
+    p.total = o;
+    return p;
+}
+
+RebuildPlan plan_rebuild(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt) {
+    (void)dt;
+    RebuildPlan p;
+    p.fast = false;
+    p.split = split_rows(K, ceil_div(h_in, 64) * ceil_div(h_out, 64), 2048, 512, 16);
+    p.total = p.split.splits > 1 ? (size_t)p.split.splits * h_in * h_out * 4 : 0;
+    return p;
+}
+
+static bool dtype_ok(dad_dtype dt) { return dt == DAD_F32 || dt == DAD_BF16; }
+
+}  // namespace dad
+
+using namespace dad;
+
+extern "C" {
+
+const char* dad_status_string(dad_status s) {
+    switch (s) {
+        case DAD_OK: return "DAD_OK";
+        case DAD_ERR_NULL: return "DAD_ERR_NULL: required pointer is NULL";
+        case DAD_ERR_SHAPE: return "DAD_ERR_SHAPE: size out of range";
+        case DAD_ERR_ALIGN: return "DAD_ERR_ALIGN: device pointer not 16-byte aligned";
+        case DAD_ERR_WORKSPACE: return "DAD_ERR_WORKSPACE: workspace too small";
+        case DAD_ERR_DTYPE: return "DAD_ERR_DTYPE: unknown element type";
+        case DAD_ERR_NUMERIC: return "DAD_ERR_NUMERIC: orthonormalisation broke down (iterate lost rank)";
+        case DAD_ERR_HIP: return "DAD_ERR_HIP: HIP runtime call failed";
+    }
+    return "unknown dad_status";
+}
+
+dad_status dad_stack_factors(int S, const void* const* A_sites, const void* const* D_sites, const int64_t* rows,
+                             int64_t h_in, int64_t h_out, dad_dtype dt, void* A_out, void* D_out, void* stream) {
+    if (!A_sites || !D_sites || !rows || !A_out || !D_out) return DAD_ERR_NULL;
+    if (!dtype_ok(dt)) return DAD_ERR_DTYPE;
+    if (S < 1 || S > DAD_MAX_SITES || h_in < 1 || h_out < 1) return DAD_ERR_SHAPE;
+    for (int s = 0; s < S; ++s) {
+        if (rows[s] < 0) return DAD_ERR_SHAPE;
+        if (rows[s] > 0 && (!A_sites[s] || !D_sites[s])) return DAD_ERR_NULL;
+    }
+    if (!aligned16(A_out) || !aligned16(D_out)) return DAD_ERR_ALIGN;
+    for (int s = 0; s < S; ++s)
+        if (rows[s] > 0 && (!aligned16(A_sites[s]) || !aligned16(D_sites[s]))) return DAD_ERR_ALIGN;
+    return launch_stack(S, A_sites, D_sites, rows, h_in, h_out, dt, A_out, D_out, (hipStream_t)stream);
+}
+
+static bool compress_shape_ok(int64_t N, int64_t h_in, int64_t h_out, int r) {
+    if (N < 1 || h_in < 1 || h_out < 1 || r < 1 || r > DAD_MAX_RANK) return false;
+    if (r > N || r > h_in || r > h_out) return false;
+    // intermediate indices are computed in int64; keep element counts well inside it
+    if (N > (int64_t)1 << 40 || h_in > (int64_t)1 << 24 || h_out > (int64_t)1 << 24) return false;
+    return true;
+}
+
+size_t dad_compress_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt) {
+    if (!dtype_ok(dt) || !compress_shape_ok(N, h_in, h_out, r)) return 0;
+    return plan_compress(N, h_in, h_out, r, dt).total;
+}
+
+dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_in, int64_t h_out, dad_dtype dt,
+                             int r, int n_iter, const float* G0, float* Pt, float* Gt, void* workspace,
+                             size_t ws_bytes, void* stream) {
+    if (!A || !D || !G0 || !Pt || !Gt || !workspace) return DAD_ERR_NULL;
+    if (!dtype_ok(dt)) return DAD_ERR_DTYPE;
+    if (!compress_shape_ok(N, h_in, h_out, r) || n_iter < 1) return DAD_ERR_SHAPE;
+    if (!aligned16(A) || !aligned16(D) || !aligned16(G0) || !aligned16(Pt) || !aligned16(Gt) ||
+        !aligned16(workspace))
+        return DAD_ERR_ALIGN;
+    const CompressPlan p = plan_compress(N, h_in, h_out, r, dt);
+    if (ws_bytes < p.total) return DAD_ERR_WORKSPACE;
+
+    hipStream_t s = (hipStream_t)stream;
+    char* ws = static_cast<char*>(workspace);
+    int* flag = reinterpret_cast<int*>(ws + p.off_flag);
+    void* V = ws + p.off_V;
+    float* part = reinterpret_cast<float*>(ws + p.off_part);
+    float* Ut = reinterpret_cast<float*>(ws + p.off_Ut);
+    float* Yt = reinterpret_cast<float*>(ws + p.off_Yt);
+    double* gram = reinterpret_cast<double*>(ws + p.off_gram);
+    float* rinv = reinterpret_cast<float*>(ws + p.off_rinv);
+    dad_status rc;
+
+    if ((rc = launch_fill_int(flag, 0, s)) != DAD_OK) return rc;
+    const float* Gcur = G0;
+    for (int it = 0; it < n_iter; ++it) {
+        if ((rc = launch_thin_nn(D, Gcur, V, N, h_out, r, dt, p.fast, s)) != DAD_OK) return rc;            // V = Delta G
+        if ((rc = launch_thin_tn(A, V, Ut, part, p.tn_in, N, h_in, r, dt, p.fast, s)) != DAD_OK) return rc;  // U = A^T V
+        if ((rc = launch_thin_nn(A, Ut, V, N, h_in, r, dt, p.fast, s)) != DAD_OK) return rc;               // W = A U
+        if ((rc = launch_thin_tn(D, V, Yt, part, p.tn_out, N, h_out, r, dt, p.fast, s)) != DAD_OK) return rc;  // Y = Delta^T W
+        if ((rc = launch_cholqr2(Yt, Gt, h_out, r, gram, p.gram_blocks, rinv, flag, s)) != DAD_OK) return rc;
+        Gcur = Gt;
+    }
+    if ((rc = launch_thin_nn(D, Gt, V, N, h_out, r, dt, p.fast, s)) != DAD_OK) return rc;             // V = Delta G
+    return launch_thin_tn(A, V, Pt, part, p.tn_in, N, h_in, r, dt, p.fast, s);                        // P = A^T V
+}
+
+static bool rebuild_shape_ok(int64_t K, int64_t h_in, int64_t h_out) {
+    return K >= 1 && h_in >= 1 && h_out >= 1 && K <= (int64_t)1 << 40 && h_in <= (int64_t)1 << 24 &&
+           h_out <= (int64_t)1 << 24;
+}
+
+size_t dad_reconstruct_workspace_bytes(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt) {
+    if (!dtype_ok(dt) || !rebuild_shape_ok(K, h_in, h_out)) return 0;
+    return plan_rebuild(K, h_in, h_out, dt).total;
+}
+
+dad_status dad_reconstruct_grad(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt,
+                                float* G, void* workspace, size_t ws_bytes, void* stream) {
+    if (!L || !R || !G) return DAD_ERR_NULL;
+    if (!dtype_ok(dt)) return DAD_ERR_DTYPE;
+    if (!rebuild_shape_ok(K, h_in, h_out)) return DAD_ERR_SHAPE;
+    const RebuildPlan p = plan_rebuild(K, h_in, h_out, dt);
+    if (p.total > 0 && !workspace) return DAD_ERR_NULL;
+    if (!aligned16(L) || !aligned16(R) || !aligned16(G) || (workspace && !aligned16(workspace))) return DAD_ERR_ALIGN;
+    if (ws_bytes < p.total) return DAD_ERR_WORKSPACE;
+    return launch_rebuild(L, R, K, h_in, h_out, dt, G, static_cast<float*>(workspace), p, (hipStream_t)stream);
+}
+
+dad_status dad_poll_numeric_status(const void* workspace, void* stream) {
+    if (!workspace) return DAD_ERR_NULL;
+    int flag = 0;
+    DAD_HIP_TRY(hipMemcpyAsync(&flag, workspace, sizeof(int), hipMemcpyDeviceToHost, (hipStream_t)stream));
+    DAD_HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    return flag ? DAD_ERR_NUMERIC : DAD_OK;
+}
+
+}  // extern "C"
+
+namespace dad {
+
+dad_status launch_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int64_t h, int r, dad_dtype dt,
+                          bool fast, hipStream_t s) {
+    (void)fast;
+    return gen_thin_nn(X, Pt, out, N, h, r, dt, s);
+}
+
+dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp, int64_t N,
+                          int64_t h, int r, dad_dtype dt, bool fast, hipStream_t s) {
+    (void)fast;
+    return gen_thin_tn(X, V, out_t, partials, sp, N, h, r, dt, s);
+}
+
+dad_status launch_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt,
+                          float* G, float* partials, const RebuildPlan& plan, hipStream_t s) {
+    return gen_rebuild(L, R, K, h_in, h_out, dt, G, partials, plan.split, s);
+}
+
+}  // namespace dad

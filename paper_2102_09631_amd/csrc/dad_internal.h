@@ -1,0 +1,101 @@
+// Internal declarations shared by the translation units of libdad (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "dad.h"
+
+namespace dad {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bit pattern
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// Round to nearest, ties to even; NaN stays NaN.
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)0x7fc0;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float ld(const T* p, int64_t i);
+template <> __device__ __forceinline__ float ld<float>(const float* p, int64_t i) { return p[i]; }
+template <> __device__ __forceinline__ float ld<bf16_t>(const bf16_t* p, int64_t i) { return bf16_to_f32(p[i]); }
+
+template <typename T> __device__ __forceinline__ void st(T* p, int64_t i, float v);
+template <> __device__ __forceinline__ void st<float>(float* p, int64_t i, float v) { p[i] = v; }
+template <> __device__ __forceinline__ void st<bf16_t>(bf16_t* p, int64_t i, float v) { p[i] = f32_to_bf16(v); }
+
+inline size_t elem_size(dad_dtype dt) { return dt == DAD_BF16 ? 2 : 4; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+#define DAD_HIP_TRY(expr)                          \
+    do {                                           \
+        if ((expr) != hipSuccess) return DAD_ERR_HIP; \
+    } while (0)
+
+#define DAD_LAUNCH_CHECK()                                 \
+    do {                                                   \
+        if (hipGetLastError() != hipSuccess) return DAD_ERR_HIP; \
+    } while (0)
+
+// ---------------------------------------------------------------- workspace plans
+
+// Split of a contraction over `rows` rows into `splits` contiguous chunks of
+// `chunk` rows (the last may be short).
+struct SplitPlan {
+    int splits;
+    int64_t chunk;
+};
+
+// Layout of the dad_compress_rank workspace (byte offsets from its start).
+struct CompressPlan {
+    size_t off_flag;      // int flag word (256 B reserved)
+    size_t off_V;         // N x r intermediate (element type of the factors)
+    size_t off_part;      // split partials, fp32
+    size_t off_Ut;        // r x h_in fp32
+    size_t off_Yt;        // r x h_out fp32
+    size_t off_gram;      // gram partials, fp64
+    size_t off_rinv;      // r x r fp32
+    size_t total;
+    SplitPlan tn_in;      // split of  A^T V   (width h_in)
+    SplitPlan tn_out;     // split of  Delta^T W (width h_out)
+    int gram_blocks;
+    bool fast;            // MFMA kernels apply to these sizes
+};
+
+CompressPlan plan_compress(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
+
+struct RebuildPlan {
+    SplitPlan split;
+    size_t total;  // bytes of partials (0 when splits == 1)
+    bool fast;
+};
+
+RebuildPlan plan_rebuild(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
+
+// ---------------------------------------------------------------- launchers (host)
+
+// out[n][j] = sum_k X[n][k] * Pt[j][k];  X is N x h (dt), Pt r x h fp32, out N x r (dt).
+dad_status launch_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int64_t h, int r,
+                          dad_dtype dt, bool fast, hipStream_t s);
+
+// out_t[j][p] = sum_n X[n][p] * V[n][j];  X N x h (dt), V N x r (dt), out_t r x h fp32.
+dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp,
+                          int64_t N, int64_t h, int r, dad_dtype dt, bool fast, hipStream_t s);
+
+// In-place orthonormalisation of the rows' transposes: Yt (r x h) -> Gt (r x h), G^T G = I.
+dad_status launch_cholqr2(const float* Yt, float* Gt, int64_t h, int r, double* gram_part, int gram_blocks,
+                          float* rinv, int* flag, hipStream_t s);
+
+dad_status launch_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt,
+                          float* G, float* partials, const RebuildPlan& plan, hipStream_t s);
+
+dad_status launch_fill_int(int* p, int value, hipStream_t s);
+
+}  // namespace dad

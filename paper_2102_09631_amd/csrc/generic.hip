@@ -1,0 +1,232 @@
+// Guarded LDS-tiled kernels that accept any shape and either element type.
+// They serve the shapes the MFMA kernels do not take (ragged widths, fp32
+// factors) and compute the same contractions with fp32 FMA.
+#include "dad_internal.h"
+
+namespace dad {
+
+// ---------------------------------------------------------------- thin N x h by h x r
+// out[n][j] = sum_k X[n][k] * Pt[j][k]   (V = Delta G and W = A U of Eq. 6)
+template <typename T>
+__global__ __launch_bounds__(256) void k_thin_nn(const T* __restrict__ X, const float* __restrict__ Pt,
+                                                 T* __restrict__ out, int64_t N, int64_t h, int r) {
+    constexpr int ROWS = 64, KC = 32;
+    __shared__ float Xs[ROWS][KC + 1];
+    __shared__ float Ps[DAD_MAX_RANK][KC + 1];
+    const int t = threadIdx.x;
+    const int row = t & 63, jg = t >> 6;
+    const int64_t n0 = (int64_t)blockIdx.x * ROWS;
+    float acc[DAD_MAX_RANK / 4];
+#pragma unroll
+    for (int m = 0; m < DAD_MAX_RANK / 4; ++m) acc[m] = 0.f;
+
+    for (int64_t k0 = 0; k0 < h; k0 += KC) {
+        for (int e = t; e < ROWS * KC; e += 256) {
+            int rr = e / KC, kk = e % KC;
+            int64_t n = n0 + rr, k = k0 + kk;
+            Xs[rr][kk] = (n < N && k < h) ? ld<T>(X, n * h + k) : 0.f;
+        }
+        for (int e = t; e < r * KC; e += 256) {
+            int j = e / KC, kk = e % KC;
+            int64_t k = k0 + kk;
+            Ps[j][kk] = (k < h) ? Pt[(int64_t)j * h + k] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int m = 0; m < DAD_MAX_RANK / 4; ++m) {
+            int j = jg + 4 * m;
+            if (j < r) {
+                float a = acc[m];
+#pragma unroll
+                for (int kk = 0; kk < KC; ++kk) a = fmaf(Xs[row][kk], Ps[j][kk], a);
+                acc[m] = a;
+            }
+        }
+        __syncthreads();
+    }
+    const int64_t n = n0 + row;
+    if (n < N) {
+#pragma unroll
+        for (int m = 0; m < DAD_MAX_RANK / 4; ++m) {
+            int j = jg + 4 * m;
+            if (j < r) st<T>(out, n * r + j, acc[m]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------- thin (N x h)^T by N x r, split over rows
+// part[s][j][p] = sum_{n in chunk s} X[n][p] * V[n][j]    (U = A^T V, Y = Delta^T W, P = A^T V)
+template <typename T>
+__global__ __launch_bounds__(256) void k_thin_tn(const T* __restrict__ X, const T* __restrict__ V,
+                                                 float* __restrict__ part, int64_t N, int64_t h, int r,
+                                                 int64_t chunk) {
+    constexpr int PW = 64, RC = 32;
+    __shared__ float Xs[RC][PW];
+    __shared__ float Vs[RC][DAD_MAX_RANK];
+    const int t = threadIdx.x;
+    const int pl = t & 63, jg = t >> 6;
+    const int64_t p0 = (int64_t)blockIdx.x * PW;
+    const int64_t nbeg = (int64_t)blockIdx.y * chunk;
+    const int64_t nend = (nbeg + chunk < N) ? nbeg + chunk : N;
+    float acc[DAD_MAX_RANK / 4];
+#pragma unroll
+    for (int m = 0; m < DAD_MAX_RANK / 4; ++m) acc[m] = 0.f;
+
+    for (int64_t n0 = nbeg; n0 < nend; n0 += RC) {
+        for (int e = t; e < RC * PW; e += 256) {
+            int rr = e / PW, pp = e % PW;
+            int64_t n = n0 + rr, p = p0 + pp;
+            Xs[rr][pp] = (n < nend && p < h) ? ld<T>(X, n * h + p) : 0.f;
+        }
+        for (int e = t; e < RC * r; e += 256) {
+            int rr = e / r, j = e % r;
+            int64_t n = n0 + rr;
+            Vs[rr][j] = (n < nend) ? ld<T>(V, n * r + j) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int m = 0; m < DAD_MAX_RANK / 4; ++m) {
+            int j = jg + 4 * m;
+            if (j < r) {
+                float a = acc[m];
+#pragma unroll
+                for (int rr = 0; rr < RC; ++rr) a = fmaf(Xs[rr][pl], Vs[rr][j], a);
+                acc[m] = a;
+            }
+        }
+        __syncthreads();
+    }
+    const int64_t p = p0 + pl;
+    if (p < h) {
+#pragma unroll
+        for (int m = 0; m < DAD_MAX_RANK / 4; ++m) {
+            int j = jg + 4 * m;
+            if (j < r) part[((int64_t)blockIdx.y * r + j) * h + p] = acc[m];
+        }
+    }
+}
+
+// out[i] = sum_s part[s*n + i], s ascending (fixed order: reruns are bit-identical)
+__global__ __launch_bounds__(256) void k_reduce_slabs(const float* __restrict__ part, float* __restrict__ out,
+                                                      int64_t n, int splits) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float a = 0.f;
+    for (int s = 0; s < splits; ++s) a += part[(int64_t)s * n + i];
+    out[i] = a;
+}
+
+// ---------------------------------------------------------------- G = L^T R, 64 x 64 tiles, split over K
+template <typename T>
+__global__ __launch_bounds__(256) void k_rebuild(const T* __restrict__ L, const T* __restrict__ R,
+                                                 float* __restrict__ out, int64_t K, int64_t h_in,
+                                                 int64_t h_out, int64_t chunk) {
+    constexpr int TM = 64, KC = 16;
+    __shared__ float Ls[KC][TM];
+    __shared__ float Rs[KC][TM];
+    const int t = threadIdx.x;
+    const int tx = t & 15, ty = t >> 4;
+    const int64_t q0 = (int64_t)blockIdx.x * TM, p0 = (int64_t)blockIdx.y * TM;
+    const int64_t kbeg = (int64_t)blockIdx.z * chunk;
+    const int64_t kend = (kbeg + chunk < K) ? kbeg + chunk : K;
+    float acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[a][b] = 0.f;
+
+    for (int64_t k0 = kbeg; k0 < kend; k0 += KC) {
+        for (int e = t; e < KC * TM; e += 256) {
+            int kk = e / TM, c = e % TM;
+            int64_t k = k0 + kk;
+            Ls[kk][c] = (k < kend && p0 + c < h_in) ? ld<T>(L, k * h_in + p0 + c) : 0.f;
+            Rs[kk][c] = (k < kend && q0 + c < h_out) ? ld<T>(R, k * h_out + q0 + c) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < KC; ++kk) {
+            float lv[4], rv[4];
+#pragma unroll
+            for (int a = 0; a < 4; ++a) lv[a] = Ls[kk][ty * 4 + a];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) rv[b] = Rs[kk][tx * 4 + b];
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) acc[a][b] = fmaf(lv[a], rv[b], acc[a][b]);
+        }
+        __syncthreads();
+    }
+    float* o = out + (int64_t)blockIdx.z * h_in * h_out;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        int64_t p = p0 + ty * 4 + a;
+        if (p >= h_in) continue;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            int64_t q = q0 + tx * 4 + b;
+            if (q < h_out) o[p * h_out + q] = acc[a][b];
+        }
+    }
+}
+
+__global__ void k_fill_int(int* p, int v) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *p = v;
+}
+
+// ---------------------------------------------------------------- host launchers
+
+dad_status gen_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int64_t h, int r, dad_dtype dt,
+                       hipStream_t s) {
+    dim3 grid((unsigned)ceil_div(N, 64));
+    if (dt == DAD_BF16)
+        hipLaunchKernelGGL(k_thin_nn<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)X, Pt, (bf16_t*)out, N, h, r);
+    else
+        hipLaunchKernelGGL(k_thin_nn<float>, grid, dim3(256), 0, s, (const float*)X, Pt, (float*)out, N, h, r);
+    DAD_LAUNCH_CHECK();
+    return DAD_OK;
+}
+
+dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s) {
+    hipLaunchKernelGGL(k_reduce_slabs, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, part, out, n, splits);
+    DAD_LAUNCH_CHECK();
+    return DAD_OK;
+}
+
+dad_status gen_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp, int64_t N,
+                       int64_t h, int r, dad_dtype dt, hipStream_t s) {
+    dim3 grid((unsigned)ceil_div(h, 64), (unsigned)sp.splits);
+    float* dst = sp.splits == 1 ? out_t : partials;
+    if (dt == DAD_BF16)
+        hipLaunchKernelGGL(k_thin_tn<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)X, (const bf16_t*)V, dst, N, h,
+                           r, sp.chunk);
+    else
+        hipLaunchKernelGGL(k_thin_tn<float>, grid, dim3(256), 0, s, (const float*)X, (const float*)V, dst, N, h, r,
+                           sp.chunk);
+    DAD_LAUNCH_CHECK();
+    if (sp.splits > 1) return reduce_slabs(partials, out_t, (int64_t)r * h, sp.splits, s);
+    return DAD_OK;
+}
+
+dad_status gen_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt, float* G,
+                       float* partials, SplitPlan sp, hipStream_t s) {
+    dim3 grid((unsigned)ceil_div(h_out, 64), (unsigned)ceil_div(h_in, 64), (unsigned)sp.splits);
+    float* dst = sp.splits == 1 ? G : partials;
+    if (dt == DAD_BF16)
+        hipLaunchKernelGGL(k_rebuild<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)L, (const bf16_t*)R, dst, K,
+                           h_in, h_out, sp.chunk);
+    else
+        hipLaunchKernelGGL(k_rebuild<float>, grid, dim3(256), 0, s, (const float*)L, (const float*)R, dst, K, h_in,
+                           h_out, sp.chunk);
+    DAD_LAUNCH_CHECK();
+    if (sp.splits > 1) return reduce_slabs(partials, G, h_in * h_out, sp.splits, s);
+    return DAD_OK;
+}
+
+dad_status launch_fill_int(int* p, int value, hipStream_t s) {
+    hipLaunchKernelGGL(k_fill_int, dim3(1), dim3(64), 0, s, p, value);
+    DAD_LAUNCH_CHECK();
+    return DAD_OK;
+}
+
+}  // namespace dad

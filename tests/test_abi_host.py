@@ -1,0 +1,100 @@
+"""The C-ABI library loads without a GPU, exports every symbol the header declares,
+and rejects bad arguments on the host before anything is enqueued (CPU only)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2102_09631_amd import binding as dad
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(dad.LIB_PATH):
+        from paper_2102_09631_amd.build import build_library
+        build_library(verbose=False)
+    return dad.lib()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    text = open(os.path.join(ROOT, "include", "dad.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(dad_[a-z_]+)\s*\(", text))
+    assert {"dad_stack_factors", "dad_compress_rank", "dad_reconstruct_grad", "dad_compress_workspace_bytes",
+            "dad_reconstruct_workspace_bytes", "dad_poll_numeric_status", "dad_status_string"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings(lib):
+    seen = set()
+    for s in range(8):
+        txt = lib.dad_status_string(s).decode()
+        assert txt and txt not in seen
+        seen.add(txt)
+    assert "unknown" in lib.dad_status_string(99).decode()
+
+
+def test_workspace_queries(lib):
+    assert lib.dad_compress_workspace_bytes(64, 784, 128, 4, dad.DAD_F32) > 64 * 4 * 4
+    assert lib.dad_compress_workspace_bytes(64, 784, 128, 0, dad.DAD_F32) == 0
+    assert lib.dad_compress_workspace_bytes(64, 784, 128, 65, dad.DAD_F32) == 0
+    assert lib.dad_compress_workspace_bytes(3, 784, 128, 4, dad.DAD_F32) == 0      # r > N
+    assert lib.dad_compress_workspace_bytes(64, 784, 128, 4, 7) == 0
+    big = lib.dad_compress_workspace_bytes(262144, 1280, 5120, 64, dad.DAD_BF16)
+    assert 262144 * 64 * 2 <= big < (1 << 30)
+    assert lib.dad_reconstruct_workspace_bytes(4, 784, 128, dad.DAD_F32) == 0     # no split for K = r
+    assert lib.dad_reconstruct_workspace_bytes(0, 784, 128, dad.DAD_F32) == 0
+
+
+def test_compress_rejects_bad_arguments_on_host(lib):
+    p = 0x1000  # fake, aligned, never dereferenced: every call below must fail before a launch
+    ws = 1 << 30
+
+    def call(A=p, D=p, N=64, hi=784, ho=128, dt=dad.DAD_F32, r=4, n=2, G0=p, Pt=p, Gt=p, w=p, wb=ws):
+        return lib.dad_compress_rank(A, D, N, hi, ho, dt, r, n, G0, Pt, Gt, w, wb, None)
+
+    assert call(A=None) == dad.DAD_ERR_NULL
+    assert call(G0=None) == dad.DAD_ERR_NULL
+    assert call(w=None) == dad.DAD_ERR_NULL
+    assert call(dt=5) == dad.DAD_ERR_DTYPE
+    assert call(r=0) == dad.DAD_ERR_SHAPE
+    assert call(r=65) == dad.DAD_ERR_SHAPE
+    assert call(N=3) == dad.DAD_ERR_SHAPE          # r > N
+    assert call(ho=2) == dad.DAD_ERR_SHAPE         # r > h_out
+    assert call(n=0) == dad.DAD_ERR_SHAPE
+    assert call(N=0) == dad.DAD_ERR_SHAPE
+    assert call(D=p + 4) == dad.DAD_ERR_ALIGN
+    assert call(wb=128) == dad.DAD_ERR_WORKSPACE
+
+
+def test_reconstruct_and_stack_reject_bad_arguments_on_host(lib):
+    p = 0x1000
+    assert lib.dad_reconstruct_grad(None, p, 4, 8, 8, 0, p, None, 0, None) == dad.DAD_ERR_NULL
+    assert lib.dad_reconstruct_grad(p, p, 0, 8, 8, 0, p, None, 0, None) == dad.DAD_ERR_SHAPE
+    assert lib.dad_reconstruct_grad(p, p, 4, 8, 8, 9, p, None, 0, None) == dad.DAD_ERR_DTYPE
+    assert lib.dad_reconstruct_grad(p, p + 2, 4, 8, 8, 0, p, None, 0, None) == dad.DAD_ERR_ALIGN
+    need = lib.dad_reconstruct_workspace_bytes(65536, 1024, 1024, dad.DAD_BF16)
+    if need:
+        assert lib.dad_reconstruct_grad(p, p, 65536, 1024, 1024, 1, p, None, 0, None) == dad.DAD_ERR_NULL
+        assert lib.dad_reconstruct_grad(p, p, 65536, 1024, 1024, 1, p, p, need - 1, None) == dad.DAD_ERR_WORKSPACE
+    ptrs = (C.c_void_p * 2)(p, p)
+    rows = (C.c_int64 * 2)(4, 4)
+    bad_rows = (C.c_int64 * 2)(4, -1)
+    assert lib.dad_stack_factors(0, ptrs, ptrs, rows, 8, 8, 0, p, p, None) == dad.DAD_ERR_SHAPE
+    assert lib.dad_stack_factors(2, ptrs, ptrs, bad_rows, 8, 8, 0, p, p, None) == dad.DAD_ERR_SHAPE
+    assert lib.dad_stack_factors(2, None, ptrs, rows, 8, 8, 0, p, p, None) == dad.DAD_ERR_NULL
+    assert lib.dad_stack_factors(2, ptrs, ptrs, rows, 8, 8, 0, p + 8, p, None) == dad.DAD_ERR_ALIGN
+    assert lib.dad_stack_factors(2, ptrs, ptrs, rows, 8, 8, 3, p, p, None) == dad.DAD_ERR_DTYPE
+    nullp = (C.c_void_p * 2)(p, None)
+    assert lib.dad_stack_factors(2, nullp, ptrs, rows, 8, 8, 0, p, p, None) == dad.DAD_ERR_NULL
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(dad, "_lib", None)
+    monkeypatch.setattr(dad, "LIB_PATH", str(tmp_path / "libdad.so"))
+    with pytest.raises(RuntimeError, match="missing"):
+        dad.lib()

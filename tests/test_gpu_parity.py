@@ -1,0 +1,175 @@
+"""Parity of the HIP path (through the C ABI) with the fp64 CPU oracle, element by
+element on the same seeded inputs.  Bars: bit-exact for the stack (a copy);
+relative Frobenius error <= 1e-5 for fp32 factors and <= 2e-2 for bf16 factors
+with fp32 accumulation.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dad_oracle as O
+from paper_2102_09631_amd import binding as dad
+from paper_2102_09631_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def to_dev(x, dtype, dev):
+    t = torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def run_layer(w, layer, h_in, h_out, dev, rows=None, sites=None, r=None, n_iter=None):
+    """Stack -> full rebuild -> compress -> rank-r rebuild on the GPU, and the same in the oracle."""
+    r = w.rank if r is None else r
+    n_iter = w.n_iter if n_iter is None else n_iter
+    A_sites, D_sites = W.host_factors(w, layer, h_in, h_out, rows=rows, sites=sites)
+    G0 = W.host_start_matrix(w, layer, h_out, r=r)
+    A, D = dad.stack_factors([to_dev(a, w.dtype, dev) for a in A_sites], [to_dev(d, w.dtype, dev) for d in D_sites])
+    G_full = dad.reconstruct_grad(A, D)
+    Pt, Gt = dad.compress_rank(A, D, r, n_iter, torch.from_numpy(G0).to(dev), check=True)
+    G_r = dad.reconstruct_grad(Pt, Gt)
+    torch.cuda.synchronize()
+    A_ref, D_ref = O.stack_factors(A_sites, D_sites)
+    out = {
+        "stack_exact": bool(np.array_equal(A.float().cpu().numpy(), A_ref)
+                            and np.array_equal(D.float().cpu().numpy(), D_ref)),
+        "e_full": O.rel_fro(G_full.cpu().numpy(), O.full_grad(A_ref, D_ref)),
+    }
+    Pt_ref, Gt_ref = O.block_spi(A_ref, D_ref, G0, n_iter)
+    out["e_rank"] = O.rel_fro(G_r.cpu().numpy(), O.rank_r_grad(Pt_ref, Gt_ref))
+    Gt_h = Gt.cpu().numpy().astype(np.float64)
+    out["orth"] = float(np.abs(Gt_h @ Gt_h.T - np.eye(r)).max())
+    out["e_G"] = O.rel_fro(Gt_h, Gt_ref)           # diagnostic only: a basis is not unique in general
+    out["shapes"] = (tuple(Pt.shape), tuple(Gt.shape), tuple(G_full.shape), tuple(G_r.shape))
+    return out
+
+
+def check(out, dtype, r, h_in, h_out):
+    assert out["shapes"] == ((r, h_in), (r, h_out), (h_in, h_out), (h_in, h_out))
+    assert out["stack_exact"]
+    assert out["e_full"] <= TOL[dtype], out
+    assert out["e_rank"] <= TOL[dtype], out
+    assert out["orth"] <= (1e-5 if dtype == "f32" else 1e-4), out
+
+
+def test_single_linear_784x128(gpu):
+    w = W.WORKLOADS[0]
+    out = run_layer(w, 0, 784, 128, gpu)
+    print(out)
+    check(out, "f32", 4, 784, 128)
+
+
+@pytest.mark.parametrize("layer", [0, 1, 2])
+def test_mlp_784_1024_1024_10(gpu, layer):
+    w = W.WORKLOADS[1]
+    _, h_in, h_out = w.all_layers()[layer]
+    out = run_layer(w, layer, h_in, h_out, gpu)
+    print(out)
+    check(out, "f32", 8, h_in, h_out)
+
+
+@pytest.mark.parametrize("layer", [0, 1, 2, 3])
+def test_encoder_d768_reduced_rows(gpu, layer):
+    """Encoder shapes with 4 sites x 640 rows: several row tiles and a K-split."""
+    w = W.WORKLOADS[2]
+    _, h_in, h_out = w.all_layers()[layer]
+    out = run_layer(w, layer, h_in, h_out, gpu, rows=640)
+    print(out)
+    check(out, "bf16", 16, h_in, h_out)
+
+
+@pytest.mark.parametrize("dtype_idx,N_rows,h_in,h_out,r", [
+    (0, 37, 50, 23, 3),      # everything ragged, fp32
+    (0, 1, 9, 5, 1),         # one sample per site
+    (2, 77, 136, 72, 8),     # bf16, widths multiple of 8 only
+    (2, 33, 65, 31, 5),      # bf16, odd widths (unaligned rows)
+    (4, 200, 256, 384, 64),  # largest rank, GELU / Student-t draws
+    (1, 300, 64, 64, 64),    # r equal to both widths
+])
+def test_ragged_and_edge_shapes(gpu, dtype_idx, N_rows, h_in, h_out, r):
+    w = W.WORKLOADS[dtype_idx]
+    out = run_layer(w, 7, h_in, h_out, gpu, rows=N_rows, sites=3, r=r, n_iter=2)
+    print(out)
+    check(out, w.dtype, r, h_in, h_out)
+
+
+def test_stack_with_empty_and_uneven_sites(gpu):
+    rng = np.random.default_rng(5)
+    rows = [5, 0, 17, 1, 64]
+    for dtype, width in (("f32", (7, 3)), ("bf16", (9, 5)), ("bf16", (64, 128))):
+        A_s = [rng.standard_normal((n, width[0])).astype(np.float32) for n in rows]
+        D_s = [rng.standard_normal((n, width[1])).astype(np.float32) for n in rows]
+        if dtype == "bf16":
+            A_s = [W.bf16_bits_to_f32(W.f32_to_bf16_bits(a)).reshape(a.shape) for a in A_s]
+            D_s = [W.bf16_bits_to_f32(W.f32_to_bf16_bits(d)).reshape(d.shape) for d in D_s]
+        # each site block gets its own 16-byte aligned allocation
+        A, D = dad.stack_factors([to_dev(a, dtype, gpu) for a in A_s], [to_dev(d, dtype, gpu) for d in D_s])
+        A_ref, D_ref = O.stack_factors(A_s, D_s)
+        assert A.shape == A_ref.shape and D.shape == D_ref.shape
+        assert np.array_equal(A.float().cpu().numpy(), A_ref)
+        assert np.array_equal(D.float().cpu().numpy(), D_ref)
+
+
+def test_rank_budget_at_least_gradient_rank_recovers_gradient(gpu):
+    """r = rank(M) = N: the rank-r gradient equals the full gradient and the truncated SVD."""
+    w = W.WORKLOADS[0]
+    A_sites, D_sites = W.host_factors(w, 3, 96, 48, rows=2, sites=2)      # N = 4
+    G0 = W.host_start_matrix(w, 3, 48, r=4)
+    A, D = dad.stack_factors([to_dev(a, "f32", gpu) for a in A_sites], [to_dev(d, "f32", gpu) for d in D_sites])
+    Pt, Gt = dad.compress_rank(A, D, 4, 2, torch.from_numpy(G0).to(gpu), check=True)
+    G_r = dad.reconstruct_grad(Pt, Gt).cpu().numpy()
+    M = O.full_grad(*O.stack_factors(A_sites, D_sites))
+    assert O.rel_fro(G_r, M) <= 1e-5
+    assert O.rel_fro(G_r, O.truncated_svd(M, 4)) <= 1e-5
+
+
+def test_rank_pairs_restack_and_recompress(gpu):
+    """Algorithm 1: per-site rank-r pairs are stacked (N' = S*r rows) and compressed again."""
+    w = W.WORKLOADS[0]
+    S, r = 3, 4
+    A_sites, D_sites = W.host_factors(w, 5, 112, 80, rows=24, sites=S)
+    G0s = [W.host_start_matrix(w, 10 + s, 80, r=r) for s in range(S)]
+    G0agg = W.host_start_matrix(w, 20, 80, r=r)
+    pairs_gpu, pairs_ref = [], []
+    for s in range(S):
+        a, d = to_dev(A_sites[s], "f32", gpu), to_dev(D_sites[s], "f32", gpu)
+        pairs_gpu.append(dad.compress_rank(a, d, r, 2, torch.from_numpy(G0s[s]).to(gpu), check=True))
+        pairs_ref.append(O.block_spi(A_sites[s], D_sites[s], G0s[s], 2))
+    Pst, Gst = dad.stack_factors([p for p, _ in pairs_gpu], [g for _, g in pairs_gpu])
+    assert tuple(Pst.shape) == (S * r, 112) and tuple(Gst.shape) == (S * r, 80)
+    Pt, Gt = dad.compress_rank(Pst, Gst, r, 2, torch.from_numpy(G0agg).to(gpu), check=True)
+    G_hat = dad.reconstruct_grad(Pt, Gt).cpu().numpy()
+    Pst_ref, Gst_ref = O.stack_factors([p for p, _ in pairs_ref], [g for _, g in pairs_ref])
+    ref = O.rank_r_grad(*O.block_spi(Pst_ref, Gst_ref, G0agg, 2))
+    assert O.rel_fro(G_hat, ref) <= 1e-5
+
+
+def test_zero_deltas_latch_numeric_breakdown(gpu):
+    A = torch.ones((16, 32), device=gpu)
+    D = torch.zeros((16, 24), device=gpu)
+    G0 = torch.from_numpy(W.host_start_matrix(W.WORKLOADS[0], 0, 24, r=2)).to(gpu)
+    ws = torch.empty(dad.compress_workspace_bytes(16, 32, 24, 2, torch.float32), dtype=torch.uint8, device=gpu)
+    dad.compress_rank(A, D, 2, 1, G0, workspace=ws)
+    assert dad.poll_numeric_status(ws) == dad.DAD_ERR_NUMERIC
+    # the flag is cleared by the next call on the same workspace
+    D2 = torch.from_numpy(W.host_factors(W.WORKLOADS[0], 1, 32, 24, rows=16, sites=1)[1][0]).to(gpu)
+    dad.compress_rank(A * torch.arange(1, 33, device=gpu), D2, 2, 1, G0, workspace=ws)
+    assert dad.poll_numeric_status(ws) == dad.DAD_OK
+
+
+def test_rerun_is_bit_identical(gpu):
+    """Fixed-order reductions (no float atomics): two runs give the same bits."""
+    w = W.WORKLOADS[1]
+    A_sites, D_sites = W.host_factors(w, 1, 1024, 1024)
+    A, D = dad.stack_factors([to_dev(a, "f32", gpu) for a in A_sites], [to_dev(d, "f32", gpu) for d in D_sites])
+    G0 = torch.from_numpy(W.host_start_matrix(w, 1, 1024)).to(gpu)
+    runs = []
+    for _ in range(2):
+        G = dad.reconstruct_grad(A, D)
+        Pt, Gt = dad.compress_rank(A, D, 8, 2, G0, check=True)
+        runs.append((G.clone(), Pt.clone(), Gt.clone()))
+    for x, y in zip(*runs):
+        assert torch.equal(x, y)
