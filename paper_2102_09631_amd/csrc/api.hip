@@ -12,6 +12,9 @@ dad_status gen_rebuild(const void*, const void*, int64_t, int64_t, int64_t, dad_
 dad_status launch_stack(int, const void* const*, const void* const*, const int64_t*, int64_t, int64_t, dad_dtype,
                         void*, void*, hipStream_t);
 int gram_blocks_for(int64_t h);
+bool rebuild_fast_ok(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
+SplitPlan rebuild_fast_split(int64_t K, int64_t h_in, int64_t h_out);
+dad_status fast_rebuild(const void*, const void*, int64_t, int64_t, int64_t, float*, float*, SplitPlan, hipStream_t);
 
 static SplitPlan split_rows(int64_t rows, int64_t tiles, int64_t target_blocks, int64_t min_chunk, int64_t quantum) {
     int64_t want = ceil_div(target_blocks, tiles);
@@ -52,10 +55,10 @@ CompressPlan plan_compress(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dt
 }
 
 RebuildPlan plan_rebuild(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt) {
-    (void)dt;
     RebuildPlan p;
-    p.fast = false;
-    p.split = split_rows(K, ceil_div(h_in, 64) * ceil_div(h_out, 64), 2048, 512, 16);
+    p.fast = rebuild_fast_ok(K, h_in, h_out, dt);
+    p.split = p.fast ? rebuild_fast_split(K, h_in, h_out)
+                     : split_rows(K, ceil_div(h_in, 64) * ceil_div(h_out, 64), 2048, 512, 16);
     p.total = p.split.splits > 1 ? (size_t)p.split.splits * h_in * h_out * 4 : 0;
     return p;
 }
@@ -195,6 +198,7 @@ dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* par
 
 dad_status launch_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt,
                           float* G, float* partials, const RebuildPlan& plan, hipStream_t s) {
+    if (plan.fast) return fast_rebuild(L, R, K, h_in, h_out, G, partials, plan.split, s);
     return gen_rebuild(L, R, K, h_in, h_out, dt, G, partials, plan.split, s);
 }
 
