@@ -12,6 +12,10 @@ dad_status gen_rebuild(const void*, const void*, int64_t, int64_t, int64_t, dad_
 dad_status launch_stack(int, const void* const*, const void* const*, const int64_t*, int64_t, int64_t, dad_dtype,
                         void*, void*, hipStream_t);
 int gram_blocks_for(int64_t h);
+bool thin_fast_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
+SplitPlan thin_tn_split(int64_t N, int64_t h, int r);
+dad_status fast_thin_nn(const void*, const float*, void*, int64_t, int64_t, int, hipStream_t);
+dad_status fast_thin_tn(const void*, const void*, float*, float*, SplitPlan, int64_t, int64_t, int, hipStream_t);
 bool rebuild_fast_ok(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
 SplitPlan rebuild_fast_split(int64_t K, int64_t h_in, int64_t h_out);
 dad_status fast_rebuild(const void*, const void*, int64_t, int64_t, int64_t, float*, float*, SplitPlan, hipStream_t);
@@ -30,9 +34,9 @@ static SplitPlan split_rows(int64_t rows, int64_t tiles, int64_t target_blocks, 
 
 CompressPlan plan_compress(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt) {
     CompressPlan p;
-    p.fast = false;
-    p.tn_in = split_rows(N, ceil_div(h_in, 64), 2048, 256, 32);
-    p.tn_out = split_rows(N, ceil_div(h_out, 64), 2048, 256, 32);
+    p.fast = thin_fast_ok(N, h_in, h_out, r, dt);
+    p.tn_in = p.fast ? thin_tn_split(N, h_in, r) : split_rows(N, ceil_div(h_in, 64), 2048, 256, 32);
+    p.tn_out = p.fast ? thin_tn_split(N, h_out, r) : split_rows(N, ceil_div(h_out, 64), 2048, 256, 32);
     p.gram_blocks = gram_blocks_for(h_out);
     size_t o = 0;
     p.off_flag = o;
@@ -186,13 +190,13 @@ namespace dad {
 
 dad_status launch_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int64_t h, int r, dad_dtype dt,
                           bool fast, hipStream_t s) {
-    (void)fast;
+    if (fast) return fast_thin_nn(X, Pt, out, N, h, r, s);
     return gen_thin_nn(X, Pt, out, N, h, r, dt, s);
 }
 
 dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp, int64_t N,
                           int64_t h, int r, dad_dtype dt, bool fast, hipStream_t s) {
-    (void)fast;
+    if (fast) return fast_thin_tn(X, V, out_t, partials, sp, N, h, r, s);
     return gen_thin_tn(X, V, out_t, partials, sp, N, h, r, dt, s);
 }
 
