@@ -1,0 +1,284 @@
+#!/usr/bin/env python3
+"""Benchmark of the dAD hot path on one MI355X.
+
+One step = one pass of the whole path over every linear layer of the workload:
+stack the S sites' factor pairs -> rank-r compress (structured power iteration)
+-> rebuild the full gradient A^T Delta -> rebuild the rank-r gradient P G^T.
+Inputs are synthetic, seeded and resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is the full-gradient rebuild rate in TFLOP/s
+(2*N*h_in*h_out flops per layer over the time between the events that bracket
+the rebuild calls); the rank-r compress time per layer, the stack rate and the
+whole-step time ride along.  `roofline` is computed for the kernel with the
+largest share of GPU time from per-kernel HIP-event timings taken by the
+library on the launch stream during the timed steps.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "dAD gradient-rebuild TFLOP/s + rank-r compress us/layer (% MFMA/HBM roofline)"
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3       # MI355X fp32 vector / matrix
+PEAK_HBM_GBPS = 8000.0         # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="gpt2_medium_stack")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def kernel_model(name, N, h_in, h_out, r, es, which, bf16=True):
+    """Algorithmic work of one launch: ("hbm", bytes) or ("mfma", flops).
+
+    `which` says which factor the launch streams ("in" = A, "out" = Delta).
+    """
+    h = h_in if which == "in" else h_out
+    if name in ("k_thin_nn_bf16", "k_thin_tn_bf16", "k_thin_nn", "k_thin_tn"):
+        return "hbm", float(N) * h * es
+    if name == "k_rebuild_bf16":
+        return "mfma", 2.0 * N * h_in * h_out
+    if name == "k_rebuild":
+        if bf16:   # only the rank-r rebuild (K = r, fp32 pairs) runs this kernel: write bound
+            return "hbm", 4.0 * h_in * h_out + 4.0 * r * (h_in + h_out)
+        return "mfma", 2.0 * N * h_in * h_out + 2.0 * r * h_in * h_out   # full + rank-r launches together
+    if name == "k_stack":
+        return "hbm", 2.0 * N * (h_in + h_out) * es
+    return None, 0.0
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (sites are simulated as row blocks on one device); "
+              "--gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2102_09631_amd import binding as dad
+    from paper_2102_09631_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dad.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = W.by_name(args.workload)
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    es = 2 if w.dtype == "bf16" else 4
+    N, r, n_iter, S, b = w.N, w.rank, w.n_iter, w.sites, w.rows_per_site
+    layers = w.all_layers()
+
+    # ---- inputs resident in HBM.  The whole stack when it fits; otherwise one block of distinct
+    # shapes that every block of the stack re-reads (each layer is far larger than any cache).
+    total_bytes = sum(N * (hi + ho) * es for _, hi, ho in layers)
+    resident = layers if total_bytes < 150e9 else layers[:len(w.shapes)]
+    sites = {}
+    for li, hi, ho in resident:
+        sites[li] = W.device_factors(w, li, hi, ho, device=dev)
+    def factors_of(li):
+        return sites[li] if li in sites else sites[li % len(w.shapes)]
+    G0 = {li: W.device_start_matrix(w, li, ho, device=dev) for li, _, ho in layers}
+    shape_ids = {s: i for i, s in enumerate(w.shapes)}
+    A_st = {s: torch.empty((N, s[0]), dtype=tdt, device=dev) for s in w.shapes}
+    D_st = {s: torch.empty((N, s[1]), dtype=tdt, device=dev) for s in w.shapes}
+    G_full = {s: torch.empty(s, dtype=torch.float32, device=dev) for s in w.shapes}
+    G_rank = {s: torch.empty(s, dtype=torch.float32, device=dev) for s in w.shapes}
+    Pt = {li: torch.empty((r, hi), dtype=torch.float32, device=dev) for li, hi, _ in layers}
+    Gt = {li: torch.empty((r, ho), dtype=torch.float32, device=dev) for li, _, ho in layers}
+    ws_c = torch.empty(max(dad.compress_workspace_bytes(N, hi, ho, r, tdt) for _, hi, ho in layers),
+                       dtype=torch.uint8, device=dev)
+    ws_r = torch.empty(max(16, max(dad.reconstruct_workspace_bytes(N, hi, ho, tdt) for _, hi, ho in layers)),
+                       dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+
+    PH = ("stack", "compress", "rebuild_full", "rebuild_rank")
+
+    def step(events=None):
+        for li, hi, ho in layers:
+            s = (hi, ho)
+            As, Ds = factors_of(li)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)] if events is not None else None
+            if ev: ev[0].record()
+            dad.stack_factors(As, Ds, A_out=A_st[s], D_out=D_st[s])
+            if ev: ev[1].record()
+            dad.compress_rank(A_st[s], D_st[s], r, n_iter, G0[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_c)
+            if ev: ev[2].record()
+            dad.reconstruct_grad(A_st[s], D_st[s], G=G_full[s], workspace=ws_r)
+            if ev: ev[3].record()
+            dad.reconstruct_grad(Pt[li], Gt[li], G=G_rank[s])
+            if ev: ev[4].record()
+            if ev: events.append(ev)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    if dad.poll_numeric_status(ws_c) != dad.DAD_OK:
+        print("bench.py: numerical breakdown latched during warm-up", file=sys.stderr)
+        sys.exit(1)
+
+    dad.profile_reset()
+    dad.profile_enable(True)
+    events = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    dad.profile_enable(False)
+    kern = dad.profile_read()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    phase_ms = dict.fromkeys(PH, 0.0)
+    for ev in events:
+        for i, ph in enumerate(PH):
+            phase_ms[ph] += ev[i].elapsed_time(ev[i + 1])
+    phase_ms = {k: v / args.steps for k, v in phase_ms.items()}
+    nl = len(layers)
+    flops_full = sum(2.0 * N * hi * ho for _, hi, ho in layers)
+    bytes_stack = sum(2.0 * N * (hi + ho) * es for _, hi, ho in layers)
+    bytes_compress = sum((2 * n_iter + 1.0) * N * (hi + ho) * es for _, hi, ho in layers)
+    bytes_rank = sum(4.0 * hi * ho + 4.0 * r * (hi + ho) for _, hi, ho in layers)
+    rebuild_tflops = flops_full / (phase_ms["rebuild_full"] * 1e-3) / 1e12
+
+    # ---- roofline per kernel from the library's per-launch events
+    # thin kernels alternate between the two factors: nn runs on Delta (n_iter+1 times) and on A
+    # (n_iter times), tn on A (n_iter+1 times) and on Delta (n_iter times), per layer and step.
+    per_step_work = {}
+    for name in kern:
+        tot, bound = 0.0, None
+        for _, hi, ho in layers:
+            if name in ("k_thin_nn_bf16", "k_thin_nn"):
+                parts = [("out", n_iter + 1), ("in", n_iter)]
+            elif name in ("k_thin_tn_bf16", "k_thin_tn"):
+                parts = [("in", n_iter + 1), ("out", n_iter)]
+            else:
+                parts = [("in", 1)]
+            for which, cnt in parts:
+                bnd, wk = kernel_model(name, N, hi, ho, r, es, which, bf16=(w.dtype == "bf16"))
+                if bnd is None:
+                    continue
+                bound = bnd
+                tot += cnt * wk
+        if bound:
+            per_step_work[name] = (bound, tot)
+    roof_all = {}
+    for name, (ms, launches) in kern.items():
+        entry = {"ms_per_step": ms / args.steps, "launches_per_step": launches / args.steps,
+                 "avg_us": ms * 1e3 / launches}
+        if name in per_step_work:
+            bound, work = per_step_work[name]
+            rate = work * args.steps / (ms * 1e-3)
+            if bound == "hbm":
+                entry.update(bound="hbm", achieved=rate / 1e9, peak=PEAK_HBM_GBPS, unit="GB/s",
+                             frac=rate / 1e9 / PEAK_HBM_GBPS)
+            else:
+                peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS
+                entry.update(bound="mfma", achieved=rate / 1e12, peak=peak, unit="TFLOP/s",
+                             frac=rate / 1e12 / peak)
+        roof_all[name] = entry
+    dominant = max(kern, key=lambda k: kern[k][0])
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(w.name, {}).get(dominant)
+        except Exception:
+            traffic = None
+    roofline = {"kernel": dominant}
+    roofline.update({k: roof_all[dominant].get(k) for k in ("bound", "achieved", "peak", "unit", "frac")})
+    roofline["avg_us"] = roof_all[dominant]["avg_us"]
+    roofline["traffic"] = traffic
+
+    # ---- CPU baseline: the fp64 oracle on one layer of the stack (bounded sample)
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import dad_oracle as O
+        li, hi, ho = min(layers, key=lambda t: t[1] * t[2])
+        As, Ds = factors_of(li)
+        A_h = torch.cat([a.float().cpu() for a in As]).numpy()
+        D_h = torch.cat([d.float().cpu() for d in Ds]).numpy()
+        G0_h = G0[li].cpu().numpy()
+        A64, D64 = A_h.astype(np.float64), D_h.astype(np.float64)
+        del A_h, D_h
+        c0 = time.perf_counter()
+        M = O.full_grad(A64, D64)
+        c1 = time.perf_counter()
+        Pt_ref, Gt_ref = O.block_spi(A64, D64, G0_h, n_iter)
+        c2 = time.perf_counter()
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            threads = os.cpu_count()
+        # same layer on the GPU, for an on-the-spot parity figure
+        s = (hi, ho)
+        dad.stack_factors(As, Ds, A_out=A_st[s], D_out=D_st[s])
+        dad.compress_rank(A_st[s], D_st[s], r, n_iter, G0[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_c)
+        dad.reconstruct_grad(A_st[s], D_st[s], G=G_full[s], workspace=ws_r)
+        dad.reconstruct_grad(Pt[li], Gt[li], G=G_rank[s])
+        torch.cuda.synchronize()
+        tol = 2e-2 if w.dtype == "bf16" else 1e-5
+        e_full = O.rel_fro(G_full[s].cpu().numpy(), M)
+        e_rank = O.rel_fro(G_rank[s].cpu().numpy(), O.rank_r_grad(Pt_ref, Gt_ref))
+        cpu = {"value": 2.0 * N * hi * ho / (c1 - c0) / 1e12, "unit": "TFLOP/s", "cores": int(threads),
+               "kind": "oracle",
+               "sample": f"1 of {nl} layers ({hi}x{ho}, N={N}): fp64 numpy full_grad {c1 - c0:.2f} s, "
+                         f"block_spi r={r} n={n_iter} {c2 - c1:.2f} s",
+               "compress_us_per_layer": (c2 - c1) * 1e6,
+               "parity_rel_fro": {"full": e_full, "rank": e_rank, "tol": tol},
+               "host_cpus": os.cpu_count()}
+        if not (e_full <= tol and e_rank <= tol):
+            print(f"bench.py: parity check failed: {e_full:.3e} {e_rank:.3e}", file=sys.stderr)
+            sys.exit(1)
+
+    out = {
+        "metric": METRIC,
+        "value": rebuild_tflops,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "layers": nl, "shapes": [list(s) for s in w.shapes], "sites": S,
+                   "rows_per_site": b, "N": N, "rank": r, "n_iter": n_iter,
+                   "resident_layers": len(resident)},
+        "rebuild_frac_of_mfma_peak": rebuild_tflops / (PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS),
+        "compress_us_per_layer": phase_ms["compress"] * 1e3 / nl,
+        "compress_GBps": bytes_compress / (phase_ms["compress"] * 1e-3) / 1e9,
+        "compress_frac_of_hbm_peak": bytes_compress / (phase_ms["compress"] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+        "stack_GBps": bytes_stack / (phase_ms["stack"] * 1e-3) / 1e9,
+        "rank_rebuild_us_per_layer": phase_ms["rebuild_rank"] * 1e3 / nl,
+        "rank_rebuild_GBps": bytes_rank / (phase_ms["rebuild_rank"] * 1e-3) / 1e9,
+        "phase_ms_per_step": phase_ms,
+        "roofline": roofline,
+        "kernels": roof_all,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -133,6 +133,20 @@ dad_status dad_reconstruct_grad(const void* L, const void* R, int64_t K, int64_t
  */
 dad_status dad_poll_numeric_status(const void* workspace, void* stream);
 
+/*
+ * Optional per-kernel timing (instrumentation, not part of the method).  While enabled, every
+ * kernel the library launches is bracketed by two HIP events on its launch stream.
+ * dad_profile_get synchronises with the recorded events and returns, for kernel `id` in
+ * [0, dad_profile_kernel_count()), the summed duration in milliseconds and the number of launches
+ * since the last dad_profile_reset.  dad_profile_kernel_name gives the kernel's function name as a
+ * profiler shows it.  Process-wide state, guarded by a mutex; disabled by default.
+ */
+dad_status dad_profile_enable(int on);
+dad_status dad_profile_reset(void);
+int dad_profile_kernel_count(void);
+const char* dad_profile_kernel_name(int id);
+dad_status dad_profile_get(int id, double* total_ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

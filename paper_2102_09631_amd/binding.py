@@ -53,6 +53,16 @@ def lib() -> C.CDLL:
     L.dad_reconstruct_grad.argtypes = [vp, vp, i64, i64, i64, C.c_int, vp, vp, sz, vp]
     L.dad_poll_numeric_status.restype = C.c_int
     L.dad_poll_numeric_status.argtypes = [vp, vp]
+    L.dad_profile_enable.restype = C.c_int
+    L.dad_profile_enable.argtypes = [C.c_int]
+    L.dad_profile_reset.restype = C.c_int
+    L.dad_profile_reset.argtypes = []
+    L.dad_profile_kernel_count.restype = C.c_int
+    L.dad_profile_kernel_count.argtypes = []
+    L.dad_profile_kernel_name.restype = C.c_char_p
+    L.dad_profile_kernel_name.argtypes = [C.c_int]
+    L.dad_profile_get.restype = C.c_int
+    L.dad_profile_get.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     _lib = L
     return L
 
@@ -170,3 +180,24 @@ def reconstruct_grad(L, R, G=None, workspace=None):
 
 def poll_numeric_status(workspace) -> int:
     return lib().dad_poll_numeric_status(workspace.data_ptr(), _stream())
+
+
+def profile_enable(on: bool):
+    """dad_profile_enable: bracket every kernel launch with HIP events on its stream."""
+    _check(lib().dad_profile_enable(1 if on else 0), "dad_profile_enable")
+
+
+def profile_reset():
+    _check(lib().dad_profile_reset(), "dad_profile_reset")
+
+
+def profile_read() -> dict:
+    """dad_profile_get for every kernel: {kernel name: (total ms, launches)} (zero-launch kernels omitted)."""
+    L = lib()
+    out = {}
+    for i in range(L.dad_profile_kernel_count()):
+        ms, n = C.c_double(0.0), C.c_int64(0)
+        _check(L.dad_profile_get(i, C.byref(ms), C.byref(n)), "dad_profile_get")
+        if n.value:
+            out[L.dad_profile_kernel_name(i).decode()] = (ms.value, n.value)
+    return out

@@ -53,7 +53,7 @@ CompressPlan plan_compress(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dt
     p.off_gram = o;
     o += align_up((size_t)p.gram_blocks * r * r * 8, 256);
     p.off_rinv = o;
-    o += align_up((size_t)r * r * 4, 256);
+    o += 2 * DAD_MAX_RANK * DAD_MAX_RANK * 4;
     p.total = o;
     return p;
 }
@@ -140,14 +140,15 @@ dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_
     float* rinv = reinterpret_cast<float*>(ws + p.off_rinv);
     dad_status rc;
 
-    if ((rc = launch_fill_int(flag, 0, s)) != DAD_OK) return rc;
+    int* counter = flag + 16;
+    if ((rc = launch_zero_header(flag, s)) != DAD_OK) return rc;
     const float* Gcur = G0;
     for (int it = 0; it < n_iter; ++it) {
         if ((rc = launch_thin_nn(D, Gcur, V, N, h_out, r, dt, p.fast, s)) != DAD_OK) return rc;            // V = Delta G
         if ((rc = launch_thin_tn(A, V, Ut, part, p.tn_in, N, h_in, r, dt, p.fast, s)) != DAD_OK) return rc;  // U = A^T V
         if ((rc = launch_thin_nn(A, Ut, V, N, h_in, r, dt, p.fast, s)) != DAD_OK) return rc;               // W = A U
         if ((rc = launch_thin_tn(D, V, Yt, part, p.tn_out, N, h_out, r, dt, p.fast, s)) != DAD_OK) return rc;  // Y = Delta^T W
-        if ((rc = launch_cholqr2(Yt, Gt, h_out, r, gram, p.gram_blocks, rinv, flag, s)) != DAD_OK) return rc;
+        if ((rc = launch_cholqr2(Yt, Gt, h_out, r, gram, p.gram_blocks, rinv, counter, flag, s)) != DAD_OK) return rc;
         Gcur = Gt;
     }
     if ((rc = launch_thin_nn(D, Gt, V, N, h_out, r, dt, p.fast, s)) != DAD_OK) return rc;             // V = Delta G

@@ -2,145 +2,310 @@
 // The iterate is held transposed (Yt: r x h, row j = column j of Y), so the
 // Gram matrix is S[i][j] = sum_k Yt[i][k] Yt[j][k].  One round is
 //   S = Y^T Y  ->  S = R^T R (upper R)  ->  Y <- Y R^{-1},
-// done twice.  The r x r factorisation runs in fp64 inside one workgroup's LDS.
+// done twice.  Three launches per orthonormalisation:
+//   1. Gram partials of Yt per 256-column slab; the workgroup that finishes last
+//      sums them (fixed order), factorises and inverts R in fp64.
+//   2. Y <- Y R^{-1} per slab, Gram partials of the result, last workgroup
+//      factorises again.
+//   3. Y <- Y R^{-1} with the second factor.
+// Products of two fp32 values are exact in fp64, so the Gram matrix carries no
+// rounding beyond its final sums and CholeskyQR tolerates condition numbers far
+// beyond the fp32 limit.
 #include "dad_internal.h"
 
 namespace dad {
 
-constexpr int GRAM_COLS = 256;  // columns of Yt per workgroup of the Gram kernel
+constexpr int QR_COLS = 64;  // columns of Yt per LDS tile
+constexpr int QR_SUB = 4;    // tiles per workgroup: few, fat Gram partials keep the final sum short
+constexpr int QR_LD = DAD_MAX_RANK + 1;
 
-// gram_part[b][i*r+j] = sum over this block's columns of Yt[i][k]*Yt[j][k]
-// Products of two fp32 values are exact in fp64, so the Gram matrix carries no rounding beyond the
-// final sums; CholeskyQR then tolerates condition numbers far beyond the fp32 limit of ~4e3.
-__global__ __launch_bounds__(256) void k_gram_partial(const float* __restrict__ Yt, double* __restrict__ gram_part,
-                                                      int64_t h, int r) {
-    constexpr int KC = 64;
-    __shared__ float Ys[DAD_MAX_RANK][KC + 1];
-    const int t = threadIdx.x;
-    const int64_t kbeg = (int64_t)blockIdx.x * GRAM_COLS;
-    const int64_t kend = (kbeg + GRAM_COLS < h) ? kbeg + GRAM_COLS : h;
-    const int nent = r * r;
-    double acc[DAD_MAX_RANK * DAD_MAX_RANK / 256];
+struct QrShared {
+    union {
+        float Ys[DAD_MAX_RANK][QR_COLS + 1];  // tile of Yt (or of the result)
+        struct {
+            double colS[2][DAD_MAX_RANK];  // column k of the running S, double buffered over k
+            double rowT[2][DAD_MAX_RANK];  // row k of the running inverse
+        } f;
+    };
+    float Rs[DAD_MAX_RANK][QR_LD];  // R^{-1} applied by this launch
+    int last;
+};
+
+// Threads form a 16 x 16 grid (ti, tj); thread (ti, tj) owns the entries (ti + 16a, tj + 16b),
+// a, b < NA, of every r x r matrix below (NA = 2 covers r <= 32, NA = 4 covers r <= 64).
+
+// acc[a][b] += sum over the tile's columns of Ys[i][k] * Ys[j][k] (fp64).
+template <int NA>
+__device__ __forceinline__ void gram_of_tile(const float (*Ys)[QR_COLS + 1], double (&acc)[NA][NA]) {
+    const int t = threadIdx.x, ti = t >> 4, tj = t & 15;
+    for (int kk = 0; kk < QR_COLS; ++kk) {
+        double ya[NA], yb[NA];
 #pragma unroll
-    for (int m = 0; m < DAD_MAX_RANK * DAD_MAX_RANK / 256; ++m) acc[m] = 0.0;
-    for (int64_t k0 = kbeg; k0 < kend; k0 += KC) {
-        for (int e = t; e < r * KC; e += 256) {
-            int i = e / KC, kk = e % KC;
-            int64_t k = k0 + kk;
-            Ys[i][kk] = (k < kend) ? Yt[(int64_t)i * h + k] : 0.f;
+        for (int a = 0; a < NA; ++a) {
+            ya[a] = (double)Ys[ti + 16 * a][kk];
+            yb[a] = (double)Ys[tj + 16 * a][kk];
         }
-        __syncthreads();
 #pragma unroll
-        for (int m = 0; m < DAD_MAX_RANK * DAD_MAX_RANK / 256; ++m) {
-            int e = t + 256 * m;
-            if (e < nent) {
-                int i = e / r, j = e % r;
-                double a = acc[m];
-#pragma unroll 16
-                for (int kk = 0; kk < KC; ++kk) a = fma((double)Ys[i][kk], (double)Ys[j][kk], a);
-                acc[m] = a;
-            }
-        }
-        __syncthreads();
-    }
+        for (int a = 0; a < NA; ++a)
 #pragma unroll
-    for (int m = 0; m < DAD_MAX_RANK * DAD_MAX_RANK / 256; ++m) {
-        int e = t + 256 * m;
-        if (e < nent) gram_part[(int64_t)blockIdx.x * nent + e] = acc[m];
+            for (int b = 0; b < NA; ++b) acc[a][b] = fma(ya[a], yb[b], acc[a][b]);
     }
 }
 
-// One workgroup: S = sum_b gram_part[b] (fp64, b ascending), S = R^T R, rinv = R^{-1} (upper, fp32 out).
-// A pivot that is not > 0 (or is NaN) latches *flag = 1 and is replaced by 1 so the kernel still
-// finishes with finite arithmetic; the outputs are then meaningless.
-__global__ __launch_bounds__(256) void k_chol_rinv(const double* __restrict__ gram_part, int nblocks,
-                                                   float* __restrict__ rinv, int r, int* __restrict__ flag) {
-    __shared__ double S[DAD_MAX_RANK][DAD_MAX_RANK + 1];  // upper: R; strict lower [j][i]: Rinv[i][j]
-    __shared__ double dinv[DAD_MAX_RANK];                 // Rinv[j][j]
-    const int t = threadIdx.x;
+// Runs in every workgroup after its Gram partial `acc` is complete; the workgroup that takes the
+// last ticket sums all partials (block order ascending) and factorises:
+// S = L L^T and X = L^{-1} by one right-looking sweep over k in fp64 registers.  Step k publishes
+// column k of the running S and row k of the running inverse T (T starts as I) through LDS; then
+//     L[i][k] = S[i][k] / sqrt(S[k][k]),  X[k][j] = T[k][j] / sqrt(S[k][k]),
+//     S[i][j] -= L[i][k] L[j][k],         T[i][j] -= L[i][k] X[k][j]      for i > k.
+// R^{-1} = X^T (upper triangular) is written as fp32.  A pivot that is not > 0 (or NaN) latches
+// *flag and is replaced by 1 so the sweep still ends with finite arithmetic.
+template <int NA>
+__device__ __forceinline__ void last_block_factor(QrShared& sh, double (&acc)[NA][NA], double* __restrict__ gram_part,
+                                                  int nblocks, int r, int* __restrict__ counter,
+                                                  float* __restrict__ rinv, int* __restrict__ flag) {
+    const int t = threadIdx.x, ti = t >> 4, tj = t & 15;
     const int nent = r * r;
-    for (int e = t; e < nent; e += 256) {
-        double a = 0.0;
-        for (int b = 0; b < nblocks; ++b) a += gram_part[(int64_t)b * nent + e];
-        S[e / r][e % r] = a;
-    }
+    double* mine = gram_part + (int64_t)blockIdx.x * nent;
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
+#pragma unroll
+        for (int b = 0; b < NA; ++b) {
+            const int i = ti + 16 * a, j = tj + 16 * b;
+            if (i < r && j < r) mine[i * r + j] = acc[a][b];
+        }
+    __threadfence();
     __syncthreads();
+    if (t == 0) sh.last = (atomicAdd(counter, 1) == nblocks - 1);
+    __syncthreads();
+    if (!sh.last) return;
+    __threadfence();
+
+    double S[NA][NA], T[NA][NA];
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
+#pragma unroll
+        for (int b = 0; b < NA; ++b) {
+            S[a][b] = 0.0;
+            T[a][b] = (ti + 16 * a == tj + 16 * b) ? 1.0 : 0.0;
+        }
+    for (int b0 = 0; b0 < nblocks; b0 += 4) {
+        double v[4][NA][NA];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int a = 0; a < NA; ++a)
+#pragma unroll
+                for (int b = 0; b < NA; ++b) {
+                    const int i = ti + 16 * a, j = tj + 16 * b;
+                    v[u][a][b] = (b0 + u < nblocks && i < r && j < r)
+                                     ? __builtin_nontemporal_load(gram_part + (int64_t)(b0 + u) * nent + i * r + j)
+                                     : 0.0;
+                }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int a = 0; a < NA; ++a)
+#pragma unroll
+                for (int b = 0; b < NA; ++b) S[a][b] += v[u][a][b];
+    }
+    // identity beyond r keeps the padded rows and columns inert
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
+#pragma unroll
+        for (int b = 0; b < NA; ++b) {
+            const int i = ti + 16 * a, j = tj + 16 * b;
+            if (i >= r || j >= r) S[a][b] = (i == j) ? 1.0 : 0.0;
+        }
+
+    bool bad = false;
     for (int k = 0; k < r; ++k) {
-        double piv = S[k][k];
+        const int buf = k & 1, ka = k >> 4, kt = k & 15;
+        if (tj == kt) {
+#pragma unroll
+            for (int b = 0; b < NA; ++b)
+                if (b == ka) {
+#pragma unroll
+                    for (int a = 0; a < NA; ++a) sh.f.colS[buf][ti + 16 * a] = S[a][b];
+                }
+        }
+        if (ti == kt) {
+#pragma unroll
+            for (int a = 0; a < NA; ++a)
+                if (a == ka) {
+#pragma unroll
+                    for (int b = 0; b < NA; ++b) sh.f.rowT[buf][tj + 16 * b] = T[a][b];
+                }
+        }
         __syncthreads();
+        double piv = sh.f.colS[buf][k];
         if (!(piv > 0.0)) {
-            if (t == 0) *flag = 1;
+            bad = true;
             piv = 1.0;
         }
-        const double d = sqrt(piv);
-        if (t == 0) S[k][k] = d;
-        for (int j = k + 1 + t; j < r; j += 256) S[k][j] = S[k][j] / d;
-        __syncthreads();
-        const int m = r - k - 1;  // trailing block, upper part only
-        for (int e = t; e < m * m; e += 256) {
-            int i = k + 1 + e / m, j = k + 1 + e % m;
-            if (i <= j) S[i][j] -= S[k][i] * S[k][j];
+        const double dinv = rsqrt(piv);
+        double l[NA], lt[NA], x[NA];
+#pragma unroll
+        for (int a = 0; a < NA; ++a) {
+            l[a] = (ti + 16 * a > k) ? sh.f.colS[buf][ti + 16 * a] * dinv : 0.0;
+            lt[a] = sh.f.colS[buf][tj + 16 * a] * dinv;
+            x[a] = sh.f.rowT[buf][tj + 16 * a] * dinv;
         }
-        __syncthreads();
-    }
-    // Back substitution, one column of R^{-1} per thread.
-    if (t < r) {
-        const int j = t;
-        const double djj = 1.0 / S[j][j];
-        dinv[j] = djj;
-        for (int i = j - 1; i >= 0; --i) {
-            double a = S[i][j] * djj;  // k = j term: R[i][j] * Rinv[j][j]
-            for (int k = i + 1; k < j; ++k) a += S[i][k] * S[j][k];  // Rinv[k][j] lives at S[j][k]
-            S[j][i] = -a / S[i][i];
+#pragma unroll
+        for (int a = 0; a < NA; ++a)
+#pragma unroll
+            for (int b = 0; b < NA; ++b) {
+                S[a][b] = fma(-l[a], lt[b], S[a][b]);
+                T[a][b] = fma(-l[a], x[b], T[a][b]);
+            }
+        if (ti == kt) {  // R^{-1}[j][k] = X[k][j]
+#pragma unroll
+            for (int b = 0; b < NA; ++b) {
+                const int j = tj + 16 * b;
+                if (j < r) rinv[j * r + k] = (float)x[b];
+            }
         }
     }
-    __syncthreads();
-    for (int e = t; e < nent; e += 256) {
-        int i = e / r, j = e % r;
-        double v = (i == j) ? dinv[j] : (i < j ? S[j][i] : 0.0);
-        rinv[e] = (float)v;
+    if (bad && t == 0) *flag = 1;
+    if (t == 0) *counter = 0;
+}
+
+// Up-front load of this workgroup's QR_SUB tiles; element m of tile `sub` is row (t + 256 m) / 64,
+// column (t + 256 m) % 64 of that tile.
+__device__ __forceinline__ void load_slab(float (&st)[QR_SUB][16], const float* Yt, int64_t h, int r, int64_t k0) {
+    const int t = threadIdx.x;
+#pragma unroll
+    for (int sub = 0; sub < QR_SUB; ++sub)
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            const int e = t + 256 * m, i = e >> 6, kk = e & 63;
+            const int64_t k = k0 + sub * QR_COLS + kk;
+            st[sub][m] = (i < r && k < h) ? Yt[(int64_t)i * h + k] : 0.f;
+        }
+}
+
+__device__ __forceinline__ void store_tile(QrShared& sh, const float (&st)[16]) {
+    const int t = threadIdx.x;
+#pragma unroll
+    for (int m = 0; m < 16; ++m) {
+        const int e = t + 256 * m;
+        sh.Ys[e >> 6][e & 63] = st[m];
     }
 }
 
-// Gt[j][k] = sum_{i<=j} rinv[i][j] * Yt[i][k]   (Y <- Y R^{-1}); Gt may alias Yt.
-__global__ __launch_bounds__(256) void k_apply_rinv(const float* Yt, float* Gt, const float* __restrict__ rinv,
-                                                    int64_t h, int r) {
-    constexpr int KC = 64;
-    __shared__ float Ys[DAD_MAX_RANK][KC + 1];
-    __shared__ float Rs[DAD_MAX_RANK][DAD_MAX_RANK + 1];
+// Launch 1: Gram partial per slab + factorisation by the last workgroup.
+template <int NA>
+__global__ __launch_bounds__(256) void k_qr_gram(const float* __restrict__ Yt, int64_t h, int r,
+                                                 double* __restrict__ gram_part, int* __restrict__ counter,
+                                                 float* __restrict__ rinv, int* __restrict__ flag) {
+    __shared__ QrShared sh;
+    const int64_t k0 = (int64_t)blockIdx.x * QR_SUB * QR_COLS;
+    float st[QR_SUB][16];
+    load_slab(st, Yt, h, r, k0);
+    double acc[NA][NA];
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
+#pragma unroll
+        for (int b = 0; b < NA; ++b) acc[a][b] = 0.0;
+#pragma unroll
+    for (int sub = 0; sub < QR_SUB; ++sub) {
+        if (k0 + sub * QR_COLS < h) {
+            if (sub) __syncthreads();
+            store_tile(sh, st[sub]);
+            __syncthreads();
+            gram_of_tile<NA>(sh.Ys, acc);
+        }
+    }
+    __syncthreads();
+    last_block_factor<NA>(sh, acc, gram_part, gridDim.x, r, counter, rinv, flag);
+}
+
+// Launches 2 and 3: Gt[j][k] = sum_{i<=j} rinv_in[i][j] * Yt[i][k]; Gt may alias Yt (each workgroup
+// reads its slab completely before it writes).  WITH_GRAM also prepares the next factor.
+template <int NA, bool WITH_GRAM>
+__global__ __launch_bounds__(256) void k_qr_apply(const float* Yt, float* Gt, const float* __restrict__ rinv_in,
+                                                  int64_t h, int r, double* __restrict__ gram_part,
+                                                  int* __restrict__ counter, float* __restrict__ rinv_out,
+                                                  int* __restrict__ flag) {
+    __shared__ QrShared sh;
     const int t = threadIdx.x;
     const int kl = t & 63, jg = t >> 6;
-    const int64_t k0 = (int64_t)blockIdx.x * KC;
-    for (int e = t; e < r * KC; e += 256) {
-        int i = e / KC, kk = e % KC;
-        Ys[i][kk] = (k0 + kk < h) ? Yt[(int64_t)i * h + k0 + kk] : 0.f;
+    const int64_t k0 = (int64_t)blockIdx.x * QR_SUB * QR_COLS;
+    float st[QR_SUB][16];
+    load_slab(st, Yt, h, r, k0);
+    for (int e = t; e < r * r; e += 256) sh.Rs[e / r][e % r] = rinv_in[e];
+    double acc[NA][NA];
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
+#pragma unroll
+        for (int b = 0; b < NA; ++b) acc[a][b] = 0.0;
+#pragma unroll
+    for (int sub = 0; sub < QR_SUB; ++sub) {
+        const int64_t kc = k0 + sub * QR_COLS + kl;
+        if (k0 + sub * QR_COLS < h) {
+            if (sub) __syncthreads();
+            store_tile(sh, st[sub]);
+            __syncthreads();
+            float out[NA * 4];
+#pragma unroll
+            for (int m = 0; m < NA * 4; ++m) {
+                const int j = jg + 4 * m;
+                float a = 0.f;
+                if (j < r)
+                    for (int i = 0; i <= j; ++i) a = fmaf(sh.Rs[i][j], sh.Ys[i][kl], a);
+                out[m] = a;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int m = 0; m < NA * 4; ++m) {
+                const int j = jg + 4 * m;
+                if (j < r) {
+                    if (kc < h) Gt[(int64_t)j * h + kc] = out[m];
+                    if (WITH_GRAM) sh.Ys[j][kl] = (kc < h) ? out[m] : 0.f;
+                }
+            }
+            if (WITH_GRAM) {
+                __syncthreads();
+                gram_of_tile<NA>(sh.Ys, acc);
+            }
+        }
     }
-    for (int e = t; e < r * r; e += 256) Rs[e / r][e % r] = rinv[e];
-    __syncthreads();
-    const int64_t k = k0 + kl;
-    for (int j = jg; j < r; j += 4) {
-        float a = 0.f;
-        for (int i = 0; i <= j; ++i) a = fmaf(Rs[i][j], Ys[i][kl], a);
-        if (k < h) Gt[(int64_t)j * h + k] = a;
+    if (WITH_GRAM) {
+        __syncthreads();
+        last_block_factor<NA>(sh, acc, gram_part, gridDim.x, r, counter, rinv_out, flag);
     }
 }
 
-dad_status launch_cholqr2(const float* Yt, float* Gt, int64_t h, int r, double* gram_part, int gram_blocks,
-                          float* rinv, int* flag, hipStream_t s) {
-    const float* src = Yt;
-    for (int round = 0; round < 2; ++round) {
-        hipLaunchKernelGGL(k_gram_partial, dim3((unsigned)gram_blocks), dim3(256), 0, s, src, gram_part, h, r);
-        DAD_LAUNCH_CHECK();
-        hipLaunchKernelGGL(k_chol_rinv, dim3(1), dim3(256), 0, s, (const double*)gram_part, gram_blocks, rinv, r, flag);
-        DAD_LAUNCH_CHECK();
-        hipLaunchKernelGGL(k_apply_rinv, dim3((unsigned)ceil_div(h, 64)), dim3(256), 0, s, src, Gt, (const float*)rinv,
-                           h, r);
-        DAD_LAUNCH_CHECK();
-        src = Gt;
+int gram_blocks_for(int64_t h) { return (int)ceil_div(h, QR_COLS * QR_SUB); }
+
+template <int NA>
+static dad_status qr2(const float* Yt, float* Gt, int64_t h, int r, double* gram_part, int nb, float* rinv,
+                      int* counter, int* flag, hipStream_t s) {
+    float* rinv2 = rinv + DAD_MAX_RANK * DAD_MAX_RANK;
+    {
+        ProfScope prof(KID_GRAM, s);
+        hipLaunchKernelGGL(k_qr_gram<NA>, dim3((unsigned)nb), dim3(256), 0, s, Yt, h, r, gram_part, counter, rinv, flag);
     }
+    DAD_LAUNCH_CHECK();
+    {
+        ProfScope prof(KID_APPLY, s);
+        hipLaunchKernelGGL((k_qr_apply<NA, true>), dim3((unsigned)nb), dim3(256), 0, s, Yt, Gt, (const float*)rinv, h, r,
+                           gram_part, counter, rinv2, flag);
+    }
+    DAD_LAUNCH_CHECK();
+    {
+        ProfScope prof(KID_APPLY2, s);
+        hipLaunchKernelGGL((k_qr_apply<NA, false>), dim3((unsigned)nb), dim3(256), 0, s, (const float*)Gt, Gt,
+                           (const float*)rinv2, h, r, gram_part, counter, rinv2, flag);
+    }
+    DAD_LAUNCH_CHECK();
     return DAD_OK;
 }
 
-int gram_blocks_for(int64_t h) { return (int)ceil_div(h, GRAM_COLS); }
+dad_status launch_cholqr2(const float* Yt, float* Gt, int64_t h, int r, double* gram_part, int gram_blocks,
+                          float* rinv, int* counter, int* flag, hipStream_t s) {
+    if (r <= 32) return qr2<2>(Yt, Gt, h, r, gram_part, gram_blocks, rinv, counter, flag, s);
+    return qr2<4>(Yt, Gt, h, r, gram_part, gram_blocks, rinv, counter, flag, s);
+}
 
 }  // namespace dad

@@ -44,6 +44,27 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
         if (hipGetLastError() != hipSuccess) return DAD_ERR_HIP; \
     } while (0)
 
+// ---------------------------------------------------------------- optional per-kernel timing
+
+enum KernelId {
+    KID_STACK = 0, KID_THIN_NN_BF16, KID_THIN_TN_BF16, KID_REDUCE, KID_GRAM, KID_APPLY, KID_APPLY2, KID_REBUILD_BF16,
+    KID_THIN_NN, KID_THIN_TN, KID_REBUILD, KID_FILL, KID_COUNT
+};
+
+// Brackets the kernel launched inside its scope with two events when timing is enabled.
+class ProfScope {
+public:
+    ProfScope(int id, hipStream_t s);
+    ~ProfScope();
+    ProfScope(const ProfScope&) = delete;
+    ProfScope& operator=(const ProfScope&) = delete;
+
+private:
+    int id_;
+    hipStream_t s_;
+    void* a_;
+};
+
 // ---------------------------------------------------------------- workspace plans
 
 // Split of a contraction over `rows` rows into `splits` contiguous chunks of
@@ -55,13 +76,13 @@ struct SplitPlan {
 
 // Layout of the dad_compress_rank workspace (byte offsets from its start).
 struct CompressPlan {
-    size_t off_flag;      // int flag word (256 B reserved)
+    size_t off_flag;      // 256 B header: int flag at +0, int ticket counter at +64
     size_t off_V;         // N x r intermediate (element type of the factors)
     size_t off_part;      // split partials, fp32
     size_t off_Ut;        // r x h_in fp32
     size_t off_Yt;        // r x h_out fp32
     size_t off_gram;      // gram partials, fp64
-    size_t off_rinv;      // r x r fp32
+    size_t off_rinv;      // two DAD_MAX_RANK^2 fp32 inverse factors
     size_t total;
     SplitPlan tn_in;      // split of  A^T V   (width h_in)
     SplitPlan tn_out;     // split of  Delta^T W (width h_out)
@@ -91,11 +112,11 @@ dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* par
 
 // In-place orthonormalisation of the rows' transposes: Yt (r x h) -> Gt (r x h), G^T G = I.
 dad_status launch_cholqr2(const float* Yt, float* Gt, int64_t h, int r, double* gram_part, int gram_blocks,
-                          float* rinv, int* flag, hipStream_t s);
+                          float* rinv, int* counter, int* flag, hipStream_t s);
 
 dad_status launch_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt,
                           float* G, float* partials, const RebuildPlan& plan, hipStream_t s);
 
-dad_status launch_fill_int(int* p, int value, hipStream_t s);
+dad_status launch_zero_header(int* p, hipStream_t s);  // clears the 256-byte workspace header
 
 }  // namespace dad

@@ -170,15 +170,14 @@ __global__ __launch_bounds__(256) void k_rebuild(const T* __restrict__ L, const 
     }
 }
 
-__global__ void k_fill_int(int* p, int v) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) *p = v;
-}
+__global__ void k_zero_header(int* p) { p[threadIdx.x] = 0; }
 
 // ---------------------------------------------------------------- host launchers
 
 dad_status gen_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int64_t h, int r, dad_dtype dt,
                        hipStream_t s) {
     dim3 grid((unsigned)ceil_div(N, 64));
+    ProfScope prof(KID_THIN_NN, s);
     if (dt == DAD_BF16)
         hipLaunchKernelGGL(k_thin_nn<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)X, Pt, (bf16_t*)out, N, h, r);
     else
@@ -188,6 +187,7 @@ dad_status gen_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int
 }
 
 dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s) {
+    ProfScope prof(KID_REDUCE, s);
     hipLaunchKernelGGL(k_reduce_slabs, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, part, out, n, splits);
     DAD_LAUNCH_CHECK();
     return DAD_OK;
@@ -197,12 +197,15 @@ dad_status gen_thin_tn(const void* X, const void* V, float* out_t, float* partia
                        int64_t h, int r, dad_dtype dt, hipStream_t s) {
     dim3 grid((unsigned)ceil_div(h, 64), (unsigned)sp.splits);
     float* dst = sp.splits == 1 ? out_t : partials;
+    {
+    ProfScope prof(KID_THIN_TN, s);
     if (dt == DAD_BF16)
         hipLaunchKernelGGL(k_thin_tn<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)X, (const bf16_t*)V, dst, N, h,
                            r, sp.chunk);
     else
         hipLaunchKernelGGL(k_thin_tn<float>, grid, dim3(256), 0, s, (const float*)X, (const float*)V, dst, N, h, r,
                            sp.chunk);
+    }
     DAD_LAUNCH_CHECK();
     if (sp.splits > 1) return reduce_slabs(partials, out_t, (int64_t)r * h, sp.splits, s);
     return DAD_OK;
@@ -212,19 +215,23 @@ dad_status gen_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, in
                        float* partials, SplitPlan sp, hipStream_t s) {
     dim3 grid((unsigned)ceil_div(h_out, 64), (unsigned)ceil_div(h_in, 64), (unsigned)sp.splits);
     float* dst = sp.splits == 1 ? G : partials;
+    {
+    ProfScope prof(KID_REBUILD, s);
     if (dt == DAD_BF16)
         hipLaunchKernelGGL(k_rebuild<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)L, (const bf16_t*)R, dst, K,
                            h_in, h_out, sp.chunk);
     else
         hipLaunchKernelGGL(k_rebuild<float>, grid, dim3(256), 0, s, (const float*)L, (const float*)R, dst, K, h_in,
                            h_out, sp.chunk);
+    }
     DAD_LAUNCH_CHECK();
     if (sp.splits > 1) return reduce_slabs(partials, G, h_in * h_out, sp.splits, s);
     return DAD_OK;
 }
 
-dad_status launch_fill_int(int* p, int value, hipStream_t s) {
-    hipLaunchKernelGGL(k_fill_int, dim3(1), dim3(64), 0, s, p, value);
+dad_status launch_zero_header(int* p, hipStream_t s) {
+    ProfScope prof(KID_FILL, s);
+    hipLaunchKernelGGL(k_zero_header, dim3(1), dim3(64), 0, s, p);
     DAD_LAUNCH_CHECK();
     return DAD_OK;
 }

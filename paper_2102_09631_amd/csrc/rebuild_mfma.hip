@@ -201,8 +201,11 @@ dad_status fast_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, i
     const int tm = (int)(h_in / rb::TILE), tn = (int)(h_out / rb::TILE);
     const int total = tm * tn * sp.splits;
     float* dst = sp.splits == 1 ? G : partials;
-    hipLaunchKernelGGL(k_rebuild_bf16, dim3((unsigned)total), dim3(256), lds, s, (const bf16_t*)L, (const bf16_t*)R, dst,
-                       K, (int)h_in, (int)h_out, sp.chunk, tm, tn, total);
+    {
+        ProfScope prof(KID_REBUILD_BF16, s);
+        hipLaunchKernelGGL(k_rebuild_bf16, dim3((unsigned)total), dim3(256), lds, s, (const bf16_t*)L, (const bf16_t*)R,
+                           dst, K, (int)h_in, (int)h_out, sp.chunk, tm, tn, total);
+    }
     DAD_LAUNCH_CHECK();
     if (sp.splits > 1) return reduce_slabs(partials, G, h_in * h_out, sp.splits, s);
     return DAD_OK;

@@ -63,6 +63,7 @@ dad_status launch_stack(int S, const void* const* A_sites, const void* const* D_
     int64_t row_off = 0;
     auto flush = [&]() -> dad_status {
         if (tb.n == 0) return DAD_OK;
+        ProfScope prof(KID_STACK, st);
         hipLaunchKernelGGL(k_stack, dim3((unsigned)tb.first_block[tb.n]), dim3(256), 0, st, tb);
         DAD_LAUNCH_CHECK();
         tb.n = 0;

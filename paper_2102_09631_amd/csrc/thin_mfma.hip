@@ -7,6 +7,8 @@
 //
 // Loads run two tiles ahead of the arithmetic through two register sets, so each workgroup keeps
 // about 40 KiB of HBM reads in flight.
+#include <cstdlib>
+
 #include "dad_internal.h"
 
 namespace dad {
@@ -317,8 +319,13 @@ bool thin_fast_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt) {
 // (splits * h * r * 4 bytes, written and read once) stay a few percent of the factor read.
 SplitPlan thin_tn_split(int64_t N, int64_t h, int r) {
     const int64_t slices = h / tn::PW;
-    int64_t want = ceil_div(1024, slices);
-    const int64_t cap_traffic = (int64_t)(0.04 * (double)N * 2.0 / (4.0 * r)) + 1;  // partials <= ~4% + 4%
+    static int target = 0;
+    if (!target) {
+        const char* e = getenv("DAD_TN_WGS");
+        target = e ? atoi(e) : 512;
+    }
+    int64_t want = target / slices;  // whole rounds of co-resident workgroups: no tail
+    const int64_t cap_traffic = (int64_t)(0.08 * (double)N * 2.0 / (4.0 * r)) + 1;  // partials <= ~8% + 8%
     if (want > cap_traffic) want = cap_traffic;
     const int64_t cap_rows = ceil_div(N, 4 * tn::BK);
     if (want > cap_rows) want = cap_rows;
@@ -338,6 +345,7 @@ static dad_status set_lds(Kern k, int bytes) {
 
 dad_status fast_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int64_t h, int r, hipStream_t s) {
     dim3 grid((unsigned)ceil_div(N, nn::RT));
+    ProfScope prof(KID_THIN_NN_BF16, s);
     if (r <= 32) {
         const int lds = 2 * (nn::XTILEB + 32 * nn::XROWB);
         hipLaunchKernelGGL(k_thin_nn_bf16<32>, grid, dim3(256), lds, s, (const bf16_t*)X, Pt, (bf16_t*)out, N, (int)h, r);
@@ -353,6 +361,8 @@ dad_status fast_thin_tn(const void* X, const void* V, float* out_t, float* parti
                         int r, hipStream_t s) {
     dim3 grid((unsigned)(h / tn::PW), (unsigned)sp.splits);
     float* dst = sp.splits == 1 ? out_t : partials;
+    {
+    ProfScope prof(KID_THIN_TN_BF16, s);
     if (r <= 32) {
         const int lds = 2 * (tn::XTILEB + tn::BK * 64);
         hipLaunchKernelGGL(k_thin_tn_bf16<32>, grid, dim3(256), lds, s, (const bf16_t*)X, (const bf16_t*)V, dst, N, (int)h,
@@ -361,6 +371,7 @@ dad_status fast_thin_tn(const void* X, const void* V, float* out_t, float* parti
         const int lds = 2 * (tn::XTILEB + tn::BK * 128);
         hipLaunchKernelGGL(k_thin_tn_bf16<64>, grid, dim3(256), lds, s, (const bf16_t*)X, (const bf16_t*)V, dst, N, (int)h,
                            r, sp.chunk);
+    }
     }
     DAD_LAUNCH_CHECK();
     if (sp.splits > 1) return reduce_slabs(partials, out_t, (int64_t)r * h, sp.splits, s);
