@@ -10,6 +10,8 @@
 // One workgroup = 4 waves (2 x 2), one 256 x 256 output tile, a contiguous chunk
 // of K.  Split-K partials are written as fp32 slabs and summed in fixed order by
 // k_reduce_slabs, so results are reproducible bit for bit.
+#include <type_traits>
+
 #include "dad_internal.h"
 
 namespace dad {
@@ -18,6 +20,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 namespace rb {
@@ -158,6 +161,167 @@ __global__ __launch_bounds__(256) void k_rebuild_bf16(const bf16_t* __restrict__
         }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Variant for K chunks that are whole multiples of BK: the operand tiles go from HBM straight into
+// LDS (no register staging), through a ring of DMA_STAGES buffers, so three tiles per workgroup are
+// in flight while the fourth is multiplied.  The XOR swizzle is applied on the global side: the
+// lane that owns LDS chunk position c' of row k fetches global chunk c' ^ ((k & 3) << 2).
+// The loads are issued through inline assembly because the compiler would otherwise wait for ALL
+// outstanding LDS-bound loads before any LDS read; the waits are placed by hand instead.
+//
+// Eight waves (2 x 4, each 128 x 64 of the tile) rather than four: a wave can keep at most fifteen
+// LDS reads in flight, and with one wave per SIMD the transpose-reads deliver only ~64 B/clk per CU,
+// exactly what four 128 x 128 waves need at full MFMA rate; two waves per SIMD roughly double it.
+namespace rb {
+constexpr int DMA_STAGES = 4;
+constexpr int DMA_THREADS = 512;
+constexpr int DMA_LOADS = 2 * TILEB / 16 / DMA_THREADS;  // 16-byte loads per thread per stage
+}  // namespace rb
+
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+__global__ __launch_bounds__(rb::DMA_THREADS) void k_rebuild_bf16_dma(const bf16_t* __restrict__ L,
+                                                                      const bf16_t* __restrict__ R,
+                                                                      float* __restrict__ out, int64_t K, int h_in,
+                                                                      int h_out, int64_t chunk, int tiles_m,
+                                                                      int tiles_n, int total) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+
+    int lid = blockIdx.x;
+    {
+        const int per = total >> 3, main = per << 3;
+        if ((int)blockIdx.x < main) lid = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+    }
+    const int tiles = tiles_m * tiles_n;
+    const int split = lid / tiles, tile = lid - split * tiles;
+    int pm, qn;
+    if (tiles_m <= tiles_n) {
+        pm = tile % tiles_m;
+        qn = tile / tiles_m;
+    } else {
+        qn = tile % tiles_n;
+        pm = tile / tiles_n;
+    }
+    const int p0 = pm * rb::TILE, q0 = qn * rb::TILE;
+    const int64_t kbeg = (int64_t)split * chunk;
+    const int64_t kend = (kbeg + chunk < K) ? kbeg + chunk : K;
+    const int nk = (int)((kend - kbeg) / rb::BK);  // host guarantees whole tiles
+
+    // this lane's two rows per operand tile: row = 4*wave + 2*i + lane/32, LDS chunk position lane%32
+    const char* gl[2];
+    const char* gr[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int row = 4 * wave + 2 * i + (lane >> 5);
+        const int c = (lane & 31) ^ ((row & 3) << 2);
+        gl[i] = reinterpret_cast<const char*>(L + (kbeg + row) * (int64_t)h_in + p0 + c * 8);
+        gr[i] = reinterpret_cast<const char*>(R + (kbeg + row) * (int64_t)h_out + q0 + c * 8);
+    }
+    const int64_t adv_l = (int64_t)rb::BK * h_in * 2, adv_r = (int64_t)rb::BK * h_out * 2;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+
+    auto issue = [&](int stage) {  // loads the next tile in sequence into ring slot `stage`
+        // wave-uniform by construction; readfirstlane lets the compiler keep it in a scalar register
+        const uint32_t base =
+            __builtin_amdgcn_readfirstlane(lds0 + stage * rb::STAGEB + (4 * wave) * rb::ROWB);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            dma16(gl[i], base + 2 * i * rb::ROWB);
+            gl[i] += adv_l;
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            dma16(gr[i], base + rb::TILEB + 2 * i * rb::ROWB);
+            gr[i] += adv_r;
+        }
+    };
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+#pragma unroll
+    for (int s = 0; s < rb::DMA_STAGES - 1; ++s)
+        if (s < nk) issue(s);
+
+    // Each K tile is two MFMA K-steps (ks = 0, 1) with fragment sets 0 and 1.  The second step of a
+    // tile is multiplied after the next tile's barrier, so the matrix cores have independent MFMAs to
+    // chew on while the first fragments of the new tile travel from LDS:
+    //   barrier | DMA(kt+3) | read set0(kt,0) | MFMA set1(kt-1,1) | read set1(kt,1) | MFMA set0(kt,0) | ...
+    bf16x8 fa0[4], fb0[2], fa1[4], fb1[2];
+    auto read_frags = [&](bf16x8 (&fa)[4], bf16x8 (&fb)[2], const char* tl, int ks) {
+        const char* tr = tl + rb::TILEB;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) fa[a] = rb_frag(tl, wm * 128 + a * 32, ks * 16, lane);
+#pragma unroll
+        for (int b = 0; b < 2; ++b) fb[b] = rb_frag(tr, wn * 64 + b * 32, ks * 16, lane);
+    };
+    auto mma = [&](const bf16x8 (&fa)[4], const bf16x8 (&fb)[2]) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+                // R fragment as the MFMA's row operand: each lane then owns four consecutive q of one p
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[b], fa[a], acc[a][b], 0, 0, 0);
+    };
+
+    // One K tile; STAGE is a compile-time ring slot so every LDS address is lane offset + constant.
+    auto step = [&](int kt, auto stage_c) {
+        constexpr int STAGE = decltype(stage_c)::value;
+        // tile kt has landed once at most DMA_STAGES-2 younger tiles are outstanding
+        if (kt + rb::DMA_STAGES - 2 < nk)
+            wait_vmcnt<rb::DMA_LOADS * (rb::DMA_STAGES - 2)>();
+        else
+            wait_vmcnt<0>();
+        __syncthreads();  // everyone's part of tile kt is in LDS, and tile kt-1's slot is free
+        if (kt + rb::DMA_STAGES - 1 < nk) issue((STAGE + rb::DMA_STAGES - 1) % rb::DMA_STAGES);
+        const char* tl = smem + STAGE * rb::STAGEB;
+        read_frags(fa0, fb0, tl, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kt > 0) mma(fa1, fb1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(fa1, fb1, tl, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(fa0, fb0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    for (int kt = 0; kt < nk; kt += rb::DMA_STAGES) {
+        step(kt, std::integral_constant<int, 0>{});
+        if (kt + 1 < nk) step(kt + 1, std::integral_constant<int, 1>{});
+        if (kt + 2 < nk) step(kt + 2, std::integral_constant<int, 2>{});
+        if (kt + 3 < nk) step(kt + 3, std::integral_constant<int, 3>{});
+    }
+    if (nk > 0) mma(fa1, fb1);
+
+    // D[q][p] layout: lane holds p = lane % 32 and q = 8*g + 4*(lane/32) + 0..3 for g = 0..3: 16-byte stores
+    float* o = out + (int64_t)split * h_in * h_out;
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int p = p0 + wm * 128 + a * 32 + (lane & 31);
+            const int qb = q0 + wn * 64 + b * 32 + ((lane >> 5) << 2);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 v4 = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
+                *reinterpret_cast<f32x4*>(o + (int64_t)p * h_out + qb + 8 * g) = v4;
+            }
+        }
+}
+
 dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s);
 
 bool rebuild_fast_ok(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt) {
@@ -192,16 +356,22 @@ SplitPlan rebuild_fast_split(int64_t K, int64_t h_in, int64_t h_out) {
 dad_status fast_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, float* G, float* partials,
                         SplitPlan sp, hipStream_t s) {
     static bool attr_set = false;
-    const int lds = rb::NSTAGE * rb::STAGEB;
+    const int lds = rb::NSTAGE * rb::STAGEB, lds_dma = rb::DMA_STAGES * rb::STAGEB;
     if (!attr_set) {
         DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_rebuild_bf16),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_rebuild_bf16_dma),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_dma));
         attr_set = true;
     }
     const int tm = (int)(h_in / rb::TILE), tn = (int)(h_out / rb::TILE);
     const int total = tm * tn * sp.splits;
     float* dst = sp.splits == 1 ? G : partials;
-    {
+    if (K % rb::BK == 0 && sp.chunk % rb::BK == 0) {
+        ProfScope prof(KID_REBUILD_BF16, s);
+        hipLaunchKernelGGL(k_rebuild_bf16_dma, dim3((unsigned)total), dim3(rb::DMA_THREADS), lds_dma, s, (const bf16_t*)L,
+                           (const bf16_t*)R, dst, K, (int)h_in, (int)h_out, sp.chunk, tm, tn, total);
+    } else {
         ProfScope prof(KID_REBUILD_BF16, s);
         hipLaunchKernelGGL(k_rebuild_bf16, dim3((unsigned)total), dim3(256), lds, s, (const bf16_t*)L, (const bf16_t*)R,
                            dst, K, (int)h_in, (int)h_out, sp.chunk, tm, tn, total);
