@@ -49,7 +49,7 @@ def kernel_model(name, N, h_in, h_out, r, es, which, bf16=True):
     h = h_in if which == "in" else h_out
     if name in ("k_thin_nn_bf16", "k_thin_tn_bf16", "k_thin_nn", "k_thin_tn"):
         return "hbm", float(N) * h * es
-    if name == "k_rebuild_bf16":
+    if name in ("k_rebuild_bf16", "k_rebuild_bf16_dma"):
         return "mfma", 2.0 * N * h_in * h_out
     if name == "k_rebuild":
         if bf16:   # only the rank-r rebuild (K = r, fp32 pairs) runs this kernel: write bound

@@ -368,7 +368,7 @@ dad_status fast_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, i
     const int total = tm * tn * sp.splits;
     float* dst = sp.splits == 1 ? G : partials;
     if (K % rb::BK == 0 && sp.chunk % rb::BK == 0) {
-        ProfScope prof(KID_REBUILD_BF16, s);
+        ProfScope prof(KID_REBUILD_BF16_DMA, s);
         hipLaunchKernelGGL(k_rebuild_bf16_dma, dim3((unsigned)total), dim3(rb::DMA_THREADS), lds_dma, s, (const bf16_t*)L,
                            (const bf16_t*)R, dst, K, (int)h_in, (int)h_out, sp.chunk, tm, tn, total);
     } else {

@@ -7,8 +7,6 @@
 //
 // Loads run two tiles ahead of the arithmetic through two register sets, so each workgroup keeps
 // about 40 KiB of HBM reads in flight.
-#include <cstdlib>
-
 #include "dad_internal.h"
 
 namespace dad {
@@ -319,12 +317,7 @@ bool thin_fast_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt) {
 // (splits * h * r * 4 bytes, written and read once) stay a few percent of the factor read.
 SplitPlan thin_tn_split(int64_t N, int64_t h, int r) {
     const int64_t slices = h / tn::PW;
-    static int target = 0;
-    if (!target) {
-        const char* e = getenv("DAD_TN_WGS");
-        target = e ? atoi(e) : 512;
-    }
-    int64_t want = target / slices;  // whole rounds of co-resident workgroups: no tail
+    int64_t want = 512 / slices;  // two co-resident workgroups per CU in one round: no tail
     const int64_t cap_traffic = (int64_t)(0.08 * (double)N * 2.0 / (4.0 * r)) + 1;  // partials <= ~8% + 8%
     if (want > cap_traffic) want = cap_traffic;
     const int64_t cap_rows = ceil_div(N, 4 * tn::BK);

@@ -1,0 +1,70 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+Factors are drawn on the device (as bench.py does) and copied to the host, so the
+oracle sees the very same bf16 values.  The full gradient is compared on sampled
+rows that the oracle computes from the definition; the rank-r gradient is
+compared in full against the oracle's block iteration on the same start matrix.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dad_oracle as O
+from paper_2102_09631_amd import binding as dad
+from paper_2102_09631_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2
+
+
+def run_full_size(w, layer, h_in, h_out, dev, rank_check=True):
+    As, Ds = W.device_factors(w, layer, h_in, h_out, device=dev)
+    G0 = W.device_start_matrix(w, layer, h_out, device=dev)
+    A, D = dad.stack_factors(As, Ds)
+    # stack: bit-exact against the oracle's concatenation, site by site
+    b = w.rows_per_site
+    for s in (0, w.sites - 1):
+        assert torch.equal(A[s * b:(s + 1) * b], As[s]) and torch.equal(D[s * b:(s + 1) * b], Ds[s])
+    G_full = dad.reconstruct_grad(A, D)
+    A_h = A.float().cpu().numpy().astype(np.float64)
+    D_h = D.float().cpu().numpy().astype(np.float64)
+    rows = np.random.default_rng(layer).choice(h_in, size=48, replace=False)
+    ref_rows = A_h[:, rows].T @ D_h                                   # Eq. 4 for the sampled rows
+    e_full = O.rel_fro(G_full[torch.from_numpy(rows).to(dev)].cpu().numpy(), ref_rows)
+    out = {"e_full_sampled": e_full}
+    assert e_full <= TOL_BF16, out
+    if rank_check:
+        Pt, Gt = dad.compress_rank(A, D, w.rank, w.n_iter, G0, check=True)
+        G_r = dad.reconstruct_grad(Pt, Gt)
+        Pt_ref, Gt_ref = O.block_spi(A_h, D_h, G0.cpu().numpy(), w.n_iter)
+        out["e_rank"] = O.rel_fro(G_r.cpu().numpy(), O.rank_r_grad(Pt_ref, Gt_ref))
+        g = Gt.cpu().numpy().astype(np.float64)
+        out["orth"] = float(np.abs(g @ g.T - np.eye(w.rank)).max())
+        assert out["e_rank"] <= TOL_BF16, out
+        assert out["orth"] <= 1e-4, out
+    print(w.name, layer, h_in, h_out, out)
+    del A, D, As, Ds
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("layer", [0, 1, 2, 3])
+def test_encoder_d768_full(gpu, layer):
+    w = W.WORKLOADS[2]
+    _, h_in, h_out = w.all_layers()[layer]
+    run_full_size(w, layer, h_in, h_out, gpu)
+
+
+@pytest.mark.parametrize("layer", [0, 1, 2, 3])
+def test_gpt2_medium_layer_shapes_full(gpu, layer):
+    w = W.WORKLOADS[3]
+    _, h_in, h_out = w.all_layers()[layer]
+    run_full_size(w, layer, h_in, h_out, gpu)
+
+
+@pytest.mark.parametrize("layer", [0, 1, 2, 3])
+def test_vit_large_layer_shapes_full(gpu, layer):
+    """N = 262144 rows, r = 64: the tall-skinny orthonormalisation and the K = 262144 contraction."""
+    w = W.WORKLOADS[4]
+    _, h_in, h_out = w.all_layers()[layer]
+    run_full_size(w, layer, h_in, h_out, gpu)
