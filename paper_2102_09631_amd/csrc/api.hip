@@ -148,7 +148,7 @@ dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_
         if ((rc = launch_thin_tn(A, V, Ut, part, p.tn_in, N, h_in, r, dt, p.fast, s)) != DAD_OK) return rc;  // U = A^T V
         if ((rc = launch_thin_nn(A, Ut, V, N, h_in, r, dt, p.fast, s)) != DAD_OK) return rc;               // W = A U
         if ((rc = launch_thin_tn(D, V, Yt, part, p.tn_out, N, h_out, r, dt, p.fast, s)) != DAD_OK) return rc;  // Y = Delta^T W
-        if ((rc = launch_cholqr2(Yt, Gt, h_out, r, gram, p.gram_blocks, rinv, counter, flag, s)) != DAD_OK) return rc;
+        if ((rc = launch_cholqr(Yt, Gt, h_out, r, (it + 1 == n_iter) ? 2 : 1, gram, p.gram_blocks, rinv, counter, flag, s)) != DAD_OK) return rc;
         Gcur = Gt;
     }
     if ((rc = launch_thin_nn(D, Gt, V, N, h_out, r, dt, p.fast, s)) != DAD_OK) return rc;             // V = Delta G

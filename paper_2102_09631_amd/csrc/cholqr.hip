@@ -2,7 +2,8 @@
 // The iterate is held transposed (Yt: r x h, row j = column j of Y), so the
 // Gram matrix is S[i][j] = sum_k Yt[i][k] Yt[j][k].  One round is
 //   S = Y^T Y  ->  S = R^T R (upper R)  ->  Y <- Y R^{-1},
-// done twice.  Three launches per orthonormalisation:
+// done twice (CholeskyQR2) for the iterate that is returned and once for the intermediate
+// iterates of the power iteration, of which only the span matters.  Launches of CholeskyQR2:
 //   1. Gram partials of Yt per 256-column slab; the workgroup that finishes last
 //      sums them (fixed order), factorises and inverts R in fp64.
 //   2. Y <- Y R^{-1} per slab, Gram partials of the result, last workgroup
@@ -172,10 +173,11 @@ __device__ __forceinline__ void last_block_factor(QrShared& sh, double (&acc)[NA
 
 // Up-front load of this workgroup's QR_SUB tiles; element m of tile `sub` is row (t + 256 m) / 64,
 // column (t + 256 m) % 64 of that tile.
-__device__ __forceinline__ void load_slab(float (&st)[QR_SUB][16], const float* Yt, int64_t h, int r, int64_t k0) {
+template <int SUB>
+__device__ __forceinline__ void load_slab(float (&st)[SUB][16], const float* Yt, int64_t h, int r, int64_t k0) {
     const int t = threadIdx.x;
 #pragma unroll
-    for (int sub = 0; sub < QR_SUB; ++sub)
+    for (int sub = 0; sub < SUB; ++sub)
 #pragma unroll
         for (int m = 0; m < 16; ++m) {
             const int e = t + 256 * m, i = e >> 6, kk = e & 63;
@@ -201,7 +203,7 @@ __global__ __launch_bounds__(256) void k_qr_gram(const float* __restrict__ Yt, i
     __shared__ QrShared sh;
     const int64_t k0 = (int64_t)blockIdx.x * QR_SUB * QR_COLS;
     float st[QR_SUB][16];
-    load_slab(st, Yt, h, r, k0);
+    load_slab<QR_SUB>(st, Yt, h, r, k0);
     double acc[NA][NA];
 #pragma unroll
     for (int a = 0; a < NA; ++a)
@@ -222,7 +224,7 @@ __global__ __launch_bounds__(256) void k_qr_gram(const float* __restrict__ Yt, i
 
 // Launches 2 and 3: Gt[j][k] = sum_{i<=j} rinv_in[i][j] * Yt[i][k]; Gt may alias Yt (each workgroup
 // reads its slab completely before it writes).  WITH_GRAM also prepares the next factor.
-template <int NA, bool WITH_GRAM>
+template <int NA, bool WITH_GRAM, int SUB>
 __global__ __launch_bounds__(256) void k_qr_apply(const float* Yt, float* Gt, const float* __restrict__ rinv_in,
                                                   int64_t h, int r, double* __restrict__ gram_part,
                                                   int* __restrict__ counter, float* __restrict__ rinv_out,
@@ -230,30 +232,34 @@ __global__ __launch_bounds__(256) void k_qr_apply(const float* Yt, float* Gt, co
     __shared__ QrShared sh;
     const int t = threadIdx.x;
     const int kl = t & 63, jg = t >> 6;
-    const int64_t k0 = (int64_t)blockIdx.x * QR_SUB * QR_COLS;
-    float st[QR_SUB][16];
-    load_slab(st, Yt, h, r, k0);
-    for (int e = t; e < r * r; e += 256) sh.Rs[e / r][e % r] = rinv_in[e];
+    const int64_t k0 = (int64_t)blockIdx.x * SUB * QR_COLS;
+    float st[SUB][16];
+    load_slab<SUB>(st, Yt, h, r, k0);
+    for (int e = t; e < DAD_MAX_RANK * DAD_MAX_RANK; e += 256) {
+        const int i = e >> 6, j = e & 63;
+        sh.Rs[i][j] = (i < r && j < r) ? rinv_in[i * r + j] : 0.f;
+    }
     double acc[NA][NA];
 #pragma unroll
     for (int a = 0; a < NA; ++a)
 #pragma unroll
         for (int b = 0; b < NA; ++b) acc[a][b] = 0.0;
 #pragma unroll
-    for (int sub = 0; sub < QR_SUB; ++sub) {
+    for (int sub = 0; sub < SUB; ++sub) {
         const int64_t kc = k0 + sub * QR_COLS + kl;
         if (k0 + sub * QR_COLS < h) {
             if (sub) __syncthreads();
             store_tile(sh, st[sub]);
             __syncthreads();
+            // R^{-1} is upper triangular and stored with its zeros, so the sum runs over all i
             float out[NA * 4];
 #pragma unroll
-            for (int m = 0; m < NA * 4; ++m) {
-                const int j = jg + 4 * m;
-                float a = 0.f;
-                if (j < r)
-                    for (int i = 0; i <= j; ++i) a = fmaf(sh.Rs[i][j], sh.Ys[i][kl], a);
-                out[m] = a;
+            for (int m = 0; m < NA * 4; ++m) out[m] = 0.f;
+#pragma unroll 4
+            for (int i = 0; i < r; ++i) {
+                const float y = sh.Ys[i][kl];
+#pragma unroll
+                for (int m = 0; m < NA * 4; ++m) out[m] = fmaf(sh.Rs[i][jg + 4 * m], y, out[m]);
             }
             __syncthreads();
 #pragma unroll
@@ -278,34 +284,44 @@ __global__ __launch_bounds__(256) void k_qr_apply(const float* Yt, float* Gt, co
 
 int gram_blocks_for(int64_t h) { return (int)ceil_div(h, QR_COLS * QR_SUB); }
 
+// `rounds` = 2: CholeskyQR2.  `rounds` = 1: a single Cholesky round, enough for an intermediate
+// iterate of the power iteration, of which only the span matters.
 template <int NA>
-static dad_status qr2(const float* Yt, float* Gt, int64_t h, int r, double* gram_part, int nb, float* rinv,
-                      int* counter, int* flag, hipStream_t s) {
+static dad_status qr(const float* Yt, float* Gt, int64_t h, int r, int rounds, double* gram_part, int nb, float* rinv,
+                     int* counter, int* flag, hipStream_t s) {
     float* rinv2 = rinv + DAD_MAX_RANK * DAD_MAX_RANK;
+    const unsigned nb1 = (unsigned)ceil_div(h, QR_COLS);
     {
         ProfScope prof(KID_GRAM, s);
         hipLaunchKernelGGL(k_qr_gram<NA>, dim3((unsigned)nb), dim3(256), 0, s, Yt, h, r, gram_part, counter, rinv, flag);
     }
     DAD_LAUNCH_CHECK();
+    if (rounds == 1) {
+        ProfScope prof(KID_APPLY2, s);
+        hipLaunchKernelGGL((k_qr_apply<NA, false, 1>), dim3(nb1), dim3(256), 0, s, Yt, Gt, (const float*)rinv, h, r,
+                           gram_part, counter, rinv2, flag);
+        DAD_LAUNCH_CHECK();
+        return DAD_OK;
+    }
     {
         ProfScope prof(KID_APPLY, s);
-        hipLaunchKernelGGL((k_qr_apply<NA, true>), dim3((unsigned)nb), dim3(256), 0, s, Yt, Gt, (const float*)rinv, h, r,
-                           gram_part, counter, rinv2, flag);
+        hipLaunchKernelGGL((k_qr_apply<NA, true, QR_SUB>), dim3((unsigned)nb), dim3(256), 0, s, Yt, Gt, (const float*)rinv,
+                           h, r, gram_part, counter, rinv2, flag);
     }
     DAD_LAUNCH_CHECK();
     {
         ProfScope prof(KID_APPLY2, s);
-        hipLaunchKernelGGL((k_qr_apply<NA, false>), dim3((unsigned)nb), dim3(256), 0, s, (const float*)Gt, Gt,
+        hipLaunchKernelGGL((k_qr_apply<NA, false, 1>), dim3(nb1), dim3(256), 0, s, (const float*)Gt, Gt,
                            (const float*)rinv2, h, r, gram_part, counter, rinv2, flag);
     }
     DAD_LAUNCH_CHECK();
     return DAD_OK;
 }
 
-dad_status launch_cholqr2(const float* Yt, float* Gt, int64_t h, int r, double* gram_part, int gram_blocks,
-                          float* rinv, int* counter, int* flag, hipStream_t s) {
-    if (r <= 32) return qr2<2>(Yt, Gt, h, r, gram_part, gram_blocks, rinv, counter, flag, s);
-    return qr2<4>(Yt, Gt, h, r, gram_part, gram_blocks, rinv, counter, flag, s);
+dad_status launch_cholqr(const float* Yt, float* Gt, int64_t h, int r, int rounds, double* gram_part, int gram_blocks,
+                         float* rinv, int* counter, int* flag, hipStream_t s) {
+    if (r <= 32) return qr<2>(Yt, Gt, h, r, rounds, gram_part, gram_blocks, rinv, counter, flag, s);
+    return qr<4>(Yt, Gt, h, r, rounds, gram_part, gram_blocks, rinv, counter, flag, s);
 }
 
 }  // namespace dad

@@ -110,9 +110,9 @@ dad_status launch_thin_nn(const void* X, const float* Pt, void* out, int64_t N, 
 dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp,
                           int64_t N, int64_t h, int r, dad_dtype dt, bool fast, hipStream_t s);
 
-// In-place orthonormalisation of the rows' transposes: Yt (r x h) -> Gt (r x h), G^T G = I.
-dad_status launch_cholqr2(const float* Yt, float* Gt, int64_t h, int r, double* gram_part, int gram_blocks,
-                          float* rinv, int* counter, int* flag, hipStream_t s);
+// Orthonormalisation Yt (r x h) -> Gt (r x h), rows of Gt orthonormal; rounds = 2 is CholeskyQR2.
+dad_status launch_cholqr(const float* Yt, float* Gt, int64_t h, int r, int rounds, double* gram_part, int gram_blocks,
+                         float* rinv, int* counter, int* flag, hipStream_t s);
 
 dad_status launch_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt,
                           float* G, float* partials, const RebuildPlan& plan, hipStream_t s);

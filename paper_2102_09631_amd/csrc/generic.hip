@@ -106,13 +106,45 @@ __global__ __launch_bounds__(256) void k_thin_tn(const T* __restrict__ X, const 
     }
 }
 
-// out[i] = sum_s part[s*n + i], s ascending (fixed order: reruns are bit-identical)
+// out[i] = sum_s part[s*n + i] in a fixed order, so reruns are bit-identical.
+// Small slabs (the r x h panels of the power iteration): latency bound, so the splits of one
+// element are shared by the four waves of a workgroup (wave g sums s = g, g+4, ... ascending) and
+// the four partial sums are combined in wave order.
 __global__ __launch_bounds__(256) void k_reduce_slabs(const float* __restrict__ part, float* __restrict__ out,
                                                       int64_t n, int splits) {
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n) return;
+    __shared__ float ps[4][64];
+    const int e = threadIdx.x & 63, g = threadIdx.x >> 6;
+    const int64_t i = (int64_t)blockIdx.x * 64 + e;
     float a = 0.f;
-    for (int s = 0; s < splits; ++s) a += part[(int64_t)s * n + i];
+    if (i < n) {
+        int s = g;
+        for (; s + 28 < splits; s += 32) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = part[(int64_t)(s + 4 * u) * n + i];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a += v[u];
+        }
+        for (; s < splits; s += 4) a += part[(int64_t)s * n + i];
+    }
+    ps[g][e] = a;
+    __syncthreads();
+    if (g == 0 && i < n) out[i] = ((ps[0][e] + ps[1][e]) + ps[2][e]) + ps[3][e];
+}
+
+// Large slabs (split-K partials of the gradient rebuild): bandwidth bound, 16 bytes per thread.
+__global__ __launch_bounds__(256) void k_reduce_slabs_wide(const float4* __restrict__ part, float4* __restrict__ out,
+                                                           int64_t n4, int splits) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n4) return;
+    float4 a = part[i];
+    for (int s = 1; s < splits; ++s) {
+        const float4 v = part[(int64_t)s * n4 + i];
+        a.x += v.x;
+        a.y += v.y;
+        a.z += v.z;
+        a.w += v.w;
+    }
     out[i] = a;
 }
 
@@ -188,7 +220,11 @@ dad_status gen_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int
 
 dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s) {
     ProfScope prof(KID_REDUCE, s);
-    hipLaunchKernelGGL(k_reduce_slabs, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, part, out, n, splits);
+    if (n >= (1 << 20) && n % 4 == 0)
+        hipLaunchKernelGGL(k_reduce_slabs_wide, dim3((unsigned)ceil_div(n / 4, 256)), dim3(256), 0, s,
+                           reinterpret_cast<const float4*>(part), reinterpret_cast<float4*>(out), n / 4, splits);
+    else
+        hipLaunchKernelGGL(k_reduce_slabs, dim3((unsigned)ceil_div(n, 64)), dim3(256), 0, s, part, out, n, splits);
     DAD_LAUNCH_CHECK();
     return DAD_OK;
 }

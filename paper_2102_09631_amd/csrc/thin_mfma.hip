@@ -45,6 +45,11 @@ __global__ __launch_bounds__(256) void k_thin_nn_bf16(const bf16_t* __restrict__
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int64_t n0 = (int64_t)blockIdx.x * nn::RT;
     const int nk = (h + nn::BK - 1) / nn::BK;
+    // Every workgroup walks the contraction columns from its own starting stage (and wraps): at any
+    // instant the workgroups then touch different column offsets of their rows, which spreads the
+    // 128-byte row pieces over the memory channels instead of piling onto the few channels that one
+    // common offset maps to when the row pitch is a large power of two.
+    const int rot = (int)((blockIdx.x * 5u) % (unsigned)nk);
 
     // X staging: thread owns 16-byte chunk xc of rows xr + 32*i
     const int xc = t & 7, xr = t >> 3;
@@ -55,7 +60,9 @@ __global__ __launch_bounds__(256) void k_thin_nn_bf16(const bf16_t* __restrict__
     f32x4 ps[2][PLOADS];
 
     auto gload = [&](int kt, int set) {
-        const int k0 = kt * nn::BK;
+        int ktr = kt + rot;
+        if (ktr >= nk) ktr -= nk;
+        const int k0 = ktr * nn::BK;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int64_t n = n0 + xr + 32 * i;
