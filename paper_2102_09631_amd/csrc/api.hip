@@ -4,7 +4,7 @@
 namespace dad {
 
 // implemented in the kernel translation units
-dad_status gen_thin_nn(const void*, const float*, void*, int64_t, int64_t, int, dad_dtype, hipStream_t);
+dad_status gen_thin_nn(const void*, const float*, void*, int64_t, int64_t, int, dad_dtype, int*, hipStream_t);
 dad_status gen_thin_tn(const void*, const void*, float*, float*, SplitPlan, int64_t, int64_t, int, dad_dtype,
                        hipStream_t);
 dad_status gen_rebuild(const void*, const void*, int64_t, int64_t, int64_t, dad_dtype, float*, float*, SplitPlan,
@@ -14,7 +14,7 @@ dad_status launch_stack(int, const void* const*, const void* const*, const int64
 int gram_blocks_for(int64_t h);
 bool thin_fast_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
 SplitPlan thin_tn_split(int64_t N, int64_t h, int r);
-dad_status fast_thin_nn(const void*, const float*, void*, int64_t, int64_t, int, hipStream_t);
+dad_status fast_thin_nn(const void*, const float*, void*, int64_t, int64_t, int, int*, hipStream_t);
 dad_status fast_thin_tn(const void*, const void*, float*, float*, SplitPlan, int64_t, int64_t, int, hipStream_t);
 bool rebuild_fast_ok(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
 SplitPlan rebuild_fast_split(int64_t K, int64_t h_in, int64_t h_out);
@@ -141,17 +141,16 @@ dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_
     dad_status rc;
 
     int* counter = flag + 16;
-    if ((rc = launch_zero_header(flag, s)) != DAD_OK) return rc;
     const float* Gcur = G0;
     for (int it = 0; it < n_iter; ++it) {
-        if ((rc = launch_thin_nn(D, Gcur, V, N, h_out, r, dt, p.fast, s)) != DAD_OK) return rc;            // V = Delta G
+        if ((rc = launch_thin_nn(D, Gcur, V, N, h_out, r, dt, p.fast, it == 0 ? flag : nullptr, s)) != DAD_OK) return rc;            // V = Delta G
         if ((rc = launch_thin_tn(A, V, Ut, part, p.tn_in, N, h_in, r, dt, p.fast, s)) != DAD_OK) return rc;  // U = A^T V
-        if ((rc = launch_thin_nn(A, Ut, V, N, h_in, r, dt, p.fast, s)) != DAD_OK) return rc;               // W = A U
+        if ((rc = launch_thin_nn(A, Ut, V, N, h_in, r, dt, p.fast, nullptr, s)) != DAD_OK) return rc;               // W = A U
         if ((rc = launch_thin_tn(D, V, Yt, part, p.tn_out, N, h_out, r, dt, p.fast, s)) != DAD_OK) return rc;  // Y = Delta^T W
         if ((rc = launch_cholqr(Yt, Gt, h_out, r, (it + 1 == n_iter) ? 2 : 1, gram, p.gram_blocks, rinv, counter, flag, s)) != DAD_OK) return rc;
         Gcur = Gt;
     }
-    if ((rc = launch_thin_nn(D, Gt, V, N, h_out, r, dt, p.fast, s)) != DAD_OK) return rc;             // V = Delta G
+    if ((rc = launch_thin_nn(D, Gt, V, N, h_out, r, dt, p.fast, nullptr, s)) != DAD_OK) return rc;             // V = Delta G
     return launch_thin_tn(A, V, Pt, part, p.tn_in, N, h_in, r, dt, p.fast, s);                        // P = A^T V
 }
 
@@ -190,9 +189,9 @@ dad_status dad_poll_numeric_status(const void* workspace, void* stream) {
 namespace dad {
 
 dad_status launch_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int64_t h, int r, dad_dtype dt,
-                          bool fast, hipStream_t s) {
-    if (fast) return fast_thin_nn(X, Pt, out, N, h, r, s);
-    return gen_thin_nn(X, Pt, out, N, h, r, dt, s);
+                          bool fast, int* zero_hdr, hipStream_t s) {
+    if (fast) return fast_thin_nn(X, Pt, out, N, h, r, zero_hdr, s);
+    return gen_thin_nn(X, Pt, out, N, h, r, dt, zero_hdr, s);
 }
 
 dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp, int64_t N,

@@ -103,8 +103,9 @@ RebuildPlan plan_rebuild(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
 // ---------------------------------------------------------------- launchers (host)
 
 // out[n][j] = sum_k X[n][k] * Pt[j][k];  X is N x h (dt), Pt r x h fp32, out N x r (dt).
+// zero_hdr, when not null, is the 256-byte workspace header the launch clears on the side.
 dad_status launch_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int64_t h, int r,
-                          dad_dtype dt, bool fast, hipStream_t s);
+                          dad_dtype dt, bool fast, int* zero_hdr, hipStream_t s);
 
 // out_t[j][p] = sum_n X[n][p] * V[n][j];  X N x h (dt), V N x r (dt), out_t r x h fp32.
 dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp,
@@ -117,6 +118,5 @@ dad_status launch_cholqr(const float* Yt, float* Gt, int64_t h, int r, int round
 dad_status launch_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt,
                           float* G, float* partials, const RebuildPlan& plan, hipStream_t s);
 
-dad_status launch_zero_header(int* p, hipStream_t s);  // clears the 256-byte workspace header
 
 }  // namespace dad

@@ -9,7 +9,10 @@ namespace dad {
 // out[n][j] = sum_k X[n][k] * Pt[j][k]   (V = Delta G and W = A U of Eq. 6)
 template <typename T>
 __global__ __launch_bounds__(256) void k_thin_nn(const T* __restrict__ X, const float* __restrict__ Pt,
-                                                 T* __restrict__ out, int64_t N, int64_t h, int r) {
+                                                 T* __restrict__ out, int64_t N, int64_t h, int r,
+                                                 int* __restrict__ zero_hdr) {
+    // the first launch of a compress call also clears the workspace header (flag, ticket counter)
+    if (zero_hdr && blockIdx.x == 0 && threadIdx.x < 64) zero_hdr[threadIdx.x] = 0;
     constexpr int ROWS = 64, KC = 32;
     __shared__ float Xs[ROWS][KC + 1];
     __shared__ float Ps[DAD_MAX_RANK][KC + 1];
@@ -202,18 +205,17 @@ __global__ __launch_bounds__(256) void k_rebuild(const T* __restrict__ L, const 
     }
 }
 
-__global__ void k_zero_header(int* p) { p[threadIdx.x] = 0; }
 
 // ---------------------------------------------------------------- host launchers
 
 dad_status gen_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int64_t h, int r, dad_dtype dt,
-                       hipStream_t s) {
+                       int* zero_hdr, hipStream_t s) {
     dim3 grid((unsigned)ceil_div(N, 64));
     ProfScope prof(KID_THIN_NN, s);
     if (dt == DAD_BF16)
-        hipLaunchKernelGGL(k_thin_nn<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)X, Pt, (bf16_t*)out, N, h, r);
+        hipLaunchKernelGGL(k_thin_nn<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)X, Pt, (bf16_t*)out, N, h, r, zero_hdr);
     else
-        hipLaunchKernelGGL(k_thin_nn<float>, grid, dim3(256), 0, s, (const float*)X, Pt, (float*)out, N, h, r);
+        hipLaunchKernelGGL(k_thin_nn<float>, grid, dim3(256), 0, s, (const float*)X, Pt, (float*)out, N, h, r, zero_hdr);
     DAD_LAUNCH_CHECK();
     return DAD_OK;
 }
@@ -265,11 +267,5 @@ dad_status gen_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, in
     return DAD_OK;
 }
 
-dad_status launch_zero_header(int* p, hipStream_t s) {
-    ProfScope prof(KID_FILL, s);
-    hipLaunchKernelGGL(k_zero_header, dim3(1), dim3(64), 0, s, p);
-    DAD_LAUNCH_CHECK();
-    return DAD_OK;
-}
 
 }  // namespace dad

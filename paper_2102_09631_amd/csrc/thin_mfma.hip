@@ -36,7 +36,10 @@ constexpr int XTILEB = RT * XROWB;
 
 template <int RP>  // RP = r rounded up to 32 or 64
 __global__ __launch_bounds__(256) void k_thin_nn_bf16(const bf16_t* __restrict__ X, const float* __restrict__ Pt,
-                                                      bf16_t* __restrict__ V, int64_t N, int h, int r) {
+                                                      bf16_t* __restrict__ V, int64_t N, int h, int r,
+                                                      int* __restrict__ zero_hdr) {
+    // the first launch of a compress call also clears the workspace header (flag, ticket counter)
+    if (zero_hdr && blockIdx.x == 0 && threadIdx.x < 64) zero_hdr[threadIdx.x] = 0;
     constexpr int JT = RP / 32;
     constexpr int PLOADS = RP * nn::BK / 4 / 256;  // float4 loads of Pt per thread per stage
     constexpr int PTILEB = RP * nn::XROWB;
@@ -343,15 +346,18 @@ static dad_status set_lds(Kern k, int bytes) {
     return DAD_OK;
 }
 
-dad_status fast_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int64_t h, int r, hipStream_t s) {
+dad_status fast_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int64_t h, int r, int* zero_hdr,
+                        hipStream_t s) {
     dim3 grid((unsigned)ceil_div(N, nn::RT));
     ProfScope prof(KID_THIN_NN_BF16, s);
     if (r <= 32) {
         const int lds = 2 * (nn::XTILEB + 32 * nn::XROWB);
-        hipLaunchKernelGGL(k_thin_nn_bf16<32>, grid, dim3(256), lds, s, (const bf16_t*)X, Pt, (bf16_t*)out, N, (int)h, r);
+        hipLaunchKernelGGL(k_thin_nn_bf16<32>, grid, dim3(256), lds, s, (const bf16_t*)X, Pt, (bf16_t*)out, N, (int)h, r,
+                           zero_hdr);
     } else {
         const int lds = 2 * (nn::XTILEB + 64 * nn::XROWB);
-        hipLaunchKernelGGL(k_thin_nn_bf16<64>, grid, dim3(256), lds, s, (const bf16_t*)X, Pt, (bf16_t*)out, N, (int)h, r);
+        hipLaunchKernelGGL(k_thin_nn_bf16<64>, grid, dim3(256), lds, s, (const bf16_t*)X, Pt, (bf16_t*)out, N, (int)h, r,
+                           zero_hdr);
     }
     DAD_LAUNCH_CHECK();
     return DAD_OK;
