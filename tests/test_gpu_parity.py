@@ -173,3 +173,45 @@ def test_rerun_is_bit_identical(gpu):
         runs.append((G.clone(), Pt.clone(), Gt.clone()))
     for x, y in zip(*runs):
         assert torch.equal(x, y)
+
+
+def test_calls_can_be_captured_in_a_hip_graph(gpu):
+    """The entry points only enqueue kernels on the caller's stream (no allocation, no sync, no memset),
+    so a caller may capture them; every replay must reproduce the eager result bit for bit."""
+    w = W.WORKLOADS[2]
+    A_sites, D_sites = W.host_factors(w, 1, 768, 768, rows=512)
+    As = [to_dev(a, "bf16", gpu) for a in A_sites]
+    Ds = [to_dev(d, "bf16", gpu) for d in D_sites]
+    G0 = torch.from_numpy(W.host_start_matrix(w, 1, 768)).to(gpu)
+    N = 4 * 512
+    A = torch.empty((N, 768), dtype=torch.bfloat16, device=gpu)
+    D = torch.empty((N, 768), dtype=torch.bfloat16, device=gpu)
+    Pt = torch.empty((16, 768), device=gpu)
+    Gt = torch.empty((16, 768), device=gpu)
+    G = torch.empty((768, 768), device=gpu)
+    Gr = torch.empty((768, 768), device=gpu)
+    ws_c = torch.empty(dad.compress_workspace_bytes(N, 768, 768, 16, torch.bfloat16), dtype=torch.uint8, device=gpu)
+    ws_r = torch.empty(max(16, dad.reconstruct_workspace_bytes(N, 768, 768, torch.bfloat16)), dtype=torch.uint8,
+                       device=gpu)
+
+    def path():
+        dad.stack_factors(As, Ds, A_out=A, D_out=D)
+        dad.compress_rank(A, D, 16, 2, G0, Pt=Pt, Gt=Gt, workspace=ws_c)
+        dad.reconstruct_grad(A, D, G=G, workspace=ws_r)
+        dad.reconstruct_grad(Pt, Gt, G=Gr)
+
+    path()                      # eager: also performs the one-time kernel attribute set-up
+    torch.cuda.synchronize()
+    ref = [x.clone() for x in (A, D, Pt, Gt, G, Gr)]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        path()
+    for rep in range(3):
+        for x in (A, D, Pt, Gt, G, Gr):
+            x.fill_(float(rep + 1))          # eager work between replays, and stale outputs to overwrite
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for x, y in zip((A, D, Pt, Gt, G, Gr), ref):
+            assert torch.equal(x, y)
+    assert dad.poll_numeric_status(ws_c) == dad.DAD_OK
