@@ -15,7 +15,10 @@ int gram_blocks_for(int64_t h);
 bool thin_fast_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
 SplitPlan thin_tn_split(int64_t N, int64_t h, int r);
 dad_status fast_thin_nn(const void*, const float*, void*, int64_t, int64_t, int, int*, hipStream_t);
-dad_status fast_thin_tn(const void*, const void*, float*, float*, SplitPlan, int64_t, int64_t, int, hipStream_t);
+dad_status fast_thin_tn(const void*, const void*, float*, float*, SplitPlan, int64_t, int64_t, int, void*, hipStream_t);
+bool thin_dma_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
+dad_status launch_panel_init(const float*, void*, void*, int64_t, int64_t, int, int*, hipStream_t);
+dad_status dma_thin_nn(const void*, const void*, void*, int64_t, int64_t, int, hipStream_t);
 bool rebuild_fast_ok(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
 SplitPlan rebuild_fast_split(int64_t K, int64_t h_in, int64_t h_out);
 dad_status fast_rebuild(const void*, const void*, int64_t, int64_t, int64_t, float*, float*, SplitPlan, hipStream_t);
@@ -54,6 +57,12 @@ CompressPlan plan_compress(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dt
     o += align_up((size_t)p.gram_blocks * r * r * 8, 256);
     p.off_rinv = o;
     o += 2 * DAD_MAX_RANK * DAD_MAX_RANK * 4;
+    p.dma = thin_dma_ok(N, h_in, h_out, r, dt);
+    const size_t rp = r <= 32 ? 32 : 64;
+    p.off_Gb = o;
+    if (p.dma) o += align_up(rp * (size_t)h_out * 2, 256);
+    p.off_Ub = o;
+    if (p.dma) o += align_up(rp * (size_t)h_in * 2, 256);
     p.total = o;
     return p;
 }
@@ -141,17 +150,36 @@ dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_
     dad_status rc;
 
     int* counter = flag + 16;
+    if (p.dma) {
+        // direct-to-LDS path: the h x r panels also exist as bf16 copies (Gb, Ub) made by their producers
+        void* Gb = ws + p.off_Gb;
+        void* Ub = ws + p.off_Ub;
+        if ((rc = launch_panel_init(G0, Gb, Ub, h_in, h_out, r, flag, s)) != DAD_OK) return rc;
+        for (int it = 0; it < n_iter; ++it) {
+            if ((rc = dma_thin_nn(D, Gb, V, N, h_out, r, s)) != DAD_OK) return rc;                                     // V = Delta G
+            if ((rc = launch_thin_tn(A, V, Ut, part, p.tn_in, N, h_in, r, dt, true, Ub, s)) != DAD_OK) return rc;      // U = A^T V
+            if ((rc = dma_thin_nn(A, Ub, V, N, h_in, r, s)) != DAD_OK) return rc;                                      // W = A U
+            if ((rc = launch_thin_tn(D, V, Yt, part, p.tn_out, N, h_out, r, dt, true, nullptr, s)) != DAD_OK) return rc;  // Y = Delta^T W
+            if ((rc = launch_cholqr(Yt, Gt, h_out, r, (it + 1 == n_iter) ? 2 : 1, gram, p.gram_blocks, rinv, counter, flag,
+                                    Gb, s)) != DAD_OK)
+                return rc;
+        }
+        if ((rc = dma_thin_nn(D, Gb, V, N, h_out, r, s)) != DAD_OK) return rc;                                         // V = Delta G
+        return launch_thin_tn(A, V, Pt, part, p.tn_in, N, h_in, r, dt, true, nullptr, s);                              // P = A^T V
+    }
     const float* Gcur = G0;
     for (int it = 0; it < n_iter; ++it) {
-        if ((rc = launch_thin_nn(D, Gcur, V, N, h_out, r, dt, p.fast, it == 0 ? flag : nullptr, s)) != DAD_OK) return rc;            // V = Delta G
-        if ((rc = launch_thin_tn(A, V, Ut, part, p.tn_in, N, h_in, r, dt, p.fast, s)) != DAD_OK) return rc;  // U = A^T V
-        if ((rc = launch_thin_nn(A, Ut, V, N, h_in, r, dt, p.fast, nullptr, s)) != DAD_OK) return rc;               // W = A U
-        if ((rc = launch_thin_tn(D, V, Yt, part, p.tn_out, N, h_out, r, dt, p.fast, s)) != DAD_OK) return rc;  // Y = Delta^T W
-        if ((rc = launch_cholqr(Yt, Gt, h_out, r, (it + 1 == n_iter) ? 2 : 1, gram, p.gram_blocks, rinv, counter, flag, s)) != DAD_OK) return rc;
+        if ((rc = launch_thin_nn(D, Gcur, V, N, h_out, r, dt, p.fast, it == 0 ? flag : nullptr, s)) != DAD_OK) return rc;  // V = Delta G
+        if ((rc = launch_thin_tn(A, V, Ut, part, p.tn_in, N, h_in, r, dt, p.fast, nullptr, s)) != DAD_OK) return rc;   // U = A^T V
+        if ((rc = launch_thin_nn(A, Ut, V, N, h_in, r, dt, p.fast, nullptr, s)) != DAD_OK) return rc;                  // W = A U
+        if ((rc = launch_thin_tn(D, V, Yt, part, p.tn_out, N, h_out, r, dt, p.fast, nullptr, s)) != DAD_OK) return rc; // Y = Delta^T W
+        if ((rc = launch_cholqr(Yt, Gt, h_out, r, (it + 1 == n_iter) ? 2 : 1, gram, p.gram_blocks, rinv, counter, flag,
+                                nullptr, s)) != DAD_OK)
+            return rc;
         Gcur = Gt;
     }
-    if ((rc = launch_thin_nn(D, Gt, V, N, h_out, r, dt, p.fast, nullptr, s)) != DAD_OK) return rc;             // V = Delta G
-    return launch_thin_tn(A, V, Pt, part, p.tn_in, N, h_in, r, dt, p.fast, s);                        // P = A^T V
+    if ((rc = launch_thin_nn(D, Gt, V, N, h_out, r, dt, p.fast, nullptr, s)) != DAD_OK) return rc;                     // V = Delta G
+    return launch_thin_tn(A, V, Pt, part, p.tn_in, N, h_in, r, dt, p.fast, nullptr, s);                                // P = A^T V
 }
 
 static bool rebuild_shape_ok(int64_t K, int64_t h_in, int64_t h_out) {
@@ -195,8 +223,8 @@ dad_status launch_thin_nn(const void* X, const float* Pt, void* out, int64_t N, 
 }
 
 dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp, int64_t N,
-                          int64_t h, int r, dad_dtype dt, bool fast, hipStream_t s) {
-    if (fast) return fast_thin_tn(X, V, out_t, partials, sp, N, h, r, s);
+                          int64_t h, int r, dad_dtype dt, bool fast, void* out_bf16, hipStream_t s) {
+    if (fast) return fast_thin_tn(X, V, out_t, partials, sp, N, h, r, out_bf16, s);
     return gen_thin_tn(X, V, out_t, partials, sp, N, h, r, dt, s);
 }
 

@@ -228,7 +228,7 @@ template <int NA, bool WITH_GRAM, int SUB>
 __global__ __launch_bounds__(256) void k_qr_apply(const float* Yt, float* Gt, const float* __restrict__ rinv_in,
                                                   int64_t h, int r, double* __restrict__ gram_part,
                                                   int* __restrict__ counter, float* __restrict__ rinv_out,
-                                                  int* __restrict__ flag) {
+                                                  int* __restrict__ flag, bf16_t* __restrict__ gt_bf16) {
     __shared__ QrShared sh;
     const int t = threadIdx.x;
     const int kl = t & 63, jg = t >> 6;
@@ -266,7 +266,10 @@ __global__ __launch_bounds__(256) void k_qr_apply(const float* Yt, float* Gt, co
             for (int m = 0; m < NA * 4; ++m) {
                 const int j = jg + 4 * m;
                 if (j < r) {
-                    if (kc < h) Gt[(int64_t)j * h + kc] = out[m];
+                    if (kc < h) {
+                        Gt[(int64_t)j * h + kc] = out[m];
+                        if (gt_bf16) gt_bf16[(int64_t)j * h + kc] = f32_to_bf16(out[m]);  // panel of the next thin_nn
+                    }
                     if (WITH_GRAM) sh.Ys[j][kl] = (kc < h) ? out[m] : 0.f;
                 }
             }
@@ -288,7 +291,7 @@ int gram_blocks_for(int64_t h) { return (int)ceil_div(h, QR_COLS * QR_SUB); }
 // iterate of the power iteration, of which only the span matters.
 template <int NA>
 static dad_status qr(const float* Yt, float* Gt, int64_t h, int r, int rounds, double* gram_part, int nb, float* rinv,
-                     int* counter, int* flag, hipStream_t s) {
+                     int* counter, int* flag, bf16_t* gt_bf16, hipStream_t s) {
     float* rinv2 = rinv + DAD_MAX_RANK * DAD_MAX_RANK;
     const unsigned nb1 = (unsigned)ceil_div(h, QR_COLS);
     {
@@ -299,29 +302,29 @@ static dad_status qr(const float* Yt, float* Gt, int64_t h, int r, int rounds, d
     if (rounds == 1) {
         ProfScope prof(KID_APPLY2, s);
         hipLaunchKernelGGL((k_qr_apply<NA, false, 1>), dim3(nb1), dim3(256), 0, s, Yt, Gt, (const float*)rinv, h, r,
-                           gram_part, counter, rinv2, flag);
+                           gram_part, counter, rinv2, flag, gt_bf16);
         DAD_LAUNCH_CHECK();
         return DAD_OK;
     }
     {
         ProfScope prof(KID_APPLY, s);
         hipLaunchKernelGGL((k_qr_apply<NA, true, QR_SUB>), dim3((unsigned)nb), dim3(256), 0, s, Yt, Gt, (const float*)rinv,
-                           h, r, gram_part, counter, rinv2, flag);
+                           h, r, gram_part, counter, rinv2, flag, (bf16_t*)nullptr);
     }
     DAD_LAUNCH_CHECK();
     {
         ProfScope prof(KID_APPLY2, s);
         hipLaunchKernelGGL((k_qr_apply<NA, false, 1>), dim3(nb1), dim3(256), 0, s, (const float*)Gt, Gt,
-                           (const float*)rinv2, h, r, gram_part, counter, rinv2, flag);
+                           (const float*)rinv2, h, r, gram_part, counter, rinv2, flag, gt_bf16);
     }
     DAD_LAUNCH_CHECK();
     return DAD_OK;
 }
 
 dad_status launch_cholqr(const float* Yt, float* Gt, int64_t h, int r, int rounds, double* gram_part, int gram_blocks,
-                         float* rinv, int* counter, int* flag, hipStream_t s) {
-    if (r <= 32) return qr<2>(Yt, Gt, h, r, rounds, gram_part, gram_blocks, rinv, counter, flag, s);
-    return qr<4>(Yt, Gt, h, r, rounds, gram_part, gram_blocks, rinv, counter, flag, s);
+                         float* rinv, int* counter, int* flag, void* gt_bf16, hipStream_t s) {
+    if (r <= 32) return qr<2>(Yt, Gt, h, r, rounds, gram_part, gram_blocks, rinv, counter, flag, (bf16_t*)gt_bf16, s);
+    return qr<4>(Yt, Gt, h, r, rounds, gram_part, gram_blocks, rinv, counter, flag, (bf16_t*)gt_bf16, s);
 }
 
 }  // namespace dad

@@ -29,6 +29,20 @@ template <typename T> __device__ __forceinline__ void st(T* p, int64_t i, float 
 template <> __device__ __forceinline__ void st<float>(float* p, int64_t i, float v) { p[i] = v; }
 template <> __device__ __forceinline__ void st<bf16_t>(bf16_t* p, int64_t i, float v) { p[i] = f32_to_bf16(v); }
 
+// 16 bytes per lane from global memory straight into LDS: lane i's data lands at lds_addr + 16*i
+// (lds_addr must be wave-uniform).  Issued through inline assembly because the compiler would
+// otherwise wait for ALL outstanding LDS-bound loads before any LDS read; callers place the waits
+// themselves with wait_vmcnt<N>() (N = number of younger loads that may still be in flight).
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_addr) {
+    lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);  // uniform by contract; this makes it a scalar register
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
 inline size_t elem_size(dad_dtype dt) { return dt == DAD_BF16 ? 2 : 4; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -83,6 +97,9 @@ struct CompressPlan {
     size_t off_Yt;        // r x h_out fp32
     size_t off_gram;      // gram partials, fp64
     size_t off_rinv;      // two DAD_MAX_RANK^2 fp32 inverse factors
+    size_t off_Gb;        // bf16 copy of the current right block, RP x h_out (direct-to-LDS path only)
+    size_t off_Ub;        // bf16 copy of U, RP x h_in
+    bool dma;             // thin_nn takes its panel as bf16 and loads straight into LDS
     size_t total;
     SplitPlan tn_in;      // split of  A^T V   (width h_in)
     SplitPlan tn_out;     // split of  Delta^T W (width h_out)
@@ -102,18 +119,24 @@ RebuildPlan plan_rebuild(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
 
 // ---------------------------------------------------------------- launchers (host)
 
+// out[i] = sum over s of part[s*n + i] in a fixed order; out_bf16 (optional) gets a bf16 copy.
+dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s, void* out_bf16 = nullptr);
+
+
 // out[n][j] = sum_k X[n][k] * Pt[j][k];  X is N x h (dt), Pt r x h fp32, out N x r (dt).
 // zero_hdr, when not null, is the 256-byte workspace header the launch clears on the side.
 dad_status launch_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int64_t h, int r,
                           dad_dtype dt, bool fast, int* zero_hdr, hipStream_t s);
 
 // out_t[j][p] = sum_n X[n][p] * V[n][j];  X N x h (dt), V N x r (dt), out_t r x h fp32.
+// out_bf16 (optional, fast path only) receives a bf16 copy of out_t.
 dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp,
-                          int64_t N, int64_t h, int r, dad_dtype dt, bool fast, hipStream_t s);
+                          int64_t N, int64_t h, int r, dad_dtype dt, bool fast, void* out_bf16, hipStream_t s);
 
 // Orthonormalisation Yt (r x h) -> Gt (r x h), rows of Gt orthonormal; rounds = 2 is CholeskyQR2.
+// gt_bf16 (optional) receives a bf16 copy of Gt.
 dad_status launch_cholqr(const float* Yt, float* Gt, int64_t h, int r, int rounds, double* gram_part, int gram_blocks,
-                         float* rinv, int* counter, int* flag, hipStream_t s);
+                         float* rinv, int* counter, int* flag, void* gt_bf16, hipStream_t s);
 
 dad_status launch_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt,
                           float* G, float* partials, const RebuildPlan& plan, hipStream_t s);

@@ -113,8 +113,8 @@ __global__ __launch_bounds__(256) void k_thin_tn(const T* __restrict__ X, const 
 // Small slabs (the r x h panels of the power iteration): latency bound, so the splits of one
 // element are shared by the four waves of a workgroup (wave g sums s = g, g+4, ... ascending) and
 // the four partial sums are combined in wave order.
-__global__ __launch_bounds__(256) void k_reduce_slabs(const float* __restrict__ part, float* __restrict__ out,
-                                                      int64_t n, int splits) {
+__global__ __launch_bounds__(256) void k_reduce_slabs(const float* part, float* out, int64_t n, int splits,
+                                                      bf16_t* __restrict__ out_bf16) {
     __shared__ float ps[4][64];
     const int e = threadIdx.x & 63, g = threadIdx.x >> 6;
     const int64_t i = (int64_t)blockIdx.x * 64 + e;
@@ -132,7 +132,11 @@ __global__ __launch_bounds__(256) void k_reduce_slabs(const float* __restrict__ 
     }
     ps[g][e] = a;
     __syncthreads();
-    if (g == 0 && i < n) out[i] = ((ps[0][e] + ps[1][e]) + ps[2][e]) + ps[3][e];
+    if (g == 0 && i < n) {
+        const float v = ((ps[0][e] + ps[1][e]) + ps[2][e]) + ps[3][e];
+        out[i] = v;
+        if (out_bf16) out_bf16[i] = f32_to_bf16(v);  // panel of the next thin_nn
+    }
 }
 
 // Large slabs (split-K partials of the gradient rebuild): bandwidth bound, 16 bytes per thread.
@@ -220,13 +224,14 @@ dad_status gen_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int
     return DAD_OK;
 }
 
-dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s) {
+dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s, void* out_bf16) {
     ProfScope prof(KID_REDUCE, s);
-    if (n >= (1 << 20) && n % 4 == 0)
+    if (n >= (1 << 20) && n % 4 == 0 && !out_bf16)
         hipLaunchKernelGGL(k_reduce_slabs_wide, dim3((unsigned)ceil_div(n / 4, 256)), dim3(256), 0, s,
                            reinterpret_cast<const float4*>(part), reinterpret_cast<float4*>(out), n / 4, splits);
     else
-        hipLaunchKernelGGL(k_reduce_slabs, dim3((unsigned)ceil_div(n, 64)), dim3(256), 0, s, part, out, n, splits);
+        hipLaunchKernelGGL(k_reduce_slabs, dim3((unsigned)ceil_div(n, 64)), dim3(256), 0, s, part, out, n, splits,
+                           (bf16_t*)out_bf16);
     DAD_LAUNCH_CHECK();
     return DAD_OK;
 }

@@ -178,15 +178,6 @@ constexpr int DMA_THREADS = 512;
 constexpr int DMA_LOADS = 2 * TILEB / 16 / DMA_THREADS;  // 16-byte loads per thread per stage
 }  // namespace rb
 
-__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gptr) : "memory");
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-
 __global__ __launch_bounds__(rb::DMA_THREADS) void k_rebuild_bf16_dma(const bf16_t* __restrict__ L,
                                                                       const bf16_t* __restrict__ R,
                                                                       float* __restrict__ out, int64_t K, int h_in,
@@ -322,7 +313,6 @@ __global__ __launch_bounds__(rb::DMA_THREADS) void k_rebuild_bf16_dma(const bf16
         }
 }
 
-dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s);
 
 bool rebuild_fast_ok(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt) {
     return dt == DAD_BF16 && h_in % rb::TILE == 0 && h_out % rb::TILE == 0 && K >= 256 && h_in <= (1 << 20) &&

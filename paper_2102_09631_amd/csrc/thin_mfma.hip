@@ -164,6 +164,124 @@ __global__ __launch_bounds__(256) void k_thin_nn_bf16(const bf16_t* __restrict__
 }
 
 // ------------------------------------------------------------------------------------------------
+// thin_nn, direct-to-LDS variant.  The h x r panel comes as bf16 (Pb: RP x h, rows >= r zero), so both
+// the X tile and the panel tile go HBM/L2 -> LDS without passing through registers, through a ring of
+// three slots.  Whole tiles only: N a multiple of 32*W rows, h a multiple of 64.  Each wave loads
+// exactly the 32 rows it multiplies.  16-byte chunk c of tile row m sits at chunk c ^ ((m >> 1) & 7),
+// which makes the 16-byte fragment reads of 16 consecutive rows hit 16 distinct bank groups; the
+// XOR is applied on the global side of the load.
+// ------------------------------------------------------------------------------------------------
+template <int RP, int W, int NS>
+__global__ __launch_bounds__(64 * W) void k_thin_nn_bf16_dma(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Pb,
+                                                            bf16_t* __restrict__ V, int64_t N, int h, int r) {
+    constexpr int JT = RP / 32, RT = 32 * W, ROWB = 128;
+    constexpr int XTILEB = RT * ROWB, PTILEB = RP * ROWB, STAGEB = XTILEB + PTILEB;
+    constexpr int PI = RP / 8;               // 1 KiB loads that make up the panel tile
+    constexpr int PL = (PI + W - 1) / W;     // per wave (waves beyond PI repeat earlier pieces)
+    constexpr int LOADS = 4 + PL;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int64_t n0 = (int64_t)blockIdx.x * RT;
+    const int nk = h / nn::BK;
+    // every workgroup starts its walk over the contraction columns at its own stage (see k_thin_nn_bf16)
+    int kidx = (int)((blockIdx.x * 5u) % (unsigned)nk);
+
+    const char* gx[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = 32 * wave + 8 * i + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
+        gx[i] = reinterpret_cast<const char*>(X + (n0 + row) * (int64_t)h) + c * 16;
+    }
+    const char* gp[PL];
+    int pi[PL];
+#pragma unroll
+    for (int i = 0; i < PL; ++i) {
+        pi[i] = (wave * PL + i) % PI;
+        const int row = 8 * pi[i] + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
+        gp[i] = reinterpret_cast<const char*>(Pb + (int64_t)row * h) + c * 16;
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+
+    auto issue = [&](int stage) {
+        const uint32_t base = lds0 + stage * STAGEB;
+        const int koff = kidx * ROWB;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dma16(gx[i] + koff, base + (32 * wave + 8 * i) * ROWB);
+#pragma unroll
+        for (int i = 0; i < PL; ++i) dma16(gp[i] + koff, base + XTILEB + pi[i] * 1024);
+        kidx = (kidx + 1 == nk) ? 0 : kidx + 1;
+    };
+
+    f32x16 acc[JT];
+#pragma unroll
+    for (int j = 0; j < JT; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (s < nk) issue(s);
+
+    const int mrow = lane & 31, swz = (mrow >> 1) & 7, khalf = lane >> 5;
+    int slot = 0;
+    for (int kt = 0; kt < nk; ++kt) {
+        if (kt + NS - 2 < nk)
+            wait_vmcnt<LOADS * (NS - 2)>();
+        else
+            wait_vmcnt<0>();
+        __syncthreads();  // tile kt complete in LDS (the panel part comes from other waves); slot of kt-1 free
+        if (kt + NS - 1 < nk) issue(slot == 0 ? NS - 1 : slot - 1);
+        const char* xb = smem + slot * STAGEB + (wave * 32 + mrow) * ROWB;
+        const char* pb = smem + slot * STAGEB + XTILEB + mrow * ROWB;
+#pragma unroll
+        for (int ks = 0; ks < nn::BK / 16; ++ks) {
+            const int c = ((ks * 2 + khalf) ^ swz) << 4;
+            bf16x8 fa = *reinterpret_cast<const bf16x8*>(xb + c);
+#pragma unroll
+            for (int j = 0; j < JT; ++j) {
+                bf16x8 fb = *reinterpret_cast<const bf16x8*>(pb + j * 32 * ROWB + c);
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[j], 0, 0, 0);
+            }
+        }
+        slot = slot == NS - 1 ? 0 : slot + 1;
+    }
+    __syncthreads();
+
+    // epilogue: fp32 -> bf16 through LDS so the tile leaves as contiguous 16-byte stores
+    bf16_t* vs = reinterpret_cast<bf16_t*>(smem);  // [RT][r]
+#pragma unroll
+    for (int j = 0; j < JT; ++j) {
+        const int col = j * 32 + (lane & 31);
+        if (col < r) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = wave * 32 + ((v >> 2) << 3) + ((lane >> 5) << 2) + (v & 3);
+                vs[row * r + col] = f32_to_bf16(acc[j][v]);
+            }
+        }
+    }
+    __syncthreads();
+    const int chunks = RT * r / 8;
+    u32x4* dst = reinterpret_cast<u32x4*>(V + n0 * r);
+    const u32x4* src = reinterpret_cast<const u32x4*>(vs);
+    for (int e = t; e < chunks; e += 64 * W) dst[e] = src[e];
+}
+
+// Start of a compress call on the direct-to-LDS path: Gb <- bf16(G0) with rows r..RP-1 zero, the same
+// zero rows in Ub, and the workspace header cleared.
+__global__ __launch_bounds__(256) void k_panel_init(const float* __restrict__ G0, bf16_t* __restrict__ Gb,
+                                                    bf16_t* __restrict__ Ub, int64_t h_in, int64_t h_out, int r, int rp,
+                                                    int* __restrict__ hdr) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (blockIdx.x == 0 && threadIdx.x < 64) hdr[threadIdx.x] = 0;
+    if (i < (int64_t)rp * h_out) Gb[i] = (i < (int64_t)r * h_out) ? f32_to_bf16(G0[i]) : (bf16_t)0;
+    const int64_t pad0 = (int64_t)r * h_in;
+    if (i < (int64_t)(rp - r) * h_in) Ub[pad0 + i] = (bf16_t)0;
+}
+
+// ------------------------------------------------------------------------------------------------
 // thin_tn
 // ------------------------------------------------------------------------------------------------
 namespace tn {
@@ -314,9 +432,124 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16(const bf16_t* __restrict__
 }
 
 // ------------------------------------------------------------------------------------------------
+// thin_tn, direct-to-LDS variant: whole 64-row tiles only (N and the row chunk multiples of 64) and
+// r in {16, 32, 64}.  X and V tiles go HBM -> LDS without passing through registers, through a ring
+// of three slots, so two tiles per workgroup are always in flight and two workgroups share a CU.
+// The swizzle of the X tile is applied on the global side, as in the rebuild kernel.
+// ------------------------------------------------------------------------------------------------
+template <int R, int PW>
+__global__ __launch_bounds__(256) void k_thin_tn_bf16_dma(const bf16_t* __restrict__ X, const bf16_t* __restrict__ V,
+                                                          float* __restrict__ part, int64_t N, int h,
+                                                          int64_t chunk_rows) {
+    constexpr int JT = R > 32 ? 2 : 1;
+    constexpr int MT = PW / 128;                  // 32-column tiles per wave
+    constexpr int XROWB = PW * 2;
+    constexpr int XTILEB = tn::BK * XROWB;
+    constexpr int XL = XTILEB / 1024 / 4;         // X loads per wave per tile
+    constexpr int RPL = 1024 / XROWB;             // tile rows covered by one load
+    constexpr int CPR = PW / 8;                   // 16-byte chunks per row
+    constexpr int VROWB = R * 2;
+    constexpr int VTILEB = tn::BK * VROWB;
+    constexpr int VSLOT = VTILEB + 256;  // R = 16: fragment reads of the unused columns 16..31 run past the tile
+    constexpr int STAGEB = XTILEB + VSLOT;
+    constexpr int NS = 3;
+    constexpr int VL = R == 64 ? 2 : 1;  // V loads per wave per tile (R = 16: waves 2, 3 repeat waves 0, 1)
+    constexpr int LOADS = XL + VL;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int p0 = blockIdx.x * PW;
+    const int64_t nbeg = (int64_t)blockIdx.y * chunk_rows;
+    const int64_t nend = (nbeg + chunk_rows < N) ? nbeg + chunk_rows : N;
+    const int nk = (int)((nend - nbeg) / tn::BK);
+
+    // X: load i of this wave covers tile rows (wave*XL + i)*RPL .. ; lane -> row += lane/CPR, LDS chunk lane%CPR
+    const char* gx[XL];
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+        const int row = (wave * XL + i) * RPL + lane / CPR;
+        const int c = (lane % CPR) ^ ((row & 3) << 2);
+        gx[i] = reinterpret_cast<const char*>(X + (nbeg + row) * (int64_t)h + p0 + c * 8);
+    }
+    // V: the tile is 64*R*2 contiguous bytes; load i of this wave covers its 1 KiB piece vi[i]
+    const char* gv[VL];
+    int vi[VL];
+#pragma unroll
+    for (int i = 0; i < VL; ++i) {
+        vi[i] = R == 16 ? (wave & 1) : (R == 32 ? wave : 2 * wave + i);
+        gv[i] = reinterpret_cast<const char*>(V + nbeg * R) + vi[i] * 1024 + lane * 16;
+    }
+    const int64_t adv_x = (int64_t)tn::BK * h * 2;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+
+    auto issue = [&](int stage) {
+        const uint32_t base = lds0 + stage * STAGEB;
+#pragma unroll
+        for (int i = 0; i < XL; ++i) {
+            dma16(gx[i], base + (wave * XL + i) * 1024);
+            gx[i] += adv_x;
+        }
+#pragma unroll
+        for (int i = 0; i < VL; ++i) {
+            dma16(gv[i], base + XTILEB + vi[i] * 1024);
+            gv[i] += VTILEB;
+        }
+    };
+
+    f32x16 acc[MT][JT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int j = 0; j < JT; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[m][j][v] = 0.f;
+
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (s < nk) issue(s);
+
+    int slot = 0;
+    for (int kt = 0; kt < nk; ++kt) {
+        if (kt + NS - 2 < nk)
+            wait_vmcnt<LOADS * (NS - 2)>();
+        else
+            wait_vmcnt<0>();
+        __syncthreads();  // tile kt is complete in LDS, and the slot of tile kt-1 is free
+        if (kt + NS - 1 < nk) issue(slot == 0 ? NS - 1 : slot - 1);
+        const char* xb = smem + slot * STAGEB;
+        const char* vb = xb + XTILEB;
+#pragma unroll
+        for (int ks = 0; ks < tn::BK / 16; ++ks) {
+            bf16x8 fv[JT];
+#pragma unroll
+            for (int j = 0; j < JT; ++j) fv[j] = tn_frag<false>(vb, VROWB, j * 32, ks * 16, lane);
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                bf16x8 fx = tn_frag<true>(xb, XROWB, (wave * MT + m) * 32, ks * 16, lane);
+#pragma unroll
+                for (int j = 0; j < JT; ++j)
+                    acc[m][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[j], fx, acc[m][j], 0, 0, 0);
+            }
+        }
+        slot = slot == NS - 1 ? 0 : slot + 1;
+    }
+
+    float* o = part + (int64_t)blockIdx.y * R * h;
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        const int p = p0 + (wave * MT + m) * 32 + (lane & 31);
+#pragma unroll
+        for (int j = 0; j < JT; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = j * 32 + ((v >> 2) << 3) + ((lane >> 5) << 2) + (v & 3);
+                if (row < R) o[(int64_t)row * h + p] = acc[m][j][v];
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
-dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s);
 
 bool thin_fast_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt) {
     return dt == DAD_BF16 && r % 8 == 0 && h_in % tn::PW == 0 && h_out % tn::PW == 0 && N >= 256 &&
@@ -325,8 +558,14 @@ bool thin_fast_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt) {
 
 // Row split of thin_tn: enough workgroups to fill the chip twice over, while the fp32 partials
 // (splits * h * r * 4 bytes, written and read once) stay a few percent of the factor read.
+// Column-slice width of thin_tn.  256-column slices halve the re-reads of V but measured no faster.
+int thin_tn_pw(int64_t h) {
+    (void)h;
+    return 128;
+}
+
 SplitPlan thin_tn_split(int64_t N, int64_t h, int r) {
-    const int64_t slices = h / tn::PW;
+    const int64_t slices = h / thin_tn_pw(h);
     int64_t want = 512 / slices;  // two co-resident workgroups per CU in one round: no tail
     const int64_t cap_traffic = (int64_t)(0.08 * (double)N * 2.0 / (4.0 * r)) + 1;  // partials <= ~8% + 8%
     if (want > cap_traffic) want = cap_traffic;
@@ -363,11 +602,84 @@ dad_status fast_thin_nn(const void* X, const float* Pt, void* out, int64_t N, in
     return DAD_OK;
 }
 
+bool thin_dma_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt) {
+    return thin_fast_ok(N, h_in, h_out, r, dt) && N % 256 == 0 && h_in % nn::BK == 0 && h_out % nn::BK == 0;
+}
+
+dad_status launch_panel_init(const float* G0, void* Gb, void* Ub, int64_t h_in, int64_t h_out, int r, int* hdr,
+                             hipStream_t s) {
+    const int rp = r <= 32 ? 32 : 64;
+    int64_t n = (int64_t)rp * h_out;
+    if ((int64_t)(rp - r) * h_in > n) n = (int64_t)(rp - r) * h_in;
+    ProfScope prof(KID_FILL, s);
+    hipLaunchKernelGGL(k_panel_init, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, G0, (bf16_t*)Gb, (bf16_t*)Ub, h_in,
+                       h_out, r, rp, hdr);
+    DAD_LAUNCH_CHECK();
+    return DAD_OK;
+}
+
+template <int RP, int W, int NS>
+static dad_status dma_thin_nn_cfg(const void* X, const void* Pb, void* out, int64_t N, int64_t h, int r, hipStream_t s) {
+    const int lds = NS * (32 * W * 128 + RP * 128);
+    static bool attr_set = false;
+    if (!attr_set) {
+        DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_thin_nn_bf16_dma<RP, W, NS>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((k_thin_nn_bf16_dma<RP, W, NS>), dim3((unsigned)(N / (32 * W))), dim3(64 * W), lds, s,
+                       (const bf16_t*)X, (const bf16_t*)Pb, (bf16_t*)out, N, (int)h, r);
+    DAD_LAUNCH_CHECK();
+    return DAD_OK;
+}
+
+dad_status dma_thin_nn(const void* X, const void* Pb, void* out, int64_t N, int64_t h, int r, hipStream_t s) {
+    ProfScope prof(KID_THIN_NN_BF16, s);
+    static int cfg = -1;
+    if (cfg < 0) { const char* e = getenv("DAD_NN_CFG"); cfg = e ? atoi(e) : 0; }
+#define DAD_NN_GO(W, NS) (r <= 32 ? dma_thin_nn_cfg<32, W, NS>(X, Pb, out, N, h, r, s) : dma_thin_nn_cfg<64, W, NS>(X, Pb, out, N, h, r, s))
+    switch (cfg) {
+        case 1: return DAD_NN_GO(8, 4);
+        case 2: return DAD_NN_GO(4, 3);
+        case 3: return DAD_NN_GO(4, 4);
+        case 4: return DAD_NN_GO(4, 6);
+        case 5: return DAD_NN_GO(2, 4);
+        default: return DAD_NN_GO(8, 3);
+    }
+#undef DAD_NN_GO
+}
+
 dad_status fast_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp, int64_t N, int64_t h,
-                        int r, hipStream_t s) {
+                        int r, void* out_bf16, hipStream_t s) {
     dim3 grid((unsigned)(h / tn::PW), (unsigned)sp.splits);
     float* dst = sp.splits == 1 ? out_t : partials;
-    {
+    if ((r == 16 || r == 32 || r == 64) && N % tn::BK == 0 && sp.chunk % tn::BK == 0) {
+        ProfScope prof(KID_THIN_TN_BF16, s);
+        const int pw = thin_tn_pw(h);
+        const int lds = 3 * (tn::BK * pw * 2 + tn::BK * r * 2 + 256);
+        dim3 g2((unsigned)(h / pw), (unsigned)sp.splits);
+#define DAD_TN_LAUNCH(RR, PP)                                                                                         \
+    do {                                                                                                              \
+        static bool attr_set = false;                                                                                 \
+        if (!attr_set) {                                                                                              \
+            DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_thin_tn_bf16_dma<RR, PP>),               \
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds));                        \
+            attr_set = true;                                                                                          \
+        }                                                                                                             \
+        hipLaunchKernelGGL((k_thin_tn_bf16_dma<RR, PP>), g2, dim3(256), lds, s, (const bf16_t*)X, (const bf16_t*)V,   \
+                           dst, N, (int)h, sp.chunk);                                                                 \
+    } while (0)
+        if (pw == 128) {
+            if (r == 16) DAD_TN_LAUNCH(16, 128);
+            else if (r == 32) DAD_TN_LAUNCH(32, 128);
+            else DAD_TN_LAUNCH(64, 128);
+        } else {
+            if (r == 16) DAD_TN_LAUNCH(16, 256);
+            else if (r == 32) DAD_TN_LAUNCH(32, 256);
+            else DAD_TN_LAUNCH(64, 256);
+        }
+#undef DAD_TN_LAUNCH
+    } else {
     ProfScope prof(KID_THIN_TN_BF16, s);
     if (r <= 32) {
         const int lds = 2 * (tn::XTILEB + tn::BK * 64);
@@ -380,7 +692,8 @@ dad_status fast_thin_tn(const void* X, const void* V, float* out_t, float* parti
     }
     }
     DAD_LAUNCH_CHECK();
-    if (sp.splits > 1) return reduce_slabs(partials, out_t, (int64_t)r * h, sp.splits, s);
+    if (sp.splits > 1) return reduce_slabs(partials, out_t, (int64_t)r * h, sp.splits, s, out_bf16);
+    if (out_bf16) return reduce_slabs(out_t, out_t, (int64_t)r * h, 1, s, out_bf16);  // copy only
     return DAD_OK;
 }
 
