@@ -437,30 +437,42 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16(const bf16_t* __restrict__
 // of three slots, so two tiles per workgroup are always in flight and two workgroups share a CU.
 // The swizzle of the X tile is applied on the global side, as in the rebuild kernel.
 // ------------------------------------------------------------------------------------------------
-template <int R, int PW>
+template <int R, int PW, int BK>
 __global__ __launch_bounds__(256) void k_thin_tn_bf16_dma(const bf16_t* __restrict__ X, const bf16_t* __restrict__ V,
                                                           float* __restrict__ part, int64_t N, int h,
-                                                          int64_t chunk_rows) {
+                                                          int64_t chunk_rows, int strips, int splits) {
     constexpr int JT = R > 32 ? 2 : 1;
     constexpr int MT = PW / 128;                  // 32-column tiles per wave
     constexpr int XROWB = PW * 2;
-    constexpr int XTILEB = tn::BK * XROWB;
+    constexpr int XTILEB = BK * XROWB;
     constexpr int XL = XTILEB / 1024 / 4;         // X loads per wave per tile
     constexpr int RPL = 1024 / XROWB;             // tile rows covered by one load
     constexpr int CPR = PW / 8;                   // 16-byte chunks per row
     constexpr int VROWB = R * 2;
-    constexpr int VTILEB = tn::BK * VROWB;
+    constexpr int VTILEB = BK * VROWB;
     constexpr int VSLOT = VTILEB + 256;  // R = 16: fragment reads of the unused columns 16..31 run past the tile
     constexpr int STAGEB = XTILEB + VSLOT;
     constexpr int NS = 3;
-    constexpr int VL = R == 64 ? 2 : 1;  // V loads per wave per tile (R = 16: waves 2, 3 repeat waves 0, 1)
+    constexpr int VP = VTILEB / 1024;             // 1 KiB pieces of the V tile
+    constexpr int VL = VP > 4 ? VP / 4 : 1;       // V loads per wave per tile (fewer pieces than waves: repeats)
     constexpr int LOADS = XL + VL;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int p0 = blockIdx.x * PW;
-    const int64_t nbeg = (int64_t)blockIdx.y * chunk_rows;
+    // Workgroups are handed to the eight XCDs round-robin by their linear index.  All column strips
+    // of one row chunk go to the same XCD, so that the chunk of V they share is fetched into one L2.
+    int strip, split;
+    if ((splits & 7) == 0) {
+        const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+        split = xcd + 8 * (q / strips);
+        strip = q % strips;
+    } else {
+        strip = blockIdx.x % strips;
+        split = blockIdx.x / strips;
+    }
+    const int p0 = strip * PW;
+    const int64_t nbeg = (int64_t)split * chunk_rows;
     const int64_t nend = (nbeg + chunk_rows < N) ? nbeg + chunk_rows : N;
-    const int nk = (int)((nend - nbeg) / tn::BK);
+    const int nk = (int)((nend - nbeg) / BK);
 
     // X: load i of this wave covers tile rows (wave*XL + i)*RPL .. ; lane -> row += lane/CPR, LDS chunk lane%CPR
     const char* gx[XL];
@@ -475,10 +487,10 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16_dma(const bf16_t* __restri
     int vi[VL];
 #pragma unroll
     for (int i = 0; i < VL; ++i) {
-        vi[i] = R == 16 ? (wave & 1) : (R == 32 ? wave : 2 * wave + i);
+        vi[i] = (wave * VL + i) % VP;
         gv[i] = reinterpret_cast<const char*>(V + nbeg * R) + vi[i] * 1024 + lane * 16;
     }
-    const int64_t adv_x = (int64_t)tn::BK * h * 2;
+    const int64_t adv_x = (int64_t)BK * h * 2;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
 
     auto issue = [&](int stage) {
@@ -518,7 +530,7 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16_dma(const bf16_t* __restri
         const char* xb = smem + slot * STAGEB;
         const char* vb = xb + XTILEB;
 #pragma unroll
-        for (int ks = 0; ks < tn::BK / 16; ++ks) {
+        for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 fv[JT];
 #pragma unroll
             for (int j = 0; j < JT; ++j) fv[j] = tn_frag<false>(vb, VROWB, j * 32, ks * 16, lane);
@@ -533,7 +545,7 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16_dma(const bf16_t* __restri
         slot = slot == NS - 1 ? 0 : slot + 1;
     }
 
-    float* o = part + (int64_t)blockIdx.y * R * h;
+    float* o = part + (int64_t)split * R * h;
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
         const int p = p0 + (wave * MT + m) * 32 + (lane & 31);
@@ -556,17 +568,15 @@ bool thin_fast_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt) {
            h_in <= (1 << 20) && h_out <= (1 << 20);
 }
 
-// Row split of thin_tn: enough workgroups to fill the chip twice over, while the fp32 partials
-// (splits * h * r * 4 bytes, written and read once) stay a few percent of the factor read.
-// Column-slice width of thin_tn.  256-column slices halve the re-reads of V but measured no faster.
-int thin_tn_pw(int64_t h) {
-    (void)h;
-    return 128;
-}
+// Column-strip width of thin_tn.  512-byte row segments use the HBM channels better than 256-byte
+// ones when the row pitch is a power of two, and halve the re-reads of V.
+int thin_tn_pw(int64_t h) { return h % 256 == 0 ? 256 : 128; }
 
+// Row split of thin_tn: about one workgroup per CU, while the fp32 partials (splits * h * r * 4
+// bytes, written and read once) stay a few percent of the factor read.
 SplitPlan thin_tn_split(int64_t N, int64_t h, int r) {
     const int64_t slices = h / thin_tn_pw(h);
-    int64_t want = 512 / slices;  // two co-resident workgroups per CU in one round: no tail
+    int64_t want = 256 / slices;  // one workgroup per CU in a single round (measured faster than two)
     const int64_t cap_traffic = (int64_t)(0.08 * (double)N * 2.0 / (4.0 * r)) + 1;  // partials <= ~8% + 8%
     if (want > cap_traffic) want = cap_traffic;
     const int64_t cap_rows = ceil_div(N, 4 * tn::BK);
@@ -635,18 +645,8 @@ static dad_status dma_thin_nn_cfg(const void* X, const void* Pb, void* out, int6
 
 dad_status dma_thin_nn(const void* X, const void* Pb, void* out, int64_t N, int64_t h, int r, hipStream_t s) {
     ProfScope prof(KID_THIN_NN_BF16, s);
-    static int cfg = -1;
-    if (cfg < 0) { const char* e = getenv("DAD_NN_CFG"); cfg = e ? atoi(e) : 0; }
-#define DAD_NN_GO(W, NS) (r <= 32 ? dma_thin_nn_cfg<32, W, NS>(X, Pb, out, N, h, r, s) : dma_thin_nn_cfg<64, W, NS>(X, Pb, out, N, h, r, s))
-    switch (cfg) {
-        case 1: return DAD_NN_GO(8, 4);
-        case 2: return DAD_NN_GO(4, 3);
-        case 3: return DAD_NN_GO(4, 4);
-        case 4: return DAD_NN_GO(4, 6);
-        case 5: return DAD_NN_GO(2, 4);
-        default: return DAD_NN_GO(8, 3);
-    }
-#undef DAD_NN_GO
+    if (r <= 32) return dma_thin_nn_cfg<32, 8, 3>(X, Pb, out, N, h, r, s);
+    return dma_thin_nn_cfg<64, 8, 3>(X, Pb, out, N, h, r, s);
 }
 
 dad_status fast_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp, int64_t N, int64_t h,
@@ -656,27 +656,28 @@ dad_status fast_thin_tn(const void* X, const void* V, float* out_t, float* parti
     if ((r == 16 || r == 32 || r == 64) && N % tn::BK == 0 && sp.chunk % tn::BK == 0) {
         ProfScope prof(KID_THIN_TN_BF16, s);
         const int pw = thin_tn_pw(h);
-        const int lds = 3 * (tn::BK * pw * 2 + tn::BK * r * 2 + 256);
-        dim3 g2((unsigned)(h / pw), (unsigned)sp.splits);
-#define DAD_TN_LAUNCH(RR, PP)                                                                                         \
+        const int bk = pw == 128 ? 64 : 32;
+        const int lds = 3 * (bk * pw * 2 + bk * r * 2 + 256);
+        const int strips = (int)(h / pw);
+#define DAD_TN_LAUNCH(RR, PP, BB)                                                                                     \
     do {                                                                                                              \
         static bool attr_set = false;                                                                                 \
         if (!attr_set) {                                                                                              \
-            DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_thin_tn_bf16_dma<RR, PP>),               \
+            DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_thin_tn_bf16_dma<RR, PP, BB>),           \
                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds));                        \
             attr_set = true;                                                                                          \
         }                                                                                                             \
-        hipLaunchKernelGGL((k_thin_tn_bf16_dma<RR, PP>), g2, dim3(256), lds, s, (const bf16_t*)X, (const bf16_t*)V,   \
-                           dst, N, (int)h, sp.chunk);                                                                 \
+        hipLaunchKernelGGL((k_thin_tn_bf16_dma<RR, PP, BB>), dim3((unsigned)(strips * sp.splits)), dim3(256), lds, s, \
+                           (const bf16_t*)X, (const bf16_t*)V, dst, N, (int)h, sp.chunk, strips, sp.splits);          \
     } while (0)
         if (pw == 128) {
-            if (r == 16) DAD_TN_LAUNCH(16, 128);
-            else if (r == 32) DAD_TN_LAUNCH(32, 128);
-            else DAD_TN_LAUNCH(64, 128);
+            if (r == 16) DAD_TN_LAUNCH(16, 128, 64);
+            else if (r == 32) DAD_TN_LAUNCH(32, 128, 64);
+            else DAD_TN_LAUNCH(64, 128, 64);
         } else {
-            if (r == 16) DAD_TN_LAUNCH(16, 256);
-            else if (r == 32) DAD_TN_LAUNCH(32, 256);
-            else DAD_TN_LAUNCH(64, 256);
+            if (r == 16) DAD_TN_LAUNCH(16, 256, 32);
+            else if (r == 32) DAD_TN_LAUNCH(32, 256, 32);
+            else DAD_TN_LAUNCH(64, 256, 32);
         }
 #undef DAD_TN_LAUNCH
     } else {
