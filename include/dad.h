@@ -90,8 +90,9 @@ size_t dad_compress_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, int 
  * G (h_out x r) is replaced by an orthonormal basis of
  *     M^T M G = Delta^T ( A ( A^T ( Delta G ) ) ),
  * evaluated right to left so that neither M nor A A^T is formed; the
- * orthonormalisation (CholeskyQR2) stands in for the peeling of Eq. 7.  Then
- * the left factor P = A^T (Delta G) is formed with the singular values left
+ * orthonormalisation (Cholesky QR: one round for the intermediate iterates,
+ * of which only the span is used, two rounds for the last one) stands in for
+ * the peeling of Eq. 7.  Then the left factor P = A^T (Delta G) is formed with the singular values left
  * inside it (footnote to Section 3.3.1), so that  M ~ P G^T = M G G^T.
  *
  *   A, D      device, N x h_in and N x h_out, element type dt
@@ -103,8 +104,10 @@ size_t dad_compress_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, int 
  *   workspace device, ws_bytes >= dad_compress_workspace_bytes(...)
  * Outputs have the factor layout (one row per component), so S such pairs can
  * be stacked and compressed again (Algorithm 1).  For dt = DAD_BF16 the two
- * N x r intermediates are rounded to bf16 between contractions; everything of
- * size h x r or r x r stays fp32 (r x r factorisation in fp64).
+ * N x r intermediates are rounded to bf16 between contractions, and on the
+ * large aligned shapes the h x r panels enter the next contraction rounded to
+ * bf16 as well; the panels themselves, the outputs and everything r x r stay
+ * fp32 (Gram matrix and r x r factorisation in fp64).
  * If the iterate loses rank (r > rank(M)) the outputs are unspecified and
  * DAD_ERR_NUMERIC is latched for dad_poll_numeric_status.
  */

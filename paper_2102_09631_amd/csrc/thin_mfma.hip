@@ -621,7 +621,7 @@ dad_status launch_panel_init(const float* G0, void* Gb, void* Ub, int64_t h_in, 
     const int rp = r <= 32 ? 32 : 64;
     int64_t n = (int64_t)rp * h_out;
     if ((int64_t)(rp - r) * h_in > n) n = (int64_t)(rp - r) * h_in;
-    ProfScope prof(KID_FILL, s);
+    ProfScope prof(KID_PANEL_INIT, s);
     hipLaunchKernelGGL(k_panel_init, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, G0, (bf16_t*)Gb, (bf16_t*)Ub, h_in,
                        h_out, r, rp, hdr);
     DAD_LAUNCH_CHECK();
