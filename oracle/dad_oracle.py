@@ -20,6 +20,9 @@ Pins (see tests/test_oracle_*.py):
   block_spi*           three unrelated routes agree; exact truncated SVD when
                        r >= rank(M); Eckart-Young bound and Pythagoras otherwise
   sequential_spi       converges to numpy's truncated SVD on a planted spectrum
+  rank_dad             stacked pairs represent the sum of the sites' estimates (brute
+                       force); exact global gradient when its rank fits both budgets;
+                       converged aggregator step = truncated SVD of that sum
 No function here is "parity unpinned".
 """
 from __future__ import annotations
@@ -225,6 +228,26 @@ def sequential_spi(A, Delta, g0t, n_iter):
         gs.append(g)
         sig.append(sigma)
     return Q, sG
+
+
+def rank_dad(A_sites, D_sites, G0t_sites, G0t_agg, n_iter):
+    """Algorithm 1 for one layer: rank reduction at every site, then once more at the aggregator.
+
+    Site s reduces its own factor pair to r rows (Algorithm 2, here block_spi with the site's
+    start matrix G0t_sites[s]).  The aggregator concatenates the sites' reduced pairs along
+    the row dimension - the r-row pairs have the layout of factors, and the stacked pair
+    represents sum_s Pt_s^T Gt_s exactly - and reduces the S*r rows to r_agg rows with its own
+    start matrix G0t_agg (r_agg = its number of rows).  Every site then rebuilds the same
+    estimate Pt_hat^T Gt_hat of the global gradient sum_s A_s^T Delta_s.
+
+    Returns (Pt_hat, Gt_hat, pairs) with pairs = [(Pt_s, Gt_s)] as sent by the sites.
+    """
+    if not (len(A_sites) == len(D_sites) == len(G0t_sites)):
+        raise ValueError("one start matrix per site")
+    pairs = [block_spi(a, d, g0, n_iter) for a, d, g0 in zip(A_sites, D_sites, G0t_sites)]
+    P_stack, G_stack = stack_factors([p for p, _ in pairs], [g for _, g in pairs])
+    Pt_hat, Gt_hat = block_spi(P_stack, G_stack, G0t_agg, n_iter)
+    return Pt_hat, Gt_hat, pairs
 
 
 # --------------------------------------------------------------------------

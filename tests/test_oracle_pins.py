@@ -240,3 +240,87 @@ def test_stacked_rank_pairs_are_factors_again():
     Pst, Gst = O.stack_factors([p for p, _ in pairs], [g for _, g in pairs])
     assert Pst.shape == (6, 12) and Gst.shape == (6, 9)
     assert np.allclose(O.full_grad(Pst, Gst), sum(O.rank_r_grad(p, g) for p, g in pairs), rtol=1e-12)
+
+
+# ---------------------------------------------------------------- Algorithm 1 (two-level rank-dAD)
+
+def _site_factors(rng, S, b, h_in, h_out, row_basis=None, col_basis=None):
+    """Per-site factor pairs; with bases given, every site's gradient lives in their spans."""
+    A_sites, D_sites = [], []
+    for _ in range(S):
+        A = rng.standard_normal((b, h_in))
+        D = rng.standard_normal((b, h_out))
+        if row_basis is not None:
+            A = rng.standard_normal((b, row_basis.shape[0])) @ row_basis
+        if col_basis is not None:
+            D = rng.standard_normal((b, col_basis.shape[0])) @ col_basis
+        A_sites.append(A)
+        D_sites.append(D)
+    return A_sites, D_sites
+
+
+def test_rank_dad_is_exact_when_the_global_gradient_fits_both_budgets():
+    """If every site's gradient, and their sum, has rank <= r, both reductions lose nothing and
+    Algorithm 1 returns the pooled-batch gradient of Eq. 4 (computed here by brute force on the
+    concatenated batch, without any of the oracle's iteration code)."""
+    rng = np.random.default_rng(31)
+    S, b, h_in, h_out, r = 4, 9, 14, 11, 3
+    col_basis = rng.standard_normal((r, h_out))        # all deltas share a 3-dimensional row space
+    A_sites, D_sites = _site_factors(rng, S, b, h_in, h_out, col_basis=col_basis)
+    G0s = [rng.standard_normal((r, h_out)) for _ in range(S)]
+    Pt, Gt, pairs = O.rank_dad(A_sites, D_sites, G0s, rng.standard_normal((r, h_out)), 2)
+    assert Pt.shape == (r, h_in) and Gt.shape == (r, h_out) and len(pairs) == S
+    A_all, D_all = np.vstack(A_sites), np.vstack(D_sites)
+    M = np.einsum("np,nq->pq", A_all, D_all)
+    assert np.linalg.matrix_rank(M) == r
+    assert O.rel_fro(O.rank_r_grad(Pt, Gt), M) < 1e-10
+    # each site's message is exact as well
+    for (p, g), a, d in zip(pairs, A_sites, D_sites):
+        assert O.rel_fro(O.rank_r_grad(p, g), a.T @ d) < 1e-10
+
+
+def test_rank_dad_aggregator_with_full_budget_returns_sum_of_site_estimates():
+    """An aggregator budget of S*r rows keeps everything the sites sent: the result is
+    sum_s P_s G_s^T, whatever was lost at the sites; and that sum is what the sites lost
+    relative to the true gradient, no more (triangle inequality on the residuals)."""
+    rng = np.random.default_rng(32)
+    S, b, h_in, h_out, r = 3, 12, 20, 16, 2
+    A_sites, D_sites = _site_factors(rng, S, b, h_in, h_out)
+    G0s = [rng.standard_normal((r, h_out)) for _ in range(S)]
+    Pt, Gt, pairs = O.rank_dad(A_sites, D_sites, G0s, rng.standard_normal((S * r, h_out)), 2)
+    site_sum = sum(p.T @ g for p, g in pairs)
+    assert O.rel_fro(O.rank_r_grad(Pt, Gt), site_sum) < 1e-10
+    M = sum(a.T @ d for a, d in zip(A_sites, D_sites))
+    lost = sum(np.linalg.norm(a.T @ d - p.T @ g) for (p, g), a, d in zip(pairs, A_sites, D_sites))
+    assert np.linalg.norm(M - site_sum) <= lost * (1 + 1e-12)
+
+
+def test_rank_dad_converged_aggregator_is_truncated_svd_of_the_sites_sum():
+    """With many iterations and a spectral gap the aggregator step is the best rank-r
+    approximation (numpy SVD) of sum_s P_s G_s^T, and its residual is the Eckart-Young value."""
+    rng = np.random.default_rng(33)
+    S, b, h_in, h_out, r = 3, 10, 18, 15, 2
+    A_sites, D_sites = [], []
+    for _ in range(S):
+        A_sites.append(rng.standard_normal((b, h_in)))
+        D_sites.append(rng.standard_normal((b, h_out)) * (0.4 ** np.arange(b))[:, None])
+    G0s = [rng.standard_normal((r, h_out)) for _ in range(S)]
+    Pt, Gt, pairs = O.rank_dad(A_sites, D_sites, G0s, rng.standard_normal((r, h_out)), 80)
+    site_sum = sum(p.T @ g for p, g in pairs)
+    U, s, Vt = np.linalg.svd(site_sum)
+    best = (U[:, :r] * s[:r]) @ Vt[:r]
+    est = O.rank_r_grad(Pt, Gt)
+    assert O.rel_fro(est, best) < 1e-8
+    assert abs(np.linalg.norm(site_sum - est) - np.sqrt(np.sum(s[r:] ** 2))) < 1e-8 * s[0]
+    assert np.allclose(Gt @ Gt.T, np.eye(r), atol=1e-12)
+
+
+def test_rank_dad_single_site_full_budget_is_one_level():
+    """S = 1 and an aggregator that keeps all r rows: the second reduction is the identity on
+    the estimate, so the two-level result equals the one-level one."""
+    rng = np.random.default_rng(34)
+    A = rng.standard_normal((20, 13))
+    D = rng.standard_normal((20, 10))
+    G0 = rng.standard_normal((3, 10))
+    Pt, Gt, _ = O.rank_dad([A], [D], [G0], rng.standard_normal((3, 10)), 2)
+    assert O.rel_fro(O.rank_r_grad(Pt, Gt), O.rank_r_grad(*O.block_spi(A, D, G0, 2))) < 1e-10
