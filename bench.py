@@ -39,6 +39,12 @@ def parse():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="gpt2_medium_stack")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mode", default="one_level", choices=["one_level", "two_level"],
+                    help="two_level: Algorithm 1 (per-site reduction, stack of the pairs, aggregator reduction, rebuild)")
+    ap.add_argument("--no-graphs", action="store_true",
+                    help="two_level: launch eagerly instead of replaying one captured HIP graph per layer")
+    ap.add_argument("--site-streams", type=int, default=8,
+                    help="two_level: HIP streams (default priority) the independent per-site reductions are spread over")
     return ap.parse_args()
 
 
@@ -61,6 +67,221 @@ def kernel_model(name, N, h_in, h_out, r, es, which, bf16=True):
     return None, 0.0
 
 
+def two_level(args, w, dad, W, torch, np, dev):
+    """Algorithm 1 per layer: every site reduces its own b rows to r (S calls), the S*r stacked
+    rows are reduced again at the aggregator, the estimate P^T G is rebuilt.  `value` is the time
+    per layer; the site-level reductions stream every factor byte 2n+1 times, as the one-level
+    path does, so `site_compress_GBps` is comparable with `compress_GBps` of the default mode."""
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    es = 2 if w.dtype == "bf16" else 4
+    N, r, n_iter, S, b = w.N, w.rank, w.n_iter, w.sites, w.rows_per_site
+    layers = w.all_layers()
+    nl = len(layers)
+    total_bytes = sum(N * (hi + ho) * es for _, hi, ho in layers)
+    resident = layers if total_bytes < 150e9 else layers[:len(w.shapes)]
+    sites = {li: W.device_factors(w, li, hi, ho, device=dev) for li, hi, ho in resident}
+    def factors_of(li):
+        return sites[li] if li in sites else sites[li % len(w.shapes)]
+    G0s = {li: [torch.from_numpy(W.host_start_matrix(w, 1000 + 64 * li + s, ho)).to(dev) for s in range(S)]
+           for li, _, ho in layers}
+    G0a = {li: torch.from_numpy(W.host_start_matrix(w, 5000 + li, ho)).to(dev) for li, _, ho in layers}
+    Ps = {sh: [torch.empty((r, sh[0]), dtype=torch.float32, device=dev) for _ in range(S)] for sh in w.shapes}
+    Gs = {sh: [torch.empty((r, sh[1]), dtype=torch.float32, device=dev) for _ in range(S)] for sh in w.shapes}
+    Pst = {sh: torch.empty((S * r, sh[0]), dtype=torch.float32, device=dev) for sh in w.shapes}
+    Gst = {sh: torch.empty((S * r, sh[1]), dtype=torch.float32, device=dev) for sh in w.shapes}
+    Pt = {li: torch.empty((r, hi), dtype=torch.float32, device=dev) for li, hi, _ in layers}
+    Gt = {li: torch.empty((r, ho), dtype=torch.float32, device=dev) for li, _, ho in layers}
+    G_hat = {sh: torch.empty(sh, dtype=torch.float32, device=dev) for sh in w.shapes}
+    n_str = max(1, min(args.site_streams, S))
+    ws_s = [torch.empty(max(dad.compress_workspace_bytes(b, hi, ho, r, tdt) for _, hi, ho in layers),
+                        dtype=torch.uint8, device=dev) for _ in range(n_str)]
+    side = [torch.cuda.Stream(device=dev) for _ in range(n_str)] if n_str > 1 else []
+    ws_a = torch.empty(max(dad.compress_workspace_bytes(S * r, hi, ho, r, torch.float32) for _, hi, ho in layers),
+                       dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    PH = ("site_compress", "stack_pairs", "agg_compress", "rebuild_rank")
+
+    def site_pass(li, sh, As, Ds):
+        """The S independent site reductions, site s on stream s mod n_str (each with its own workspace)."""
+        if not side:
+            for s_ in range(S):
+                dad.compress_rank(As[s_], Ds[s_], r, n_iter, G0s[li][s_], Pt=Ps[sh][s_], Gt=Gs[sh][s_], workspace=ws_s[0])
+            return
+        main = torch.cuda.current_stream()
+        fork = torch.cuda.Event()
+        fork.record(main)
+        for k, st in enumerate(side):
+            st.wait_event(fork)
+            with torch.cuda.stream(st):
+                for s_ in range(k, S, n_str):
+                    dad.compress_rank(As[s_], Ds[s_], r, n_iter, G0s[li][s_], Pt=Ps[sh][s_], Gt=Gs[sh][s_],
+                                      workspace=ws_s[k])
+        for st in side:
+            main.wait_stream(st)
+
+    graphs = {}
+
+    def step(events=None, replay=False):
+        if replay:
+            for li, _, _ in layers:
+                graphs[li].replay()
+            return
+        for li, hi, ho in layers:
+            sh = (hi, ho)
+            As, Ds = factors_of(li)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)] if events is not None else None
+            if ev: ev[0].record()
+            site_pass(li, sh, As, Ds)
+            if ev: ev[1].record()
+            dad.stack_factors(Ps[sh], Gs[sh], A_out=Pst[sh], D_out=Gst[sh])
+            if ev: ev[2].record()
+            dad.compress_rank(Pst[sh], Gst[sh], r, n_iter, G0a[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_a)
+            if ev: ev[3].record()
+            dad.reconstruct_grad(Pt[li], Gt[li], G=G_hat[sh])
+            if ev: ev[4].record()
+            if ev: events.append(ev)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    if any(dad.poll_numeric_status(x) != dad.DAD_OK for x in ws_s + [ws_a]):
+        print("bench.py: numerical breakdown latched during warm-up", file=sys.stderr)
+        sys.exit(1)
+    # The path is launch bound at these sizes (about 190 small launches per layer), so the timed
+    # region replays one captured HIP graph per layer; phase times come from an eager pass after it.
+    use_graphs = not args.no_graphs
+    if use_graphs:
+        if args.warmup == 0:
+            step()   # function attributes are set on first use; that must not happen under capture
+            torch.cuda.synchronize()
+        def one_layer(li, hi, ho):
+            sh = (hi, ho)
+            As, Ds = factors_of(li)
+            site_pass(li, sh, As, Ds)
+            dad.stack_factors(Ps[sh], Gs[sh], A_out=Pst[sh], D_out=Gst[sh])
+            dad.compress_rank(Pst[sh], Gst[sh], r, n_iter, G0a[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_a)
+            dad.reconstruct_grad(Pt[li], Gt[li], G=G_hat[sh])
+        for li, hi, ho in layers:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                one_layer(li, hi, ho)
+            graphs[li] = g
+        step(replay=True)
+        torch.cuda.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(replay=use_graphs)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    events = []
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    dad.profile_reset()
+    dad.profile_enable(True)
+    prof_steps = 1   # one repeat is enough here: a step has thousands of launches, each with two events
+    for _ in range(prof_steps):
+        step()
+    torch.cuda.synchronize()
+    dad.profile_enable(False)
+    kern = dad.profile_read()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    phase_ms = dict.fromkeys(PH, 0.0)
+    for ev in events:
+        for i, ph in enumerate(PH):
+            phase_ms[ph] += ev[i].elapsed_time(ev[i + 1])
+    phase_ms = {k: v / args.steps for k, v in phase_ms.items()}
+    bytes_site = sum((2 * n_iter + 1.0) * N * (hi + ho) * es for _, hi, ho in layers)
+    bytes_agg = sum((2 * n_iter + 1.0) * S * r * (hi + ho) * 4 for _, hi, ho in layers)
+
+    # site-level thin kernels: the S calls together stream each factor once per contraction
+    work = {}
+    for name in kern:
+        tot = 0.0
+        for _, hi, ho in layers:
+            if name in ("k_thin_nn_bf16", "k_thin_nn"):
+                parts = [(ho, n_iter + 1), (hi, n_iter)]
+            elif name in ("k_thin_tn_bf16", "k_thin_tn"):
+                parts = [(hi, n_iter + 1), (ho, n_iter)]
+            else:
+                continue
+            rows, e = (N, es) if (name.endswith("bf16") or w.dtype != "bf16") else (S * r, 4)
+            if w.dtype != "bf16":   # fp32 workloads: site and aggregator calls share the guarded kernels
+                rows = N + S * r
+            tot += sum(cnt * float(rows) * h * e for h, cnt in parts)
+        if tot:
+            work[name] = tot
+    roof_all = {}
+    for name, (ms, launches) in kern.items():
+        entry = {"ms_per_step": ms / prof_steps, "launches_per_step": launches / prof_steps,
+                 "avg_us": ms * 1e3 / launches}
+        if name in work:
+            rate = work[name] * prof_steps / (ms * 1e-3)
+            entry.update(bound="hbm", achieved=rate / 1e9, peak=PEAK_HBM_GBPS, unit="GB/s",
+                         frac=rate / 1e9 / PEAK_HBM_GBPS)
+        roof_all[name] = entry
+    dominant = max(work, key=lambda k: kern[k][0])
+    roofline = {"kernel": dominant}
+    roofline.update({k: roof_all[dominant].get(k) for k in ("bound", "achieved", "peak", "unit", "frac")})
+    roofline["avg_us"] = roof_all[dominant]["avg_us"]
+    roofline["traffic"] = None
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import dad_oracle as O
+        li, hi, ho = min(layers, key=lambda t: t[1] * t[2])
+        sh = (hi, ho)
+        As, Ds = factors_of(li)
+        A_h = [a.float().cpu().numpy().astype(np.float64) for a in As]
+        D_h = [d.float().cpu().numpy().astype(np.float64) for d in Ds]
+        c0 = time.perf_counter()
+        Pt_ref, Gt_ref, _ = O.rank_dad(A_h, D_h, [g.cpu().numpy() for g in G0s[li]], G0a[li].cpu().numpy(), n_iter)
+        c1 = time.perf_counter()
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            threads = os.cpu_count()
+        site_pass(li, sh, As, Ds)
+        dad.stack_factors(Ps[sh], Gs[sh], A_out=Pst[sh], D_out=Gst[sh])
+        dad.compress_rank(Pst[sh], Gst[sh], r, n_iter, G0a[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_a)
+        dad.reconstruct_grad(Pt[li], Gt[li], G=G_hat[sh])
+        torch.cuda.synchronize()
+        tol = 2e-2 if w.dtype == "bf16" else 1e-5
+        e = O.rel_fro(G_hat[sh].cpu().numpy(), O.rank_r_grad(Pt_ref, Gt_ref))
+        cpu = {"value": (c1 - c0) * 1e6, "unit": "us/layer", "cores": int(threads), "kind": "oracle",
+               "sample": f"1 of {nl} layers ({hi}x{ho}, S={S} sites of {b} rows): fp64 numpy rank_dad r={r} n={n_iter}",
+               "parity_rel_fro": {"two_level": e, "tol": tol}, "host_cpus": os.cpu_count()}
+        if not e <= tol:
+            print(f"bench.py: parity check failed: {e:.3e}", file=sys.stderr)
+            sys.exit(1)
+
+    us_layer = ms_per_step * 1e3 / nl
+    out = {
+        "metric": "rank-dAD two-level reduction us/layer (% HBM roofline)",
+        "value": us_layer, "unit": "us/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name + "/two_level", "layers": nl, "shapes": [list(s_) for s_ in w.shapes],
+                   "sites": S, "rows_per_site": b, "aggregator_rows": S * r, "rank": r, "n_iter": n_iter,
+                   "site_streams": n_str, "hip_graphs": use_graphs,
+                   "resident_layers": len(resident)},
+        "site_compress_us_per_layer": phase_ms["site_compress"] * 1e3 / nl,
+        "site_compress_GBps": bytes_site / (phase_ms["site_compress"] * 1e-3) / 1e9,
+        "site_compress_frac_of_hbm_peak": bytes_site / (phase_ms["site_compress"] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+        "agg_compress_us_per_layer": phase_ms["agg_compress"] * 1e3 / nl,
+        "agg_compress_GBps": bytes_agg / (phase_ms["agg_compress"] * 1e-3) / 1e9,
+        "stack_pairs_us_per_layer": phase_ms["stack_pairs"] * 1e3 / nl,
+        "rank_rebuild_us_per_layer": phase_ms["rebuild_rank"] * 1e3 / nl,
+        "phase_ms_per_step_eager": phase_ms,
+        "roofline": roofline,
+        "kernels": roof_all,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -81,6 +302,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     w = W.by_name(args.workload)
+    if args.mode == "two_level":
+        return two_level(args, w, dad, W, torch, np, dev)
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     es = 2 if w.dtype == "bf16" else 4
     N, r, n_iter, S, b = w.N, w.rank, w.n_iter, w.sites, w.rows_per_site

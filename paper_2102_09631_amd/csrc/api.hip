@@ -4,7 +4,9 @@
 namespace dad {
 
 // implemented in the kernel translation units
-dad_status gen_thin_nn(const void*, const float*, void*, int64_t, int64_t, int, dad_dtype, int*, hipStream_t);
+dad_status gen_thin_nn(const void*, const float*, void*, float*, SplitPlan, int64_t, int64_t, int, dad_dtype, int*,
+                       hipStream_t);
+SplitPlan gen_thin_nn_split(int64_t N, int64_t h);
 dad_status gen_thin_tn(const void*, const void*, float*, float*, SplitPlan, int64_t, int64_t, int, dad_dtype,
                        hipStream_t);
 dad_status gen_rebuild(const void*, const void*, int64_t, int64_t, int64_t, dad_dtype, float*, float*, SplitPlan,
@@ -38,8 +40,10 @@ static SplitPlan split_rows(int64_t rows, int64_t tiles, int64_t target_blocks, 
 CompressPlan plan_compress(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt) {
     CompressPlan p;
     p.fast = thin_fast_ok(N, h_in, h_out, r, dt);
-    p.tn_in = p.fast ? thin_tn_split(N, h_in, r) : split_rows(N, ceil_div(h_in, 64), 2048, 256, 32);
-    p.tn_out = p.fast ? thin_tn_split(N, h_out, r) : split_rows(N, ceil_div(h_out, 64), 2048, 256, 32);
+    p.tn_in = p.fast ? thin_tn_split(N, h_in, r) : split_rows(N, ceil_div(h_in, 64), 1024, 32, 32);
+    p.tn_out = p.fast ? thin_tn_split(N, h_out, r) : split_rows(N, ceil_div(h_out, 64), 1024, 32, 32);
+    p.nn_in = gen_thin_nn_split(N, h_in);
+    p.nn_out = gen_thin_nn_split(N, h_out);
     p.gram_blocks = gram_blocks_for(h_out);
     size_t o = 0;
     p.off_flag = o;
@@ -48,7 +52,14 @@ CompressPlan plan_compress(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dt
     o += align_up((size_t)N * r * elem_size(dt), 256);
     size_t part_in = (size_t)p.tn_in.splits * r * h_in * 4, part_out = (size_t)p.tn_out.splits * r * h_out * 4;
     p.off_part = o;
-    o += align_up(part_in > part_out ? part_in : part_out, 256);
+    size_t part_max = part_in > part_out ? part_in : part_out;
+    if (!p.fast) {  // column-split slabs of the guarded thin_nn share the region
+        const size_t nn_in = p.nn_in.splits > 1 ? (size_t)p.nn_in.splits * N * r * 4 : 0;
+        const size_t nn_out = p.nn_out.splits > 1 ? (size_t)p.nn_out.splits * N * r * 4 : 0;
+        if (nn_in > part_max) part_max = nn_in;
+        if (nn_out > part_max) part_max = nn_out;
+    }
+    o += align_up(part_max, 256);
     p.off_Ut = o;
     o += align_up((size_t)r * h_in * 4, 256);
     p.off_Yt = o;
@@ -169,16 +180,16 @@ dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_
     }
     const float* Gcur = G0;
     for (int it = 0; it < n_iter; ++it) {
-        if ((rc = launch_thin_nn(D, Gcur, V, N, h_out, r, dt, p.fast, it == 0 ? flag : nullptr, s)) != DAD_OK) return rc;  // V = Delta G
+        if ((rc = launch_thin_nn(D, Gcur, V, part, p.nn_out, N, h_out, r, dt, p.fast, it == 0 ? flag : nullptr, s)) != DAD_OK) return rc;  // V = Delta G
         if ((rc = launch_thin_tn(A, V, Ut, part, p.tn_in, N, h_in, r, dt, p.fast, nullptr, s)) != DAD_OK) return rc;   // U = A^T V
-        if ((rc = launch_thin_nn(A, Ut, V, N, h_in, r, dt, p.fast, nullptr, s)) != DAD_OK) return rc;                  // W = A U
+        if ((rc = launch_thin_nn(A, Ut, V, part, p.nn_in, N, h_in, r, dt, p.fast, nullptr, s)) != DAD_OK) return rc;                  // W = A U
         if ((rc = launch_thin_tn(D, V, Yt, part, p.tn_out, N, h_out, r, dt, p.fast, nullptr, s)) != DAD_OK) return rc; // Y = Delta^T W
         if ((rc = launch_cholqr(Yt, Gt, h_out, r, (it + 1 == n_iter) ? 2 : 1, gram, p.gram_blocks, rinv, counter, flag,
                                 nullptr, s)) != DAD_OK)
             return rc;
         Gcur = Gt;
     }
-    if ((rc = launch_thin_nn(D, Gt, V, N, h_out, r, dt, p.fast, nullptr, s)) != DAD_OK) return rc;                     // V = Delta G
+    if ((rc = launch_thin_nn(D, Gt, V, part, p.nn_out, N, h_out, r, dt, p.fast, nullptr, s)) != DAD_OK) return rc;                     // V = Delta G
     return launch_thin_tn(A, V, Pt, part, p.tn_in, N, h_in, r, dt, p.fast, nullptr, s);                                // P = A^T V
 }
 
@@ -216,10 +227,10 @@ dad_status dad_poll_numeric_status(const void* workspace, void* stream) {
 
 namespace dad {
 
-dad_status launch_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int64_t h, int r, dad_dtype dt,
-                          bool fast, int* zero_hdr, hipStream_t s) {
+dad_status launch_thin_nn(const void* X, const float* Pt, void* out, float* partials, SplitPlan sp, int64_t N,
+                          int64_t h, int r, dad_dtype dt, bool fast, int* zero_hdr, hipStream_t s) {
     if (fast) return fast_thin_nn(X, Pt, out, N, h, r, zero_hdr, s);
-    return gen_thin_nn(X, Pt, out, N, h, r, dt, zero_hdr, s);
+    return gen_thin_nn(X, Pt, out, partials, sp, N, h, r, dt, zero_hdr, s);
 }
 
 dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp, int64_t N,

@@ -11,7 +11,7 @@
 //   3. Y <- Y R^{-1} with the second factor.
 // Products of two fp32 values are exact in fp64, so the Gram matrix carries no
 // rounding beyond its final sums and CholeskyQR tolerates condition numbers far
-// beyond the fp32 limit.
+// beyond the fp32 limit.  The partials are accumulated by the fp64 matrix instruction.
 #include "dad_internal.h"
 
 namespace dad {
@@ -32,24 +32,41 @@ struct QrShared {
     int last;
 };
 
-// Threads form a 16 x 16 grid (ti, tj); thread (ti, tj) owns the entries (ti + 16a, tj + 16b),
-// a, b < NA, of every r x r matrix below (NA = 2 covers r <= 32, NA = 4 covers r <= 64).
+// In the factorisation threads form a 16 x 16 grid (ti, tj); thread (ti, tj) owns the entries
+// (ti + 16a, tj + 16b), a, b < NA, of every r x r matrix (NA = 2 covers r <= 32, NA = 4 r <= 64).
+//
+// The Gram partials are accumulated with the fp64 matrix instruction (16x16 output block, 4 columns
+// of the tile per issue): products of fp32 values are exact in fp64.  The NA*NA blocks are dealt to
+// the four waves, NA*NA/4 each; block q = wave*NBW + u covers rows 16*(q / NA), columns 16*(q % NA).
+// Operand layout: lane l supplies row l%16 of its block at tile column 4*kk + l/16; result element
+// v of lane l is entry (4v + l/16, l%16) of the block.
+typedef double f64x4 __attribute__((ext_vector_type(4)));
 
-// acc[a][b] += sum over the tile's columns of Ys[i][k] * Ys[j][k] (fp64).
 template <int NA>
-__device__ __forceinline__ void gram_of_tile(const float (*Ys)[QR_COLS + 1], double (&acc)[NA][NA]) {
-    const int t = threadIdx.x, ti = t >> 4, tj = t & 15;
-    for (int kk = 0; kk < QR_COLS; ++kk) {
-        double ya[NA], yb[NA];
+struct GramAcc {
+    static constexpr int NBW = NA * NA / 4;
+    f64x4 v[NBW];
+    __device__ __forceinline__ void zero() {
 #pragma unroll
-        for (int a = 0; a < NA; ++a) {
-            ya[a] = (double)Ys[ti + 16 * a][kk];
-            yb[a] = (double)Ys[tj + 16 * a][kk];
+        for (int u = 0; u < NBW; ++u) v[u] = f64x4{0.0, 0.0, 0.0, 0.0};
+    }
+};
+
+template <int NA>
+__device__ __forceinline__ void gram_of_tile(const float (*Ys)[QR_COLS + 1], GramAcc<NA>& acc) {
+    constexpr int NBW = GramAcc<NA>::NBW;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int li = lane & 15, lk = lane >> 4;
+    const int a = (wave * NBW) / NA;  // the blocks of one wave share their row index
+#pragma unroll 4
+    for (int kk = 0; kk < QR_COLS / 4; ++kk) {
+        const double ya = (double)Ys[16 * a + li][4 * kk + lk];
+#pragma unroll
+        for (int u = 0; u < NBW; ++u) {
+            const int b = (wave * NBW + u) % NA;
+            const double yb = (double)Ys[16 * b + li][4 * kk + lk];
+            acc.v[u] = __builtin_amdgcn_mfma_f64_16x16x4f64(ya, yb, acc.v[u], 0, 0, 0);
         }
-#pragma unroll
-        for (int a = 0; a < NA; ++a)
-#pragma unroll
-            for (int b = 0; b < NA; ++b) acc[a][b] = fma(ya[a], yb[b], acc[a][b]);
     }
 }
 
@@ -62,19 +79,26 @@ __device__ __forceinline__ void gram_of_tile(const float (*Ys)[QR_COLS + 1], dou
 // R^{-1} = X^T (upper triangular) is written as fp32.  A pivot that is not > 0 (or NaN) latches
 // *flag and is replaced by 1 so the sweep still ends with finite arithmetic.
 template <int NA>
-__device__ __forceinline__ void last_block_factor(QrShared& sh, double (&acc)[NA][NA], double* __restrict__ gram_part,
+__device__ __forceinline__ void last_block_factor(QrShared& sh, const GramAcc<NA>& acc, double* __restrict__ gram_part,
                                                   int nblocks, int r, int* __restrict__ counter,
                                                   float* __restrict__ rinv, int* __restrict__ flag) {
     const int t = threadIdx.x, ti = t >> 4, tj = t & 15;
     const int nent = r * r;
     double* mine = gram_part + (int64_t)blockIdx.x * nent;
+    {
+        constexpr int NBW = GramAcc<NA>::NBW;
+        const int lane = t & 63, wave = t >> 6;
 #pragma unroll
-    for (int a = 0; a < NA; ++a)
+        for (int u = 0; u < NBW; ++u) {
+            const int q = wave * NBW + u;
+            const int j = 16 * (q % NA) + (lane & 15);
 #pragma unroll
-        for (int b = 0; b < NA; ++b) {
-            const int i = ti + 16 * a, j = tj + 16 * b;
-            if (i < r && j < r) mine[i * r + j] = acc[a][b];
+            for (int v = 0; v < 4; ++v) {
+                const int i = 16 * (q / NA) + 4 * v + (lane >> 4);
+                if (i < r && j < r) mine[i * r + j] = acc.v[u][v];
+            }
         }
+    }
     __threadfence();
     __syncthreads();
     if (t == 0) sh.last = (atomicAdd(counter, 1) == nblocks - 1);
@@ -247,11 +271,8 @@ __global__ __launch_bounds__(256) void k_qr_gram(const float* __restrict__ Yt, i
     const int64_t k0 = (int64_t)blockIdx.x * QR_SUB * QR_COLS;
     float st[QR_SUB][16];
     load_slab<QR_SUB>(st, Yt, h, r, k0);
-    double acc[NA][NA];
-#pragma unroll
-    for (int a = 0; a < NA; ++a)
-#pragma unroll
-        for (int b = 0; b < NA; ++b) acc[a][b] = 0.0;
+    GramAcc<NA> acc;
+    acc.zero();
 #pragma unroll
     for (int sub = 0; sub < QR_SUB; ++sub) {
         if (k0 + sub * QR_COLS < h) {
@@ -282,11 +303,8 @@ __global__ __launch_bounds__(256) void k_qr_apply(const float* Yt, float* Gt, co
         const int i = e >> 6, j = e & 63;
         sh.Rs[i][j] = (i < r && j < r) ? rinv_in[i * r + j] : 0.f;
     }
-    double acc[NA][NA];
-#pragma unroll
-    for (int a = 0; a < NA; ++a)
-#pragma unroll
-        for (int b = 0; b < NA; ++b) acc[a][b] = 0.0;
+    GramAcc<NA> acc;
+    acc.zero();
 #pragma unroll
     for (int sub = 0; sub < SUB; ++sub) {
         const int64_t kc = k0 + sub * QR_COLS + kl;

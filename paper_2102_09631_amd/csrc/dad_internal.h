@@ -103,6 +103,8 @@ struct CompressPlan {
     size_t total;
     SplitPlan tn_in;      // split of  A^T V   (width h_in)
     SplitPlan tn_out;     // split of  Delta^T W (width h_out)
+    SplitPlan nn_in;      // column split of  A U  (guarded kernel only; chunk = columns)
+    SplitPlan nn_out;     // column split of  Delta G
     int gram_blocks;
     bool fast;            // MFMA kernels apply to these sizes
 };
@@ -125,8 +127,9 @@ dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hi
 
 // out[n][j] = sum_k X[n][k] * Pt[j][k];  X is N x h (dt), Pt r x h fp32, out N x r (dt).
 // zero_hdr, when not null, is the 256-byte workspace header the launch clears on the side.
-dad_status launch_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int64_t h, int r,
-                          dad_dtype dt, bool fast, int* zero_hdr, hipStream_t s);
+// partials/sp: fp32 slabs and column split of the guarded kernel (ignored by the MFMA kernel).
+dad_status launch_thin_nn(const void* X, const float* Pt, void* out, float* partials, SplitPlan sp, int64_t N,
+                          int64_t h, int r, dad_dtype dt, bool fast, int* zero_hdr, hipStream_t s);
 
 // out_t[j][p] = sum_n X[n][p] * V[n][j];  X N x h (dt), V N x r (dt), out_t r x h fp32.
 // out_bf16 (optional, fast path only) receives a bf16 copy of out_t.

@@ -7,59 +7,66 @@ namespace dad {
 
 // ---------------------------------------------------------------- thin N x h by h x r
 // out[n][j] = sum_k X[n][k] * Pt[j][k]   (V = Delta G and W = A U of Eq. 6)
-template <typename T>
+// With few rows (the N << h case) the contraction is also split over column chunks of `kchunk`
+// (blockIdx.y); each chunk then writes an fp32 slab part[chunk][n][j] for reduce_slabs.
+// MA = accumulators per thread (columns jg, jg+4, ...): 4, 8 or 16 for r <= 16, 32, 64.
+template <typename T, int MA>
 __global__ __launch_bounds__(256) void k_thin_nn(const T* __restrict__ X, const float* __restrict__ Pt,
-                                                 T* __restrict__ out, int64_t N, int64_t h, int r,
-                                                 int* __restrict__ zero_hdr) {
+                                                 T* __restrict__ out, float* __restrict__ part, int64_t N, int64_t h,
+                                                 int r, int64_t kchunk, int* __restrict__ zero_hdr) {
     // the first launch of a compress call also clears the workspace header (flag, ticket counter)
-    if (zero_hdr && blockIdx.x == 0 && threadIdx.x < 64) zero_hdr[threadIdx.x] = 0;
+    if (zero_hdr && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 64) zero_hdr[threadIdx.x] = 0;
     constexpr int ROWS = 64, KC = 32;
     __shared__ float Xs[ROWS][KC + 1];
     __shared__ float Ps[DAD_MAX_RANK][KC + 1];
     const int t = threadIdx.x;
     const int row = t & 63, jg = t >> 6;
     const int64_t n0 = (int64_t)blockIdx.x * ROWS;
-    float acc[DAD_MAX_RANK / 4];
+    float acc[MA];
 #pragma unroll
-    for (int m = 0; m < DAD_MAX_RANK / 4; ++m) acc[m] = 0.f;
+    for (int m = 0; m < MA; ++m) acc[m] = 0.f;
 
-    for (int64_t k0 = 0; k0 < h; k0 += KC) {
+    const int64_t kbeg = (int64_t)blockIdx.y * kchunk;
+    const int64_t kend = (kbeg + kchunk < h) ? kbeg + kchunk : h;
+    for (int64_t k0 = kbeg; k0 < kend; k0 += KC) {
         for (int e = t; e < ROWS * KC; e += 256) {
             int rr = e / KC, kk = e % KC;
             int64_t n = n0 + rr, k = k0 + kk;
-            Xs[rr][kk] = (n < N && k < h) ? ld<T>(X, n * h + k) : 0.f;
+            Xs[rr][kk] = (n < N && k < kend) ? ld<T>(X, n * h + k) : 0.f;
         }
         for (int e = t; e < r * KC; e += 256) {
             int j = e / KC, kk = e % KC;
             int64_t k = k0 + kk;
-            Ps[j][kk] = (k < h) ? Pt[(int64_t)j * h + k] : 0.f;
+            Ps[j][kk] = (k < kend) ? Pt[(int64_t)j * h + k] : 0.f;
         }
         __syncthreads();
+        // rows of Ps beyond r are never written: their products land in accumulators nobody stores
+#pragma unroll 8
+        for (int kk = 0; kk < KC; ++kk) {
+            const float x = Xs[row][kk];
 #pragma unroll
-        for (int m = 0; m < DAD_MAX_RANK / 4; ++m) {
-            int j = jg + 4 * m;
-            if (j < r) {
-                float a = acc[m];
-#pragma unroll
-                for (int kk = 0; kk < KC; ++kk) a = fmaf(Xs[row][kk], Ps[j][kk], a);
-                acc[m] = a;
-            }
+            for (int m = 0; m < MA; ++m) acc[m] = fmaf(x, Ps[jg + 4 * m][kk], acc[m]);
         }
         __syncthreads();
     }
     const int64_t n = n0 + row;
     if (n < N) {
 #pragma unroll
-        for (int m = 0; m < DAD_MAX_RANK / 4; ++m) {
+        for (int m = 0; m < MA; ++m) {
             int j = jg + 4 * m;
-            if (j < r) st<T>(out, n * r + j, acc[m]);
+            if (j < r) {
+                if (part)
+                    part[((int64_t)blockIdx.y * N + n) * r + j] = acc[m];
+                else
+                    st<T>(out, n * r + j, acc[m]);
+            }
         }
     }
 }
 
 // ---------------------------------------------------------------- thin (N x h)^T by N x r, split over rows
 // part[s][j][p] = sum_{n in chunk s} X[n][p] * V[n][j]    (U = A^T V, Y = Delta^T W, P = A^T V)
-template <typename T>
+template <typename T, int MA>
 __global__ __launch_bounds__(256) void k_thin_tn(const T* __restrict__ X, const T* __restrict__ V,
                                                  float* __restrict__ part, int64_t N, int64_t h, int r,
                                                  int64_t chunk) {
@@ -71,9 +78,9 @@ __global__ __launch_bounds__(256) void k_thin_tn(const T* __restrict__ X, const 
     const int64_t p0 = (int64_t)blockIdx.x * PW;
     const int64_t nbeg = (int64_t)blockIdx.y * chunk;
     const int64_t nend = (nbeg + chunk < N) ? nbeg + chunk : N;
-    float acc[DAD_MAX_RANK / 4];
+    float acc[MA];
 #pragma unroll
-    for (int m = 0; m < DAD_MAX_RANK / 4; ++m) acc[m] = 0.f;
+    for (int m = 0; m < MA; ++m) acc[m] = 0.f;
 
     for (int64_t n0 = nbeg; n0 < nend; n0 += RC) {
         for (int e = t; e < RC * PW; e += 256) {
@@ -87,22 +94,18 @@ __global__ __launch_bounds__(256) void k_thin_tn(const T* __restrict__ X, const 
             Vs[rr][j] = (n < nend) ? ld<T>(V, n * r + j) : 0.f;
         }
         __syncthreads();
+#pragma unroll 8
+        for (int rr = 0; rr < RC; ++rr) {
+            const float x = Xs[rr][pl];
 #pragma unroll
-        for (int m = 0; m < DAD_MAX_RANK / 4; ++m) {
-            int j = jg + 4 * m;
-            if (j < r) {
-                float a = acc[m];
-#pragma unroll
-                for (int rr = 0; rr < RC; ++rr) a = fmaf(Xs[rr][pl], Vs[rr][j], a);
-                acc[m] = a;
-            }
+            for (int m = 0; m < MA; ++m) acc[m] = fmaf(x, Vs[rr][jg + 4 * m], acc[m]);
         }
         __syncthreads();
     }
     const int64_t p = p0 + pl;
     if (p < h) {
 #pragma unroll
-        for (int m = 0; m < DAD_MAX_RANK / 4; ++m) {
+        for (int m = 0; m < MA; ++m) {
             int j = jg + 4 * m;
             if (j < r) part[((int64_t)blockIdx.y * r + j) * h + p] = acc[m];
         }
@@ -212,16 +215,43 @@ __global__ __launch_bounds__(256) void k_rebuild(const T* __restrict__ L, const 
 
 // ---------------------------------------------------------------- host launchers
 
-dad_status gen_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int64_t h, int r, dad_dtype dt,
-                       int* zero_hdr, hipStream_t s) {
-    dim3 grid((unsigned)ceil_div(N, 64));
-    ProfScope prof(KID_THIN_NN, s);
-    if (dt == DAD_BF16)
-        hipLaunchKernelGGL(k_thin_nn<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)X, Pt, (bf16_t*)out, N, h, r, zero_hdr);
-    else
-        hipLaunchKernelGGL(k_thin_nn<float>, grid, dim3(256), 0, s, (const float*)X, Pt, (float*)out, N, h, r, zero_hdr);
+// Column split of the guarded thin_nn: with fewer than 128 row blocks the contraction is cut into
+// chunks so that a few hundred workgroups run.
+SplitPlan gen_thin_nn_split(int64_t N, int64_t h) {
+    const int64_t rowblocks = ceil_div(N, 64);
+    int64_t want = rowblocks >= 128 ? 1 : ceil_div(256, rowblocks);
+    const int64_t cap = ceil_div(h, 64);
+    if (want > cap) want = cap;
+    SplitPlan sp;
+    sp.chunk = (int64_t)align_up((size_t)ceil_div(h, want), 32);
+    sp.splits = (int)ceil_div(h, sp.chunk);
+    return sp;
+}
+
+dad_status gen_thin_nn(const void* X, const float* Pt, void* out, float* partials, SplitPlan sp, int64_t N, int64_t h,
+                       int r, dad_dtype dt, int* zero_hdr, hipStream_t s) {
+    dim3 grid((unsigned)ceil_div(N, 64), (unsigned)sp.splits);
+    float* part = sp.splits == 1 ? nullptr : partials;
+    {
+        ProfScope prof(KID_THIN_NN, s);
+#define DAD_GEN_NN(MA)                                                                                              \
+    do {                                                                                                            \
+        if (dt == DAD_BF16)                                                                                         \
+            hipLaunchKernelGGL((k_thin_nn<bf16_t, MA>), grid, dim3(256), 0, s, (const bf16_t*)X, Pt, (bf16_t*)out, part, N, \
+                               h, r, sp.chunk, zero_hdr);                                                           \
+        else                                                                                                        \
+            hipLaunchKernelGGL((k_thin_nn<float, MA>), grid, dim3(256), 0, s, (const float*)X, Pt, (float*)out, part, N, h, \
+                               r, sp.chunk, zero_hdr);                                                              \
+    } while (0)
+        if (r <= 16) DAD_GEN_NN(4);
+        else if (r <= 32) DAD_GEN_NN(8);
+        else DAD_GEN_NN(16);
+#undef DAD_GEN_NN
+    }
     DAD_LAUNCH_CHECK();
-    return DAD_OK;
+    if (sp.splits == 1) return DAD_OK;
+    if (dt == DAD_BF16) return reduce_slabs(part, part, N * r, sp.splits, s, out);  // fp32 sum in place, bf16 copy out
+    return reduce_slabs(part, (float*)out, N * r, sp.splits, s);
 }
 
 dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s, void* out_bf16) {
@@ -242,12 +272,19 @@ dad_status gen_thin_tn(const void* X, const void* V, float* out_t, float* partia
     float* dst = sp.splits == 1 ? out_t : partials;
     {
     ProfScope prof(KID_THIN_TN, s);
-    if (dt == DAD_BF16)
-        hipLaunchKernelGGL(k_thin_tn<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)X, (const bf16_t*)V, dst, N, h,
-                           r, sp.chunk);
-    else
-        hipLaunchKernelGGL(k_thin_tn<float>, grid, dim3(256), 0, s, (const float*)X, (const float*)V, dst, N, h, r,
-                           sp.chunk);
+#define DAD_GEN_TN(MA)                                                                                              \
+    do {                                                                                                            \
+        if (dt == DAD_BF16)                                                                                         \
+            hipLaunchKernelGGL((k_thin_tn<bf16_t, MA>), grid, dim3(256), 0, s, (const bf16_t*)X, (const bf16_t*)V, dst, N, \
+                               h, r, sp.chunk);                                                                     \
+        else                                                                                                        \
+            hipLaunchKernelGGL((k_thin_tn<float, MA>), grid, dim3(256), 0, s, (const float*)X, (const float*)V, dst, N, h, \
+                               r, sp.chunk);                                                                        \
+    } while (0)
+    if (r <= 16) DAD_GEN_TN(4);
+    else if (r <= 32) DAD_GEN_TN(8);
+    else DAD_GEN_TN(16);
+#undef DAD_GEN_TN
     }
     DAD_LAUNCH_CHECK();
     if (sp.splits > 1) return reduce_slabs(partials, out_t, (int64_t)r * h, sp.splits, s);

@@ -68,3 +68,41 @@ def test_vit_large_layer_shapes_full(gpu, layer):
     w = W.WORKLOADS[4]
     _, h_in, h_out = w.all_layers()[layer]
     run_full_size(w, layer, h_in, h_out, gpu)
+
+
+def run_two_level(w, layer, h_in, h_out, dev):
+    """Algorithm 1 at the workload's sizes: every site reduces its own b rows, the S*r-row
+    stack of the pairs is reduced again, the estimate is rebuilt; the oracle does the same in
+    fp64 from the same factors and start matrices."""
+    As, Ds = W.device_factors(w, layer, h_in, h_out, device=dev)
+    S, r, n = w.sites, w.rank, w.n_iter
+    G0s = [W.host_start_matrix(w, 1000 + 64 * layer + s, h_out) for s in range(S)]
+    G0a = W.host_start_matrix(w, 5000 + layer, h_out)
+    pairs = [dad.compress_rank(a, d, r, n, torch.from_numpy(g0).to(dev), check=True) for a, d, g0 in zip(As, Ds, G0s)]
+    Pst, Gst = dad.stack_factors([p for p, _ in pairs], [g for _, g in pairs])
+    assert tuple(Pst.shape) == (S * r, h_in) and tuple(Gst.shape) == (S * r, h_out)
+    Pt, Gt = dad.compress_rank(Pst, Gst, r, n, torch.from_numpy(G0a).to(dev), check=True)
+    G_hat = dad.reconstruct_grad(Pt, Gt).cpu().numpy()
+    A_h = [a.float().cpu().numpy().astype(np.float64) for a in As]
+    D_h = [d.float().cpu().numpy().astype(np.float64) for d in Ds]
+    Pt_ref, Gt_ref, pairs_ref = O.rank_dad(A_h, D_h, G0s, G0a, n)
+    out = {"e_two_level": O.rel_fro(G_hat, O.rank_r_grad(Pt_ref, Gt_ref)),
+           "e_site_max": max(O.rel_fro(dad.reconstruct_grad(p, g).cpu().numpy(), O.rank_r_grad(pr, gr))
+                             for (p, g), (pr, gr) in zip(pairs[:2], pairs_ref[:2]))}
+    g = Gt.cpu().numpy().astype(np.float64)
+    out["orth"] = float(np.abs(g @ g.T - np.eye(r)).max())
+    print(w.name, "two-level", layer, h_in, h_out, out)
+    assert out["e_site_max"] <= TOL_BF16, out
+    assert out["e_two_level"] <= TOL_BF16, out
+    assert out["orth"] <= 1e-4, out
+    del As, Ds
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("widx,layer", [(2, 0), (2, 3), (3, 2), (3, 3), (4, 2)])
+def test_two_level_rank_dad_full(gpu, widx, layer):
+    """Site-level reduction at b rows per site (bf16 factors), aggregator-level reduction of the
+    S*r stacked fp32 rows (64, 256 and 1024 rows for the three transformer workloads)."""
+    w = W.WORKLOADS[widx]
+    _, h_in, h_out = w.all_layers()[layer]
+    run_two_level(w, layer, h_in, h_out, gpu)

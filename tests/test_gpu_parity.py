@@ -88,6 +88,11 @@ def test_encoder_d768_reduced_rows(gpu, layer):
     (2, 33, 65, 31, 5),      # bf16, odd widths (unaligned rows)
     (4, 200, 256, 384, 64),  # largest rank, GELU / Student-t draws
     (1, 300, 64, 64, 64),    # r equal to both widths
+    (2, 100, 2050, 520, 16),  # bf16, few rows and wide: column-split guarded thin_nn, ragged last chunk
+    (0, 20, 3000, 700, 4),    # fp32, N << h: many column chunks, finest row split
+    (3, 512, 1024, 768, 32),  # direct-to-LDS kernels, 3 column strips, 2 row chunks (plain strip mapping)
+    (3, 2048, 512, 2048, 32), # direct-to-LDS kernels, 8 row chunks (strips of a chunk share an XCD)
+    (3, 600, 1024, 1024, 32), # N not a multiple of 256: register-staged MFMA kernels, ragged row tile
 ])
 def test_ragged_and_edge_shapes(gpu, dtype_idx, N_rows, h_in, h_out, r):
     w = W.WORKLOADS[dtype_idx]
