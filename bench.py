@@ -424,7 +424,9 @@ def main():
                 entry.update(bound="mfma", achieved=rate / 1e12, peak=peak, unit="TFLOP/s",
                              frac=rate / 1e12 / peak)
         roof_all[name] = entry
-    dominant = max(kern, key=lambda k: kern[k][0])
+    # the kernel with the largest total time among those with a roofline model (the launch-bound
+    # helpers of the tiny workloads have none)
+    dominant = max((k for k in kern if k in per_step_work), key=lambda k: kern[k][0])
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
