@@ -5,8 +5,10 @@
 //   thin_nn : V[n][j]   = sum_k X[n][k] * Pt[j][k]       (V = Delta G,  W = A U)
 //   thin_tn : Ot[j][p]  = sum_n V[n][j] * X[n][p]        (U = A^T V, Y = Delta^T W, P = A^T V)
 //
-// Loads run two tiles ahead of the arithmetic through two register sets, so each workgroup keeps
-// about 40 KiB of HBM reads in flight.
+// Two families.  The *_dma kernels take whole tiles only (N a multiple of 256, h of 64): tiles go
+// from HBM straight into LDS through a ring of three stages, and thin_nn takes its h x r panel as
+// bf16 (its producers write that copy).  The register-staged kernels take any N and an fp32 panel:
+// their loads run two tiles ahead of the arithmetic through two register sets.
 #include "dad_internal.h"
 
 namespace dad {

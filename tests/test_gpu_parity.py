@@ -93,6 +93,9 @@ def test_encoder_d768_reduced_rows(gpu, layer):
     (3, 512, 1024, 768, 32),  # direct-to-LDS kernels, 3 column strips, 2 row chunks (plain strip mapping)
     (3, 2048, 512, 2048, 32), # direct-to-LDS kernels, 8 row chunks (strips of a chunk share an XCD)
     (3, 600, 1024, 1024, 32), # N not a multiple of 256: register-staged MFMA kernels, ragged row tile
+    (3, 256, 512, 256, 24),   # direct-to-LDS thin_nn with a padded panel (r < 32), register-staged thin_tn
+    (4, 256, 256, 384, 48),   # the same with r between 32 and 64
+    (2, 256, 384, 640, 8),    # smallest rank the MFMA kernels take
 ])
 def test_ragged_and_edge_shapes(gpu, dtype_idx, N_rows, h_in, h_out, r):
     w = W.WORKLOADS[dtype_idx]
