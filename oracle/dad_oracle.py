@@ -15,6 +15,8 @@ width h_in = h_{i-1} and output width h_out = h_i,
 
 Pins (see tests/test_oracle_*.py):
   mlp_factors          central finite differences of the loss
+  backprop_delta       central finite differences of the loss w.r.t. the pre-activations;
+                       identity activation = plain product; ReLU = masked product
   stack_factors        pooled-batch gradient of the MLP equals gradient of stack
   full_grad            brute-force triple loop, N=1 outer product, linearity
   block_spi*           three unrelated routes agree; exact truncated SVD when
@@ -87,6 +89,19 @@ def mlp_factors(Ws, Bs, acts, X, Y, n_global=None):
     for i in range(L - 2, -1, -1):
         deltas[i] = (deltas[i + 1] @ np.asarray(Ws[i + 1], F64).T) * _ACT[acts[i]][1](Z[i])
     return [(A[i], deltas[i]) for i in range(L)]
+
+
+def backprop_delta(D_next, W_next, Z, act):
+    """Section 3.1, Eq. 3, one step: Delta_i = (Delta_{i+1} W_{i+1}^T) (.) phi'_i(Z_i).
+
+    D_next: N x h_{i+1}; W_next: h_i x h_{i+1} (the shape Eq. 1 needs); Z: N x h_i, the layer's
+    pre-activations; act names phi_i.  Row n of the result depends on row n of the inputs only,
+    so per-site deltas written at their row offsets are the stacked delta of Section 3.2.
+    """
+    D_next = np.asarray(D_next, F64)
+    W_next = np.asarray(W_next, F64)
+    Z = np.asarray(Z, F64)
+    return (D_next @ W_next.T) * _ACT[act][1](Z)
 
 
 # --------------------------------------------------------------------------

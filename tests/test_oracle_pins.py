@@ -324,3 +324,55 @@ def test_rank_dad_single_site_full_budget_is_one_level():
     G0 = rng.standard_normal((3, 10))
     Pt, Gt, _ = O.rank_dad([A], [D], [G0], rng.standard_normal((3, 10)), 2)
     assert O.rel_fro(O.rank_r_grad(Pt, Gt), O.rank_r_grad(*O.block_spi(A, D, G0, 2))) < 1e-10
+
+
+# ---------------------------------------------------------------- Eq. 3, one step
+
+@pytest.mark.parametrize("acts", [("tanh", "sigmoid", "identity"), ("relu", "tanh", "tanh")])
+def test_backprop_delta_is_the_derivative_wrt_pre_activations(acts):
+    """Delta_i of Eq. 3 is dLoss/dZ_i: perturb single entries of Z_i, run the tail of the
+    network from the perturbed pre-activations, and compare central differences of the loss."""
+    rng = np.random.default_rng(51)
+    Ws, Bs, acts = _tiny_mlp(rng, acts=acts)
+    X = rng.standard_normal((6, 5))
+    Y = rng.standard_normal((6, 3))
+    A, Z = O.mlp_forward(Ws, Bs, acts, X)
+    L = len(Ws)
+
+    def loss_from_Z(i, Zi):
+        """Loss as a function of the pre-activations of layer i+1 (0-based i)."""
+        a = O._ACT[acts[i]][0](Zi)
+        for k in range(i + 1, L):
+            a = O._ACT[acts[k]][0](a @ Ws[k] + Bs[k])
+        return 0.5 * np.sum((a - Y) ** 2) / X.shape[0]
+
+    # last layer's delta from the definition (Eq. 2), then walk down with the function under test
+    delta = (A[L] - Y) / X.shape[0] * O._ACT[acts[L - 1]][1](Z[L - 1])
+    eps = 1e-6
+    for i in range(L - 2, -1, -1):
+        delta = O.backprop_delta(delta, Ws[i + 1], Z[i], acts[i])
+        fd = np.zeros_like(delta)
+        for n in range(delta.shape[0]):
+            for p in range(delta.shape[1]):
+                Zp, Zm = Z[i].copy(), Z[i].copy()
+                Zp[n, p] += eps
+                Zm[n, p] -= eps
+                fd[n, p] = (loss_from_Z(i, Zp) - loss_from_Z(i, Zm)) / (2 * eps)
+        assert np.allclose(delta, fd, rtol=1e-5, atol=1e-9), i
+
+
+def test_backprop_delta_special_cases():
+    rng = np.random.default_rng(52)
+    Dn = rng.standard_normal((7, 4))
+    W = rng.standard_normal((5, 4))
+    Z = rng.standard_normal((7, 5))
+    brute = np.zeros((7, 5))
+    for n in range(7):
+        for p in range(5):
+            brute[n, p] = sum(Dn[n, q] * W[p, q] for q in range(4))
+    assert np.allclose(O.backprop_delta(Dn, W, Z, "identity"), brute, rtol=1e-13)
+    assert np.allclose(O.backprop_delta(Dn, W, Z, "relu"), brute * (Z > 0), rtol=1e-13)
+    # rows are independent: computing two row blocks separately and stacking them is the same
+    both = O.backprop_delta(Dn, W, Z, "tanh")
+    parts = np.vstack([O.backprop_delta(Dn[:3], W, Z[:3], "tanh"), O.backprop_delta(Dn[3:], W, Z[3:], "tanh")])
+    assert np.array_equal(both, parts)
