@@ -129,6 +129,33 @@ size_t dad_reconstruct_workspace_bytes(int64_t K, int64_t h_in, int64_t h_out, d
 dad_status dad_reconstruct_grad(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out,
                                 dad_dtype dt, float* G, void* workspace, size_t ws_bytes, void* stream);
 
+/* Activation functions phi whose derivative dad_backprop_delta applies. */
+typedef enum {
+    DAD_ACT_IDENTITY = 0,
+    DAD_ACT_RELU = 1,
+    DAD_ACT_TANH = 2,
+    DAD_ACT_SIGMOID = 3
+} dad_activation;
+
+/*
+ * dad_backprop_delta - Section 3.1, Eq. 3, one step of the delta recursion (the step that
+ * produces the factor Delta_i the calls above consume):
+ *     D_out[n][p] = ( sum_q D_next[n][q] * W_next[p][q] ) * phi'(Z[n][p])
+ *   D_next    device, N x h_next, element type dt: Delta_{i+1}
+ *   W_next    device, h x h_next, dt: W_{i+1} in the orientation of Eq. 1 (row p holds the
+ *             weights leaving unit p of layer i)
+ *   Z         device, N x h, dt: pre-activations Z_i
+ *   act       phi_i
+ *   D_out     device out, N x h, dt, dense rows of pitch h, overwritten.  Rows are independent,
+ *             so a site passes the address of its first row inside the stacked buffer and its
+ *             own row count N, and the delta is born in the stacked layout of Section 3.2.
+ * For dt = DAD_BF16 the contraction accumulates in fp32 and the result is rounded once.
+ * No workspace.  Errors: DAD_ERR_NULL, DAD_ERR_DTYPE, DAD_ERR_SHAPE (sizes or act out of range),
+ * DAD_ERR_ALIGN (bf16 shapes served by the MFMA kernel need 16-byte aligned pointers).
+ */
+dad_status dad_backprop_delta(const void* D_next, const void* W_next, const void* Z, int64_t N, int64_t h,
+                              int64_t h_next, dad_dtype dt, dad_activation act, void* D_out, void* stream);
+
 /*
  * Synchronises `stream`, reads the flag a previous dad_compress_rank latched in
  * `workspace` and returns DAD_OK or DAD_ERR_NUMERIC (DAD_ERR_HIP if the sync or

@@ -18,6 +18,7 @@ DAD_F32, DAD_BF16 = 0, 1
 DAD_OK, DAD_ERR_NULL, DAD_ERR_SHAPE, DAD_ERR_ALIGN, DAD_ERR_WORKSPACE, DAD_ERR_DTYPE, DAD_ERR_NUMERIC, \
     DAD_ERR_HIP = range(8)
 DAD_MAX_RANK = 64
+DAD_ACT = {"identity": 0, "relu": 1, "tanh": 2, "sigmoid": 3}
 
 _lib = None
 
@@ -51,6 +52,8 @@ def lib() -> C.CDLL:
     L.dad_reconstruct_workspace_bytes.argtypes = [i64, i64, i64, C.c_int]
     L.dad_reconstruct_grad.restype = C.c_int
     L.dad_reconstruct_grad.argtypes = [vp, vp, i64, i64, i64, C.c_int, vp, vp, sz, vp]
+    L.dad_backprop_delta.restype = C.c_int
+    L.dad_backprop_delta.argtypes = [vp, vp, vp, i64, i64, i64, C.c_int, C.c_int, vp, vp]
     L.dad_poll_numeric_status.restype = C.c_int
     L.dad_poll_numeric_status.argtypes = [vp, vp]
     L.dad_profile_enable.restype = C.c_int
@@ -176,6 +179,30 @@ def reconstruct_grad(L, R, G=None, workspace=None):
                                       workspace.numel() if workspace is not None else 0, _stream()),
            "dad_reconstruct_grad")
     return G
+
+
+def backprop_delta(D_next, W_next, Z, act, D_out=None):
+    """dad_backprop_delta: D_out = (D_next W_next^T) * phi'(Z), rows of D_out dense with pitch h.
+
+    D_out may be a row slice of a larger (stacked) buffer of the same width.
+    """
+    _dense2d(D_next, "D_next")
+    _dense2d(W_next, "W_next")
+    _dense2d(Z, "Z")
+    N, h_next = D_next.shape
+    h = W_next.shape[0]
+    if W_next.shape[1] != h_next or tuple(Z.shape) != (N, h) or not (D_next.dtype == W_next.dtype == Z.dtype):
+        raise ValueError("D_next (N x h_next), W_next (h x h_next) and Z (N x h) disagree in shape or dtype")
+    if act not in DAD_ACT:
+        raise ValueError(f"unknown activation {act!r}")
+    if D_out is None:
+        D_out = torch.empty((N, h), dtype=Z.dtype, device=Z.device)
+    _dense2d(D_out, "D_out")
+    if tuple(D_out.shape) != (N, h) or D_out.dtype != Z.dtype:
+        raise ValueError("D_out must be N x h of the factors' dtype")
+    _check(lib().dad_backprop_delta(D_next.data_ptr(), W_next.data_ptr(), Z.data_ptr(), N, h, h_next, _dt(Z),
+                                    DAD_ACT[act], D_out.data_ptr(), _stream()), "dad_backprop_delta")
+    return D_out
 
 
 def poll_numeric_status(workspace) -> int:
