@@ -30,20 +30,21 @@ __device__ __forceinline__ float act_derivative(float z) {
 // ---------------------------------------------------------------------------------------------
 // bf16 MFMA kernel: whole 256 x 256 output tiles (N and h multiples of 256), h_next a multiple of 32.
 // Eight waves (2 x 4, each 128 rows x 64 columns).  Per stage the tile rows of D_next and of W_next
-// contribute 32 contraction elements (64 bytes) each; they go from memory straight into LDS through
-// a ring of four stages.  LDS row = 64 bytes = four 16-byte chunks; chunk c of row r sits in slot
-// c ^ ((r >> 2) & 3), applied on the global side of the load, so that the 16 lanes of one pass of a
-// fragment read (16 consecutive rows, same chunk) fall on 16 different bank groups.
+// contribute 64 contraction elements each: 128 bytes, a whole cache line per row, which the memory
+// pipeline moves at twice the rate of half lines (32-element stages through a deeper ring measured
+// 25 % slower).  Two 64 KiB stages alternate; the tiles go from memory straight into LDS.  LDS row =
+// eight 16-byte chunks; chunk c of row r sits in slot c ^ ((r >> 1) & 7), applied on the global side
+// of the load, so that the 16 lanes of one pass of a fragment read (16 consecutive rows, same chunk)
+// fall on 16 different bank groups.
 // ---------------------------------------------------------------------------------------------
 namespace bp {
 constexpr int TILE = 256;
-constexpr int BK = 32;
+constexpr int BK = 64;
 constexpr int ROWB = BK * 2;
 constexpr int TILEB = TILE * ROWB;   // one operand tile per stage
 constexpr int STAGEB = 2 * TILEB;
-constexpr int STAGES = 4;
+constexpr int STAGES = 2;
 constexpr int THREADS = 512;
-constexpr int LOADS = 4;             // 16-byte loads per thread per stage
 }  // namespace bp
 
 template <int ACT>
@@ -66,13 +67,13 @@ __global__ __launch_bounds__(bp::THREADS) void k_backprop_bf16(const bf16_t* __r
     const int p0 = qn * bp::TILE;
     const int nk = hn / bp::BK;
 
-    // load i of this wave covers tile rows 32*wave + 16*i .. +15: lane -> row += lane/4, slot lane%4
-    const char* ga[2];
-    const char* gb[2];
+    // load i of this wave covers tile rows 32*wave + 8*i .. +7: lane -> row += lane/8, slot lane%8
+    const char* ga[4];
+    const char* gb[4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int row = 32 * wave + 16 * i + (lane >> 2);
-        const int c = (lane & 3) ^ ((row >> 2) & 3);
+    for (int i = 0; i < 4; ++i) {
+        const int row = 32 * wave + 8 * i + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
         ga[i] = reinterpret_cast<const char*>(Dn + (n0 + row) * (int64_t)hn) + c * 16;
         gb[i] = reinterpret_cast<const char*>(Wn + (int64_t)(p0 + row) * hn) + c * 16;
     }
@@ -81,13 +82,13 @@ __global__ __launch_bounds__(bp::THREADS) void k_backprop_bf16(const bf16_t* __r
     auto issue = [&](int stage) {
         const uint32_t base = lds0 + stage * bp::STAGEB + (32 * wave) * bp::ROWB;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            dma16(ga[i], base + 16 * i * bp::ROWB);
+        for (int i = 0; i < 4; ++i) {
+            dma16(ga[i], base + 8 * i * bp::ROWB);
             ga[i] += bp::ROWB;
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            dma16(gb[i], base + bp::TILEB + 16 * i * bp::ROWB);
+        for (int i = 0; i < 4; ++i) {
+            dma16(gb[i], base + bp::TILEB + 8 * i * bp::ROWB);
             gb[i] += bp::ROWB;
         }
     };
@@ -100,44 +101,69 @@ __global__ __launch_bounds__(bp::THREADS) void k_backprop_bf16(const bf16_t* __r
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-#pragma unroll
-    for (int s = 0; s < bp::STAGES - 1; ++s)
-        if (s < nk) issue(s);
+    if (nk > 0) issue(0);
 
     // fragment of 32 rows starting at row0: lane -> row row0 + lane%32, contraction elements
     // 16*ks + 8*(lane/32) .. +7, i.e. chunk 2*ks + lane/32 of that row
-    const int frow = lane & 31, fsw = (frow >> 2) & 3, fhalf = lane >> 5;
+    const int frow = lane & 31, fsw = (frow >> 1) & 7, fhalf = lane >> 5;
     auto frag = [&](const char* tile, int row0, int ks) -> bf16x8 {
         const int slot = (2 * ks + fhalf) ^ fsw;
         return *reinterpret_cast<const bf16x8*>(tile + (row0 + frow) * bp::ROWB + (slot << 4));
     };
 
-    int slot = 0;
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + bp::STAGES - 2 < nk)
-            wait_vmcnt<bp::LOADS * (bp::STAGES - 2)>();
-        else
-            wait_vmcnt<0>();
-        __syncthreads();  // tile kt is complete in LDS, and the slot of tile kt-1 is free
-        if (kt + bp::STAGES - 1 < nk) issue(slot == 0 ? bp::STAGES - 1 : slot - 1);
-        const char* ta = smem + slot * bp::STAGEB;
+    // Each stage is four MFMA K-steps; fragment sets 0 and 1 alternate.  The last step of a stage is
+    // multiplied after the next stage's barrier, so the matrix cores have independent MFMAs to chew on
+    // while the first fragments of the new stage travel from LDS.
+    bf16x8 fa0[4], fb0[2], fa1[4], fb1[2];
+    auto read_frags = [&](bf16x8 (&fa)[4], bf16x8 (&fb)[2], const char* ta, int ks) {
         const char* tb = ta + bp::TILEB;
 #pragma unroll
-        for (int ks = 0; ks < bp::BK / 16; ++ks) {
-            bf16x8 fa[4], fb[2];
+        for (int a = 0; a < 4; ++a) fa[a] = frag(ta, wm * 128 + a * 32, ks);
 #pragma unroll
-            for (int a = 0; a < 4; ++a) fa[a] = frag(ta, wm * 128 + a * 32, ks);
+        for (int b = 0; b < 2; ++b) fb[b] = frag(tb, wn * 64 + b * 32, ks);
+    };
+    auto mma = [&](const bf16x8 (&fa)[4], const bf16x8 (&fb)[2]) {
 #pragma unroll
-            for (int b = 0; b < 2; ++b) fb[b] = frag(tb, wn * 64 + b * 32, ks);
+        for (int a = 0; a < 4; ++a)
 #pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-                    // W fragment as the row operand: a lane then owns four consecutive p of one n
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[b], fa[a], acc[a][b], 0, 0, 0);
-        }
-        slot = slot == bp::STAGES - 1 ? 0 : slot + 1;
+            for (int b = 0; b < 2; ++b)
+                // W fragment as the row operand: a lane then owns four consecutive p of one n
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[b], fa[a], acc[a][b], 0, 0, 0);
+    };
+    for (int kt = 0; kt < nk; ++kt) {
+        wait_vmcnt<0>();
+        __syncthreads();  // tile kt is complete in LDS, and every wave has its fragments of tile kt-1
+        if (kt + 1 < nk) issue((kt + 1) & 1);
+        const char* ta = smem + (kt & 1) * bp::STAGEB;
+        read_frags(fa0, fb0, ta, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (kt > 0) mma(fa1, fb1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(fa1, fb1, ta, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(fa0, fb0);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(fa0, fb0, ta, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(fa1, fb1);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(fa1, fb1, ta, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(fa0, fb0);
+        __builtin_amdgcn_sched_barrier(0);
     }
+    // this wave's 16 pieces of Z (eight lanes per row, 16 bytes each) are requested now, so that
+    // their latency passes while the last MFMAs drain and the accumulators are staged
+    u32x4 zraw[2][8];
+#pragma unroll
+    for (int rnd = 0; rnd < 2; ++rnd)
+#pragma unroll
+        for (int pass = 0; pass < 8; ++pass) {
+            const int64_t n = n0 + wm * 128 + rnd * 64 + pass * 8 + (lane >> 3);
+            zraw[rnd][pass] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4*>(Z + n * h + p0 + wn * 64 + (lane & 7) * 8));
+        }
+    if (nk > 0) mma(fa1, fb1);
     __syncthreads();  // every wave is done with the ring: its memory now stages the output
 
     // Epilogue.  Each wave owns 16 KiB of LDS: an fp32 [64 n][64 p] block, two rounds for its 128 rows.
@@ -168,14 +194,14 @@ __global__ __launch_bounds__(bp::THREADS) void k_backprop_bf16(const bf16_t* __r
             const f32x4 hi = *reinterpret_cast<const f32x4*>(stg + nl * 64 + (((2 * pc + 1) ^ (nl & 15)) << 2));
             const int64_t n = n0 + wm * 128 + rnd * 64 + nl;
             const int p = p0 + wn * 64 + pc * 8;
-            const u32x4 zraw = *reinterpret_cast<const u32x4*>(Z + n * h + p);
+            const u32x4 zr = zraw[rnd][pass];
             float o[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
             uint32_t packed[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float z0 = __uint_as_float(zraw[e] << 16), z1 = __uint_as_float(zraw[e] & 0xffff0000u);
+                const float z0 = __uint_as_float(zr[e] << 16), z1 = __uint_as_float(zr[e] & 0xffff0000u);
                 const float r0 = o[2 * e] * act_derivative<ACT>(z0), r1 = o[2 * e + 1] * act_derivative<ACT>(z1);
-                packed[e] = (uint32_t)f32_to_bf16(r0) | ((uint32_t)f32_to_bf16(r1) << 16);
+                packed[e] = pack_bf16x2(r0, r1);
             }
             *reinterpret_cast<u32x4*>(Dout + n * h + p) = u32x4{packed[0], packed[1], packed[2], packed[3]};
         }

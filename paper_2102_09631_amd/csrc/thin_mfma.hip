@@ -22,10 +22,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-    return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
-}
-
 // ------------------------------------------------------------------------------------------------
 // thin_nn
 // ------------------------------------------------------------------------------------------------

@@ -39,10 +39,11 @@ def to_dev(x, dtype, dev):
     ("f32", 130, 64, 200, "relu"),
     ("bf16", 77, 136, 72, "relu"),        # guarded kernel, bf16
     ("bf16", 33, 65, 31, "identity"),     # odd widths
-    ("bf16", 256, 256, 32, "relu"),       # one MFMA tile, one stage
-    ("bf16", 512, 768, 96, "tanh"),       # 2 x 3 tiles, 3 stages (ring not yet full)
-    ("bf16", 768, 512, 1024, "sigmoid"),  # 32 stages
-    ("bf16", 256, 1024, 160, "identity"), # 5 stages
+    ("bf16", 256, 256, 32, "relu"),       # tile-aligned but h_next not a multiple of 64: guarded kernel
+    ("bf16", 256, 256, 64, "relu"),       # one MFMA tile, one stage
+    ("bf16", 512, 768, 192, "tanh"),      # 2 x 3 tiles, 3 stages
+    ("bf16", 768, 512, 1024, "sigmoid"),  # 16 stages
+    ("bf16", 256, 1024, 320, "identity"), # 5 stages (odd count)
     ("bf16", 512, 256, 3072, "relu"),     # long contraction
 ])
 def test_backprop_delta_matches_oracle(gpu, dtype, N, h, hn, act):
