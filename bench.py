@@ -39,8 +39,11 @@ def parse():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="gpt2_medium_stack")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--mode", default="one_level", choices=["one_level", "two_level"],
-                    help="two_level: Algorithm 1 (per-site reduction, stack of the pairs, aggregator reduction, rebuild)")
+    ap.add_argument("--mode", default="one_level", choices=["one_level", "two_level", "backprop"],
+                    help="two_level: Algorithm 1 (per-site reduction, stack of the pairs, aggregator reduction, rebuild); "
+                         "backprop: the delta recursion of Eq. 3, every site writing its rows into the stacked buffer")
+    ap.add_argument("--per-site-calls", action="store_true",
+                    help="backprop: one call per site (b rows each) instead of one call over all N rows")
     ap.add_argument("--no-graphs", action="store_true",
                     help="two_level: launch eagerly instead of replaying one captured HIP graph per layer")
     ap.add_argument("--site-streams", type=int, default=8,
@@ -282,6 +285,110 @@ def two_level(args, w, dad, W, torch, np, dev):
     print(json.dumps(out))
 
 
+
+def backprop(args, w, dad, W, torch, np, dev):
+    """Eq. 3 per layer: Delta_i = (Delta_{i+1} W_{i+1}^T) (.) phi'(Z_i) for the N = S*b rows of all
+    simulated sites in one call (rows are independent: the S per-site calls at their row offsets
+    give the same buffer, which --per-site-calls times instead).  The delta is born in the stacked
+    layout; the copy of Delta in dad_stack_factors is not needed on this route.  Layer l has width
+    h = h_out[l]; the layer after it in the list supplies h_next = h_out[l+1] (cyclically), which
+    gives the FFN pairs (4096 <- 1024, 1024 <- 3072 ...) of the transformer workloads.  ReLU networks
+    use its mask; the others use tanh as the transcendental stand-in for their activation."""
+    if w.dtype != "bf16":
+        print("bench.py --mode backprop: bf16 workloads only", file=sys.stderr)
+        sys.exit(2)
+    N, S, b = w.N, w.sites, w.rows_per_site
+    shapes = list(w.shapes)
+    pairs = [(shapes[i][1], shapes[(i + 1) % len(shapes)][1]) for i in range(len(shapes))]
+    layers = [pairs[li % len(pairs)] for li, _, _ in w.all_layers()]
+    act = "relu" if w.act == "relu" else "tanh"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20210209 + 31 * w.index)
+    Dn, Wn, Zs, out = {}, {}, {}, {}
+    for h, hn in set(pairs):     # one resident set per distinct shape (each is far larger than any cache)
+        Dn[(h, hn)] = (torch.randn(N, hn, generator=gen, device=dev) * w.delta_scale).to(torch.bfloat16)
+        Wn[(h, hn)] = (torch.randn(h, hn, generator=gen, device=dev) / hn ** 0.5).to(torch.bfloat16)
+        Zs[(h, hn)] = torch.randn(N, h, generator=gen, device=dev).to(torch.bfloat16)
+        out[(h, hn)] = torch.empty((N, h), dtype=torch.bfloat16, device=dev)
+    torch.cuda.synchronize()
+
+    def step():
+        for key in layers:
+            D, Wt, Z, O_ = Dn[key], Wn[key], Zs[key], out[key]
+            if not args.per_site_calls:
+                dad.backprop_delta(D, Wt, Z, act, D_out=O_)
+                continue
+            for s_ in range(S):
+                r0 = s_ * b
+                dad.backprop_delta(D[r0:r0 + b], Wt, Z[r0:r0 + b], act, D_out=O_[r0:r0 + b])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    dad.profile_reset()
+    dad.profile_enable(True)
+    step()
+    torch.cuda.synchronize()
+    dad.profile_enable(False)
+    kern = dad.profile_read()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    flops = sum(2.0 * N * h * hn for h, hn in layers)
+    bytes_ = sum(2.0 * (N * hn + h * hn + 2.0 * N * h) for h, hn in layers)
+    tflops = flops / (ms_per_step * 1e-3) / 1e12
+    ms, launches = kern["k_backprop_bf16"]
+    k_rate = flops / (ms * 1e-3) / 1e12
+    roofline = {"kernel": "k_backprop_bf16", "bound": "mfma", "achieved": k_rate, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": k_rate / PEAK_BF16_TFLOPS, "avg_us": ms * 1e3 / launches, "traffic": None}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import dad_oracle as O
+        key = min(set(pairs), key=lambda t: t[0] * t[1])
+        h, hn = key
+        rows = 4096
+        Dh = Dn[key][:rows].float().cpu().numpy().astype(np.float64)
+        Wh = Wn[key].float().cpu().numpy().astype(np.float64)
+        Zh = Zs[key][:rows].float().cpu().numpy().astype(np.float64)
+        c0 = time.perf_counter()
+        ref = O.backprop_delta(Dh, Wh, Zh, act)
+        c1 = time.perf_counter()
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            threads = os.cpu_count()
+        got = dad.backprop_delta(Dn[key][:rows], Wn[key], Zs[key][:rows], act).float().cpu().numpy()
+        e = O.rel_fro(got, ref)
+        cpu = {"value": 2.0 * rows * h * hn / (c1 - c0) / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+               "sample": f"{rows} of {N} rows of one layer (h={h}, h_next={hn}): fp64 numpy backprop_delta {c1 - c0:.2f} s",
+               "parity_rel_fro": {"delta": e, "tol": 2e-2}, "host_cpus": os.cpu_count()}
+        if not e <= 2e-2:
+            print(f"bench.py: parity check failed: {e:.3e}", file=sys.stderr)
+            sys.exit(1)
+
+    out_json = {
+        "metric": "dAD delta back-propagation (Eq. 3) TFLOP/s into the stacked layout (% MFMA roofline)",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name + "/backprop", "layers": len(layers), "shapes_h_hnext": [list(p) for p in pairs],
+                   "sites": S, "rows_per_site": b, "N": N, "activation": act,
+                   "per_site_calls": bool(args.per_site_calls)},
+        "frac_of_mfma_peak": tflops / PEAK_BF16_TFLOPS,
+        "hbm_GBps": bytes_ / (ms_per_step * 1e-3) / 1e9,
+        "us_per_layer": ms_per_step * 1e3 / len(layers),
+        "roofline": roofline,
+        "kernels": {k: {"ms_per_step": v[0], "launches_per_step": v[1], "avg_us": v[0] * 1e3 / v[1]} for k, v in kern.items()},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out_json))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -304,6 +411,8 @@ def main():
     w = W.by_name(args.workload)
     if args.mode == "two_level":
         return two_level(args, w, dad, W, torch, np, dev)
+    if args.mode == "backprop":
+        return backprop(args, w, dad, W, torch, np, dev)
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     es = 2 if w.dtype == "bf16" else 4
     N, r, n_iter, S, b = w.N, w.rank, w.n_iter, w.sites, w.rows_per_site

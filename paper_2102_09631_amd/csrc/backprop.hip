@@ -13,16 +13,22 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-template <int ACT>
+// phi'(z).  FAST uses the hardware exponential (a few ulp), enough for a result rounded to bf16;
+// the guarded kernel, which also serves fp32, uses the library functions.
+template <int ACT, bool FAST>
 __device__ __forceinline__ float act_derivative(float z) {
     if (ACT == DAD_ACT_RELU) return z > 0.f ? 1.f : 0.f;
     if (ACT == DAD_ACT_TANH) {
-        const float t = tanhf(z);
-        return 1.f - t * t;
+        // 1 - tanh^2 = 4 e / (1 + e)^2 with e = exp(-2|z|) <= 1: no overflow, no cancellation
+        const float e = FAST ? __expf(-2.f * fabsf(z)) : expf(-2.f * fabsf(z));
+        const float d = 1.f + e;
+        return 4.f * e / (d * d);
     }
     if (ACT == DAD_ACT_SIGMOID) {
-        const float s = 1.f / (1.f + expf(-z));
-        return s * (1.f - s);
+        // s (1 - s) = e / (1 + e)^2 with e = exp(-|z|)
+        const float e = FAST ? __expf(-fabsf(z)) : expf(-fabsf(z));
+        const float d = 1.f + e;
+        return e / (d * d);
     }
     return 1.f;
 }
@@ -200,7 +206,7 @@ __global__ __launch_bounds__(bp::THREADS) void k_backprop_bf16(const bf16_t* __r
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float z0 = __uint_as_float(zr[e] << 16), z1 = __uint_as_float(zr[e] & 0xffff0000u);
-                const float r0 = o[2 * e] * act_derivative<ACT>(z0), r1 = o[2 * e + 1] * act_derivative<ACT>(z1);
+                const float r0 = o[2 * e] * act_derivative<ACT, true>(z0), r1 = o[2 * e + 1] * act_derivative<ACT, true>(z1);
                 packed[e] = pack_bf16x2(r0, r1);
             }
             *reinterpret_cast<u32x4*>(Dout + n * h + p) = u32x4{packed[0], packed[1], packed[2], packed[3]};
@@ -258,9 +264,9 @@ __global__ __launch_bounds__(256) void k_backprop(const T* __restrict__ Dn, cons
             if (p >= h) continue;
             const float z = ld<T>(Z, n * h + p);
             float d = 1.f;
-            if (act == DAD_ACT_RELU) d = act_derivative<DAD_ACT_RELU>(z);
-            else if (act == DAD_ACT_TANH) d = act_derivative<DAD_ACT_TANH>(z);
-            else if (act == DAD_ACT_SIGMOID) d = act_derivative<DAD_ACT_SIGMOID>(z);
+            if (act == DAD_ACT_RELU) d = act_derivative<DAD_ACT_RELU, false>(z);
+            else if (act == DAD_ACT_TANH) d = act_derivative<DAD_ACT_TANH, false>(z);
+            else if (act == DAD_ACT_SIGMOID) d = act_derivative<DAD_ACT_SIGMOID, false>(z);
             st<T>(Dout, n * h + p, acc[a][b] * d);
         }
     }
