@@ -23,7 +23,7 @@ def test_every_declared_symbol_is_exported(lib):
     text = open(os.path.join(ROOT, "include", "dad.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(dad_[a-z_]+)\s*\(", text))
-    assert {"dad_stack_factors", "dad_compress_rank", "dad_reconstruct_grad", "dad_compress_workspace_bytes",
+    assert {"dad_stack_factors", "dad_compress_rank", "dad_reconstruct_grad", "dad_backprop_delta", "dad_compress_workspace_bytes",
             "dad_reconstruct_workspace_bytes", "dad_poll_numeric_status", "dad_status_string"} <= names
     for n in names:
         assert hasattr(lib, n), n
@@ -91,6 +91,23 @@ def test_reconstruct_and_stack_reject_bad_arguments_on_host(lib):
     assert lib.dad_stack_factors(2, ptrs, ptrs, rows, 8, 8, 3, p, p, None) == dad.DAD_ERR_DTYPE
     nullp = (C.c_void_p * 2)(p, None)
     assert lib.dad_stack_factors(2, nullp, ptrs, rows, 8, 8, 0, p, p, None) == dad.DAD_ERR_NULL
+
+
+def test_backprop_rejects_bad_arguments_on_host(lib):
+    p = 0x1000  # never dereferenced: every call below must fail before a launch
+
+    def call(Dn=p, Wn=p, Z=p, N=256, h=256, hn=64, dt=dad.DAD_BF16, act=1, out=p):
+        return lib.dad_backprop_delta(Dn, Wn, Z, N, h, hn, dt, act, out, None)
+
+    assert call(Dn=None) == dad.DAD_ERR_NULL
+    assert call(out=None) == dad.DAD_ERR_NULL
+    assert call(dt=4) == dad.DAD_ERR_DTYPE
+    assert call(act=4) == dad.DAD_ERR_SHAPE
+    assert call(act=-1) == dad.DAD_ERR_SHAPE
+    assert call(N=0) == dad.DAD_ERR_SHAPE
+    assert call(hn=0) == dad.DAD_ERR_SHAPE
+    assert call(h=(1 << 24) + 1) == dad.DAD_ERR_SHAPE
+    assert call(Z=p + 2) == dad.DAD_ERR_ALIGN      # shape served by the MFMA kernel
 
 
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
