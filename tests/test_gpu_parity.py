@@ -134,6 +134,30 @@ def test_rank_budget_at_least_gradient_rank_recovers_gradient(gpu):
     assert O.rel_fro(G_r, O.truncated_svd(M, 4)) <= 1e-5
 
 
+@pytest.mark.parametrize("ratio,N,h_in,h_out,r", [(0.8, 64, 96, 80, 8), (0.5, 64, 96, 80, 8), (0.3, 64, 96, 80, 8),
+                                                   (0.5, 512, 256, 384, 16), (0.1, 64, 96, 80, 8)])
+def test_steep_spectrum_keeps_orthonormality_and_degrades_gracefully(gpu, ratio, N, h_in, h_out, r):
+    """Delta rows scaled geometrically: sigma_1/sigma_r up to 1e7.  The Cholesky orthonormalisation
+    (fp64 Gram and factorisation) must not break down and G must stay orthonormal to fp32 accuracy.
+    The fp32 contractions resolve a direction of relative size sigma_r/sigma_1 only to
+    eps32 * sigma_1/sigma_r, which bounds the distance to the fp64 oracle."""
+    rng = np.random.default_rng([11, int(ratio * 10), N])
+    A = rng.standard_normal((N, h_in)).astype(np.float32)
+    D = (rng.standard_normal((N, h_out)) * (ratio ** np.arange(N))[:, None]).astype(np.float32)
+    G0 = rng.standard_normal((r, h_out)).astype(np.float32)
+    ws = torch.empty(dad.compress_workspace_bytes(N, h_in, h_out, r, torch.float32), dtype=torch.uint8, device=gpu)
+    Pt, Gt = dad.compress_rank(torch.from_numpy(A).to(gpu), torch.from_numpy(D).to(gpu), r, 2,
+                               torch.from_numpy(G0).to(gpu), workspace=ws)
+    assert dad.poll_numeric_status(ws) == dad.DAD_OK
+    g = Gt.cpu().numpy().astype(np.float64)
+    assert np.abs(g @ g.T - np.eye(r)).max() <= 1e-5
+    s = np.linalg.svd(A.astype(np.float64).T @ D.astype(np.float64), compute_uv=False)
+    bound = 1e-5 + np.finfo(np.float32).eps * s[0] / s[r - 1]
+    err = O.rel_fro(dad.reconstruct_grad(Pt, Gt).cpu().numpy(), O.rank_r_grad(*O.block_spi(A, D, G0, 2)))
+    print(ratio, N, r, "sigma_1/sigma_r", s[0] / s[r - 1], "err", err, "bound", bound)
+    assert err <= bound
+
+
 def test_rank_pairs_restack_and_recompress(gpu):
     """Algorithm 1: per-site rank-r pairs are stacked (N' = S*r rows) and compressed again."""
     w = W.WORKLOADS[0]
