@@ -161,36 +161,39 @@ dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_
     dad_status rc;
 
     int* counter = flag + 16;
-    if (p.dma) {
-        // direct-to-LDS path: the h x r panels also exist as bf16 copies (Gb, Ub) made by their producers
-        void* Gb = ws + p.off_Gb;
-        void* Ub = ws + p.off_Ub;
-        if ((rc = launch_panel_init(G0, Gb, Ub, h_in, h_out, r, flag, s)) != DAD_OK) return rc;
-        for (int it = 0; it < n_iter; ++it) {
-            if ((rc = dma_thin_nn(D, Gb, V, N, h_out, r, s)) != DAD_OK) return rc;                                     // V = Delta G
-            if ((rc = launch_thin_tn(A, V, Ut, part, p.tn_in, N, h_in, r, dt, true, Ub, s)) != DAD_OK) return rc;      // U = A^T V
-            if ((rc = dma_thin_nn(A, Ub, V, N, h_in, r, s)) != DAD_OK) return rc;                                      // W = A U
-            if ((rc = launch_thin_tn(D, V, Yt, part, p.tn_out, N, h_out, r, dt, true, nullptr, s)) != DAD_OK) return rc;  // Y = Delta^T W
-            if ((rc = launch_cholqr(Yt, Gt, h_out, r, (it + 1 == n_iter) ? 2 : 1, gram, p.gram_blocks, rinv, counter, flag,
-                                    Gb, s)) != DAD_OK)
-                return rc;
-        }
-        if ((rc = dma_thin_nn(D, Gb, V, N, h_out, r, s)) != DAD_OK) return rc;                                         // V = Delta G
-        return launch_thin_tn(A, V, Pt, part, p.tn_in, N, h_in, r, dt, true, nullptr, s);                              // P = A^T V
-    }
-    const float* Gcur = G0;
+    // bf16 copies of the two h x r panels, made by their producers (direct-to-LDS path only)
+    void* Gb = p.dma ? ws + p.off_Gb : nullptr;
+    void* Ub = p.dma ? ws + p.off_Ub : nullptr;
+
+    // V <- X * panel (N x r); the direct-to-LDS kernel takes the bf16 copy of the panel
+    auto nn = [&](const void* X, const float* panel, const void* panel_bf16, int64_t h, SplitPlan sp, int* hdr) {
+        if (p.dma) return dma_thin_nn(X, panel_bf16, V, N, h, r, s);
+        return launch_thin_nn(X, panel, V, part, sp, N, h, r, dt, p.fast, hdr, s);
+    };
+    // out (r x h) <- V^T X, with an optional bf16 copy
+    auto tn = [&](const void* X, float* out, int64_t h, SplitPlan sp, void* out_bf16) {
+        return launch_thin_tn(X, V, out, part, sp, N, h, r, dt, p.fast, out_bf16, s);
+    };
+#define DAD_TRY(expr)                      \
+    do {                                   \
+        if ((rc = (expr)) != DAD_OK) return rc; \
+    } while (0)
+    // the workspace header is cleared by the first launch of the call
+    if (p.dma) DAD_TRY(launch_panel_init(G0, Gb, Ub, h_in, h_out, r, flag, s));
+    const float* G = G0;
     for (int it = 0; it < n_iter; ++it) {
-        if ((rc = launch_thin_nn(D, Gcur, V, part, p.nn_out, N, h_out, r, dt, p.fast, it == 0 ? flag : nullptr, s)) != DAD_OK) return rc;  // V = Delta G
-        if ((rc = launch_thin_tn(A, V, Ut, part, p.tn_in, N, h_in, r, dt, p.fast, nullptr, s)) != DAD_OK) return rc;   // U = A^T V
-        if ((rc = launch_thin_nn(A, Ut, V, part, p.nn_in, N, h_in, r, dt, p.fast, nullptr, s)) != DAD_OK) return rc;                  // W = A U
-        if ((rc = launch_thin_tn(D, V, Yt, part, p.tn_out, N, h_out, r, dt, p.fast, nullptr, s)) != DAD_OK) return rc; // Y = Delta^T W
-        if ((rc = launch_cholqr(Yt, Gt, h_out, r, (it + 1 == n_iter) ? 2 : 1, gram, p.gram_blocks, rinv, counter, flag,
-                                nullptr, s)) != DAD_OK)
-            return rc;
-        Gcur = Gt;
+        DAD_TRY(nn(D, G, Gb, h_out, p.nn_out, it == 0 ? flag : nullptr));  // V = Delta G
+        DAD_TRY(tn(A, Ut, h_in, p.tn_in, Ub));                             // U = A^T V
+        DAD_TRY(nn(A, Ut, Ub, h_in, p.nn_in, nullptr));                    // W = A U
+        DAD_TRY(tn(D, Yt, h_out, p.tn_out, nullptr));                      // Y = Delta^T W
+        // G = orth(Y): two Cholesky rounds for the iterate that is returned, one for the others
+        DAD_TRY(launch_cholqr(Yt, Gt, h_out, r, (it + 1 == n_iter) ? 2 : 1, gram, p.gram_blocks, rinv, counter, flag, Gb,
+                              s));
+        G = Gt;
     }
-    if ((rc = launch_thin_nn(D, Gt, V, part, p.nn_out, N, h_out, r, dt, p.fast, nullptr, s)) != DAD_OK) return rc;                     // V = Delta G
-    return launch_thin_tn(A, V, Pt, part, p.tn_in, N, h_in, r, dt, p.fast, nullptr, s);                                // P = A^T V
+    DAD_TRY(nn(D, Gt, Gb, h_out, p.nn_out, nullptr));  // V = Delta G
+    return tn(A, Pt, h_in, p.tn_in, nullptr);          // P = A^T V
+#undef DAD_TRY
 }
 
 static bool rebuild_shape_ok(int64_t K, int64_t h_in, int64_t h_out) {
