@@ -649,7 +649,6 @@ dad_status dma_thin_nn(const void* X, const void* Pb, void* out, int64_t N, int6
 
 dad_status fast_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp, int64_t N, int64_t h,
                         int r, void* out_bf16, hipStream_t s) {
-    dim3 grid((unsigned)(h / tn::PW), (unsigned)sp.splits);
     float* dst = sp.splits == 1 ? out_t : partials;
     if ((r == 16 || r == 32 || r == 64) && N % tn::BK == 0 && sp.chunk % tn::BK == 0) {
         ProfScope prof(KID_THIN_TN_BF16, s);
@@ -678,17 +677,18 @@ dad_status fast_thin_tn(const void* X, const void* V, float* out_t, float* parti
             else DAD_TN_LAUNCH(64, 256, 32);
         }
 #undef DAD_TN_LAUNCH
-    } else {
-    ProfScope prof(KID_THIN_TN_BF16, s);
-    if (r <= 32) {
-        const int lds = 2 * (tn::XTILEB + tn::BK * 64);
-        hipLaunchKernelGGL(k_thin_tn_bf16<32>, grid, dim3(256), lds, s, (const bf16_t*)X, (const bf16_t*)V, dst, N, (int)h,
-                           r, sp.chunk);
-    } else {
-        const int lds = 2 * (tn::XTILEB + tn::BK * 128);
-        hipLaunchKernelGGL(k_thin_tn_bf16<64>, grid, dim3(256), lds, s, (const bf16_t*)X, (const bf16_t*)V, dst, N, (int)h,
-                           r, sp.chunk);
-    }
+    } else {  // ragged row count or a rank the direct-to-LDS kernel is not built for
+        ProfScope prof(KID_THIN_TN_BF16, s);
+        const dim3 grid((unsigned)(h / tn::PW), (unsigned)sp.splits);
+        if (r <= 32) {
+            const int lds = 2 * (tn::XTILEB + tn::BK * 64);
+            hipLaunchKernelGGL(k_thin_tn_bf16<32>, grid, dim3(256), lds, s, (const bf16_t*)X, (const bf16_t*)V, dst, N,
+                               (int)h, r, sp.chunk);
+        } else {
+            const int lds = 2 * (tn::XTILEB + tn::BK * 128);
+            hipLaunchKernelGGL(k_thin_tn_bf16<64>, grid, dim3(256), lds, s, (const bf16_t*)X, (const bf16_t*)V, dst, N,
+                               (int)h, r, sp.chunk);
+        }
     }
     DAD_LAUNCH_CHECK();
     if (sp.splits > 1) return reduce_slabs(partials, out_t, (int64_t)r * h, sp.splits, s, out_bf16);
