@@ -15,18 +15,35 @@ struct SegTable {
     int64_t bytes[MAX_SEG];
     int first_block[MAX_SEG + 1];  // prefix sum of chunk counts
     int unit[MAX_SEG];             // 16, 8, 4 or 2: widest access that stays aligned
+    int nt[MAX_SEG];               // non-temporal stores: the stacked matrix is larger than the Infinity Cache
     int n;
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-template <typename U>
+// Eight units per thread in flight.  The sources are read once: non-temporal loads.  The stores are
+// non-temporal only when the stacked matrix does not fit the Infinity Cache anyway (6 % faster then;
+// a small one is better left there for the call that reads it next).
+template <typename U, bool NT>
 __device__ __forceinline__ void copy_units(const char* __restrict__ s, char* __restrict__ d, int64_t bytes) {
     const U* sp = reinterpret_cast<const U*>(s);
     U* dp = reinterpret_cast<U*>(d);
     const int64_t n = bytes / (int64_t)sizeof(U);
-    for (int64_t i = threadIdx.x; i < n; i += 256) dp[i] = __builtin_nontemporal_load(sp + i);
+    int64_t i = threadIdx.x;
+    for (; i + 7 * 256 < n; i += 8 * 256) {
+        U v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(sp + i + u * 256);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (NT)
+                __builtin_nontemporal_store(v[u], dp + i + u * 256);
+            else
+                dp[i + u * 256] = v[u];
+        }
+    }
+    for (; i < n; i += 256) dp[i] = __builtin_nontemporal_load(sp + i);
 }
 
 __global__ __launch_bounds__(256) void k_stack(SegTable tb) {
@@ -39,10 +56,15 @@ __global__ __launch_bounds__(256) void k_stack(SegTable tb) {
     const char* s = tb.src[seg] + off;
     char* d = tb.dst[seg] + off;
     switch (tb.unit[seg]) {
-        case 16: copy_units<u32x4>(s, d, len); break;
-        case 8: copy_units<u32x2>(s, d, len); break;
-        case 4: copy_units<uint32_t>(s, d, len); break;
-        default: copy_units<uint16_t>(s, d, len); break;
+        case 16:
+            if (tb.nt[seg])
+                copy_units<u32x4, true>(s, d, len);
+            else
+                copy_units<u32x4, false>(s, d, len);
+            break;
+        case 8: copy_units<u32x2, false>(s, d, len); break;
+        case 4: copy_units<uint32_t, false>(s, d, len); break;
+        default: copy_units<uint16_t, false>(s, d, len); break;
     }
 }
 
@@ -70,7 +92,7 @@ dad_status launch_stack(int S, const void* const* A_sites, const void* const* D_
         tb.first_block[0] = 0;
         return DAD_OK;
     };
-    auto push = [&](const void* src, char* dst, int64_t bytes) -> dad_status {
+    auto push = [&](const void* src, char* dst, int64_t bytes, int nt) -> dad_status {
         // a segment whose chunk count would overflow the int prefix goes out in pieces
         const int64_t max_piece = CHUNK * (int64_t)(1 << 20);
         const char* sp = static_cast<const char*>(src);
@@ -81,6 +103,7 @@ dad_status launch_stack(int S, const void* const* A_sites, const void* const* D_
             tb.dst[i] = dst;
             tb.bytes[i] = piece;
             tb.unit[i] = widest_unit(sp, dst, piece);
+            tb.nt[i] = nt;
             tb.first_block[i + 1] = tb.first_block[i] + (int)ceil_div(piece, CHUNK);
             tb.n = i + 1;
             if (tb.n == MAX_SEG || tb.first_block[tb.n] > (1 << 28)) {
@@ -93,11 +116,15 @@ dad_status launch_stack(int S, const void* const* A_sites, const void* const* D_
         }
         return DAD_OK;
     };
+    int64_t total_rows = 0;
+    for (int s = 0; s < S; ++s) total_rows += rows[s];
+    const int64_t big = (int64_t)200 << 20;
+    const int nt_a = total_rows * h_in * es > big, nt_d = total_rows * h_out * es > big;
     for (int s = 0; s < S; ++s) {
         if (rows[s] > 0) {
-            dad_status rc = push(A_sites[s], static_cast<char*>(A_out) + row_off * h_in * es, rows[s] * h_in * es);
+            dad_status rc = push(A_sites[s], static_cast<char*>(A_out) + row_off * h_in * es, rows[s] * h_in * es, nt_a);
             if (rc != DAD_OK) return rc;
-            rc = push(D_sites[s], static_cast<char*>(D_out) + row_off * h_out * es, rows[s] * h_out * es);
+            rc = push(D_sites[s], static_cast<char*>(D_out) + row_off * h_out * es, rows[s] * h_out * es, nt_d);
             if (rc != DAD_OK) return rc;
         }
         row_off += rows[s];
