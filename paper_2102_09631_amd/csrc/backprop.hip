@@ -209,7 +209,9 @@ __global__ __launch_bounds__(bp::THREADS) void k_backprop_bf16(const bf16_t* __r
                 const float r0 = o[2 * e] * act_derivative<ACT, true>(z0), r1 = o[2 * e + 1] * act_derivative<ACT, true>(z1);
                 packed[e] = pack_bf16x2(r0, r1);
             }
-            *reinterpret_cast<u32x4*>(Dout + n * h + p) = u32x4{packed[0], packed[1], packed[2], packed[3]};
+            // written once, read by a later call: keep it out of the caches the operand tiles live in
+            __builtin_nontemporal_store(u32x4{packed[0], packed[1], packed[2], packed[3]},
+                                        reinterpret_cast<u32x4*>(Dout + n * h + p));
         }
     }
 }
