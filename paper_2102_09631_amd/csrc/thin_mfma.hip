@@ -653,10 +653,17 @@ static dad_status dma_thin_nn_cfg(const void* X, const void* Pb, void* out, int6
     return DAD_OK;
 }
 
+// Rows per workgroup: 256 (eight waves) when that still gives one workgroup per CU, fewer for
+// shorter factors so that the chip stays filled (a site's 8192 rows: 256 single-wave workgroups).
 dad_status dma_thin_nn(const void* X, const void* Pb, void* out, int64_t N, int64_t h, int r, hipStream_t s) {
     ProfScope prof(KID_THIN_NN_BF16, s);
-    if (r <= 32) return dma_thin_nn_cfg<32, 8, 3>(X, Pb, out, N, h, r, s);
-    return dma_thin_nn_cfg<64, 8, 3>(X, Pb, out, N, h, r, s);
+    const int64_t want = 256;  // workgroups
+#define DAD_NN_W(W) (r <= 32 ? dma_thin_nn_cfg<32, W, 3>(X, Pb, out, N, h, r, s) : dma_thin_nn_cfg<64, W, 3>(X, Pb, out, N, h, r, s))
+    if (N / 256 >= want) return DAD_NN_W(8);
+    if (N / 128 >= want) return DAD_NN_W(4);
+    if (N / 64 >= want) return DAD_NN_W(2);
+    return DAD_NN_W(1);
+#undef DAD_NN_W
 }
 
 dad_status fast_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp, int64_t N, int64_t h,
