@@ -200,13 +200,20 @@ __global__ __launch_bounds__(256) void k_rebuild(const T* __restrict__ L, const 
         __syncthreads();
     }
     float* o = out + (int64_t)blockIdx.z * h_in * h_out;
+    const int64_t qb = q0 + tx * 4;
+    const bool vec = (h_out & 3) == 0 && qb + 3 < h_out;  // rows stay 16-byte aligned: one store per row
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
         int64_t p = p0 + ty * 4 + a;
         if (p >= h_in) continue;
+        if (vec) {
+            typedef float f4 __attribute__((ext_vector_type(4)));
+            *reinterpret_cast<f4*>(o + p * h_out + qb) = f4{acc[a][0], acc[a][1], acc[a][2], acc[a][3]};
+            continue;
+        }
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-            int64_t q = q0 + tx * 4 + b;
+            int64_t q = qb + b;
             if (q < h_out) o[p * h_out + q] = acc[a][b];
         }
     }
