@@ -22,8 +22,8 @@ bool thin_dma_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
 dad_status launch_panel_init(const float*, void*, void*, int64_t, int64_t, int, int*, hipStream_t);
 dad_status dma_thin_nn(const void*, const void*, void*, int64_t, int64_t, int, hipStream_t);
 bool rebuild_fast_ok(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
-SplitPlan rebuild_fast_split(int64_t K, int64_t h_in, int64_t h_out);
-dad_status fast_rebuild(const void*, const void*, int64_t, int64_t, int64_t, float*, float*, SplitPlan, hipStream_t);
+SplitPlan rebuild_fast_split(int64_t K, int64_t h_in, int64_t h_out, int* tile);
+dad_status fast_rebuild(const void*, const void*, int64_t, int64_t, int64_t, float*, float*, SplitPlan, int, hipStream_t);
 
 static SplitPlan split_rows(int64_t rows, int64_t tiles, int64_t target_blocks, int64_t min_chunk, int64_t quantum) {
     int64_t want = ceil_div(target_blocks, tiles);
@@ -81,7 +81,8 @@ CompressPlan plan_compress(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dt
 RebuildPlan plan_rebuild(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt) {
     RebuildPlan p;
     p.fast = rebuild_fast_ok(K, h_in, h_out, dt);
-    p.split = p.fast ? rebuild_fast_split(K, h_in, h_out)
+    p.tile = 0;
+    p.split = p.fast ? rebuild_fast_split(K, h_in, h_out, &p.tile)
                      : split_rows(K, ceil_div(h_in, 64) * ceil_div(h_out, 64), 2048, 512, 16);
     p.total = p.split.splits > 1 ? (size_t)p.split.splits * h_in * h_out * 4 : 0;
     return p;
@@ -244,7 +245,7 @@ dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* par
 
 dad_status launch_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt,
                           float* G, float* partials, const RebuildPlan& plan, hipStream_t s) {
-    if (plan.fast) return fast_rebuild(L, R, K, h_in, h_out, G, partials, plan.split, s);
+    if (plan.fast) return fast_rebuild(L, R, K, h_in, h_out, G, partials, plan.split, plan.tile, s);
     return gen_rebuild(L, R, K, h_in, h_out, dt, G, partials, plan.split, s);
 }
 

@@ -126,6 +126,7 @@ struct RebuildPlan {
     SplitPlan split;
     size_t total;  // bytes of partials (0 when splits == 1)
     bool fast;
+    int tile;      // output tile edge of the MFMA kernel (256 or 128)
 };
 
 RebuildPlan plan_rebuild(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);

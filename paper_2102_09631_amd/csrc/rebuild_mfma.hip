@@ -32,18 +32,20 @@ constexpr int STAGEB = 2 * TILEB;     // L tile + R tile
 constexpr int NSTAGE = 2;
 }  // namespace rb
 
-// byte offset of 16-byte chunk `chunk` of row k inside an operand tile
-__device__ __forceinline__ int rb_lds_off(int k, int chunk) { return k * rb::ROWB + ((chunk ^ ((k & 3) << 2)) << 4); }
+// byte offset of 16-byte chunk `chunk` of row k inside an operand tile whose rows are ROWB bytes
+template <int ROWB = rb::ROWB>
+__device__ __forceinline__ int rb_lds_off(int k, int chunk) { return k * ROWB + ((chunk ^ ((k & 3) << 2)) << 4); }
 
 typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
 
 // Eight K-consecutive bf16 of column (m0 + lane%32), K rows kb + 8*(lane/32) .. +7, from a [k][col] tile.
+template <int ROWB = rb::ROWB>
 __device__ __forceinline__ bf16x8 rb_frag(const char* tile, int m0, int kb, int lane) {
     const int b = lane >> 4, s = lane & 15, j = s >> 2, g = s & 3;
     const int m = m0 + ((b & 1) << 4) + (g << 2);
     const int k = kb + ((b >> 1) << 3) + j;
-    const char* p0 = tile + rb_lds_off(k, m >> 3) + ((g & 1) << 3);
-    const char* p1 = tile + rb_lds_off(k + 4, m >> 3) + ((g & 1) << 3);
+    const char* p0 = tile + rb_lds_off<ROWB>(k, m >> 3) + ((g & 1) << 3);
+    const char* p1 = tile + rb_lds_off<ROWB>(k + 4, m >> 3) + ((g & 1) << 3);
     s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0));
     s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p1));
     s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -174,18 +176,30 @@ __global__ __launch_bounds__(256) void k_rebuild_bf16(const bf16_t* __restrict__
 // exactly what four 128 x 128 waves need at full MFMA rate; two waves per SIMD roughly double it.
 namespace rb {
 constexpr int DMA_STAGES = 4;
-constexpr int DMA_THREADS = 512;
-constexpr int DMA_LOADS = 2 * TILEB / 16 / DMA_THREADS;  // 16-byte loads per thread per stage
+constexpr int DMA_LOADS = 4;  // 16-byte loads per thread per stage, for both tile sizes
 }  // namespace rb
 
-__global__ __launch_bounds__(rb::DMA_THREADS) void k_rebuild_bf16_dma(const bf16_t* __restrict__ L,
-                                                                      const bf16_t* __restrict__ R,
-                                                                      float* __restrict__ out, int64_t K, int h_in,
-                                                                      int h_out, int64_t chunk, int tiles_m,
-                                                                      int tiles_n, int total) {
+// T = tile edge, WM x WN waves, each (T/WM) x (T/WN) of the tile.  T = 256 with 2 x 4 waves is the
+// kernel for large gradients.  T = 128 with 2 x 2 waves (two workgroups per CU) serves gradients with
+// few 256-tiles, where filling the chip would otherwise take so many K chunks that their fp32
+// partial slabs outweigh the operand reads.
+template <int T, int WM, int WN>
+__global__ __launch_bounds__(64 * WM * WN) void k_rebuild_bf16_dma(const bf16_t* __restrict__ L,
+                                                                  const bf16_t* __restrict__ R,
+                                                                  float* __restrict__ out, int64_t K, int h_in,
+                                                                  int h_out, int64_t chunk, int tiles_m,
+                                                                  int tiles_n, int total) {
+    constexpr int WAVES = WM * WN;
+    constexpr int FA = T / (32 * WM), FB = T / (32 * WN);  // 32-wide fragments per wave
+    constexpr int ROWB = T * 2;                            // bytes per LDS row
+    constexpr int TILEB = rb::BK * ROWB;
+    constexpr int STAGEB = 2 * TILEB;
+    constexpr int CPR = ROWB / 16;                         // 16-byte chunks per row
+    constexpr int RPI = 64 / CPR;                          // tile rows covered by one load of a wave
+    static_assert(rb::BK == 2 * RPI * WAVES, "two loads per wave and operand cover a stage");
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int wm = wave >> 2, wn = wave & 3;
+    const int wm = wave / WN, wn = wave % WN;
 
     int lid = blockIdx.x;
     {
@@ -202,18 +216,18 @@ __global__ __launch_bounds__(rb::DMA_THREADS) void k_rebuild_bf16_dma(const bf16
         qn = tile % tiles_n;
         pm = tile / tiles_n;
     }
-    const int p0 = pm * rb::TILE, q0 = qn * rb::TILE;
+    const int p0 = pm * T, q0 = qn * T;
     const int64_t kbeg = (int64_t)split * chunk;
     const int64_t kend = (kbeg + chunk < K) ? kbeg + chunk : K;
     const int nk = (int)((kend - kbeg) / rb::BK);  // host guarantees whole tiles
 
-    // this lane's two rows per operand tile: row = 4*wave + 2*i + lane/32, LDS chunk position lane%32
+    // this lane's two rows per operand tile: row = 2*RPI*wave + RPI*i + lane/CPR, LDS chunk position lane%CPR
     const char* gl[2];
     const char* gr[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-        const int row = 4 * wave + 2 * i + (lane >> 5);
-        const int c = (lane & 31) ^ ((row & 3) << 2);
+        const int row = 2 * RPI * wave + RPI * i + lane / CPR;
+        const int c = (lane % CPR) ^ ((row & 3) << 2);
         gl[i] = reinterpret_cast<const char*>(L + (kbeg + row) * (int64_t)h_in + p0 + c * 8);
         gr[i] = reinterpret_cast<const char*>(R + (kbeg + row) * (int64_t)h_out + q0 + c * 8);
     }
@@ -222,25 +236,24 @@ __global__ __launch_bounds__(rb::DMA_THREADS) void k_rebuild_bf16_dma(const bf16
 
     auto issue = [&](int stage) {  // loads the next tile in sequence into ring slot `stage`
         // wave-uniform by construction; readfirstlane lets the compiler keep it in a scalar register
-        const uint32_t base =
-            __builtin_amdgcn_readfirstlane(lds0 + stage * rb::STAGEB + (4 * wave) * rb::ROWB);
+        const uint32_t base = __builtin_amdgcn_readfirstlane(lds0 + stage * STAGEB + (2 * RPI * wave) * ROWB);
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            dma16(gl[i], base + 2 * i * rb::ROWB);
+            dma16(gl[i], base + RPI * i * ROWB);
             gl[i] += adv_l;
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            dma16(gr[i], base + rb::TILEB + 2 * i * rb::ROWB);
+            dma16(gr[i], base + TILEB + RPI * i * ROWB);
             gr[i] += adv_r;
         }
     };
 
-    f32x16 acc[4][2];
+    f32x16 acc[FA][FB];
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < FA; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < FB; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
@@ -252,19 +265,19 @@ __global__ __launch_bounds__(rb::DMA_THREADS) void k_rebuild_bf16_dma(const bf16
     // tile is multiplied after the next tile's barrier, so the matrix cores have independent MFMAs to
     // chew on while the first fragments of the new tile travel from LDS:
     //   barrier | DMA(kt+3) | read set0(kt,0) | MFMA set1(kt-1,1) | read set1(kt,1) | MFMA set0(kt,0) | ...
-    bf16x8 fa0[4], fb0[2], fa1[4], fb1[2];
-    auto read_frags = [&](bf16x8 (&fa)[4], bf16x8 (&fb)[2], const char* tl, int ks) {
-        const char* tr = tl + rb::TILEB;
+    bf16x8 fa0[FA], fb0[FB], fa1[FA], fb1[FB];
+    auto read_frags = [&](bf16x8 (&fa)[FA], bf16x8 (&fb)[FB], const char* tl, int ks) {
+        const char* tr = tl + TILEB;
 #pragma unroll
-        for (int a = 0; a < 4; ++a) fa[a] = rb_frag(tl, wm * 128 + a * 32, ks * 16, lane);
+        for (int a = 0; a < FA; ++a) fa[a] = rb_frag<ROWB>(tl, wm * (FA * 32) + a * 32, ks * 16, lane);
 #pragma unroll
-        for (int b = 0; b < 2; ++b) fb[b] = rb_frag(tr, wn * 64 + b * 32, ks * 16, lane);
+        for (int b = 0; b < FB; ++b) fb[b] = rb_frag<ROWB>(tr, wn * (FB * 32) + b * 32, ks * 16, lane);
     };
-    auto mma = [&](const bf16x8 (&fa)[4], const bf16x8 (&fb)[2]) {
+    auto mma = [&](const bf16x8 (&fa)[FA], const bf16x8 (&fb)[FB]) {
 #pragma unroll
-        for (int a = 0; a < 4; ++a)
+        for (int a = 0; a < FA; ++a)
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
+            for (int b = 0; b < FB; ++b)
                 // R fragment as the MFMA's row operand: each lane then owns four consecutive q of one p
                 acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[b], fa[a], acc[a][b], 0, 0, 0);
     };
@@ -279,7 +292,7 @@ __global__ __launch_bounds__(rb::DMA_THREADS) void k_rebuild_bf16_dma(const bf16
             wait_vmcnt<0>();
         __syncthreads();  // everyone's part of tile kt is in LDS, and tile kt-1's slot is free
         if (kt + rb::DMA_STAGES - 1 < nk) issue((STAGE + rb::DMA_STAGES - 1) % rb::DMA_STAGES);
-        const char* tl = smem + STAGE * rb::STAGEB;
+        const char* tl = smem + STAGE * STAGEB;
         read_frags(fa0, fb0, tl, 0);
         __builtin_amdgcn_sched_barrier(0);
         if (kt > 0) mma(fa1, fb1);
@@ -300,11 +313,11 @@ __global__ __launch_bounds__(rb::DMA_THREADS) void k_rebuild_bf16_dma(const bf16
     // D[q][p] layout: lane holds p = lane % 32 and q = 8*g + 4*(lane/32) + 0..3 for g = 0..3: 16-byte stores
     float* o = out + (int64_t)split * h_in * h_out;
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < FA; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int p = p0 + wm * 128 + a * 32 + (lane & 31);
-            const int qb = q0 + wn * 64 + b * 32 + ((lane >> 5) << 2);
+        for (int b = 0; b < FB; ++b) {
+            const int p = p0 + wm * (FA * 32) + a * 32 + (lane & 31);
+            const int qb = q0 + wn * (FB * 32) + b * 32 + ((lane >> 5) << 2);
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 f32x4 v4 = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
@@ -315,58 +328,89 @@ __global__ __launch_bounds__(rb::DMA_THREADS) void k_rebuild_bf16_dma(const bf16
 
 
 bool rebuild_fast_ok(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt) {
-    return dt == DAD_BF16 && h_in % rb::TILE == 0 && h_out % rb::TILE == 0 && K >= 256 && h_in <= (1 << 20) &&
-           h_out <= (1 << 20);
+    if (dt != DAD_BF16 || K < 256 || h_in > (1 << 20) || h_out > (1 << 20)) return false;
+    if (h_in % 256 == 0 && h_out % 256 == 0) return true;
+    return h_in % 128 == 0 && h_out % 128 == 0 && K % rb::BK == 0;  // 128-tiles: whole K stages only
 }
 
-// Number of K chunks: fill the 256 CUs with whole rounds of workgroups while keeping the fp32
-// partial traffic (splits * h_in * h_out * 4 bytes) small next to the operand reads.
-SplitPlan rebuild_fast_split(int64_t K, int64_t h_in, int64_t h_out) {
-    const int64_t tiles = (h_in / rb::TILE) * (h_out / rb::TILE);
-    int best = 1;
+// Score of a tiling: share of the CU slots that whole rounds of workgroups fill, discounted by the
+// fp32 partial traffic (splits * h_in * h_out * 4 bytes written, read, and the result written) next
+// to the operand reads, and for 128-tiles by their doubled L2->LDS traffic per flop.
+static double rebuild_score(int64_t K, int64_t h_in, int64_t h_out, int tile, int s) {
+    const int64_t wg = (h_in / tile) * (h_out / tile) * s;
+    const int64_t slots = tile == 256 ? 256 : 512;
+    const double eff = (double)wg / (double)(ceil_div(wg, slots) * slots);
+    const double ops = (double)K * (h_in + h_out) * 2.0;
+    const double extra = s > 1 ? (2.0 * s + 1.0) * h_in * h_out * 4.0 : 0.0;
+    return eff / (1.0 + extra / ops) * (tile == 256 ? 1.0 : 0.8);
+}
+
+// Tile edge and number of K chunks.
+SplitPlan rebuild_fast_split(int64_t K, int64_t h_in, int64_t h_out, int* tile_out) {
+    int best = 1, best_tile = 0;
     double best_score = -1.0;
-    for (int s = 1; s <= 64; ++s) {
-        if (s > 1 && K / s < 1024) break;
-        const int64_t wg = tiles * s;
-        const double eff = (double)wg / (double)(ceil_div(wg, 256) * 256);
-        const double ops = (double)K * (h_in + h_out) * 2.0;
-        const double extra = s > 1 ? (2.0 * s + 1.0) * h_in * h_out * 4.0 : 0.0;
-        const double score = eff / (1.0 + extra / ops);
-        if (score > best_score * 1.02) {
-            best_score = score;
-            best = s;
+    for (int tile : {256, 128}) {
+        if (h_in % tile || h_out % tile) continue;
+        if (tile == 128 && K % rb::BK) continue;
+        for (int s = 1; s <= 64; ++s) {
+            if (s > 1 && K / s < 1024) break;
+            const double score = rebuild_score(K, h_in, h_out, tile, s);
+            if (score > best_score * 1.02) {
+                best_score = score;
+                best = s;
+                best_tile = tile;
+            }
         }
     }
     SplitPlan sp;
     sp.chunk = (int64_t)align_up((size_t)ceil_div(K, best), rb::BK);
     sp.splits = (int)ceil_div(K, sp.chunk);
+    *tile_out = best_tile;
     return sp;
 }
 
-dad_status fast_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, float* G, float* partials,
-                        SplitPlan sp, hipStream_t s) {
+template <int T, int WM, int WN>
+static dad_status launch_rebuild_dma(const void* L, const void* R, float* dst, int64_t K, int64_t h_in, int64_t h_out,
+                                     SplitPlan sp, hipStream_t s) {
+    const int lds = rb::DMA_STAGES * 2 * rb::BK * T * 2;
     static bool attr_set = false;
-    const int lds = rb::NSTAGE * rb::STAGEB, lds_dma = rb::DMA_STAGES * rb::STAGEB;
     if (!attr_set) {
-        DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_rebuild_bf16),
+        DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_rebuild_bf16_dma<T, WM, WN>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-        DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_rebuild_bf16_dma),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_dma));
         attr_set = true;
     }
-    const int tm = (int)(h_in / rb::TILE), tn = (int)(h_out / rb::TILE);
+    const int tm = (int)(h_in / T), tn = (int)(h_out / T);
     const int total = tm * tn * sp.splits;
+    ProfScope prof(KID_REBUILD_BF16_DMA, s);
+    hipLaunchKernelGGL((k_rebuild_bf16_dma<T, WM, WN>), dim3((unsigned)total), dim3(64 * WM * WN), lds, s, (const bf16_t*)L,
+                       (const bf16_t*)R, dst, K, (int)h_in, (int)h_out, sp.chunk, tm, tn, total);
+    DAD_LAUNCH_CHECK();
+    return DAD_OK;
+}
+
+dad_status fast_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, float* G, float* partials,
+                        SplitPlan sp, int tile, hipStream_t s) {
     float* dst = sp.splits == 1 ? G : partials;
+    dad_status rc;
     if (K % rb::BK == 0 && sp.chunk % rb::BK == 0) {
-        ProfScope prof(KID_REBUILD_BF16_DMA, s);
-        hipLaunchKernelGGL(k_rebuild_bf16_dma, dim3((unsigned)total), dim3(rb::DMA_THREADS), lds_dma, s, (const bf16_t*)L,
-                           (const bf16_t*)R, dst, K, (int)h_in, (int)h_out, sp.chunk, tm, tn, total);
-    } else {
+        rc = tile == 128 ? launch_rebuild_dma<128, 2, 2>(L, R, dst, K, h_in, h_out, sp, s)
+                         : launch_rebuild_dma<256, 2, 4>(L, R, dst, K, h_in, h_out, sp, s);
+        if (rc != DAD_OK) return rc;
+    } else {  // ragged K: register-staged kernel, 256-tiles (the plan never picks 128-tiles here)
+        static bool attr_set = false;
+        const int lds = rb::NSTAGE * rb::STAGEB;
+        if (!attr_set) {
+            DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_rebuild_bf16),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+            attr_set = true;
+        }
+        const int tm = (int)(h_in / rb::TILE), tn = (int)(h_out / rb::TILE);
+        const int total = tm * tn * sp.splits;
         ProfScope prof(KID_REBUILD_BF16, s);
         hipLaunchKernelGGL(k_rebuild_bf16, dim3((unsigned)total), dim3(256), lds, s, (const bf16_t*)L, (const bf16_t*)R,
                            dst, K, (int)h_in, (int)h_out, sp.chunk, tm, tn, total);
+        DAD_LAUNCH_CHECK();
     }
-    DAD_LAUNCH_CHECK();
     if (sp.splits > 1) return reduce_slabs(partials, G, h_in * h_out, sp.splits, s);
     return DAD_OK;
 }

@@ -95,7 +95,8 @@ def test_encoder_d768_reduced_rows(gpu, layer):
     (3, 600, 1024, 1024, 32), # N not a multiple of 256: register-staged MFMA kernels, ragged row tile
     (3, 256, 512, 256, 24),   # direct-to-LDS thin_nn with a padded panel (r < 32), register-staged thin_tn
     (4, 256, 256, 384, 48),   # the same with r between 32 and 64
-    (2, 256, 384, 640, 8),    # smallest rank the MFMA kernels take
+    (2, 256, 384, 640, 8),    # smallest rank the MFMA kernels take; widths multiples of 128 only: 128-tile rebuild
+    (3, 352, 640, 128, 16),   # 128-tile rebuild with a single column of tiles and K = 1056 (33 stages)
 ])
 def test_ragged_and_edge_shapes(gpu, dtype_idx, N_rows, h_in, h_out, r):
     w = W.WORKLOADS[dtype_idx]
