@@ -55,6 +55,13 @@ def test_encoder_d768_full(gpu, layer):
     run_full_size(w, layer, h_in, h_out, gpu)
 
 
+def test_encoder_shape_with_32768_rows(gpu):
+    """N = 32768: the thin_nn variant with 128 rows per workgroup (the workloads' own N use 64 and 256)."""
+    import dataclasses
+    w = dataclasses.replace(W.WORKLOADS[2], rows_per_site=8192)
+    run_full_size(w, 1, 768, 768, gpu)
+
+
 @pytest.mark.parametrize("layer", [0, 1, 2, 3])
 def test_gpt2_medium_layer_shapes_full(gpu, layer):
     w = W.WORKLOADS[3]

@@ -97,6 +97,8 @@ def test_encoder_d768_reduced_rows(gpu, layer):
     (4, 256, 256, 384, 48),   # the same with r between 32 and 64
     (2, 256, 384, 640, 8),    # smallest rank the MFMA kernels take; widths multiples of 128 only: 128-tile rebuild
     (3, 352, 640, 128, 16),   # 128-tile rebuild with a single column of tiles and K = 1056 (33 stages)
+    (3, 256, 384, 640, 16),   # direct-to-LDS thin_tn with 128-column strips (widths not multiples of 256)
+    (3, 256, 640, 384, 32),
 ])
 def test_ragged_and_edge_shapes(gpu, dtype_idx, N_rows, h_in, h_out, r):
     w = W.WORKLOADS[dtype_idx]
