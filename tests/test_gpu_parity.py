@@ -161,6 +161,28 @@ def test_steep_spectrum_keeps_orthonormality_and_degrades_gracefully(gpu, ratio,
     assert err <= bound
 
 
+@pytest.mark.parametrize("ratio,r", [(0.9, 32), (0.8, 32), (0.5, 16)])
+def test_steep_spectrum_bf16_path(gpu, ratio, r):
+    """The same on the bf16 MFMA path (sigma_1/sigma_r from 3e1 to 3e4): the N x r intermediates and the
+    panels are rounded to bf16, which puts a floor of about 2e-3 under the error but must not cost
+    rank or orthonormality."""
+    N, h_in, h_out = 1024, 256, 512
+    rng = np.random.default_rng([12, int(ratio * 10), r])
+    rnd = lambda x: W.bf16_bits_to_f32(W.f32_to_bf16_bits(x.astype(np.float32)))
+    A = rnd(rng.standard_normal((N, h_in)))
+    D = rnd(rng.standard_normal((N, h_out)) * (ratio ** np.arange(N))[:, None])
+    G0 = rng.standard_normal((r, h_out)).astype(np.float32)
+    ws = torch.empty(dad.compress_workspace_bytes(N, h_in, h_out, r, torch.bfloat16), dtype=torch.uint8, device=gpu)
+    Pt, Gt = dad.compress_rank(to_dev(A, "bf16", gpu), to_dev(D, "bf16", gpu), r, 2, torch.from_numpy(G0).to(gpu),
+                               workspace=ws)
+    assert dad.poll_numeric_status(ws) == dad.DAD_OK
+    g = Gt.cpu().numpy().astype(np.float64)
+    assert np.abs(g @ g.T - np.eye(r)).max() <= 1e-4
+    err = O.rel_fro(dad.reconstruct_grad(Pt, Gt).cpu().numpy(), O.rank_r_grad(*O.block_spi(A, D, G0, 2)))
+    print(ratio, r, err)
+    assert err <= TOL["bf16"]
+
+
 def test_rank_pairs_restack_and_recompress(gpu):
     """Algorithm 1: per-site rank-r pairs are stacked (N' = S*r rows) and compressed again."""
     w = W.WORKLOADS[0]
