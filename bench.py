@@ -39,9 +39,10 @@ def parse():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="gpt2_medium_stack")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--mode", default="one_level", choices=["one_level", "two_level", "backprop"],
+    ap.add_argument("--mode", default="one_level", choices=["one_level", "two_level", "backprop", "sequential"],
                     help="two_level: Algorithm 1 (per-site reduction, stack of the pairs, aggregator reduction, rebuild); "
-                         "backprop: the delta recursion of Eq. 3, every site writing its rows into the stacked buffer")
+                         "backprop: the delta recursion of Eq. 3, every site writing its rows into the stacked buffer; "
+                         "sequential: Algorithm 2 one singular pair at a time with peeling, one block of the stack")
     ap.add_argument("--per-site-calls", action="store_true",
                     help="backprop: one call per site (b rows each) instead of one call over all N rows")
     ap.add_argument("--no-graphs", action="store_true",
@@ -396,6 +397,102 @@ def backprop(args, w, dad, W, torch, np, dev):
     print(json.dumps(out_json))
 
 
+def sequential(args, w, dad, W, torch, np, dev):
+    """Algorithm 2 one singular pair at a time (dad_compress_rank_sequential) on the stacked factors
+    of ONE block of the model (its distinct layer shapes): r components x (4 n_iter + 2) thin passes,
+    each over a whole factor.  A step is one pass over that block; the metric is the time per layer,
+    to be read beside compress_us_per_layer of the default mode (the block form of the same method)."""
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    es = 2 if w.dtype == "bf16" else 4
+    N, r, n_iter = w.N, w.rank, w.n_iter
+    layers = w.all_layers()[:len(w.shapes)]
+    A, D, G0, Qt, sGt, sig = {}, {}, {}, {}, {}, {}
+    for li, hi, ho in layers:
+        As, Ds = W.device_factors(w, li, hi, ho, device=dev)
+        A[li], D[li] = dad.stack_factors(As, Ds)
+        del As, Ds
+        G0[li] = W.device_start_matrix(w, li, ho, device=dev)
+        Qt[li] = torch.empty((r, hi), dtype=torch.float32, device=dev)
+        sGt[li] = torch.empty((r, ho), dtype=torch.float32, device=dev)
+        sig[li] = torch.empty((r,), dtype=torch.float32, device=dev)
+    ws = torch.empty(max(dad.lib().dad_compress_sequential_workspace_bytes(N, hi, ho, dad._dt(A[li]))
+                         for li, hi, ho in layers), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+
+    def step():
+        for li, hi, ho in layers:
+            dad.compress_rank_sequential(A[li], D[li], r, n_iter, G0[li], Qt=Qt[li], sGt=sGt[li], sigma=sig[li],
+                                         workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    status = dad.poll_numeric_status(ws)
+    dad.profile_reset()
+    dad.profile_enable(True)
+    step()
+    torch.cuda.synchronize()
+    dad.profile_enable(False)
+    kern = dad.profile_read()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    passes = r * (2 * n_iter + 1)                      # over each of the two factors, per layer
+    bytes_ = sum(float(passes) * N * (hi + ho) * es for _, hi, ho in layers)
+    thin = {k: v for k, v in kern.items() if k.startswith("k_thin") and v[1] > 0}
+    thin_ms = sum(v[0] for v in thin.values())
+    dom = max(thin, key=lambda k: thin[k][0])
+    k_rate = bytes_ / (thin_ms * 1e-3) / 1e9           # all thin launches together stream `bytes_`
+    roofline = {"kernel": "+".join(sorted(thin)), "dominant": dom, "bound": "hbm", "achieved": k_rate,
+                "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": k_rate / PEAK_HBM_GBPS,
+                "avg_us": thin_ms * 1e3 / sum(v[1] for v in thin.values()), "traffic": None}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import dad_oracle as O
+        li, hi, ho = min(layers, key=lambda t: t[1] * t[2])
+        rows, rr = min(N, 16384), min(r, 8)
+        Ah = A[li][:rows].float().cpu().numpy().astype(np.float64)
+        Dh = D[li][:rows].float().cpu().numpy().astype(np.float64)
+        g0 = G0[li][:rr].cpu().numpy()
+        c0 = time.perf_counter()
+        Q_ref, sG_ref = O.sequential_spi(Ah, Dh, g0, n_iter)
+        c1 = time.perf_counter()
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            threads = os.cpu_count()
+        q, sg, _ = dad.compress_rank_sequential(A[li][:rows].contiguous(), D[li][:rows].contiguous(), rr, n_iter,
+                                                G0[li][:rr].contiguous(), check=True)
+        e = O.rel_fro(dad.reconstruct_grad(q, sg).cpu().numpy(), Q_ref.T @ sG_ref)
+        tol = 2e-2 if w.dtype == "bf16" else 1e-5
+        cpu = {"value": (c1 - c0) * 1e6, "unit": "us/layer", "cores": int(threads), "kind": "oracle",
+               "sample": f"{rows} of {N} rows, {rr} of {r} components of one layer ({hi}x{ho}): "
+                         f"fp64 numpy sequential_spi {c1 - c0:.2f} s",
+               "parity_rel_fro": {"rank_r_gradient": e, "tol": tol}, "host_cpus": os.cpu_count()}
+        if not e <= tol:
+            print(f"bench.py: parity check failed: {e:.3e}", file=sys.stderr)
+            sys.exit(1)
+
+    print(json.dumps({
+        "metric": "dAD sequential SPI (Algorithm 2 with peeling) time per layer on the stacked factors",
+        "value": ms_per_step * 1e3 / len(layers), "unit": "us/layer", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name + "/sequential", "layers": len(layers), "shapes": [list(x[1:]) for x in layers],
+                   "N": N, "rank": r, "n_iter": n_iter, "factor_passes_per_layer": 2 * passes},
+        "hbm_GBps": bytes_ / (ms_per_step * 1e-3) / 1e9, "numeric_status": int(status),
+        "roofline": roofline,
+        "kernels": {k: {"ms_per_step": v[0], "launches_per_step": v[1], "avg_us": v[0] * 1e3 / v[1]}
+                    for k, v in kern.items() if v[1] > 0},
+        "cpu_baseline": cpu,
+    }))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -420,6 +517,8 @@ def main():
         return two_level(args, w, dad, W, torch, np, dev)
     if args.mode == "backprop":
         return backprop(args, w, dad, W, torch, np, dev)
+    if args.mode == "sequential":
+        return sequential(args, w, dad, W, torch, np, dev)
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     es = 2 if w.dtype == "bf16" else 4
     N, r, n_iter, S, b = w.N, w.rank, w.n_iter, w.sites, w.rows_per_site

@@ -115,6 +115,31 @@ dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_
                              dad_dtype dt, int r, int n_iter, const float* G0, float* Pt, float* Gt,
                              void* workspace, size_t ws_bytes, void* stream);
 
+/* Bytes of device workspace dad_compress_rank_sequential needs (0 on invalid sizes). */
+size_t dad_compress_sequential_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, dad_dtype dt);
+
+/*
+ * dad_compress_rank_sequential - Algorithm 2 as printed (Section 3.3.1, Eq. 5-7): one singular
+ * pair at a time, with peeling.  Component j starts from g = G0[j] / ||G0[j]|| and applies
+ *     g <- normalise( M^T M g - sum_{i<j} sigma_i^2 g_i (g_i^T g) )
+ * exactly n_iter times (the deflation of M^T M by the pairs already found stands in for the printed
+ * Q (G^T g), whose vectors have two different lengths; the threshold theta of the listing is not
+ * implemented).  Then v = Delta g, sigma_j = ||A^T v||, q_j = A^T v / sigma_j.
+ *
+ *   A, D, N, h_in, h_out, dt, r, n_iter, G0   as for dad_compress_rank
+ *   Qt        device out, r x h_in fp32: row j = q_j, unit length
+ *   sGt       device out, r x h_out fp32: row j = sigma_j g_j, so that M ~ Qt^T sGt and the pair can
+ *             be passed to dad_reconstruct_grad or stacked like the pair of dad_compress_rank
+ *   sigma     device out, r fp32 singular-value estimates, or NULL
+ *   workspace device, ws_bytes >= dad_compress_sequential_workspace_bytes(...)
+ * Every thin pass over a factor costs the same for one vector as for r of them, so this call costs
+ * about r times dad_compress_rank; it exists as the paper's own recurrence.  A vanishing iterate
+ * (rank exhausted) latches DAD_ERR_NUMERIC for dad_poll_numeric_status.
+ */
+dad_status dad_compress_rank_sequential(const void* A, const void* D, int64_t N, int64_t h_in, int64_t h_out,
+                                        dad_dtype dt, int r, int n_iter, const float* G0, float* Qt, float* sGt,
+                                        float* sigma, void* workspace, size_t ws_bytes, void* stream);
+
 /* Bytes of device workspace dad_reconstruct_grad needs (may be 0 for small K; 0 on invalid sizes). */
 size_t dad_reconstruct_workspace_bytes(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
 

@@ -52,6 +52,10 @@ def lib() -> C.CDLL:
     L.dad_reconstruct_workspace_bytes.argtypes = [i64, i64, i64, C.c_int]
     L.dad_reconstruct_grad.restype = C.c_int
     L.dad_reconstruct_grad.argtypes = [vp, vp, i64, i64, i64, C.c_int, vp, vp, sz, vp]
+    L.dad_compress_sequential_workspace_bytes.restype = sz
+    L.dad_compress_sequential_workspace_bytes.argtypes = [i64, i64, i64, C.c_int]
+    L.dad_compress_rank_sequential.restype = C.c_int
+    L.dad_compress_rank_sequential.argtypes = [vp, vp, i64, i64, i64, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, sz, vp]
     L.dad_backprop_delta.restype = C.c_int
     L.dad_backprop_delta.argtypes = [vp, vp, vp, i64, i64, i64, C.c_int, C.c_int, vp, vp]
     L.dad_poll_numeric_status.restype = C.c_int
@@ -154,6 +158,36 @@ def compress_rank(A, D, r, n_iter, G0, Pt=None, Gt=None, workspace=None, check=F
     if check:
         _check(lib().dad_poll_numeric_status(workspace.data_ptr(), _stream()), "dad_poll_numeric_status")
     return Pt, Gt
+
+
+def compress_rank_sequential(A, D, r, n_iter, G0, Qt=None, sGt=None, sigma=None, workspace=None, check=False):
+    """dad_compress_rank_sequential: the one-vector-at-a-time recurrence with peeling.
+
+    Returns (Qt r x h_in unit rows, sGt r x h_out rows sigma_j g_j, sigma r).
+    """
+    _dense2d(A, "A")
+    _dense2d(D, "D")
+    _dense2d(G0, "G0")
+    N, h_in = A.shape
+    h_out = D.shape[1]
+    if D.shape[0] != N or D.dtype != A.dtype:
+        raise ValueError("A and D disagree in rows or dtype")
+    if tuple(G0.shape) != (r, h_out) or G0.dtype != torch.float32:
+        raise ValueError("G0 must be r x h_out float32")
+    dt = _dt(A)
+    dev = A.device
+    Qt = torch.empty((r, h_in), dtype=torch.float32, device=dev) if Qt is None else Qt
+    sGt = torch.empty((r, h_out), dtype=torch.float32, device=dev) if sGt is None else sGt
+    sigma = torch.empty((r,), dtype=torch.float32, device=dev) if sigma is None else sigma
+    if workspace is None:
+        workspace = torch.empty(lib().dad_compress_sequential_workspace_bytes(N, h_in, h_out, dt), dtype=torch.uint8,
+                                device=dev)
+    _check(lib().dad_compress_rank_sequential(A.data_ptr(), D.data_ptr(), N, h_in, h_out, dt, r, n_iter, G0.data_ptr(),
+                                              Qt.data_ptr(), sGt.data_ptr(), sigma.data_ptr(), workspace.data_ptr(),
+                                              workspace.numel(), _stream()), "dad_compress_rank_sequential")
+    if check:
+        _check(lib().dad_poll_numeric_status(workspace.data_ptr(), _stream()), "dad_poll_numeric_status")
+    return Qt, sGt, sigma
 
 
 def reconstruct_workspace_bytes(K, h_in, h_out, dtype) -> int:

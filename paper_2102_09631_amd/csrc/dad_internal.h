@@ -122,6 +122,9 @@ struct CompressPlan {
 
 CompressPlan plan_compress(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
 
+// True when the bf16 MFMA thin kernels serve these sizes (otherwise the guarded kernels do).
+bool thin_fast_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
+
 struct RebuildPlan {
     SplitPlan split;
     size_t total;  // bytes of partials (0 when splits == 1)

@@ -110,6 +110,29 @@ def test_backprop_rejects_bad_arguments_on_host(lib):
     assert call(Z=p + 2) == dad.DAD_ERR_ALIGN      # shape served by the MFMA kernel
 
 
+def test_sequential_rejects_bad_arguments_on_host(lib):
+    p = 0x1000  # never dereferenced: every call below must fail before a launch
+    ws = 1 << 30
+
+    def call(A=p, D=p, N=64, hi=784, ho=128, dt=dad.DAD_F32, r=4, n=2, G0=p, Q=p, sG=p, sig=p, w=p, wb=ws):
+        return lib.dad_compress_rank_sequential(A, D, N, hi, ho, dt, r, n, G0, Q, sG, sig, w, wb, None)
+
+    assert call(A=None) == dad.DAD_ERR_NULL
+    assert call(Q=None) == dad.DAD_ERR_NULL
+    assert call(w=None) == dad.DAD_ERR_NULL
+    assert call(dt=2) == dad.DAD_ERR_DTYPE
+    assert call(r=0) == dad.DAD_ERR_SHAPE
+    assert call(r=65) == dad.DAD_ERR_SHAPE
+    assert call(N=3) == dad.DAD_ERR_SHAPE          # r > N
+    assert call(n=0) == dad.DAD_ERR_SHAPE
+    assert call(G0=p + 4) == dad.DAD_ERR_ALIGN
+    assert call(wb=16) == dad.DAD_ERR_WORKSPACE
+    need = lib.dad_compress_sequential_workspace_bytes(64, 784, 128, dad.DAD_F32)
+    assert need > 64 * 4 and call(wb=need - 1) == dad.DAD_ERR_WORKSPACE
+    assert lib.dad_compress_sequential_workspace_bytes(0, 784, 128, dad.DAD_F32) == 0
+    assert lib.dad_compress_sequential_workspace_bytes(64, 784, 128, 9) == 0
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(dad, "_lib", None)
     monkeypatch.setattr(dad, "LIB_PATH", str(tmp_path / "libdad.so"))
