@@ -47,6 +47,9 @@ def parse():
                     help="backprop: one call per site (b rows each) instead of one call over all N rows")
     ap.add_argument("--no-graphs", action="store_true",
                     help="two_level: launch eagerly instead of replaying one captured HIP graph per layer")
+    ap.add_argument("--agg-route", default="gram", choices=["gram", "block"],
+                    help="two_level: the aggregator's reduction of the S*r stacked rows runs on the Gram matrices "
+                         "of the stack (dad_compress_rank_gram, when S*r <= 1024) or as the block power iteration")
     ap.add_argument("--site-streams", type=int, default=8,
                     help="two_level: HIP streams (default priority) the independent per-site reductions are spread over")
     return ap.parse_args()
@@ -100,7 +103,10 @@ def two_level(args, w, dad, W, torch, np, dev):
     ws_s = [torch.empty(max(dad.compress_workspace_bytes(b, hi, ho, r, tdt) for _, hi, ho in layers),
                         dtype=torch.uint8, device=dev) for _ in range(n_str)]
     side = [torch.cuda.Stream(device=dev) for _ in range(n_str)] if n_str > 1 else []
-    ws_a = torch.empty(max(dad.compress_workspace_bytes(S * r, hi, ho, r, torch.float32) for _, hi, ho in layers),
+    agg_gram = args.agg_route == "gram" and S * r <= dad.DAD_GRAM_MAX_ROWS
+    agg_bytes = dad.compress_gram_workspace_bytes if agg_gram else dad.compress_workspace_bytes
+    agg_call = dad.compress_rank_gram if agg_gram else dad.compress_rank
+    ws_a = torch.empty(max(agg_bytes(S * r, hi, ho, r, torch.float32) for _, hi, ho in layers),
                        dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
     PH = ("site_compress", "stack_pairs", "agg_compress", "rebuild_rank")
@@ -146,7 +152,7 @@ def two_level(args, w, dad, W, torch, np, dev):
             if ev: ev[1].record()
             dad.stack_factors(Ps[sh], Gs[sh], A_out=Pst[sh], D_out=Gst[sh])
             if ev: ev[2].record()
-            dad.compress_rank(Pst[sh], Gst[sh], r, n_iter, G0a[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_a)
+            agg_call(Pst[sh], Gst[sh], r, n_iter, G0a[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_a)
             if ev: ev[3].record()
             dad.reconstruct_grad(Pt[li], Gt[li], G=G_hat[sh])
             if ev: ev[4].record()
@@ -170,7 +176,7 @@ def two_level(args, w, dad, W, torch, np, dev):
             As, Ds = factors_of(li)
             site_pass(li, sh, As, Ds)
             dad.stack_factors(Ps[sh], Gs[sh], A_out=Pst[sh], D_out=Gst[sh])
-            dad.compress_rank(Pst[sh], Gst[sh], r, n_iter, G0a[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_a)
+            agg_call(Pst[sh], Gst[sh], r, n_iter, G0a[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_a)
             dad.reconstruct_grad(Pt[li], Gt[li], G=G_hat[sh])
         for li, hi, ho in layers:
             g = torch.cuda.CUDAGraph()
@@ -204,7 +210,8 @@ def two_level(args, w, dad, W, torch, np, dev):
             phase_ms[ph] += ev[i].elapsed_time(ev[i + 1])
     phase_ms = {k: v / args.steps for k, v in phase_ms.items()}
     bytes_site = sum((2 * n_iter + 1.0) * N * (hi + ho) * es for _, hi, ho in layers)
-    bytes_agg = sum((2 * n_iter + 1.0) * S * r * (hi + ho) * 4 for _, hi, ho in layers)
+    agg_passes = 2.0 if agg_gram else 2 * n_iter + 1.0    # reads of each stacked factor
+    bytes_agg = sum(agg_passes * S * r * (hi + ho) * 4 for _, hi, ho in layers)
 
     # site-level thin kernels: the S calls together stream each factor once per contraction
     work = {}
@@ -218,7 +225,7 @@ def two_level(args, w, dad, W, torch, np, dev):
             else:
                 continue
             rows, e = (N, es) if (name.endswith("bf16") or w.dtype != "bf16") else (S * r, 4)
-            if w.dtype != "bf16":   # fp32 workloads: site and aggregator calls share the guarded kernels
+            if w.dtype != "bf16" and not agg_gram:   # fp32 workloads: site and aggregator calls share the guarded kernels
                 rows = N + S * r
             tot += sum(cnt * float(rows) * h * e for h, cnt in parts)
         if tot:
@@ -256,7 +263,7 @@ def two_level(args, w, dad, W, torch, np, dev):
             threads = os.cpu_count()
         site_pass(li, sh, As, Ds)
         dad.stack_factors(Ps[sh], Gs[sh], A_out=Pst[sh], D_out=Gst[sh])
-        dad.compress_rank(Pst[sh], Gst[sh], r, n_iter, G0a[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_a)
+        agg_call(Pst[sh], Gst[sh], r, n_iter, G0a[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_a)
         dad.reconstruct_grad(Pt[li], Gt[li], G=G_hat[sh])
         torch.cuda.synchronize()
         tol = 2e-2 if w.dtype == "bf16" else 1e-5
@@ -277,6 +284,7 @@ def two_level(args, w, dad, W, torch, np, dev):
         "config": {"workload": w.name + "/two_level", "layers": nl, "shapes": [list(s_) for s_ in w.shapes],
                    "sites": S, "rows_per_site": b, "aggregator_rows": S * r, "rank": r, "n_iter": n_iter,
                    "site_streams": n_str, "hip_graphs": use_graphs,
+                   "agg_route": "gram" if agg_gram else "block",
                    "resident_layers": len(resident)},
         "site_compress_us_per_layer": phase_ms["site_compress"] * 1e3 / nl,
         "site_compress_GBps": bytes_site / (phase_ms["site_compress"] * 1e-3) / 1e9,

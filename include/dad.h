@@ -58,6 +58,7 @@ typedef enum {
 } dad_status;
 
 #define DAD_MAX_RANK 64    /* largest r accepted by dad_compress_rank */
+#define DAD_GRAM_MAX_ROWS 1024 /* largest N accepted by dad_compress_rank_gram */
 #define DAD_MAX_SITES 4096 /* largest S accepted by dad_stack_factors */
 
 /* Human-readable name of a status code; static storage, never NULL. */
@@ -114,6 +115,31 @@ size_t dad_compress_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, int 
 dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_in, int64_t h_out,
                              dad_dtype dt, int r, int n_iter, const float* G0, float* Pt, float* Gt,
                              void* workspace, size_t ws_bytes, void* stream);
+
+/* Bytes of device workspace dad_compress_rank_gram needs (0 on invalid sizes, N > DAD_GRAM_MAX_ROWS included). */
+size_t dad_compress_gram_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
+
+/*
+ * dad_compress_rank_gram - the few-rows form of dad_compress_rank (Algorithm 2 with its
+ * precomputation C = A A^T, Eq. 6; the regime N << h of Section 3.3.1).  C = A A^T, E = D D^T and
+ * H0 = D G0^T are formed once in fp64; with every iterate written as G_k = D^T T_k the block power
+ * iteration and its Cholesky orthonormalisation (two rounds for the returned iterate, one for the
+ * others) run on N x N and N x r fp64 matrices:
+ *     Z_1 = C H0,  Z_k = C (E T_{k-1}),  Z_k^T E Z_k = R^T R,  T_k = Z_k R^-1,
+ * and the pair is Gt = T_n^T D, Pt = (E T_n)^T A.  Each factor is read twice instead of
+ * 2 n_iter + 1 times and the call is 9 launches for n_iter = 2.
+ *
+ * Arguments, outputs and errors are those of dad_compress_rank, with 1 <= N <= DAD_GRAM_MAX_ROWS
+ * (else DAD_ERR_SHAPE) and workspace >= dad_compress_gram_workspace_bytes(...).  Pt^T Gt is the same
+ * matrix as dad_compress_rank's up to rounding (the span of the iterate is the same); Pt and Gt
+ * themselves agree with it whenever the iterate is well conditioned (both come from Cholesky
+ * factors with a positive diagonal).  Squared conditioning is the price of the Gram form: the
+ * orthonormalisation holds to about 1e-16 cond(Y)^2 per round, and a non-positive pivot latches
+ * DAD_ERR_NUMERIC for dad_poll_numeric_status.
+ */
+dad_status dad_compress_rank_gram(const void* A, const void* D, int64_t N, int64_t h_in, int64_t h_out, dad_dtype dt,
+                                  int r, int n_iter, const float* G0, float* Pt, float* Gt, void* workspace,
+                                  size_t ws_bytes, void* stream);
 
 /* Bytes of device workspace dad_compress_rank_sequential needs (0 on invalid sizes). */
 size_t dad_compress_sequential_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, dad_dtype dt);

@@ -18,6 +18,7 @@ DAD_F32, DAD_BF16 = 0, 1
 DAD_OK, DAD_ERR_NULL, DAD_ERR_SHAPE, DAD_ERR_ALIGN, DAD_ERR_WORKSPACE, DAD_ERR_DTYPE, DAD_ERR_NUMERIC, \
     DAD_ERR_HIP = range(8)
 DAD_MAX_RANK = 64
+DAD_GRAM_MAX_ROWS = 1024
 DAD_ACT = {"identity": 0, "relu": 1, "tanh": 2, "sigmoid": 3}
 
 _lib = None
@@ -52,6 +53,10 @@ def lib() -> C.CDLL:
     L.dad_reconstruct_workspace_bytes.argtypes = [i64, i64, i64, C.c_int]
     L.dad_reconstruct_grad.restype = C.c_int
     L.dad_reconstruct_grad.argtypes = [vp, vp, i64, i64, i64, C.c_int, vp, vp, sz, vp]
+    L.dad_compress_gram_workspace_bytes.restype = sz
+    L.dad_compress_gram_workspace_bytes.argtypes = [i64, i64, i64, C.c_int, C.c_int]
+    L.dad_compress_rank_gram.restype = C.c_int
+    L.dad_compress_rank_gram.argtypes = [vp, vp, i64, i64, i64, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, sz, vp]
     L.dad_compress_sequential_workspace_bytes.restype = sz
     L.dad_compress_sequential_workspace_bytes.argtypes = [i64, i64, i64, C.c_int]
     L.dad_compress_rank_sequential.restype = C.c_int
@@ -155,6 +160,38 @@ def compress_rank(A, D, r, n_iter, G0, Pt=None, Gt=None, workspace=None, check=F
     _check(lib().dad_compress_rank(A.data_ptr(), D.data_ptr(), N, h_in, h_out, dt, r, n_iter, G0.data_ptr(),
                                    Pt.data_ptr(), Gt.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()),
            "dad_compress_rank")
+    if check:
+        _check(lib().dad_poll_numeric_status(workspace.data_ptr(), _stream()), "dad_poll_numeric_status")
+    return Pt, Gt
+
+
+def compress_gram_workspace_bytes(N, h_in, h_out, r, dtype) -> int:
+    return lib().dad_compress_gram_workspace_bytes(N, h_in, h_out, r, DAD_BF16 if dtype == torch.bfloat16 else DAD_F32)
+
+
+def compress_rank_gram(A, D, r, n_iter, G0, Pt=None, Gt=None, workspace=None, check=False):
+    """dad_compress_rank_gram: dad_compress_rank for N <= DAD_GRAM_MAX_ROWS rows, iterating on A A^T and
+    Delta Delta^T; same arguments and outputs as compress_rank."""
+    _dense2d(A, "A")
+    _dense2d(D, "Delta")
+    _dense2d(G0, "G0")
+    N, h_in = A.shape
+    h_out = D.shape[1]
+    if D.shape[0] != N or D.dtype != A.dtype:
+        raise ValueError("A and Delta disagree in rows or dtype")
+    if G0.dtype != torch.float32 or tuple(G0.shape) != (r, h_out):
+        raise ValueError("G0 must be float32 of shape (r, h_out)")
+    dt = _dt(A)
+    if workspace is None:
+        nbytes = lib().dad_compress_gram_workspace_bytes(N, h_in, h_out, r, dt)
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=A.device)
+    if Pt is None:
+        Pt = torch.empty((r, h_in), dtype=torch.float32, device=A.device)
+    if Gt is None:
+        Gt = torch.empty((r, h_out), dtype=torch.float32, device=A.device)
+    _check(lib().dad_compress_rank_gram(A.data_ptr(), D.data_ptr(), N, h_in, h_out, dt, r, n_iter, G0.data_ptr(),
+                                        Pt.data_ptr(), Gt.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()),
+           "dad_compress_rank_gram")
     if check:
         _check(lib().dad_poll_numeric_status(workspace.data_ptr(), _stream()), "dad_poll_numeric_status")
     return Pt, Gt

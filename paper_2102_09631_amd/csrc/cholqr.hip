@@ -12,6 +12,7 @@
 // Products of two fp32 values are exact in fp64, so the Gram matrix carries no
 // rounding beyond its final sums and CholeskyQR tolerates condition numbers far
 // beyond the fp32 limit.  The partials are accumulated by the fp64 matrix instruction.
+#include "chol_factor.h"
 #include "dad_internal.h"
 
 namespace dad {
@@ -23,10 +24,7 @@ constexpr int QR_LD = DAD_MAX_RANK + 1;
 struct QrShared {
     union {
         float Ys[DAD_MAX_RANK][QR_COLS + 1];  // tile of Yt (or of the result)
-        struct {
-            double colS[2][2][DAD_MAX_RANK];  // columns k, k+1 of the running S, double buffered over steps
-            double rowT[2][2][DAD_MAX_RANK];  // rows k, k+1 of the running inverse
-        } f;
+        FactorShared f;
     };
     float Rs[DAD_MAX_RANK][QR_LD];  // R^{-1} applied by this launch
     int last;
@@ -70,19 +68,14 @@ __device__ __forceinline__ void gram_of_tile(const float (*Ys)[QR_COLS + 1], Gra
     }
 }
 
-// Runs in every workgroup after its Gram partial `acc` is complete; the workgroup that takes the
-// last ticket sums all partials (block order ascending) and factorises:
-// S = L L^T and X = L^{-1} by one right-looking sweep over k in fp64 registers.  Pivot k needs
-// column k of the running S and row k of the running inverse T (T starts as I), published through LDS; then
-//     L[i][k] = S[i][k] / sqrt(S[k][k]),  X[k][j] = T[k][j] / sqrt(S[k][k]),
-//     S[i][j] -= L[i][k] L[j][k],         T[i][j] -= L[i][k] X[k][j]      for i > k.
-// R^{-1} = X^T (upper triangular) is written as fp32.  A pivot that is not > 0 (or NaN) latches
-// *flag and is replaced by 1 so the sweep still ends with finite arithmetic.
+// Runs in every workgroup after its Gram partial `acc` is complete: the partial is published and the
+// workgroup that takes the last ticket sums all partials and factorises (factor_partials); R^{-1}
+// is written as fp32.
 template <int NA>
 __device__ __forceinline__ void last_block_factor(QrShared& sh, const GramAcc<NA>& acc, double* __restrict__ gram_part,
                                                   int nblocks, int r, int* __restrict__ counter,
                                                   float* __restrict__ rinv, int* __restrict__ flag) {
-    const int t = threadIdx.x, ti = t >> 4, tj = t & 15;
+    const int t = threadIdx.x;
     const int nent = r * r;
     double* mine = gram_part + (int64_t)blockIdx.x * nent;
     {
@@ -106,135 +99,7 @@ __device__ __forceinline__ void last_block_factor(QrShared& sh, const GramAcc<NA
     if (!sh.last) return;
     __threadfence();
 
-    double S[NA][NA], T[NA][NA];
-#pragma unroll
-    for (int a = 0; a < NA; ++a)
-#pragma unroll
-        for (int b = 0; b < NA; ++b) {
-            S[a][b] = 0.0;
-            T[a][b] = (ti + 16 * a == tj + 16 * b) ? 1.0 : 0.0;
-        }
-    constexpr int NB = NA == 2 ? 8 : 4;  // partials in flight per thread
-    for (int b0 = 0; b0 < nblocks; b0 += NB) {
-        double v[NB][NA][NA];
-#pragma unroll
-        for (int u = 0; u < NB; ++u)
-#pragma unroll
-            for (int a = 0; a < NA; ++a)
-#pragma unroll
-                for (int b = 0; b < NA; ++b) {
-                    const int i = ti + 16 * a, j = tj + 16 * b;
-                    v[u][a][b] = (b0 + u < nblocks && i < r && j < r)
-                                     ? __builtin_nontemporal_load(gram_part + (int64_t)(b0 + u) * nent + i * r + j)
-                                     : 0.0;
-                }
-#pragma unroll
-        for (int u = 0; u < NB; ++u)
-#pragma unroll
-            for (int a = 0; a < NA; ++a)
-#pragma unroll
-                for (int b = 0; b < NA; ++b) S[a][b] += v[u][a][b];
-    }
-    // identity beyond r keeps the padded rows and columns inert
-#pragma unroll
-    for (int a = 0; a < NA; ++a)
-#pragma unroll
-        for (int b = 0; b < NA; ++b) {
-            const int i = ti + 16 * a, j = tj + 16 * b;
-            if (i >= r || j >= r) S[a][b] = (i == j) ? 1.0 : 0.0;
-        }
-
-    // Two pivots per step: columns k, k+1 of S and rows k, k+1 of T are published together and every
-    // thread redoes the small update of the second by the first (same operations, in the same order,
-    // as two single steps), which halves the number of barriers on this serial path.  For odd r the
-    // last step's second pivot is the inert identity padding.
-    bool bad = false;
-    for (int k = 0; k < r; k += 2) {
-        const int buf = (k >> 1) & 1, ka = k >> 4, kt = k & 15;
-        if (tj == kt || tj == kt + 1) {
-            const int which = tj - kt;
-#pragma unroll
-            for (int b = 0; b < NA; ++b)
-                if (b == ka) {
-#pragma unroll
-                    for (int a = 0; a < NA; ++a) sh.f.colS[buf][which][ti + 16 * a] = S[a][b];
-                }
-        }
-        if (ti == kt || ti == kt + 1) {
-            const int which = ti - kt;
-#pragma unroll
-            for (int a = 0; a < NA; ++a)
-                if (a == ka) {
-#pragma unroll
-                    for (int b = 0; b < NA; ++b) sh.f.rowT[buf][which][tj + 16 * b] = T[a][b];
-                }
-        }
-        __syncthreads();
-        const double* c0 = sh.f.colS[buf][0];
-        const double* c1 = sh.f.colS[buf][1];
-        const double* t0 = sh.f.rowT[buf][0];
-        const double* t1 = sh.f.rowT[buf][1];
-        // every LDS operand of the step is read up front and pinned, so that the reads are issued
-        // together and waited for once instead of one at a time inside the selects below
-        double piv0 = c0[k], ck1 = c0[k + 1], piv1 = c1[k + 1];
-        double ci0[NA], ci1[NA], cj0[NA], cj1[NA], tj0[NA], tj1[NA];
-#pragma unroll
-        for (int a = 0; a < NA; ++a) {
-            ci0[a] = c0[ti + 16 * a];
-            ci1[a] = c1[ti + 16 * a];
-            cj0[a] = c0[tj + 16 * a];
-            cj1[a] = c1[tj + 16 * a];
-            tj0[a] = t0[tj + 16 * a];
-            tj1[a] = t1[tj + 16 * a];
-        }
-        asm volatile("" : "+v"(piv0), "+v"(ck1), "+v"(piv1));
-#pragma unroll
-        for (int a = 0; a < NA; ++a)
-            asm volatile("" : "+v"(ci0[a]), "+v"(ci1[a]), "+v"(cj0[a]), "+v"(cj1[a]), "+v"(tj0[a]), "+v"(tj1[a]));
-        if (!(piv0 > 0.0)) {
-            bad = true;
-            piv0 = 1.0;
-        }
-        const double d0 = rsqrt(piv0);
-        const double m = ck1 * d0;  // L[k+1][k]
-        piv1 = fma(-m, m, piv1);
-        if (!(piv1 > 0.0)) {
-            bad = true;
-            piv1 = 1.0;
-        }
-        const double d1 = rsqrt(piv1);
-        double l0[NA], l1[NA], lt0[NA], lt1[NA], x0[NA], x1[NA];
-#pragma unroll
-        for (int a = 0; a < NA; ++a) {
-            const int i = ti + 16 * a;
-            const double v0 = ci0[a] * d0;
-            const double v1 = fma(-v0, m, ci1[a]) * d1;
-            l0[a] = (i > k) ? v0 : 0.0;
-            l1[a] = (i > k + 1) ? v1 : 0.0;
-            lt0[a] = cj0[a] * d0;
-            lt1[a] = fma(-lt0[a], m, cj1[a]) * d1;
-            x0[a] = tj0[a] * d0;
-            x1[a] = fma(-m, x0[a], tj1[a]) * d1;
-        }
-#pragma unroll
-        for (int a = 0; a < NA; ++a)
-#pragma unroll
-            for (int b = 0; b < NA; ++b) {
-                S[a][b] = fma(-l1[a], lt1[b], fma(-l0[a], lt0[b], S[a][b]));
-                T[a][b] = fma(-l1[a], x1[b], fma(-l0[a], x0[b], T[a][b]));
-            }
-        if (ti == kt) {  // R^{-1}[j][k] = X[k][j]
-#pragma unroll
-            for (int b = 0; b < NA; ++b) {
-                const int j = tj + 16 * b;
-                if (j < r) {
-                    rinv[j * r + k] = (float)x0[b];
-                    if (k + 1 < r) rinv[j * r + k + 1] = (float)x1[b];
-                }
-            }
-        }
-    }
-    if (bad && t == 0) *flag = 1;
+    factor_partials<NA, float>(sh.f, gram_part, nblocks, r, rinv, flag);
     if (t == 0) *counter = 0;
 }
 

@@ -73,7 +73,8 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 enum KernelId {
     KID_STACK = 0, KID_THIN_NN_BF16, KID_THIN_TN_BF16, KID_REDUCE, KID_GRAM, KID_APPLY, KID_APPLY2, KID_REBUILD_BF16,
-    KID_THIN_NN, KID_THIN_TN, KID_REBUILD, KID_PANEL_INIT, KID_REBUILD_BF16_DMA, KID_BACKPROP_BF16, KID_BACKPROP, KID_COUNT
+    KID_THIN_NN, KID_THIN_TN, KID_REBUILD, KID_PANEL_INIT, KID_REBUILD_BF16_DMA, KID_BACKPROP_BF16, KID_BACKPROP,
+    KID_GRAM_TILES, KID_GRAM_GATHER, KID_NS_STEP, KID_NS_PROJECT, KID_COUNT
 };
 
 // Brackets the kernel launched inside its scope with two events when timing is enabled.

@@ -110,6 +110,29 @@ def test_backprop_rejects_bad_arguments_on_host(lib):
     assert call(Z=p + 2) == dad.DAD_ERR_ALIGN      # shape served by the MFMA kernel
 
 
+def test_gram_route_rejects_bad_arguments_on_host(lib):
+    p = 0x1000  # never dereferenced: every call below must fail before a launch
+    ws = 1 << 30
+
+    def call(A=p, D=p, N=64, hi=784, ho=128, dt=dad.DAD_F32, r=4, n=2, G0=p, Pt=p, Gt=p, w=p, wb=ws):
+        return lib.dad_compress_rank_gram(A, D, N, hi, ho, dt, r, n, G0, Pt, Gt, w, wb, None)
+
+    assert call(D=None) == dad.DAD_ERR_NULL
+    assert call(Gt=None) == dad.DAD_ERR_NULL
+    assert call(dt=5) == dad.DAD_ERR_DTYPE
+    assert call(N=dad.DAD_GRAM_MAX_ROWS + 1) == dad.DAD_ERR_SHAPE
+    assert call(N=0) == dad.DAD_ERR_SHAPE
+    assert call(r=65) == dad.DAD_ERR_SHAPE
+    assert call(N=3) == dad.DAD_ERR_SHAPE          # r > N
+    assert call(n=0) == dad.DAD_ERR_SHAPE
+    assert call(Pt=p + 8) == dad.DAD_ERR_ALIGN
+    need = lib.dad_compress_gram_workspace_bytes(64, 784, 128, 4, dad.DAD_F32)
+    assert need > 2 * 64 * 64 * 8 and call(wb=need - 1) == dad.DAD_ERR_WORKSPACE
+    assert lib.dad_compress_gram_workspace_bytes(dad.DAD_GRAM_MAX_ROWS + 1, 784, 128, 4, dad.DAD_F32) == 0
+    assert lib.dad_compress_gram_workspace_bytes(64, 784, 128, 4, 3) == 0
+    assert lib.dad_compress_gram_workspace_bytes(1024, 1280, 5120, 64, dad.DAD_F32) < (1 << 27)
+
+
 def test_sequential_rejects_bad_arguments_on_host(lib):
     p = 0x1000  # never dereferenced: every call below must fail before a launch
     ws = 1 << 30
