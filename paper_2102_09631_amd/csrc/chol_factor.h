@@ -20,10 +20,13 @@ struct FactorShared {
 //     S[i][j] -= L[i][k] L[j][k],         T[i][j] -= L[i][k] X[k][j]      for i > k.
 // R^{-1} = X^T (upper triangular, row-major r x r) is written in the type RT.  A pivot that is not
 // > 0 (or NaN) latches *flag and is replaced by 1 so the sweep still ends with finite arithmetic.
+// piv_range, when given, receives the smallest and the largest pivot (squares of the diagonal of R):
+// their ratio bounds the squared condition number of the factorised iterate from below.
 // Every thread of the workgroup must call it; the caller synchronises before `f` is reused.
 template <int NA, typename RT>
 __device__ __forceinline__ void factor_partials(FactorShared& f, const double* __restrict__ gram_part, int nblocks, int r,
-                                                RT* __restrict__ rinv, int* __restrict__ flag) {
+                                                RT* __restrict__ rinv, int* __restrict__ flag,
+                                                double* __restrict__ piv_range = nullptr) {
     const int t = threadIdx.x, ti = t >> 4, tj = t & 15;
     const int nent = r * r;
     double S[NA][NA], T[NA][NA];
@@ -69,6 +72,7 @@ __device__ __forceinline__ void factor_partials(FactorShared& f, const double* _
     // as two single steps), which halves the number of barriers on this serial path.  For odd r the
     // last step's second pivot is the inert identity padding.
     bool bad = false;
+    double pmin = 1.7976931348623157e308, pmax = 0.0;
     for (int k = 0; k < r; k += 2) {
         const int buf = (k >> 1) & 1, ka = k >> 4, kt = k & 15;
         if (tj == kt || tj == kt + 1) {
@@ -115,12 +119,18 @@ __device__ __forceinline__ void factor_partials(FactorShared& f, const double* _
             bad = true;
             piv0 = 1.0;
         }
+        pmin = piv0 < pmin ? piv0 : pmin;
+        pmax = piv0 > pmax ? piv0 : pmax;
         const double d0 = rsqrt(piv0);
         const double m = ck1 * d0;  // L[k+1][k]
         piv1 = fma(-m, m, piv1);
         if (!(piv1 > 0.0)) {
             bad = true;
             piv1 = 1.0;
+        }
+        if (k + 1 < r) {  // not the inert padding of an odd r
+            pmin = piv1 < pmin ? piv1 : pmin;
+            pmax = piv1 > pmax ? piv1 : pmax;
         }
         const double d1 = rsqrt(piv1);
         double l0[NA], l1[NA], lt0[NA], lt1[NA], x0[NA], x1[NA];
@@ -155,6 +165,10 @@ __device__ __forceinline__ void factor_partials(FactorShared& f, const double* _
         }
     }
     if (bad && t == 0) *flag = 1;
+    if (piv_range && t == 0) {
+        piv_range[0] = bad ? 0.0 : pmin;  // a breakdown reads as infinitely ill conditioned
+        piv_range[1] = pmax;
+    }
 }
 
 }  // namespace dad

@@ -40,15 +40,15 @@ __device__ __forceinline__ void tri_decode(int id, int nt, int& ti, int& tj) {
     tj = ti + id;
 }
 
-// Stage rows [row0, row0+64) x columns [k0, k0+64) of the virtual matrix [X; aug] (X: N x h of T,
-// aug: naug x h fp32, rows beyond both are zero, columns beyond kend are zero) into LDS as fp32.
+// Thread t's 16 entries (row t / 4, columns 16 (t % 4) ..) of the 64 x 64 block at rows row0..,
+// columns k0.. of the virtual matrix [X; aug] (X: N x h of T, aug: naug x h fp32; rows beyond both
+// and columns from kend on read as zero), as fp32 in registers.
 template <typename T>
-__device__ __forceinline__ void stage_rows(float (*Xs)[GLD], const T* __restrict__ X, const float* __restrict__ aug,
-                                           int64_t N, int naug, int64_t h, int64_t row0, int64_t k0, int64_t kend,
-                                           bool vec) {
+__device__ __forceinline__ void load_rows(float (&v)[16], const T* __restrict__ X, const float* __restrict__ aug,
+                                          int64_t N, int naug, int64_t h, int64_t row0, int64_t k0, int64_t kend,
+                                          bool vec) {
     const int t = threadIdx.x, row = t >> 2, seg = (t & 3) * 16;
     const int64_t gi = row0 + row, k = k0 + seg;
-    float v[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) v[i] = 0.f;
     if (gi < N) {
@@ -83,6 +83,10 @@ __device__ __forceinline__ void stage_rows(float (*Xs)[GLD], const T* __restrict
         for (int i = 0; i < 16; ++i)
             if (k + i < kend) v[i] = p[i];
     }
+}
+
+__device__ __forceinline__ void store_rows(float (*Xs)[GLD], const float (&v)[16]) {
+    const int t = threadIdx.x, row = t >> 2, seg = (t & 3) * 16;
 #pragma unroll
     for (int q = 0; q < 4; ++q)
         *reinterpret_cast<float4*>(&Xs[row][seg + 4 * q]) = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
@@ -131,15 +135,26 @@ __global__ __launch_bounds__(256) void k_gram_tiles(const T* __restrict__ A, con
     for (int p = 0; p < 2; ++p)
 #pragma unroll
         for (int q = 0; q < 2; ++q) acc[p][q] = f64x4{0.0, 0.0, 0.0, 0.0};
+    // a diagonal pair multiplies one block of rows by itself; the next stage's loads are in flight
+    // while the current one is multiplied
+    const bool diag = ti == tj;
+    const float (*Jp)[GLD] = diag ? Is : Js;
+    float vi[16], vj[16];
+    load_rows<T>(vi, X, G0, N, naug, h, (int64_t)ti * GT, kbeg, kend, vec);
+    if (!diag) load_rows<T>(vj, X, G0, N, naug, h, (int64_t)tj * GT, kbeg, kend, vec);
     for (int64_t k0 = kbeg; k0 < kend; k0 += GK) {
         __syncthreads();
-        stage_rows<T>(Is, X, G0, N, naug, h, (int64_t)ti * GT, k0, kend, vec);
-        stage_rows<T>(Js, X, G0, N, naug, h, (int64_t)tj * GT, k0, kend, vec);
+        store_rows(Is, vi);
+        if (!diag) store_rows(Js, vj);
         __syncthreads();
+        if (k0 + GK < kend) {
+            load_rows<T>(vi, X, G0, N, naug, h, (int64_t)ti * GT, k0 + GK, kend, vec);
+            if (!diag) load_rows<T>(vj, X, G0, N, naug, h, (int64_t)tj * GT, k0 + GK, kend, vec);
+        }
 #pragma unroll 4
         for (int kk = 0; kk < GK / 4; ++kk) {
             const double a0 = (double)Is[wr + li][4 * kk + lk], a1 = (double)Is[wr + 16 + li][4 * kk + lk];
-            const double b0 = (double)Js[wc + li][4 * kk + lk], b1 = (double)Js[wc + 16 + li][4 * kk + lk];
+            const double b0 = (double)Jp[wc + li][4 * kk + lk], b1 = (double)Jp[wc + 16 + li][4 * kk + lk];
             acc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc[0][0], 0, 0, 0);
             acc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc[0][1], 0, 0, 0);
             acc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc[1][0], 0, 0, 0);
@@ -181,10 +196,12 @@ __global__ __launch_bounds__(256) void k_gram_gather(const double* __restrict__ 
         for (int q0 = 0; q0 < splits; q0 += 8) {  // eight loads in flight, summed in ascending order
             double v[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
-                v[u] = q0 + u < splits ? __builtin_nontemporal_load(src + (int64_t)(q0 + u) * (GT * GT) + e) : 0.0;
+            for (int u = 0; u < 8; ++u) {  // always a valid address, so that no load waits on a branch
+                const int q = q0 + u < splits ? q0 + u : splits - 1;
+                v[u] = __builtin_nontemporal_load(src + (int64_t)q * (GT * GT) + e);
+            }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) s += v[u];
+            for (int u = 0; u < 8; ++u) s += q0 + u < splits ? v[u] : 0.0;
         }
         const int64_t i = (int64_t)ti * GT + e / GT, j = (int64_t)tj * GT + e % GT;
         if (isC) {
@@ -208,16 +225,21 @@ __global__ __launch_bounds__(256) void k_gram_gather(const double* __restrict__ 
 enum { NS_CV = 0, NS_EZ = 1, NS_REFINE = 2, NS_APPLY = 3 };
 
 constexpr int NS_ROWS = 16;   // rows of the N x r matrices per workgroup
-constexpr int NS_CH = 64;     // rows of the right operand per LDS stage
+constexpr int NS_IN = 8192;   // entries of the right operand per LDS stage (NS_IN / (16 NA) rows)
 constexpr int NS_LD = DAD_MAX_RANK + 1;
+// Largest ratio of Cholesky pivots (squared diagonal of R) up to which one round is taken to be enough:
+// the orthonormality error of one fp64 round is about 1e-16 cond(Y)^2, and cond(Y)^2 is at least this ratio.
+constexpr double NS_REFINE_SPREAD = 1e6;
 
-// The product phase and the phases after it never overlap in time, so they share LDS.
+// Lives in dynamic LDS (about 100 KB).  The product phase and the phases after it never overlap in
+// time, so they share storage.
 template <int NA>
 struct NsShared {
+    static constexpr int CH = NS_IN / (16 * NA);  // rows of the right operand per stage: 256 or 128
     union {
         struct {
-            double In[NS_CH * 16 * NA];     // NS_CH rows x r of the right operand, as in memory
-            double Ss[NS_ROWS][NS_CH + 1];  // 16 rows x NS_CH columns of the symmetric matrix
+            double In[NS_IN];             // CH rows x r of the right operand, as in memory
+            double Ss[NS_ROWS][CH + 1];   // 16 rows x CH columns of the symmetric matrix
         } m;
         struct {
             double Zs[NS_ROWS][NS_LD];
@@ -225,26 +247,34 @@ struct NsShared {
             FactorShared f;
         } g;
     };
-    double Rp[16 * NA * (16 * NA + 1) / 2];  // upper triangle of R^-1, column by column: (i, j) at j (j + 1) / 2 + i
+    double Rs[16 * NA][16 * NA + 1];  // R^-1 (upper triangular; the zeros below the diagonal are stored)
     int last;
 };
 
-// out[col] = sum_{i <= col} tile[row][i] * R^-1[i][col] for the NA columns this thread owns.
+// out[col] = sum_{i <= col} tile[row][i] * R^-1[i][col] for the NA columns this thread owns; eight
+// terms are read from LDS together (the index is clamped; terms beyond the column are masked).
 template <int NA>
-__device__ __forceinline__ void tri_apply(const double (*tile)[NS_LD], const double* Rp, int row, int cg, int r,
-                                          double (&out)[NA]) {
+__device__ __forceinline__ void tri_apply(const double (*tile)[NS_LD], const double (*Rs)[16 * NA + 1], int row, int cg,
+                                          int r, double (&out)[NA]) {
 #pragma unroll
     for (int b = 0; b < NA; ++b) {
         const int col = cg + 16 * b;
         double s0 = 0.0, s1 = 0.0;
         if (col < r) {
-            const double* rc = Rp + col * (col + 1) / 2;
-            int i = 0;
-            for (; i + 1 <= col; i += 2) {
-                s0 = fma(tile[row][i], rc[i], s0);
-                s1 = fma(tile[row][i + 1], rc[i + 1], s1);
+            for (int i0 = 0; i0 <= col; i0 += 8) {
+                double a[8], c[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int i = i0 + u <= col ? i0 + u : col;
+                    a[u] = tile[row][i];
+                    c[u] = Rs[i][col];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; u += 2) {
+                    s0 = fma(i0 + u <= col ? a[u] : 0.0, c[u], s0);
+                    s1 = fma(i0 + u + 1 <= col ? a[u + 1] : 0.0, c[u + 1], s1);
+                }
             }
-            if (i <= col) s0 = fma(tile[row][i], rc[i], s0);
         }
         out[b] = s0 + s1;
     }
@@ -256,78 +286,165 @@ __device__ __forceinline__ void tri_apply(const double (*tile)[NS_LD], const dou
 //   NS_EZ      F = S Z                  S = E; then Gram partial Z^T F, last workgroup -> rout
 //   NS_REFINE  Z <- Z Rin^-1, F <- F Rin^-1 in place; Gram partial of the result -> rout
 //   NS_APPLY   Tf = Z Rin^-1, Vf = F Rin^-1 as fp32 with row pitch `pitch` (columns r.. zero)
-// The product streams S and In through LDS in stages of NS_CH rows; the loads of the next stage are
+// The product streams S and In through LDS in stages of CH rows; the loads of the next stage are
 // in flight while the current one is multiplied.
 template <int NA, int MODE>
 __global__ __launch_bounds__(256) void k_ns_step(const double* __restrict__ S, const double* In, double* Z, double* F,
                                                  const double* __restrict__ rin, double* __restrict__ rout,
                                                  float* __restrict__ Tf, float* __restrict__ Vf, int pitch, int64_t N,
                                                  int r, double* __restrict__ gram_part, int* __restrict__ counter,
-                                                 int* __restrict__ flag) {
-    __shared__ NsShared<NA> sh;
+                                                 int* __restrict__ flag, double* __restrict__ piv_range) {
+    extern __shared__ __attribute__((aligned(16))) char ns_smem[];
+    NsShared<NA>& sh = *reinterpret_cast<NsShared<NA>*>(ns_smem);
+    constexpr int CH = NsShared<NA>::CH;
     const int t = threadIdx.x, row = t >> 4, cg = t & 15;
     const int64_t g0 = (int64_t)blockIdx.x * NS_ROWS, gi = g0 + row;
     const bool live = gi < N;
-    if (MODE != NS_EZ && rin) {
-        for (int e = t; e < r * r; e += 256) {
-            const int i = e / r, j = e % r;
-            if (i <= j) sh.Rp[j * (j + 1) / 2 + i] = rin[e];
+    if (MODE == NS_REFINE) {
+        // The pivots of the first round bound the conditioning of the iterate from below; when their
+        // spread is small the first factor already orthonormalises to fp32 accuracy and more, and the
+        // second round reduces to handing that factor on.
+        const double pmin = piv_range[0], pmax = piv_range[1];
+        if (pmin > 0.0 && pmax <= NS_REFINE_SPREAD * pmin) {
+            if (blockIdx.x == 0)
+                for (int e = t; e < r * r; e += 256) rout[e] = rin[e];
+            return;
         }
     }
+    // R^-1 travels global -> registers now (clamped addresses, so that the loads go out together)
+    // and registers -> LDS just before the barrier in front of its first use.
+    double rv[NA * NA];
+    const bool use_r = MODE != NS_EZ && rin != nullptr;
+    if (use_r) {
+#pragma unroll
+        for (int m = 0; m < NA * NA; ++m) rv[m] = rin[t + 256 * m < r * r ? t + 256 * m : r * r - 1];
+    }
+    auto store_r = [&]() {
+        if (!use_r) return;
+#pragma unroll
+        for (int m = 0; m < NA * NA; ++m) {
+            const int e = t + 256 * m, i = e / r, j = e % r;
+            if (e < r * r) sh.Rs[i][j] = rv[m];
+        }
+    };
     double acc[NA];
 #pragma unroll
     for (int b = 0; b < NA; ++b) acc[b] = 0.0;
     double zown[NA];  // this thread's entries of Z (all modes but NS_CV)
     if (MODE != NS_CV) {
 #pragma unroll
-        for (int b = 0; b < NA; ++b) zown[b] = (live && cg + 16 * b < r) ? Z[gi * r + cg + 16 * b] : 0.0;
+        for (int b = 0; b < NA; ++b) {
+            const double v = Z[(live ? gi : N - 1) * r + (cg + 16 * b < r ? cg + 16 * b : r - 1)];
+            zown[b] = (live && cg + 16 * b < r) ? v : 0.0;
+        }
     }
     if (MODE == NS_CV || MODE == NS_EZ) {
         const double* src = MODE == NS_CV ? In : Z;
         const int64_t total = N * r;
-        constexpr int NI = 4 * NA;  // right-operand entries per thread and stage (NS_CH * r <= 256 NI)
-        double pin[NI], ps[4];
+        typedef double f64x2 __attribute__((ext_vector_type(2)));
+        constexpr int NI = NS_IN / 512;  // pairs of right-operand entries per thread and stage
+        constexpr int NSS = CH / 16;     // entries of S per thread and stage
+        f64x2 pin[NI];
+        double ps[NSS];
+        // Every load has a valid (clamped) address and its value is selected only when it is written
+        // to LDS a stage later: a load under a branch, or a select right behind it, would be waited
+        // for before the next load is issued.
+        const int64_t lastpair = total >= 2 ? ((total - 2) & ~(int64_t)1) : 0;  // the buffer is padded to 256 B
+        double tail = 0.0;
         auto fetch = [&](int64_t n0) {
+            tail = src[total - 1];
 #pragma unroll
             for (int m = 0; m < NI; ++m) {
-                const int e = t + 256 * m;
-                const int64_t idx = n0 * r + e;
-                pin[m] = (e < NS_CH * r && idx < total) ? src[idx] : 0.0;
+                const int64_t idx = n0 * r + 2 * (t + 256 * m);  // even: CH is even, and src is 16-byte aligned
+                pin[m] = *reinterpret_cast<const f64x2*>(src + (idx < lastpair ? idx : lastpair));
             }
 #pragma unroll
-            for (int m = 0; m < 4; ++m) {
-                const int e = t + 256 * m, rr = e >> 6, cc = e & 63;
-                ps[m] = (g0 + rr < N && n0 + cc < N) ? S[(g0 + rr) * N + n0 + cc] : 0.0;
+            for (int m = 0; m < NSS; ++m) {
+                const int e = t + 256 * m, rr = e / CH, cc = e % CH;
+                const int64_t gr = g0 + rr < N ? g0 + rr : N - 1, gc = n0 + cc < N ? n0 + cc : N - 1;
+                ps[m] = S[gr * N + gc];
             }
         };
-        fetch(0);
-        for (int64_t n0 = 0; n0 < N; n0 += NS_CH) {
-            __syncthreads();
+        auto commit = [&](int64_t n0) {
 #pragma unroll
-            for (int m = 0; m < NI; ++m)
-                if (t + 256 * m < NS_CH * 16 * NA) sh.m.In[t + 256 * m] = pin[m];
-#pragma unroll
-            for (int m = 0; m < 4; ++m) sh.m.Ss[(t + 256 * m) >> 6][(t + 256 * m) & 63] = ps[m];
-            __syncthreads();
-            if (n0 + NS_CH < N) fetch(n0 + NS_CH);
-#pragma unroll 8
-            for (int n = 0; n < NS_CH; ++n) {
-                const double c = sh.m.Ss[row][n];
-#pragma unroll
-                for (int b = 0; b < NA; ++b) {
-                    const int col = cg + 16 * b < r ? cg + 16 * b : 0;
-                    acc[b] = fma(c, sh.m.In[n * r + col], acc[b]);
+            for (int m = 0; m < NI; ++m) {
+                const int e = 2 * (t + 256 * m);
+                const int64_t idx = n0 * r + e;
+                f64x2 v = {0.0, 0.0};
+                if (e < CH * r) {
+                    if (idx + 1 < total)
+                        v = pin[m];
+                    else if (idx < total)
+                        v.x = tail;
                 }
+                *reinterpret_cast<f64x2*>(&sh.m.In[e]) = v;
+            }
+#pragma unroll
+            for (int m = 0; m < NSS; ++m) {
+                const int e = t + 256 * m, rr = e / CH, cc = e % CH;
+                sh.m.Ss[rr][cc] = (g0 + rr < N && n0 + cc < N) ? ps[m] : 0.0;
+            }
+        };
+        constexpr int LC = 4 * NA, TR = NA;  // lanes along the columns; rows per lane
+        const int lane = t & 63, wave = t >> 6, tc = lane % LC, tr = lane / LC;
+        int pcol[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) pcol[j] = tc + LC * j < r ? tc + LC * j : 0;  // columns from r on are not kept
+        double pacc[TR][4];
+#pragma unroll
+        for (int a = 0; a < TR; ++a)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) pacc[a][j] = 0.0;
+        fetch(0);
+        for (int64_t n0 = 0; n0 < N; n0 += CH) {
+            __syncthreads();
+            commit(n0);
+            __syncthreads();
+            if (n0 + CH < N) fetch(n0 + CH);
+            // LDS bandwidth bounds this product, so each lane owns a TR x 4 block of the 16 x r result
+            // (TR + 4 reads for 4 TR multiply-adds) and the four waves split the rows of the stage.
+            const int64_t rest = N - n0;
+            const int nlim = rest < CH ? (int)((rest + 15) & ~(int64_t)15) : CH;  // rows beyond N hold zeros
+            const int per = nlim / 4;
+            for (int n = wave * per; n < (wave + 1) * per; n += 4) {
+                double c[4][TR], v[4][4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+#pragma unroll
+                    for (int a = 0; a < TR; ++a) c[u][a] = sh.m.Ss[TR * tr + a][n + u];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v[u][j] = sh.m.In[(n + u) * r + pcol[j]];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int a = 0; a < TR; ++a)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) pacc[a][j] = fma(c[u][a], v[u][j], pacc[a][j]);
             }
         }
         __syncthreads();  // the product's LDS is free from here on
+        // the four waves' partial sums meet in LDS and are added in wave order
+        double (*red)[NS_ROWS][NS_LD] = reinterpret_cast<double (*)[NS_ROWS][NS_LD]>(sh.m.In);
+#pragma unroll
+        for (int a = 0; a < TR; ++a)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) red[wave][TR * tr + a][tc + LC * j] = pacc[a][j];
+        __syncthreads();
+#pragma unroll
+        for (int b = 0; b < NA; ++b) {
+            const int col = cg + 16 * b;
+            acc[b] = ((red[0][row][col] + red[1][row][col]) + red[2][row][col]) + red[3][row][col];
+        }
+        __syncthreads();
     }
     if (MODE == NS_CV) {
         if (rin) {
 #pragma unroll
             for (int b = 0; b < NA; ++b) sh.g.Zs[row][cg + 16 * b] = acc[b];
+            store_r();
             __syncthreads();
-            tri_apply<NA>(sh.g.Zs, sh.Rp, row, cg, r, acc);
+            tri_apply<NA>(sh.g.Zs, sh.Rs, row, cg, r, acc);
         }
         if (live) {
 #pragma unroll
@@ -342,14 +459,17 @@ __global__ __launch_bounds__(256) void k_ns_step(const double* __restrict__ S, c
         const int col = cg + 16 * b;
         const bool in = live && col < r;
         sh.g.Zs[row][col] = zown[b];
-        sh.g.Fs[row][col] = MODE == NS_EZ ? (in ? acc[b] : 0.0) : (in ? F[gi * r + col] : 0.0);
+        double fv = 0.0;
+        if (MODE != NS_EZ) fv = F[(live ? gi : N - 1) * r + (col < r ? col : r - 1)];
+        sh.g.Fs[row][col] = in ? (MODE == NS_EZ ? acc[b] : fv) : 0.0;
         if (MODE == NS_EZ && in) F[gi * r + col] = acc[b];
     }
+    store_r();
     __syncthreads();
     if (MODE == NS_REFINE || MODE == NS_APPLY) {
         double z[NA], f[NA];
-        tri_apply<NA>(sh.g.Zs, sh.Rp, row, cg, r, z);
-        tri_apply<NA>(sh.g.Fs, sh.Rp, row, cg, r, f);
+        tri_apply<NA>(sh.g.Zs, sh.Rs, row, cg, r, z);
+        tri_apply<NA>(sh.g.Fs, sh.Rs, row, cg, r, f);
         if (MODE == NS_APPLY) {
             if (live) {
 #pragma unroll
@@ -397,93 +517,107 @@ __global__ __launch_bounds__(256) void k_ns_step(const double* __restrict__ S, c
     __syncthreads();
     if (!sh.last) return;
     __threadfence();
-    factor_partials<NA, double>(sh.g.f, gram_part, (int)gridDim.x, r, rout, flag);
+    factor_partials<NA, double>(sh.g.f, gram_part, (int)gridDim.x, r, rout, flag, piv_range);
     if (t == 0) *counter = 0;
 }
 
 // ------------------------------------------------------------------------------------ projection
 
-constexpr int PJ_COLS = 64;       // columns per workgroup
+constexpr int PJ_COLS = 16;       // columns per workgroup
 constexpr int PJ_STAGE = 8192;    // floats of W per LDS stage (PJ_STAGE / RP rows)
-constexpr int PJ_BATCH = 32;      // rows of the factor whose loads a wave keeps in flight
 
-// out_t[j][c] = sum_n W[n][j] X[n][c] for one 64-column strip of X (N x h of T); W is N x RP fp32
+// out_t[j][c] = sum_n W[n][j] X[n][c] for one 16-column strip of X (N x h of T); W is N x RP fp32
 // (columns r.. are zero).  Strips [0, strips_in) belong to (A, Vf) -> Pt, the rest to (Delta, Tf)
-// -> Gt.  A stage of W is copied to LDS as it lies in memory; each wave takes a quarter of the
-// stage's rows with RP accumulators per lane, and the four waves are summed in wave order.
+// -> Gt.  Thread (rg = t / 16, col = t % 16) takes the rows rg, rg + 16, ... with RP accumulators:
+// narrow strips give a few hundred workgroups, and a wave reads four rows of W per LDS access.
+// The 16 row groups are summed in a fixed order (8..15 onto 0..7, then 0..7 in sequence).
 template <typename T, int RP>
 __global__ __launch_bounds__(256) void k_ns_project(const T* __restrict__ A, const T* __restrict__ D,
                                                     const float* __restrict__ Vf, const float* __restrict__ Tf,
                                                     float* __restrict__ Pt, float* __restrict__ Gt, int64_t N,
                                                     int64_t h_in, int64_t h_out, int r, int strips_in) {
     constexpr int SR = PJ_STAGE / RP;  // rows per stage
-    constexpr int WR = SR / 4;         // rows per wave and stage
-    constexpr int NBUF = 3 * RP * PJ_COLS > PJ_STAGE ? 3 * RP * PJ_COLS : PJ_STAGE;
-    // one buffer: the staged rows of W during the loop, the partial sums of waves 1..3 after it
-    __shared__ __attribute__((aligned(16))) float buf[NBUF];
+    constexpr int TRW = SR / 16;       // rows per thread and stage
+    // one buffer: the staged rows of W during the loop, the partial sums of the row groups after it
+    __shared__ __attribute__((aligned(16))) float buf[PJ_STAGE];
     float (*Ws)[RP] = reinterpret_cast<float (*)[RP]>(buf);
-    float (*red)[RP][PJ_COLS] = reinterpret_cast<float (*)[RP][PJ_COLS]>(buf);
+    float (*red)[RP][PJ_COLS] = reinterpret_cast<float (*)[RP][PJ_COLS]>(buf);  // 8 x RP x 16 <= PJ_STAGE
     const bool left = (int)blockIdx.x < strips_in;
     const T* X = left ? A : D;
     const float* W = left ? Vf : Tf;
     float* out = left ? Pt : Gt;
     const int64_t h = left ? h_in : h_out;
     const int64_t c0 = (int64_t)(left ? blockIdx.x : blockIdx.x - strips_in) * PJ_COLS;
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int64_t c = c0 + lane;
+    const int t = threadIdx.x, col = t & 15, rg = t >> 4;
+    const int64_t c = c0 + col;
     const bool colok = c < h;
+    const int64_t cc = colok ? c : h - 1;
     const int64_t wtotal = N * RP;
     float acc[RP];
 #pragma unroll
     for (int j = 0; j < RP; ++j) acc[j] = 0.f;
     for (int64_t n0 = 0; n0 < N; n0 += SR) {
+        // clamped addresses and no selects behind the loads, so that all of them go out together:
+        // rows from N on meet zero rows of W, columns from h on are not stored
         float4 wv[PJ_STAGE / 1024];
 #pragma unroll
         for (int m = 0; m < PJ_STAGE / 1024; ++m) {
             const int64_t idx = n0 * RP + 4 * (t + 256 * m);
-            wv[m] = idx < wtotal ? *reinterpret_cast<const float4*>(W + idx) : make_float4(0.f, 0.f, 0.f, 0.f);
+            wv[m] = *reinterpret_cast<const float4*>(W + (idx < wtotal ? idx : wtotal - 4));
+        }
+        float x[TRW];
+#pragma unroll
+        for (int i = 0; i < TRW; ++i) {
+            const int64_t n = n0 + rg + 16 * i;
+            x[i] = ld<T>(X, (n < N ? n : N - 1) * h + cc);
         }
         __syncthreads();
 #pragma unroll
-        for (int m = 0; m < PJ_STAGE / 1024; ++m) reinterpret_cast<float4*>(buf)[t + 256 * m] = wv[m];
+        for (int m = 0; m < PJ_STAGE / 1024; ++m) {
+            const float keep = n0 * RP + 4 * (t + 256 * m) < wtotal ? 1.f : 0.f;  // rows from N on become zero
+            reinterpret_cast<float4*>(buf)[t + 256 * m] =
+                make_float4(keep * wv[m].x, keep * wv[m].y, keep * wv[m].z, keep * wv[m].w);
+        }
         __syncthreads();
-        const int64_t left_rows = N - n0;  // rows of this stage that exist
-#pragma unroll 1
-        for (int b0 = 0; b0 < WR; b0 += PJ_BATCH) {
-            const int w0 = wave * WR + b0;  // first row of the batch inside the stage
-            if (w0 >= left_rows) break;
-            float x[PJ_BATCH];
+        const int64_t rest = N - n0;
 #pragma unroll
-            for (int i = 0; i < PJ_BATCH; ++i) {
-                const int64_t n = n0 + w0 + i;
-                x[i] = (colok && i < WR - b0 && n < N) ? ld<T>(X, n * h + c) : 0.f;
-            }
+        for (int i = 0; i < TRW; ++i) {
+            if (16 * i < rest) {  // uniform: skips the row groups of a short last stage
+                const float4* w4 = reinterpret_cast<const float4*>(Ws[rg + 16 * i]);
 #pragma unroll
-            for (int i = 0; i < PJ_BATCH; ++i) {
-                if (i < WR - b0) {
-                    const float4* w4 = reinterpret_cast<const float4*>(Ws[w0 + i]);
-#pragma unroll
-                    for (int q = 0; q < RP / 4; ++q) {
-                        const float4 w = w4[q];
-                        acc[4 * q] = fmaf(w.x, x[i], acc[4 * q]);
-                        acc[4 * q + 1] = fmaf(w.y, x[i], acc[4 * q + 1]);
-                        acc[4 * q + 2] = fmaf(w.z, x[i], acc[4 * q + 2]);
-                        acc[4 * q + 3] = fmaf(w.w, x[i], acc[4 * q + 3]);
-                    }
+                for (int q = 0; q < RP / 4; ++q) {
+                    const float4 w = w4[q];
+                    acc[4 * q] = fmaf(w.x, x[i], acc[4 * q]);
+                    acc[4 * q + 1] = fmaf(w.y, x[i], acc[4 * q + 1]);
+                    acc[4 * q + 2] = fmaf(w.z, x[i], acc[4 * q + 2]);
+                    acc[4 * q + 3] = fmaf(w.w, x[i], acc[4 * q + 3]);
                 }
             }
         }
     }
     __syncthreads();
-    if (wave > 0) {
+    if (rg >= 8) {
 #pragma unroll
-        for (int j = 0; j < RP; ++j) red[wave - 1][j][lane] = acc[j];
+        for (int j = 0; j < RP; ++j) red[rg - 8][j][col] = acc[j];
     }
     __syncthreads();
-    if (wave == 0 && colok) {
+    if (rg < 8) {
 #pragma unroll
-        for (int j = 0; j < RP; ++j)
-            if (j < r) out[(int64_t)j * h + c] = ((acc[j] + red[0][j][lane]) + red[1][j][lane]) + red[2][j][lane];
+        for (int j = 0; j < RP; ++j) acc[j] += red[rg][j][col];
+    }
+    __syncthreads();
+    if (rg < 8) {
+#pragma unroll
+        for (int j = 0; j < RP; ++j) red[rg][j][col] = acc[j];
+    }
+    __syncthreads();
+    // RP x 16 results, 8 partials each
+    for (int e = t; e < RP * PJ_COLS; e += 256) {
+        const int j = e / PJ_COLS, cl = e % PJ_COLS;
+        float s = red[0][j][cl];
+#pragma unroll
+        for (int g = 1; g < 8; ++g) s += red[g][j][cl];
+        if (j < r && c0 + cl < h) out[(int64_t)j * h + c0 + cl] = s;
     }
 }
 
@@ -505,12 +639,12 @@ static GramPlan plan_gram(int64_t N, int64_t h_in, int64_t h_out, int r) {
     J.nta = (int)ceil_div(N + r, GT);
     J.jobsC = tri_count(J.nt);
     J.jobsE = tri_count(J.nta);
-    // the longest column chunk that still gives about two workgroups per compute unit
+    // the longest column chunk that still gives about three workgroups per compute unit
     const int64_t hmax = h_in > h_out ? h_in : h_out;
     int64_t ck = (int64_t)align_up((size_t)hmax, GK);
     for (;;) {
         const int64_t wgs = J.jobsC * ceil_div(h_in, ck) + J.jobsE * ceil_div(h_out, ck);
-        if (wgs >= 384 || ck <= 2 * GK) break;
+        if (wgs >= 768 || ck <= 2 * GK) break;
         ck = (int64_t)align_up((size_t)(ck / 2), GK);
     }
     J.ck = ck;
@@ -547,37 +681,51 @@ static dad_status ns_steps(const GramPlan& p, char* ws, int64_t N, int r, int n_
     float* Vf = reinterpret_cast<float*>(ws + p.off_Vf);
     int* flag = reinterpret_cast<int*>(ws + p.off_hdr);
     int* counter = flag + 16;
+    double* piv = reinterpret_cast<double*>(ws + p.off_hdr + 128);  // smallest and largest pivot of the last factor
     const dim3 grid((unsigned)p.rows16), block(256);
+    const size_t lds = sizeof(NsShared<NA>);
+    static bool attr_set = false;  // more than 64 KB of LDS has to be asked for once per kernel
+    if (!attr_set) {
+        DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_ns_step<NA, NS_CV>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_ns_step<NA, NS_EZ>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_ns_step<NA, NS_REFINE>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_ns_step<NA, NS_APPLY>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_set = true;
+    }
     int cur = 0;  // rinv[cur] holds the factor of the latest Gram matrix
     for (int it = 0; it < n_iter; ++it) {
         {
             ProfScope ps(KID_NS_STEP, s);
-            hipLaunchKernelGGL((k_ns_step<NA, NS_CV>), grid, block, 0, s, C, it == 0 ? H0 : (const double*)F, Z, F,
+            hipLaunchKernelGGL((k_ns_step<NA, NS_CV>), grid, block, lds, s, C, it == 0 ? H0 : (const double*)F, Z, F,
                                it == 0 ? (const double*)nullptr : (const double*)rinv[cur], (double*)nullptr,
-                               (float*)nullptr, (float*)nullptr, 0, N, r, gp, counter, flag);
+                               (float*)nullptr, (float*)nullptr, 0, N, r, gp, counter, flag, piv);
         }
         DAD_LAUNCH_CHECK();
         cur ^= 1;
         {
             ProfScope ps(KID_NS_STEP, s);
-            hipLaunchKernelGGL((k_ns_step<NA, NS_EZ>), grid, block, 0, s, E, (const double*)nullptr, Z, F,
+            hipLaunchKernelGGL((k_ns_step<NA, NS_EZ>), grid, block, lds, s, E, (const double*)nullptr, Z, F,
                                (const double*)nullptr, rinv[cur], (float*)nullptr, (float*)nullptr, 0, N, r, gp, counter,
-                               flag);
+                               flag, piv);
         }
         DAD_LAUNCH_CHECK();
     }
     {   // second Cholesky round for the iterate that is returned
         ProfScope ps(KID_NS_STEP, s);
-        hipLaunchKernelGGL((k_ns_step<NA, NS_REFINE>), grid, block, 0, s, (const double*)nullptr, (const double*)nullptr,
+        hipLaunchKernelGGL((k_ns_step<NA, NS_REFINE>), grid, block, lds, s, (const double*)nullptr, (const double*)nullptr,
                            Z, F, (const double*)rinv[cur], rinv[cur ^ 1], (float*)nullptr, (float*)nullptr, 0, N, r, gp,
-                           counter, flag);
+                           counter, flag, piv);
     }
     DAD_LAUNCH_CHECK();
     cur ^= 1;
     {
         ProfScope ps(KID_NS_STEP, s);
-        hipLaunchKernelGGL((k_ns_step<NA, NS_APPLY>), grid, block, 0, s, (const double*)nullptr, (const double*)nullptr, Z,
-                           F, (const double*)rinv[cur], (double*)nullptr, Tf, Vf, proj_pitch(r), N, r, gp, counter, flag);
+        hipLaunchKernelGGL((k_ns_step<NA, NS_APPLY>), grid, block, lds, s, (const double*)nullptr, (const double*)nullptr, Z,
+                           F, (const double*)rinv[cur], (double*)nullptr, Tf, Vf, proj_pitch(r), N, r, gp, counter, flag, piv);
     }
     DAD_LAUNCH_CHECK();
     return DAD_OK;
