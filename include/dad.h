@@ -123,8 +123,8 @@ size_t dad_compress_gram_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out,
  * dad_compress_rank_gram - the few-rows form of dad_compress_rank (Algorithm 2 with its
  * precomputation C = A A^T, Eq. 6; the regime N << h of Section 3.3.1).  C = A A^T, E = D D^T and
  * H0 = D G0^T are formed once in fp64; with every iterate written as G_k = D^T T_k the block power
- * iteration and its Cholesky orthonormalisation (two rounds for the returned iterate, one for the
- * others) run on N x N and N x r fp64 matrices:
+ * iteration and its Cholesky orthonormalisation (one round per iterate; a second one for the returned
+ * iterate when the pivots of the first differ by more than 1e6) run on N x N and N x r fp64 matrices:
  *     Z_1 = C H0,  Z_k = C (E T_{k-1}),  Z_k^T E Z_k = R^T R,  T_k = Z_k R^-1,
  * and the pair is Gt = T_n^T D, Pt = (E T_n)^T A.  Each factor is read twice instead of
  * 2 n_iter + 1 times and the call is 9 launches for n_iter = 2.
@@ -135,7 +135,9 @@ size_t dad_compress_gram_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out,
  * themselves agree with it whenever the iterate is well conditioned (both come from Cholesky
  * factors with a positive diagonal).  Squared conditioning is the price of the Gram form: the
  * orthonormalisation holds to about 1e-16 cond(Y)^2 per round, and a non-positive pivot latches
- * DAD_ERR_NUMERIC for dad_poll_numeric_status.
+ * DAD_ERR_NUMERIC for dad_poll_numeric_status.  It is the faster call for N <= 512 (about half the
+ * time at N <= 256) and for N <= 1024 with r >= 32; with many rows and a small r the N^2 (h_in + h_out)
+ * flops of the two Gram matrices cost more than the thin passes they replace.
  */
 dad_status dad_compress_rank_gram(const void* A, const void* D, int64_t N, int64_t h_in, int64_t h_out, dad_dtype dt,
                                   int r, int n_iter, const float* G0, float* Pt, float* Gt, void* workspace,

@@ -2,8 +2,9 @@
 // The iterate is held transposed (Yt: r x h, row j = column j of Y), so the
 // Gram matrix is S[i][j] = sum_k Yt[i][k] Yt[j][k].  One round is
 //   S = Y^T Y  ->  S = R^T R (upper R)  ->  Y <- Y R^{-1},
-// done twice (CholeskyQR2) for the iterate that is returned and once for the intermediate
-// iterates of the power iteration, of which only the span matters.  Launches of CholeskyQR2:
+// done twice (CholeskyQR2) for the iterate that is returned - unless the pivots of the first round
+// show that one is enough - and once for the intermediate iterates of the power iteration, of
+// which only the span matters.  Launches of CholeskyQR2:
 //   1. Gram partials of Yt per 256-column slab; the workgroup that finishes last
 //      sums them (fixed order), factorises and inverts R in fp64.
 //   2. Y <- Y R^{-1} per slab, Gram partials of the result, last workgroup
@@ -74,7 +75,8 @@ __device__ __forceinline__ void gram_of_tile(const float (*Ys)[QR_COLS + 1], Gra
 template <int NA>
 __device__ __forceinline__ void last_block_factor(QrShared& sh, const GramAcc<NA>& acc, double* __restrict__ gram_part,
                                                   int nblocks, int r, int* __restrict__ counter,
-                                                  float* __restrict__ rinv, int* __restrict__ flag) {
+                                                  float* __restrict__ rinv, int* __restrict__ flag,
+                                                  double* __restrict__ piv_range) {
     const int t = threadIdx.x;
     const int nent = r * r;
     double* mine = gram_part + (int64_t)blockIdx.x * nent;
@@ -99,7 +101,7 @@ __device__ __forceinline__ void last_block_factor(QrShared& sh, const GramAcc<NA
     if (!sh.last) return;
     __threadfence();
 
-    factor_partials<NA, float>(sh.f, gram_part, nblocks, r, rinv, flag);
+    factor_partials<NA, float>(sh.f, gram_part, nblocks, r, rinv, flag, piv_range);
     if (t == 0) *counter = 0;
 }
 
@@ -131,7 +133,8 @@ __device__ __forceinline__ void store_tile(QrShared& sh, const float (&st)[16]) 
 template <int NA>
 __global__ __launch_bounds__(256) void k_qr_gram(const float* __restrict__ Yt, int64_t h, int r,
                                                  double* __restrict__ gram_part, int* __restrict__ counter,
-                                                 float* __restrict__ rinv, int* __restrict__ flag) {
+                                                 float* __restrict__ rinv, int* __restrict__ flag,
+                                                 double* __restrict__ piv_range) {
     __shared__ QrShared sh;
     const int64_t k0 = (int64_t)blockIdx.x * QR_SUB * QR_COLS;
     float st[QR_SUB][16];
@@ -148,17 +151,40 @@ __global__ __launch_bounds__(256) void k_qr_gram(const float* __restrict__ Yt, i
         }
     }
     __syncthreads();
-    last_block_factor<NA>(sh, acc, gram_part, gridDim.x, r, counter, rinv, flag);
+    last_block_factor<NA>(sh, acc, gram_part, gridDim.x, r, counter, rinv, flag, piv_range);
+}
+
+// One Cholesky round leaves G^T G - I at about eps32 * cond(Y) (the rounding of Y R^-1 in fp32); the
+// second round brings it to eps32.  The pivots of the first factor are the squared diagonal of R,
+// whose ratio bounds cond(Y)^2 from below: when it is at most QR_ONE_ROUND_SPREAD the first round is
+// kept as the result (the flat spectra of dense layers' gradients) and the second is not run.
+constexpr double QR_ONE_ROUND_SPREAD = 16.0;
+
+__device__ __forceinline__ bool one_round_enough(const double* __restrict__ piv_first) {
+    const double pmin = piv_first[0], pmax = piv_first[1];
+    return pmin > 0.0 && pmax <= QR_ONE_ROUND_SPREAD * pmin;
 }
 
 // Launches 2 and 3: Gt[j][k] = sum_{i<=j} rinv_in[i][j] * Yt[i][k]; Gt may alias Yt (each workgroup
 // reads its slab completely before it writes).  WITH_GRAM also prepares the next factor.
+// piv_first (CholeskyQR2 only, else null) holds the pivot range of the first factor: when one round
+// is enough, the WITH_GRAM launch returns at once and the launch after it applies the first factor
+// (rinv_first) to the iterate itself (Y_first) instead of the second factor to the first result.
 template <int NA, bool WITH_GRAM, int SUB>
 __global__ __launch_bounds__(256) void k_qr_apply(const float* Yt, float* Gt, const float* __restrict__ rinv_in,
                                                   int64_t h, int r, double* __restrict__ gram_part,
                                                   int* __restrict__ counter, float* __restrict__ rinv_out,
-                                                  int* __restrict__ flag, bf16_t* __restrict__ gt_bf16) {
+                                                  int* __restrict__ flag, bf16_t* __restrict__ gt_bf16,
+                                                  const double* __restrict__ piv_first,
+                                                  double* __restrict__ piv_second, const float* Y_first,
+                                                  const float* __restrict__ rinv_first) {
     __shared__ QrShared sh;
+    const bool single = piv_first != nullptr && one_round_enough(piv_first);  // uniform over the grid
+    if (WITH_GRAM && single) return;
+    if (!WITH_GRAM && single) {
+        Yt = Y_first;
+        rinv_in = rinv_first;
+    }
     const int t = threadIdx.x;
     const int kl = t & 63, jg = t >> 6;
     const int64_t k0 = (int64_t)blockIdx.x * SUB * QR_COLS;
@@ -207,7 +233,7 @@ __global__ __launch_bounds__(256) void k_qr_apply(const float* Yt, float* Gt, co
     }
     if (WITH_GRAM) {
         __syncthreads();
-        last_block_factor<NA>(sh, acc, gram_part, gridDim.x, r, counter, rinv_out, flag);
+        last_block_factor<NA>(sh, acc, gram_part, gridDim.x, r, counter, rinv_out, flag, piv_second);
     }
 }
 
@@ -219,29 +245,34 @@ template <int NA>
 static dad_status qr(const float* Yt, float* Gt, int64_t h, int r, int rounds, double* gram_part, int nb, float* rinv,
                      int* counter, int* flag, bf16_t* gt_bf16, hipStream_t s) {
     float* rinv2 = rinv + DAD_MAX_RANK * DAD_MAX_RANK;
+    // pivot ranges of the two factors: four doubles at byte 128 of the 256-byte workspace header
+    double* piv = reinterpret_cast<double*>(reinterpret_cast<char*>(flag) + 128);
     const unsigned nb1 = (unsigned)ceil_div(h, QR_COLS);
     {
         ProfScope prof(KID_GRAM, s);
-        hipLaunchKernelGGL(k_qr_gram<NA>, dim3((unsigned)nb), dim3(256), 0, s, Yt, h, r, gram_part, counter, rinv, flag);
+        hipLaunchKernelGGL(k_qr_gram<NA>, dim3((unsigned)nb), dim3(256), 0, s, Yt, h, r, gram_part, counter, rinv, flag, piv);
     }
     DAD_LAUNCH_CHECK();
     if (rounds == 1) {
         ProfScope prof(KID_APPLY2, s);
         hipLaunchKernelGGL((k_qr_apply<NA, false, 1>), dim3(nb1), dim3(256), 0, s, Yt, Gt, (const float*)rinv, h, r,
-                           gram_part, counter, rinv2, flag, gt_bf16);
+                           gram_part, counter, rinv2, flag, gt_bf16, (const double*)nullptr, (double*)nullptr,
+                           (const float*)nullptr, (const float*)nullptr);
         DAD_LAUNCH_CHECK();
         return DAD_OK;
     }
     {
         ProfScope prof(KID_APPLY, s);
         hipLaunchKernelGGL((k_qr_apply<NA, true, QR_SUB>), dim3((unsigned)nb), dim3(256), 0, s, Yt, Gt, (const float*)rinv,
-                           h, r, gram_part, counter, rinv2, flag, (bf16_t*)nullptr);
+                           h, r, gram_part, counter, rinv2, flag, (bf16_t*)nullptr, (const double*)piv, piv + 2,
+                           (const float*)nullptr, (const float*)nullptr);
     }
     DAD_LAUNCH_CHECK();
     {
         ProfScope prof(KID_APPLY2, s);
         hipLaunchKernelGGL((k_qr_apply<NA, false, 1>), dim3(nb1), dim3(256), 0, s, (const float*)Gt, Gt,
-                           (const float*)rinv2, h, r, gram_part, counter, rinv2, flag, gt_bf16);
+                           (const float*)rinv2, h, r, gram_part, counter, rinv2, flag, gt_bf16, (const double*)piv,
+                           (double*)nullptr, Yt, (const float*)rinv);
     }
     DAD_LAUNCH_CHECK();
     return DAD_OK;

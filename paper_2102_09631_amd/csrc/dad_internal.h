@@ -102,7 +102,7 @@ struct SplitPlan {
 
 // Layout of the dad_compress_rank workspace (byte offsets from its start).
 struct CompressPlan {
-    size_t off_flag;      // 256 B header: int flag at +0, int ticket counter at +64
+    size_t off_flag;      // 256 B header: int flag at +0, int ticket counter at +64, pivot ranges (4 doubles) at +128
     size_t off_V;         // N x r intermediate (element type of the factors)
     size_t off_part;      // split partials, fp32
     size_t off_Ut;        // r x h_in fp32

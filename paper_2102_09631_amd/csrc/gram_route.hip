@@ -14,8 +14,10 @@
 //                  split over the columns, fp64 matrix instruction
 //   k_gram_gather  sums the column splits in a fixed order, mirrors, and files E and H0
 //   k_ns_step      CV: Z = (C F) R^-1 | EZ: F = E Z, Gram, last workgroup factorises |
-//                  REFINE: second Cholesky round in place | APPLY: fp32 T = Z R^-1, V = F R^-1
-//   k_ns_project   Gt = T^T Delta and Pt = V^T A, one 64-column strip per workgroup
+//                  REFINE: second Cholesky round in place for the returned iterate, a hand-over
+//                  of the first factor when its pivots are within 1e6 of each other |
+//                  APPLY: fp32 T = Z R^-1, V = F R^-1
+//   k_ns_project   Gt = T^T Delta and Pt = V^T A, one 16-column strip per workgroup
 #include "chol_factor.h"
 #include "dad_internal.h"
 

@@ -107,10 +107,11 @@ def test_gram_route_equals_block_route_on_the_gpu(gpu):
     assert O.rel_fro(Gg.cpu().numpy(), Gb.cpu().numpy().astype(np.float64)) <= 1e-4
 
 
-@pytest.mark.parametrize("ratio", [0.8, 0.5])
+@pytest.mark.parametrize("ratio", [0.8, 0.5, 0.3])
 def test_gram_route_planted_spectrum(gpu, ratio):
-    """Delta rows scaled geometrically (sigma_1/sigma_r = 5 and 128): the Gram form squares the
-    conditioning of the iterate but works in fp64, and G stays orthonormal."""
+    """Delta rows scaled geometrically (sigma_1/sigma_r = 5, 1e2 and 6e3): the Gram form squares the
+    conditioning of the iterate but works in fp64; G stays orthonormal and the result stays at
+    fp32 rounding distance from the oracle.  The steeper two take the second Cholesky round."""
     N, h_in, h_out, r = 64, 96, 80, 8
     rng = np.random.default_rng([34, int(ratio * 10)])
     A = rng.standard_normal((N, h_in)).astype(np.float32)
@@ -119,6 +120,28 @@ def test_gram_route_planted_spectrum(gpu, ratio):
     out = run(A, D, G0, r, 2, "f32", gpu)
     print(ratio, out)
     assert out["e_rank"] <= TOL["f32"] and out["orth"] <= 1e-5, out
+
+
+def test_gram_route_beyond_its_conditioning_range_says_so(gpu):
+    """sigma_1/sigma_r = 1e7: the Gram matrix of the iterate (condition number 1e28) is beyond fp64.
+    The call must either latch DAD_ERR_NUMERIC or deliver a valid pair - never a silent wrong answer -
+    and the outputs stay finite."""
+    N, h_in, h_out, r = 64, 96, 80, 8
+    rng = np.random.default_rng([34, 1])
+    A = rng.standard_normal((N, h_in)).astype(np.float32)
+    D = (rng.standard_normal((N, h_out)) * (0.1 ** np.arange(N))[:, None]).astype(np.float32)
+    G0 = rng.standard_normal((r, h_out)).astype(np.float32)
+    ws = torch.empty(dad.compress_gram_workspace_bytes(N, h_in, h_out, r, torch.float32), dtype=torch.uint8, device=gpu)
+    Pt, Gt = dad.compress_rank_gram(torch.from_numpy(A).to(gpu), torch.from_numpy(D).to(gpu), r, 2,
+                                    torch.from_numpy(G0).to(gpu), workspace=ws)
+    status = dad.poll_numeric_status(ws)
+    assert torch.isfinite(Pt).all() and torch.isfinite(Gt).all()
+    if status == dad.DAD_OK:
+        g = Gt.cpu().numpy().astype(np.float64)
+        assert np.abs(g @ g.T - np.eye(r)).max() <= 1e-5
+        assert O.rel_fro(dad.reconstruct_grad(Pt, Gt).cpu().numpy(), O.rank_r_grad(*O.block_spi(A, D, G0, 2))) <= 1e-4
+    else:
+        assert status == dad.DAD_ERR_NUMERIC
 
 
 def test_gram_route_rank_budget_equal_to_rank_recovers_gradient(gpu):
