@@ -92,7 +92,8 @@ size_t dad_compress_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, int 
  *     M^T M G = Delta^T ( A ( A^T ( Delta G ) ) ),
  * evaluated right to left so that neither M nor A A^T is formed; the
  * orthonormalisation (Cholesky QR: one round for the intermediate iterates,
- * of which only the span is used, two rounds for the last one) stands in for
+ * of which only the span is used; for the last one a second round unless the
+ * pivots of the first differ by at most 16x, decided on the device) stands in for
  * the peeling of Eq. 7.  Then the left factor P = A^T (Delta G) is formed with the singular values left
  * inside it (footnote to Section 3.3.1), so that  M ~ P G^T = M G G^T.
  *
