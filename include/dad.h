@@ -32,6 +32,11 @@
  *     rounding order.
  *   - Overlapping calls that share a workspace race; use one workspace per
  *     stream.
+ *   - Every call but dad_poll_numeric_status (which copies one word to the host
+ *     and waits for it) may be recorded into a HIP graph: nothing is allocated,
+ *     copied or cleared by memset.  dad_compress_rank_gram and
+ *     dad_backprop_delta ask the runtime once per process for more than 64 KB
+ *     of LDS on their first call: make that first call outside a capture.
  */
 #ifndef DAD_H
 #define DAD_H
