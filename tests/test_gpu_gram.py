@@ -212,3 +212,36 @@ def test_gram_route_reruns_are_bit_identical_and_graph_capturable(gpu):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(Pt, P0) and torch.equal(Gt, G0ref)
+
+
+def test_one_workspace_serves_all_compress_entry_points_in_turn(gpu):
+    """The three compressions keep their flag and ticket words at the same place of the workspace and
+    clear them at the start of every call: one buffer, used by one call after the other, gives each
+    of them the result it gives on a fresh buffer, bit for bit."""
+    rng = np.random.default_rng(38)
+    mk = lambda *shape: torch.from_numpy(rng.standard_normal(shape).astype(np.float32)).to(gpu)
+    A1, D1, G1 = mk(512, 256), mk(512, 384), mk(16, 384)        # block route (guarded kernels, fp32)
+    A2, D2, G2 = mk(96, 200), mk(96, 136), mk(8, 136)           # Gram route
+    A3, D3, G3 = mk(300, 64), mk(300, 80), mk(3, 80)            # sequential route
+    A4 = mk(1024, 256).to(torch.bfloat16)                        # block route, bf16 MFMA kernels
+    D4, G4 = mk(1024, 512).to(torch.bfloat16), mk(32, 512)
+    calls = [
+        (dad.compress_rank, (A1, D1, 16, 2, G1), dad.compress_workspace_bytes(512, 256, 384, 16, torch.float32)),
+        (dad.compress_rank_gram, (A2, D2, 8, 2, G2), dad.compress_gram_workspace_bytes(96, 200, 136, 8, torch.float32)),
+        (dad.compress_rank_sequential, (A3, D3, 3, 2, G3),
+         dad.lib().dad_compress_sequential_workspace_bytes(300, 64, 80, dad.DAD_F32)),
+        (dad.compress_rank, (A4, D4, 32, 2, G4), dad.compress_workspace_bytes(1024, 256, 512, 32, torch.bfloat16)),
+    ]
+    fresh = []
+    for fn, args, nbytes in calls:
+        ws = torch.full((nbytes,), 0xA5, dtype=torch.uint8, device=gpu)      # not zero on purpose
+        fresh.append([x.clone() for x in fn(*args, workspace=ws)])
+        assert dad.poll_numeric_status(ws) == dad.DAD_OK
+    shared = torch.full((max(c[2] for c in calls),), 0x5A, dtype=torch.uint8, device=gpu)
+    for rounds in range(2):
+        for (fn, args, _), ref in zip(calls, fresh):
+            out = fn(*args, workspace=shared)
+            torch.cuda.synchronize()
+            assert dad.poll_numeric_status(shared) == dad.DAD_OK
+            for x, y in zip(out, ref):
+                assert torch.equal(x, y)

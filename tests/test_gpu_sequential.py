@@ -136,3 +136,28 @@ def test_sequential_reruns_are_bit_identical(gpu):
     b = dad.compress_rank_sequential(A, D, 3, 2, G0)
     for x, y in zip(a, b):
         assert torch.equal(x, y)
+
+
+def test_sequential_replays_from_a_hip_graph(gpu):
+    """The call records into a HIP graph (no memset, no host copy); every replay equals the eager result."""
+    rng = np.random.default_rng(25)
+    A = to_dev(bf16_round(rng.standard_normal((1024, 256))), "bf16", gpu)
+    D = to_dev(bf16_round(rng.standard_normal((1024, 384))), "bf16", gpu)
+    G0 = torch.from_numpy(rng.standard_normal((2, 384)).astype(np.float32)).to(gpu)
+    ws = torch.empty(dad.lib().dad_compress_sequential_workspace_bytes(1024, 256, 384, dad.DAD_BF16), dtype=torch.uint8,
+                     device=gpu)
+    Qt, sGt, sig = dad.compress_rank_sequential(A, D, 2, 2, G0, workspace=ws)
+    torch.cuda.synchronize()
+    ref = [Qt.clone(), sGt.clone(), sig.clone()]
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            dad.compress_rank_sequential(A, D, 2, 2, G0, Qt=Qt, sGt=sGt, sigma=sig, workspace=ws)
+    for _ in range(3):
+        Qt.zero_(); sGt.zero_(); sig.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for x, y in zip((Qt, sGt, sig), ref):
+            assert torch.equal(x, y)
