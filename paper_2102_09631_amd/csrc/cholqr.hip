@@ -21,10 +21,13 @@ namespace dad {
 constexpr int QR_COLS = 64;  // columns of Yt per LDS tile
 constexpr int QR_SUB = 4;    // tiles per workgroup: few, fat Gram partials keep the final sum short
 constexpr int QR_LD = DAD_MAX_RANK + 1;
+// Row pitch of the LDS tile: 4 banks from row to row, so that the 16 rows x 4 columns one operand read of
+// the fp64 matrix instruction touches fall into 64 different banks (pitch 65 gave 35 % conflict cycles).
+constexpr int QR_PITCH = QR_COLS + 4;
 
 struct QrShared {
     union {
-        float Ys[DAD_MAX_RANK][QR_COLS + 1];  // tile of Yt (or of the result)
+        float Ys[DAD_MAX_RANK][QR_PITCH];  // tile of Yt (or of the result)
         FactorShared f;
     };
     float Rs[DAD_MAX_RANK][QR_LD];  // R^{-1} applied by this launch
@@ -52,7 +55,7 @@ struct GramAcc {
 };
 
 template <int NA>
-__device__ __forceinline__ void gram_of_tile(const float (*Ys)[QR_COLS + 1], GramAcc<NA>& acc) {
+__device__ __forceinline__ void gram_of_tile(const float (*Ys)[QR_PITCH], GramAcc<NA>& acc) {
     constexpr int NBW = GramAcc<NA>::NBW;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int li = lane & 15, lk = lane >> 4;
