@@ -187,7 +187,7 @@ dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_
         DAD_TRY(tn(A, Ut, h_in, p.tn_in, Ub));                             // U = A^T V
         DAD_TRY(nn(A, Ut, Ub, h_in, p.nn_in, nullptr));                    // W = A U
         DAD_TRY(tn(D, Yt, h_out, p.tn_out, nullptr));                      // Y = Delta^T W
-        // G = orth(Y): two Cholesky rounds for the iterate that is returned, one for the others
+        // G = orth(Y): up to two Cholesky rounds for the iterate that is returned, one for the others
         DAD_TRY(launch_cholqr(Yt, Gt, h_out, r, (it + 1 == n_iter) ? 2 : 1, gram, p.gram_blocks, rinv, counter, flag, Gb,
                               s));
         G = Gt;
