@@ -28,18 +28,42 @@ __global__ __launch_bounds__(256) void k_thin_nn(const T* __restrict__ X, const 
 
     const int64_t kbeg = (int64_t)blockIdx.y * kchunk;
     const int64_t kend = (kbeg + kchunk < h) ? kbeg + kchunk : h;
+    // Tiles travel global -> registers -> LDS.  Every load has a valid (clamped) address and its value
+    // is selected only at the LDS store, so that the loads of a tile go out together, and the next
+    // tile's loads are in flight while the current one is multiplied.
+    constexpr int XL = ROWS * KC / 256, PL = MA / 2;  // r <= 4 MA, so r * KC / 256 <= MA / 2
+    float xr[XL], pr[PL];
+    auto fetch = [&](int64_t k0) {
+#pragma unroll
+        for (int m = 0; m < XL; ++m) {
+            const int e = t + 256 * m, rr = e / KC, kk = e % KC;
+            const int64_t n = n0 + rr < N ? n0 + rr : N - 1, k = k0 + kk < kend ? k0 + kk : kend - 1;
+            xr[m] = ld<T>(X, n * h + k);
+        }
+#pragma unroll
+        for (int m = 0; m < PL; ++m) {
+            const int e = t + 256 * m, j = e / KC < r ? e / KC : r - 1, kk = e % KC;
+            const int64_t k = k0 + kk < kend ? k0 + kk : kend - 1;
+            pr[m] = Pt[(int64_t)j * h + k];
+        }
+    };
+    auto commit = [&](int64_t k0) {
+#pragma unroll
+        for (int m = 0; m < XL; ++m) {
+            const int e = t + 256 * m, rr = e / KC, kk = e % KC;
+            Xs[rr][kk] = (n0 + rr < N && k0 + kk < kend) ? xr[m] : 0.f;
+        }
+#pragma unroll
+        for (int m = 0; m < PL; ++m) {
+            const int e = t + 256 * m, j = e / KC, kk = e % KC;
+            if (j < r) Ps[j][kk] = (k0 + kk < kend) ? pr[m] : 0.f;
+        }
+    };
+    fetch(kbeg);
     for (int64_t k0 = kbeg; k0 < kend; k0 += KC) {
-        for (int e = t; e < ROWS * KC; e += 256) {
-            int rr = e / KC, kk = e % KC;
-            int64_t n = n0 + rr, k = k0 + kk;
-            Xs[rr][kk] = (n < N && k < kend) ? ld<T>(X, n * h + k) : 0.f;
-        }
-        for (int e = t; e < r * KC; e += 256) {
-            int j = e / KC, kk = e % KC;
-            int64_t k = k0 + kk;
-            Ps[j][kk] = (k < kend) ? Pt[(int64_t)j * h + k] : 0.f;
-        }
+        commit(k0);
         __syncthreads();
+        if (k0 + KC < kend) fetch(k0 + KC);
         // rows of Ps beyond r are never written: their products land in accumulators nobody stores
 #pragma unroll 8
         for (int kk = 0; kk < KC; ++kk) {
@@ -82,18 +106,41 @@ __global__ __launch_bounds__(256) void k_thin_tn(const T* __restrict__ X, const 
 #pragma unroll
     for (int m = 0; m < MA; ++m) acc[m] = 0.f;
 
+    // global -> registers -> LDS with clamped addresses, the next tile in flight during the arithmetic
+    // (see k_thin_nn)
+    constexpr int XL = RC * PW / 256, VL = MA / 2;  // r <= 4 MA, so RC * r / 256 <= MA / 2
+    float xr[XL], vr[VL];
+    auto fetch = [&](int64_t n0) {
+#pragma unroll
+        for (int m = 0; m < XL; ++m) {
+            const int e = t + 256 * m, rr = e / PW, pp = e % PW;
+            const int64_t n = n0 + rr < nend ? n0 + rr : nend - 1, p = p0 + pp < h ? p0 + pp : h - 1;
+            xr[m] = ld<T>(X, n * h + p);
+        }
+#pragma unroll
+        for (int m = 0; m < VL; ++m) {
+            const int e = t + 256 * m < RC * r ? t + 256 * m : RC * r - 1, rr = e / r, j = e % r;
+            const int64_t n = n0 + rr < nend ? n0 + rr : nend - 1;
+            vr[m] = ld<T>(V, n * r + j);
+        }
+    };
+    auto commit = [&](int64_t n0) {
+#pragma unroll
+        for (int m = 0; m < XL; ++m) {
+            const int e = t + 256 * m, rr = e / PW, pp = e % PW;
+            Xs[rr][pp] = (n0 + rr < nend && p0 + pp < h) ? xr[m] : 0.f;
+        }
+#pragma unroll
+        for (int m = 0; m < VL; ++m) {
+            const int e = t + 256 * m, rr = e / r, j = e % r;
+            if (e < RC * r) Vs[rr][j] = (n0 + rr < nend) ? vr[m] : 0.f;
+        }
+    };
+    fetch(nbeg);
     for (int64_t n0 = nbeg; n0 < nend; n0 += RC) {
-        for (int e = t; e < RC * PW; e += 256) {
-            int rr = e / PW, pp = e % PW;
-            int64_t n = n0 + rr, p = p0 + pp;
-            Xs[rr][pp] = (n < nend && p < h) ? ld<T>(X, n * h + p) : 0.f;
-        }
-        for (int e = t; e < RC * r; e += 256) {
-            int rr = e / r, j = e % r;
-            int64_t n = n0 + rr;
-            Vs[rr][j] = (n < nend) ? ld<T>(V, n * r + j) : 0.f;
-        }
+        commit(n0);
         __syncthreads();
+        if (n0 + RC < nend) fetch(n0 + RC);
 #pragma unroll 8
         for (int rr = 0; rr < RC; ++rr) {
             const float x = Xs[rr][pl];
@@ -177,14 +224,33 @@ __global__ __launch_bounds__(256) void k_rebuild(const T* __restrict__ L, const 
 #pragma unroll
         for (int b = 0; b < 4; ++b) acc[a][b] = 0.f;
 
-    for (int64_t k0 = kbeg; k0 < kend; k0 += KC) {
-        for (int e = t; e < KC * TM; e += 256) {
-            int kk = e / TM, c = e % TM;
-            int64_t k = k0 + kk;
-            Ls[kk][c] = (k < kend && p0 + c < h_in) ? ld<T>(L, k * h_in + p0 + c) : 0.f;
-            Rs[kk][c] = (k < kend && q0 + c < h_out) ? ld<T>(R, k * h_out + q0 + c) : 0.f;
+    // global -> registers -> LDS with clamped addresses, the next tile in flight during the arithmetic
+    // (see k_thin_nn)
+    constexpr int TL = KC * TM / 256;
+    float lr[TL], rr_[TL];
+    auto fetch = [&](int64_t k0) {
+#pragma unroll
+        for (int m = 0; m < TL; ++m) {
+            const int e = t + 256 * m, kk = e / TM, c = e % TM;
+            const int64_t k = k0 + kk < kend ? k0 + kk : kend - 1;
+            lr[m] = ld<T>(L, k * h_in + (p0 + c < h_in ? p0 + c : h_in - 1));
+            rr_[m] = ld<T>(R, k * h_out + (q0 + c < h_out ? q0 + c : h_out - 1));
         }
+    };
+    auto commit = [&](int64_t k0) {
+#pragma unroll
+        for (int m = 0; m < TL; ++m) {
+            const int e = t + 256 * m, kk = e / TM, c = e % TM;
+            const bool kin = k0 + kk < kend;
+            Ls[kk][c] = (kin && p0 + c < h_in) ? lr[m] : 0.f;
+            Rs[kk][c] = (kin && q0 + c < h_out) ? rr_[m] : 0.f;
+        }
+    };
+    fetch(kbeg);
+    for (int64_t k0 = kbeg; k0 < kend; k0 += KC) {
+        commit(k0);
         __syncthreads();
+        if (k0 + KC < kend) fetch(k0 + KC);
 #pragma unroll
         for (int kk = 0; kk < KC; ++kk) {
             float lv[4], rv[4];
