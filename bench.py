@@ -49,7 +49,7 @@ def parse():
                     help="two_level: launch eagerly instead of replaying one captured HIP graph per layer")
     ap.add_argument("--agg-route", default="gram", choices=["gram", "block"],
                     help="two_level: the aggregator's reduction of the S*r stacked rows runs on the Gram matrices "
-                         "of the stack (dad_compress_rank_gram, when S*r <= 1024) or as the block power iteration")
+                         "of the stack (dad_compress_rank_gram, when S*r <= 512) or as the block power iteration")
     ap.add_argument("--site-streams", type=int, default=8,
                     help="two_level: HIP streams (default priority) the independent per-site reductions are spread over")
     return ap.parse_args()
@@ -103,7 +103,7 @@ def two_level(args, w, dad, W, torch, np, dev):
     ws_s = [torch.empty(max(dad.compress_workspace_bytes(b, hi, ho, r, tdt) for _, hi, ho in layers),
                         dtype=torch.uint8, device=dev) for _ in range(n_str)]
     side = [torch.cuda.Stream(device=dev) for _ in range(n_str)] if n_str > 1 else []
-    agg_gram = args.agg_route == "gram" and S * r <= dad.DAD_GRAM_MAX_ROWS
+    agg_gram = args.agg_route == "gram" and S * r <= 512      # beyond that the block form is the faster one
     agg_bytes = dad.compress_gram_workspace_bytes if agg_gram else dad.compress_workspace_bytes
     agg_call = dad.compress_rank_gram if agg_gram else dad.compress_rank
     ws_a = torch.empty(max(agg_bytes(S * r, hi, ho, r, torch.float32) for _, hi, ho in layers),

@@ -141,9 +141,9 @@ size_t dad_compress_gram_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out,
  * themselves agree with it whenever the iterate is well conditioned (both come from Cholesky
  * factors with a positive diagonal).  Squared conditioning is the price of the Gram form: the
  * orthonormalisation holds to about 1e-16 cond(Y)^2 per round, and a non-positive pivot latches
- * DAD_ERR_NUMERIC for dad_poll_numeric_status.  It is the faster call for N <= 512 (about half the
- * time at N <= 256) and for N <= 1024 with r >= 32; with many rows and a small r the N^2 (h_in + h_out)
- * flops of the two Gram matrices cost more than the thin passes they replace.
+ * DAD_ERR_NUMERIC for dad_poll_numeric_status.  It is the faster call for N <= 256 (0.6 to 0.75 of
+ * dad_compress_rank's time) and even with it at N = 512; with more rows the N^2 (h_in + h_out) flops
+ * of the two Gram matrices cost more than the thin passes they replace.
  */
 dad_status dad_compress_rank_gram(const void* A, const void* D, int64_t N, int64_t h_in, int64_t h_out, dad_dtype dt,
                                   int r, int n_iter, const float* G0, float* Pt, float* Gt, void* workspace,
