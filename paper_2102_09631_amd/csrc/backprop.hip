@@ -234,14 +234,43 @@ __global__ __launch_bounds__(256) void k_backprop(const T* __restrict__ Dn, cons
     for (int a = 0; a < 4; ++a)
 #pragma unroll
         for (int b = 0; b < 4; ++b) acc[a][b] = 0.f;
-    for (int64_t k0 = 0; k0 < hn; k0 += KC) {
-        for (int e = t; e < TM * KC; e += 256) {
-            const int rr = e / KC, kk = e % KC;
-            const int64_t k = k0 + kk;
-            As[rr][kk] = (n0 + rr < N && k < hn) ? ld<T>(Dn, (n0 + rr) * hn + k) : 0.f;
-            Bs[rr][kk] = (p0 + rr < h && k < hn) ? ld<T>(Wn, (p0 + rr) * hn + k) : 0.f;
+    // Tiles travel global -> registers -> LDS: every load has a valid (clamped) address and its value
+    // is selected only at the LDS store, so that the loads of a tile go out together, and the next
+    // tile's loads are in flight while the current one is multiplied.
+    constexpr int TL = TM * KC / 256;
+    float ar[TL], br[TL];
+    auto fetch = [&](int64_t k0) {
+#pragma unroll
+        for (int m = 0; m < TL; ++m) {
+            const int e = t + 256 * m, rr = e / KC, kk = e % KC;
+            const int64_t k = k0 + kk < hn ? k0 + kk : hn - 1;
+            ar[m] = ld<T>(Dn, (n0 + rr < N ? n0 + rr : N - 1) * hn + k);
+            br[m] = ld<T>(Wn, (p0 + rr < h ? p0 + rr : h - 1) * hn + k);
         }
+    };
+    auto commit = [&](int64_t k0) {
+#pragma unroll
+        for (int m = 0; m < TL; ++m) {
+            const int e = t + 256 * m, rr = e / KC, kk = e % KC;
+            const bool kin = k0 + kk < hn;
+            As[rr][kk] = (kin && n0 + rr < N) ? ar[m] : 0.f;
+            Bs[rr][kk] = (kin && p0 + rr < h) ? br[m] : 0.f;
+        }
+    };
+    // the 4 x 4 values of Z this thread needs at the end are requested up front as well
+    float zr[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int64_t n = n0 + ty * 4 + a, pp = p0 + tx * 4 + b;
+            zr[a][b] = ld<T>(Z, (n < N ? n : N - 1) * h + (pp < h ? pp : h - 1));
+        }
+    fetch(0);
+    for (int64_t k0 = 0; k0 < hn; k0 += KC) {
+        commit(k0);
         __syncthreads();
+        if (k0 + KC < hn) fetch(k0 + KC);
 #pragma unroll
         for (int kk = 0; kk < KC; ++kk) {
             float av[4], bv[4];
@@ -264,7 +293,7 @@ __global__ __launch_bounds__(256) void k_backprop(const T* __restrict__ Dn, cons
         for (int b = 0; b < 4; ++b) {
             const int64_t p = p0 + tx * 4 + b;
             if (p >= h) continue;
-            const float z = ld<T>(Z, n * h + p);
+            const float z = zr[a][b];
             float d = 1.f;
             if (act == DAD_ACT_RELU) d = act_derivative<DAD_ACT_RELU, false>(z);
             else if (act == DAD_ACT_TANH) d = act_derivative<DAD_ACT_TANH, false>(z);
