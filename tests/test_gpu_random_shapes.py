@@ -1,0 +1,95 @@
+"""Seeded sweep over small random shapes (ragged, tiny, r = 1, widths below a tile) for every entry
+point against the fp64 oracle: the guarded kernels' bounds handling is what this exercises."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dad_oracle as O
+from paper_2102_09631_amd import binding as dad
+
+pytestmark = pytest.mark.gpu
+
+
+def shapes(seed, count, n_max, h_max, r_max):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        N = int(rng.integers(1, n_max + 1))
+        h_in = int(rng.integers(1, h_max + 1))
+        h_out = int(rng.integers(1, h_max + 1))
+        r = int(rng.integers(1, min(N, h_in, h_out, r_max) + 1))
+        out.append((N, h_in, h_out, r, int(rng.integers(1, 4))))
+    return out
+
+
+def factors(N, h_in, h_out, r, seed):
+    rng = np.random.default_rng([seed, N, h_in, h_out, r])
+    A = rng.standard_normal((N, h_in)).astype(np.float32)
+    # rows of Delta decay gently: separated singular values keep the comparison well posed
+    D = (rng.standard_normal((N, h_out)) * (0.9 ** np.arange(N))[:, None]).astype(np.float32)
+    G0 = rng.standard_normal((r, h_out)).astype(np.float32)
+    return A, D, G0
+
+
+def bound(A, D, r):
+    """1e-5 plus the fp32 resolution of the weakest kept direction (see the steep-spectrum tests)."""
+    s = np.linalg.svd(A.astype(np.float64).T @ D.astype(np.float64), compute_uv=False)
+    return 1e-5 + 4 * np.finfo(np.float32).eps * s[0] / max(s[r - 1], 1e-300)
+
+
+@pytest.mark.parametrize("N,h_in,h_out,r,n_iter", shapes(101, 24, 300, 400, 48))
+def test_random_shapes_block_route_and_rebuild(gpu, N, h_in, h_out, r, n_iter):
+    A, D, G0 = factors(N, h_in, h_out, r, 1)
+    a, d = torch.from_numpy(A).to(gpu), torch.from_numpy(D).to(gpu)
+    G_full = dad.reconstruct_grad(a, d).cpu().numpy()
+    assert O.rel_fro(G_full, O.full_grad(A, D)) <= 1e-5
+    Pt, Gt = dad.compress_rank(a, d, r, n_iter, torch.from_numpy(G0).to(gpu), check=True)
+    ref = O.rank_r_grad(*O.block_spi(A, D, G0, n_iter))
+    err = O.rel_fro(dad.reconstruct_grad(Pt, Gt).cpu().numpy(), ref)
+    assert err <= bound(A, D, r), (err, bound(A, D, r))
+    g = Gt.cpu().numpy().astype(np.float64)
+    assert np.abs(g @ g.T - np.eye(r)).max() <= 1e-5
+
+
+@pytest.mark.parametrize("N,h_in,h_out,r,n_iter", shapes(102, 24, 300, 400, 48))
+def test_random_shapes_gram_route(gpu, N, h_in, h_out, r, n_iter):
+    A, D, G0 = factors(N, h_in, h_out, r, 2)
+    ws = torch.empty(dad.compress_gram_workspace_bytes(N, h_in, h_out, r, torch.float32), dtype=torch.uint8, device=gpu)
+    Pt, Gt = dad.compress_rank_gram(torch.from_numpy(A).to(gpu), torch.from_numpy(D).to(gpu), r, n_iter,
+                                    torch.from_numpy(G0).to(gpu), workspace=ws)
+    status = dad.poll_numeric_status(ws)
+    s = np.linalg.svd(A.astype(np.float64).T @ D.astype(np.float64), compute_uv=False)
+    if status != dad.DAD_OK:
+        # only beyond its stated range (Gram matrix of the iterate outside fp64) may the route give up
+        assert status == dad.DAD_ERR_NUMERIC and (s[0] / max(s[r - 1], 1e-300)) ** (2 * n_iter) > 1e12
+        return
+    ref = O.rank_r_grad(*O.block_spi(A, D, G0, n_iter))
+    err = O.rel_fro(dad.reconstruct_grad(Pt, Gt).cpu().numpy(), ref)
+    assert err <= bound(A, D, r), (err, bound(A, D, r))
+    g = Gt.cpu().numpy().astype(np.float64)
+    assert np.abs(g @ g.T - np.eye(r)).max() <= 1e-5
+
+
+@pytest.mark.parametrize("N,h_in,h_out,r,n_iter", shapes(103, 12, 200, 300, 6))
+def test_random_shapes_sequential_route(gpu, N, h_in, h_out, r, n_iter):
+    A, D, G0 = factors(N, h_in, h_out, r, 3)
+    Qt, sGt, sigma = dad.compress_rank_sequential(torch.from_numpy(A).to(gpu), torch.from_numpy(D).to(gpu), r, n_iter,
+                                                  torch.from_numpy(G0).to(gpu), check=True)
+    Q_ref, sG_ref = O.sequential_spi(A, D, G0, n_iter)
+    s = np.linalg.svd(A.astype(np.float64).T @ D.astype(np.float64), compute_uv=False)
+    tol = 1e-5 + 4 * np.finfo(np.float32).eps * (s[0] / max(s[r - 1], 1e-300)) ** 2   # peeling: squared ratio
+    err = O.rel_fro(dad.reconstruct_grad(Qt, sGt).cpu().numpy(), Q_ref.T @ sG_ref)
+    assert err <= tol, (err, tol)
+
+
+@pytest.mark.parametrize("N,h,h_next,act", [(int(a), int(b), int(c), ["identity", "relu", "tanh", "sigmoid"][int(k)])
+                                            for a, b, c, k in np.random.default_rng(104).integers(
+                                                [1, 1, 1, 0], [300, 300, 300, 4], size=(16, 4))])
+def test_random_shapes_backprop(gpu, N, h, h_next, act):
+    rng = np.random.default_rng([105, N, h, h_next])
+    Dn = rng.standard_normal((N, h_next)).astype(np.float32)
+    Wn = rng.standard_normal((h, h_next)).astype(np.float32)
+    Z = rng.standard_normal((N, h)).astype(np.float32)
+    got = dad.backprop_delta(torch.from_numpy(Dn).to(gpu), torch.from_numpy(Wn).to(gpu), torch.from_numpy(Z).to(gpu),
+                             act).cpu().numpy()
+    assert O.rel_fro(got, O.backprop_delta(Dn, Wn, Z, act)) <= 1e-5
