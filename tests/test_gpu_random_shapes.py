@@ -93,3 +93,40 @@ def test_random_shapes_backprop(gpu, N, h, h_next, act):
     got = dad.backprop_delta(torch.from_numpy(Dn).to(gpu), torch.from_numpy(Wn).to(gpu), torch.from_numpy(Z).to(gpu),
                              act).cpu().numpy()
     assert O.rel_fro(got, O.backprop_delta(Dn, Wn, Z, act)) <= 1e-5
+
+
+def bf16_cases():
+    rng = np.random.default_rng(106)
+    out = []
+    for i in range(18):
+        aligned = i % 3 != 2           # two of three: widths the MFMA kernels take (multiples of 128, r of 8)
+        N = int(rng.integers(256, 1400)) if aligned else int(rng.integers(1, 700))
+        if i % 6 == 0:
+            N = 256 * int(rng.integers(1, 5))                      # the direct-to-LDS kernels' row counts
+        if aligned:
+            h_in, h_out = 128 * int(rng.integers(1, 6)), 128 * int(rng.integers(1, 6))
+            r = 8 * int(rng.integers(1, 9))
+        else:
+            h_in, h_out = int(rng.integers(8, 500)), int(rng.integers(8, 500))
+            r = int(rng.integers(1, min(N, h_in, h_out, 40) + 1))
+        out.append((N, h_in, h_out, min(r, N)))
+    return out
+
+
+@pytest.mark.parametrize("N,h_in,h_out,r", bf16_cases())
+def test_random_shapes_bf16(gpu, N, h_in, h_out, r):
+    """bf16 factors on all three kernel families: direct-to-LDS MFMA (N a multiple of 256),
+    register-staged MFMA (ragged N) and guarded kernels (ragged widths)."""
+    from paper_2102_09631_amd import workloads as W
+    rng = np.random.default_rng([107, N, h_in, h_out, r])
+    rb = lambda x: W.bf16_bits_to_f32(W.f32_to_bf16_bits(x.astype(np.float32)))
+    A, D = rb(rng.standard_normal((N, h_in))), rb(rng.standard_normal((N, h_out)) * 0.01)
+    G0 = rng.standard_normal((r, h_out)).astype(np.float32)
+    a = torch.from_numpy(A).to(gpu).to(torch.bfloat16)
+    d = torch.from_numpy(D).to(gpu).to(torch.bfloat16)
+    assert O.rel_fro(dad.reconstruct_grad(a, d).cpu().numpy(), O.full_grad(A, D)) <= 2e-2
+    Pt, Gt = dad.compress_rank(a, d, r, 2, torch.from_numpy(G0).to(gpu), check=True)
+    err = O.rel_fro(dad.reconstruct_grad(Pt, Gt).cpu().numpy(), O.rank_r_grad(*O.block_spi(A, D, G0, 2)))
+    assert err <= 2e-2, err
+    g = Gt.cpu().numpy().astype(np.float64)
+    assert np.abs(g @ g.T - np.eye(r)).max() <= 1e-4
