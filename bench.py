@@ -100,13 +100,13 @@ def two_level(args, w, dad, W, torch, np, dev):
     Gt = {li: torch.empty((r, ho), dtype=torch.float32, device=dev) for li, _, ho in layers}
     G_hat = {sh: torch.empty(sh, dtype=torch.float32, device=dev) for sh in w.shapes}
     n_str = max(1, min(args.site_streams, S))
-    ws_s = [torch.empty(max(dad.compress_workspace_bytes(b, hi, ho, r, tdt) for _, hi, ho in layers),
+    ws_s = [torch.zeros(max(dad.compress_workspace_bytes(b, hi, ho, r, tdt) for _, hi, ho in layers),
                         dtype=torch.uint8, device=dev) for _ in range(n_str)]
     side = [torch.cuda.Stream(device=dev) for _ in range(n_str)] if n_str > 1 else []
     agg_gram = args.agg_route == "gram" and S * r <= 512      # beyond that the block form is the faster one
     agg_bytes = dad.compress_gram_workspace_bytes if agg_gram else dad.compress_workspace_bytes
     agg_call = dad.compress_rank_gram if agg_gram else dad.compress_rank
-    ws_a = torch.empty(max(agg_bytes(S * r, hi, ho, r, torch.float32) for _, hi, ho in layers),
+    ws_a = torch.zeros(max(agg_bytes(S * r, hi, ho, r, torch.float32) for _, hi, ho in layers),
                        dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
     PH = ("site_compress", "stack_pairs", "agg_compress", "rebuild_rank")
@@ -423,7 +423,7 @@ def sequential(args, w, dad, W, torch, np, dev):
         Qt[li] = torch.empty((r, hi), dtype=torch.float32, device=dev)
         sGt[li] = torch.empty((r, ho), dtype=torch.float32, device=dev)
         sig[li] = torch.empty((r,), dtype=torch.float32, device=dev)
-    ws = torch.empty(max(dad.lib().dad_compress_sequential_workspace_bytes(N, hi, ho, dad._dt(A[li]))
+    ws = torch.zeros(max(dad.lib().dad_compress_sequential_workspace_bytes(N, hi, ho, dad._dt(A[li]))
                          for li, hi, ho in layers), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
 
@@ -549,9 +549,9 @@ def main():
     G_rank = {s: torch.empty(s, dtype=torch.float32, device=dev) for s in w.shapes}
     Pt = {li: torch.empty((r, hi), dtype=torch.float32, device=dev) for li, hi, _ in layers}
     Gt = {li: torch.empty((r, ho), dtype=torch.float32, device=dev) for li, _, ho in layers}
-    ws_c = torch.empty(max(dad.compress_workspace_bytes(N, hi, ho, r, tdt) for _, hi, ho in layers),
+    ws_c = torch.zeros(max(dad.compress_workspace_bytes(N, hi, ho, r, tdt) for _, hi, ho in layers),
                        dtype=torch.uint8, device=dev)
-    ws_r = torch.empty(max(16, max(dad.reconstruct_workspace_bytes(N, hi, ho, tdt) for _, hi, ho in layers)),
+    ws_r = torch.zeros(max(16, max(dad.reconstruct_workspace_bytes(N, hi, ho, tdt) for _, hi, ho in layers)),
                        dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
 
