@@ -16,11 +16,12 @@ dad_status launch_stack(int, const void* const*, const void* const*, const int64
 int gram_blocks_for(int64_t h);
 bool thin_fast_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
 SplitPlan thin_tn_split(int64_t N, int64_t h, int r);
-dad_status fast_thin_nn(const void*, const float*, void*, int64_t, int64_t, int, int*, hipStream_t);
-dad_status fast_thin_tn(const void*, const void*, float*, float*, SplitPlan, int64_t, int64_t, int, void*, hipStream_t);
+dad_status fast_thin_nn(const void*, const float*, void*, int64_t, int64_t, int, int*, int, hipStream_t);
+dad_status fast_thin_tn(const void*, const void*, float*, float*, SplitPlan, int64_t, int64_t, int, void*, int,
+                        hipStream_t);
 bool thin_dma_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
 dad_status launch_panel_init(const float*, void*, void*, int64_t, int64_t, int, int*, hipStream_t);
-dad_status dma_thin_nn(const void*, const void*, void*, int64_t, int64_t, int, hipStream_t);
+dad_status dma_thin_nn(const void*, const void*, void*, int64_t, int64_t, int, int, hipStream_t);
 bool rebuild_fast_ok(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
 SplitPlan rebuild_fast_split(int64_t K, int64_t h_in, int64_t h_out, int* tile);
 dad_status fast_rebuild(const void*, const void*, int64_t, int64_t, int64_t, float*, float*, SplitPlan, int, hipStream_t);
@@ -49,7 +50,7 @@ CompressPlan plan_compress(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dt
     p.off_flag = o;
     o += 256;
     p.off_V = o;
-    o += align_up((size_t)N * r * elem_size(dt), 256);
+    o += align_up((size_t)N * r * 4, 256);  // fp32, or two bf16 planes
     size_t part_in = (size_t)p.tn_in.splits * r * h_in * 4, part_out = (size_t)p.tn_out.splits * r * h_out * 4;
     p.off_part = o;
     size_t part_max = part_in > part_out ? part_in : part_out;
@@ -167,14 +168,20 @@ dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_
     void* Ub = p.dma ? ws + p.off_Ub : nullptr;
 
     // V <- X * panel (N x r); the direct-to-LDS kernel takes the bf16 copy of the panel
-    auto nn = [&](const void* X, const float* panel, const void* panel_bf16, int64_t h, SplitPlan sp, int* hdr) {
-        if (p.dma) return dma_thin_nn(X, panel_bf16, V, N, h, r, s);
-        return launch_thin_nn(X, panel, V, part, sp, N, h, r, dt, p.fast, hdr, s);
+    auto nn = [&](const void* X, const float* panel, const void* panel_bf16, int64_t h, SplitPlan sp, int* hdr,
+                  int planes) {
+        if (p.dma) return dma_thin_nn(X, panel_bf16, V, N, h, r, planes, s);
+        return launch_thin_nn(X, panel, V, part, sp, N, h, r, dt, p.fast, hdr, planes, s);
     };
     // out (r x h) <- V^T X, with an optional bf16 copy
-    auto tn = [&](const void* X, float* out, int64_t h, SplitPlan sp, void* out_bf16) {
-        return launch_thin_tn(X, V, out, part, sp, N, h, r, dt, p.fast, out_bf16, s);
+    auto tn = [&](const void* X, float* out, int64_t h, SplitPlan sp, void* out_bf16, int planes) {
+        return launch_thin_tn(X, V, out, part, sp, N, h, r, dt, p.fast, out_bf16, planes, s);
     };
+    // On the MFMA path the N x r intermediates are bf16.  V = Delta G goes as one plane.  W = A U goes
+    // as two (rounded value + rounded remainder): activations with a non-zero mean (ReLU, GELU) give
+    // the rows of W a large common component, and one bf16 rounding of it drowns the row-to-row
+    // differences that the next contraction with Delta extracts.
+    const int PV = 1, PW = 2;
 #define DAD_TRY(expr)                      \
     do {                                   \
         if ((rc = (expr)) != DAD_OK) return rc; \
@@ -183,17 +190,17 @@ dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_
     if (p.dma) DAD_TRY(launch_panel_init(G0, Gb, Ub, h_in, h_out, r, flag, s));
     const float* G = G0;
     for (int it = 0; it < n_iter; ++it) {
-        DAD_TRY(nn(D, G, Gb, h_out, p.nn_out, it == 0 ? flag : nullptr));  // V = Delta G
-        DAD_TRY(tn(A, Ut, h_in, p.tn_in, Ub));                             // U = A^T V
-        DAD_TRY(nn(A, Ut, Ub, h_in, p.nn_in, nullptr));                    // W = A U
-        DAD_TRY(tn(D, Yt, h_out, p.tn_out, nullptr));                      // Y = Delta^T W
+        DAD_TRY(nn(D, G, Gb, h_out, p.nn_out, it == 0 ? flag : nullptr, PV));  // V = Delta G
+        DAD_TRY(tn(A, Ut, h_in, p.tn_in, Ub, PV));                             // U = A^T V
+        DAD_TRY(nn(A, Ut, Ub, h_in, p.nn_in, nullptr, PW));                    // W = A U
+        DAD_TRY(tn(D, Yt, h_out, p.tn_out, nullptr, PW));                      // Y = Delta^T W
         // G = orth(Y): up to two Cholesky rounds for the iterate that is returned, one for the others
         DAD_TRY(launch_cholqr(Yt, Gt, h_out, r, (it + 1 == n_iter) ? 2 : 1, gram, p.gram_blocks, rinv, counter, flag, Gb,
                               s));
         G = Gt;
     }
-    DAD_TRY(nn(D, Gt, Gb, h_out, p.nn_out, nullptr));  // V = Delta G
-    return tn(A, Pt, h_in, p.tn_in, nullptr);          // P = A^T V
+    DAD_TRY(nn(D, Gt, Gb, h_out, p.nn_out, nullptr, PV));  // V = Delta G
+    return tn(A, Pt, h_in, p.tn_in, nullptr, PV);          // P = A^T V
 #undef DAD_TRY
 }
 
@@ -232,14 +239,14 @@ dad_status dad_poll_numeric_status(const void* workspace, void* stream) {
 namespace dad {
 
 dad_status launch_thin_nn(const void* X, const float* Pt, void* out, float* partials, SplitPlan sp, int64_t N,
-                          int64_t h, int r, dad_dtype dt, bool fast, int* zero_hdr, hipStream_t s) {
-    if (fast) return fast_thin_nn(X, Pt, out, N, h, r, zero_hdr, s);
+                          int64_t h, int r, dad_dtype dt, bool fast, int* zero_hdr, int planes, hipStream_t s) {
+    if (fast) return fast_thin_nn(X, Pt, out, N, h, r, zero_hdr, planes, s);
     return gen_thin_nn(X, Pt, out, partials, sp, N, h, r, dt, zero_hdr, s);
 }
 
 dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp, int64_t N,
-                          int64_t h, int r, dad_dtype dt, bool fast, void* out_bf16, hipStream_t s) {
-    if (fast) return fast_thin_tn(X, V, out_t, partials, sp, N, h, r, out_bf16, s);
+                          int64_t h, int r, dad_dtype dt, bool fast, void* out_bf16, int planes, hipStream_t s) {
+    if (fast) return fast_thin_tn(X, V, out_t, partials, sp, N, h, r, out_bf16, planes, s);
     return gen_thin_tn(X, V, out_t, partials, sp, N, h, r, dt, s);
 }
 

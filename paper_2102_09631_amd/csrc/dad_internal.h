@@ -103,7 +103,7 @@ struct SplitPlan {
 // Layout of the dad_compress_rank workspace (byte offsets from its start).
 struct CompressPlan {
     size_t off_flag;      // 256 B header: int flag at +0, int ticket counter at +64, pivot ranges (4 doubles) at +128
-    size_t off_V;         // N x r intermediate (element type of the factors)
+    size_t off_V;         // N x r intermediate: fp32, or on the MFMA path up to two bf16 planes (hi, lo) N*r apart
     size_t off_part;      // split partials, fp32
     size_t off_Ut;        // r x h_in fp32
     size_t off_Yt;        // r x h_out fp32
@@ -141,16 +141,20 @@ RebuildPlan plan_rebuild(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
 dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s, void* out_bf16 = nullptr);
 
 
-// out[n][j] = sum_k X[n][k] * Pt[j][k];  X is N x h (dt), Pt r x h fp32, out N x r (dt).
+// out[n][j] = sum_k X[n][k] * Pt[j][k];  X is N x h (dt), Pt r x h fp32.  out is N x r: fp32 from the
+// guarded kernels (fast = false); from the MFMA kernels `planes` bf16 planes N*r elements apart,
+// plane 0 = the rounded value, plane 1 (planes = 2) = the rounded remainder.
 // zero_hdr, when not null, is the 256-byte workspace header the launch clears on the side.
 // partials/sp: fp32 slabs and column split of the guarded kernel (ignored by the MFMA kernel).
 dad_status launch_thin_nn(const void* X, const float* Pt, void* out, float* partials, SplitPlan sp, int64_t N,
-                          int64_t h, int r, dad_dtype dt, bool fast, int* zero_hdr, hipStream_t s);
+                          int64_t h, int r, dad_dtype dt, bool fast, int* zero_hdr, int planes, hipStream_t s);
 
-// out_t[j][p] = sum_n X[n][p] * V[n][j];  X N x h (dt), V N x r (dt), out_t r x h fp32.
+// out_t[j][p] = sum_n X[n][p] * V[n][j];  X N x h (dt), V N x r as launch_thin_nn wrote it with the
+// same `fast` and `planes` (the planes are summed), out_t r x h fp32.
 // out_bf16 (optional, fast path only) receives a bf16 copy of out_t.
 dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp,
-                          int64_t N, int64_t h, int r, dad_dtype dt, bool fast, void* out_bf16, hipStream_t s);
+                          int64_t N, int64_t h, int r, dad_dtype dt, bool fast, void* out_bf16, int planes,
+                          hipStream_t s);
 
 // Orthonormalisation Yt (r x h) -> Gt (r x h), rows of Gt orthonormal; rounds = 2 is CholeskyQR2.
 // gt_bf16 (optional) receives a bf16 copy of Gt.

@@ -6,13 +6,14 @@
 namespace dad {
 
 // ---------------------------------------------------------------- thin N x h by h x r
-// out[n][j] = sum_k X[n][k] * Pt[j][k]   (V = Delta G and W = A U of Eq. 6)
+// out[n][j] = sum_k X[n][k] * Pt[j][k]   (V = Delta G and W = A U of Eq. 6); the N x r result is fp32
+// whatever the factors' element type.
 // With few rows (the N << h case) the contraction is also split over column chunks of `kchunk`
 // (blockIdx.y); each chunk then writes an fp32 slab part[chunk][n][j] for reduce_slabs.
 // MA = accumulators per thread (columns jg, jg+4, ...): 4, 8 or 16 for r <= 16, 32, 64.
 template <typename T, int MA>
 __global__ __launch_bounds__(256) void k_thin_nn(const T* __restrict__ X, const float* __restrict__ Pt,
-                                                 T* __restrict__ out, float* __restrict__ part, int64_t N, int64_t h,
+                                                 float* __restrict__ out, float* __restrict__ part, int64_t N, int64_t h,
                                                  int r, int64_t kchunk, int* __restrict__ zero_hdr) {
     // the first launch of a compress call also clears the workspace header (flag, ticket counter)
     if (zero_hdr && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 64) zero_hdr[threadIdx.x] = 0;
@@ -82,16 +83,16 @@ __global__ __launch_bounds__(256) void k_thin_nn(const T* __restrict__ X, const 
                 if (part)
                     part[((int64_t)blockIdx.y * N + n) * r + j] = acc[m];
                 else
-                    st<T>(out, n * r + j, acc[m]);
+                    out[n * r + j] = acc[m];
             }
         }
     }
 }
 
 // ---------------------------------------------------------------- thin (N x h)^T by N x r, split over rows
-// part[s][j][p] = sum_{n in chunk s} X[n][p] * V[n][j]    (U = A^T V, Y = Delta^T W, P = A^T V)
+// part[s][j][p] = sum_{n in chunk s} X[n][p] * V[n][j]    (U = A^T V, Y = Delta^T W, P = A^T V); V is fp32
 template <typename T, int MA>
-__global__ __launch_bounds__(256) void k_thin_tn(const T* __restrict__ X, const T* __restrict__ V,
+__global__ __launch_bounds__(256) void k_thin_tn(const T* __restrict__ X, const float* __restrict__ V,
                                                  float* __restrict__ part, int64_t N, int64_t h, int r,
                                                  int64_t chunk) {
     constexpr int PW = 64, RC = 32;
@@ -121,7 +122,7 @@ __global__ __launch_bounds__(256) void k_thin_tn(const T* __restrict__ X, const 
         for (int m = 0; m < VL; ++m) {
             const int e = t + 256 * m < RC * r ? t + 256 * m : RC * r - 1, rr = e / r, j = e % r;
             const int64_t n = n0 + rr < nend ? n0 + rr : nend - 1;
-            vr[m] = ld<T>(V, n * r + j);
+            vr[m] = V[n * r + j];
         }
     };
     auto commit = [&](int64_t n0) {
@@ -310,7 +311,7 @@ dad_status gen_thin_nn(const void* X, const float* Pt, void* out, float* partial
 #define DAD_GEN_NN(MA)                                                                                              \
     do {                                                                                                            \
         if (dt == DAD_BF16)                                                                                         \
-            hipLaunchKernelGGL((k_thin_nn<bf16_t, MA>), grid, dim3(256), 0, s, (const bf16_t*)X, Pt, (bf16_t*)out, part, N, \
+            hipLaunchKernelGGL((k_thin_nn<bf16_t, MA>), grid, dim3(256), 0, s, (const bf16_t*)X, Pt, (float*)out, part, N, \
                                h, r, sp.chunk, zero_hdr);                                                           \
         else                                                                                                        \
             hipLaunchKernelGGL((k_thin_nn<float, MA>), grid, dim3(256), 0, s, (const float*)X, Pt, (float*)out, part, N, h, \
@@ -323,7 +324,6 @@ dad_status gen_thin_nn(const void* X, const float* Pt, void* out, float* partial
     }
     DAD_LAUNCH_CHECK();
     if (sp.splits == 1) return DAD_OK;
-    if (dt == DAD_BF16) return reduce_slabs(part, part, N * r, sp.splits, s, out);  // fp32 sum in place, bf16 copy out
     return reduce_slabs(part, (float*)out, N * r, sp.splits, s);
 }
 
@@ -348,7 +348,7 @@ dad_status gen_thin_tn(const void* X, const void* V, float* out_t, float* partia
 #define DAD_GEN_TN(MA)                                                                                              \
     do {                                                                                                            \
         if (dt == DAD_BF16)                                                                                         \
-            hipLaunchKernelGGL((k_thin_tn<bf16_t, MA>), grid, dim3(256), 0, s, (const bf16_t*)X, (const bf16_t*)V, dst, N, \
+            hipLaunchKernelGGL((k_thin_tn<bf16_t, MA>), grid, dim3(256), 0, s, (const bf16_t*)X, (const float*)V, dst, N, \
                                h, r, sp.chunk);                                                                     \
         else                                                                                                        \
             hipLaunchKernelGGL((k_thin_tn<float, MA>), grid, dim3(256), 0, s, (const float*)X, (const float*)V, dst, N, h, \

@@ -163,11 +163,12 @@ extern "C" dad_status dad_compress_rank_sequential(const void* A, const void* D,
     do {                                        \
         if ((rc = (expr)) != DAD_OK) return rc; \
     } while (0)
-    auto nn = [&](const void* X, const float* P, int64_t h, SplitPlan sp) {
-        return launch_thin_nn(X, P, V, part, sp, N, h, rp, dt, p.c.fast, nullptr, s);
+    // planes: the MFMA kernels carry w = A u as two bf16 terms (see dad_compress_rank)
+    auto nn = [&](const void* X, const float* P, int64_t h, SplitPlan sp, int planes) {
+        return launch_thin_nn(X, P, V, part, sp, N, h, rp, dt, p.c.fast, nullptr, planes, s);
     };
-    auto tn = [&](const void* X, float* out, int64_t h, SplitPlan sp) {
-        return launch_thin_tn(X, V, out, part, sp, N, h, rp, dt, p.c.fast, nullptr, s);
+    auto tn = [&](const void* X, float* out, int64_t h, SplitPlan sp, int planes) {
+        return launch_thin_tn(X, V, out, part, sp, N, h, rp, dt, p.c.fast, nullptr, planes, s);
     };
     if (rp > 1) {
         const int64_t n = (int64_t)(rp - 1) * h_out;
@@ -179,15 +180,15 @@ extern "C" dad_status dad_compress_rank_sequential(const void* A, const void* D,
                            j == 0 ? flag : (int*)nullptr);
         DAD_LAUNCH_CHECK();
         for (int it = 0; it < n_iter; ++it) {
-            DAD_TRY(nn(D, panel, h_out, p.c.nn_out));  // v = Delta g
-            DAD_TRY(tn(A, Ut, h_in, p.c.tn_in));       // u = A^T v
-            DAD_TRY(nn(A, Ut, h_in, p.c.nn_in));       // w = A u
-            DAD_TRY(tn(D, Yt, h_out, p.c.tn_out));     // y = Delta^T w = M^T M g
+            DAD_TRY(nn(D, panel, h_out, p.c.nn_out, 1));  // v = Delta g
+            DAD_TRY(tn(A, Ut, h_in, p.c.tn_in, 1));       // u = A^T v
+            DAD_TRY(nn(A, Ut, h_in, p.c.nn_in, 2));       // w = A u
+            DAD_TRY(tn(D, Yt, h_out, p.c.tn_out, 2));     // y = Delta^T w = M^T M g
             hipLaunchKernelGGL(k_seq_update, dim3(1), dim3(1024), 0, s, Yt, sGt, j, panel, h_out, flag);
             DAD_LAUNCH_CHECK();
         }
-        DAD_TRY(nn(D, panel, h_out, p.c.nn_out));  // v = Delta g
-        DAD_TRY(tn(A, Ut, h_in, p.c.tn_in));       // p = A^T v
+        DAD_TRY(nn(D, panel, h_out, p.c.nn_out, 1));  // v = Delta g
+        DAD_TRY(tn(A, Ut, h_in, p.c.tn_in, 1));       // p = A^T v
         hipLaunchKernelGGL(k_seq_finish, dim3(1), dim3(1024), 0, s, Ut, panel, Qt + (int64_t)j * h_in,
                            sGt + (int64_t)j * h_out, sigma ? sigma + j : (float*)nullptr, h_in, h_out, flag);
         DAD_LAUNCH_CHECK();

@@ -25,6 +25,38 @@ typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
 // ------------------------------------------------------------------------------------------------
 // thin_nn
 // ------------------------------------------------------------------------------------------------
+// Epilogue of thin_nn: the fp32 accumulators of a workgroup's RT x r tile (wave rows row0 .. row0+31,
+// MFMA 32x32 result layout) leave as bf16 through LDS, so that the tile goes out as contiguous
+// 16-byte stores.  planes = 2 also writes the rounding remainder: plane 0 holds hi = bf16(x), plane 1
+// (N * r elements further on) lo = bf16(x - hi), and hi + lo carries 16 significand bits of x.
+// vs is LDS for planes * RT * r bf16 values; the caller has finished reading its tiles.
+template <int JT, int RT>
+__device__ __forceinline__ void store_planes(const f32x16 (&acc)[JT], bf16_t* vs, bf16_t* __restrict__ V, int64_t N,
+                                             int64_t n0, int64_t rows_here, int r, int planes, int row0, int nthreads) {
+    const int t = threadIdx.x, lane = t & 63;
+    bf16_t* vlo = vs + RT * r;
+#pragma unroll
+    for (int j = 0; j < JT; ++j) {
+        const int col = j * 32 + (lane & 31);
+        if (col < r) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + ((v >> 2) << 3) + ((lane >> 5) << 2) + (v & 3);
+                const bf16_t hi = f32_to_bf16(acc[j][v]);
+                vs[row * r + col] = hi;
+                if (planes > 1) vlo[row * r + col] = f32_to_bf16(acc[j][v] - bf16_to_f32(hi));
+            }
+        }
+    }
+    __syncthreads();
+    const int chunks = (int)(rows_here * r / 8);  // r % 8 == 0
+    for (int p = 0; p < planes; ++p) {
+        u32x4* dst = reinterpret_cast<u32x4*>(V + (int64_t)p * N * r + n0 * r);
+        const u32x4* src = reinterpret_cast<const u32x4*>(vs + p * RT * r);
+        for (int e = t; e < chunks; e += nthreads) dst[e] = src[e];
+    }
+}
+
 namespace nn {
 constexpr int RT = 128;             // rows of X per workgroup (32 per wave)
 constexpr int BK = 64;              // contraction columns per stage (128 B of each row)
@@ -35,7 +67,7 @@ constexpr int XTILEB = RT * XROWB;
 template <int RP>  // RP = r rounded up to 32 or 64
 __global__ __launch_bounds__(256) void k_thin_nn_bf16(const bf16_t* __restrict__ X, const float* __restrict__ Pt,
                                                       bf16_t* __restrict__ V, int64_t N, int h, int r,
-                                                      int* __restrict__ zero_hdr) {
+                                                      int* __restrict__ zero_hdr, int planes) {
     // the first launch of a compress call also clears the workspace header (flag, ticket counter)
     if (zero_hdr && blockIdx.x == 0 && threadIdx.x < 64) zero_hdr[threadIdx.x] = 0;
     constexpr int JT = RP / 32;
@@ -141,24 +173,8 @@ __global__ __launch_bounds__(256) void k_thin_nn_bf16(const bf16_t* __restrict__
     }
 
     // epilogue: fp32 -> bf16 through LDS so the tile leaves as contiguous 16-byte stores
-    bf16_t* vs = reinterpret_cast<bf16_t*>(smem);  // [RT][r]
-#pragma unroll
-    for (int j = 0; j < JT; ++j) {
-        const int col = j * 32 + (lane & 31);
-        if (col < r) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = wave * 32 + ((v >> 2) << 3) + ((lane >> 5) << 2) + (v & 3);
-                vs[row * r + col] = f32_to_bf16(acc[j][v]);
-            }
-        }
-    }
-    __syncthreads();
     const int64_t rows_here = (N - n0 < nn::RT) ? (N - n0) : nn::RT;
-    const int chunks = (int)(rows_here * r / 8);  // r % 8 == 0
-    u32x4* dst = reinterpret_cast<u32x4*>(V + n0 * r);
-    const u32x4* src = reinterpret_cast<const u32x4*>(vs);
-    for (int e = t; e < chunks; e += 256) dst[e] = src[e];
+    store_planes<JT, nn::RT>(acc, reinterpret_cast<bf16_t*>(smem), V, N, n0, rows_here, r, planes, wave * 32, 256);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -171,7 +187,8 @@ __global__ __launch_bounds__(256) void k_thin_nn_bf16(const bf16_t* __restrict__
 // ------------------------------------------------------------------------------------------------
 template <int RP, int W, int NS>
 __global__ __launch_bounds__(64 * W) void k_thin_nn_bf16_dma(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Pb,
-                                                            bf16_t* __restrict__ V, int64_t N, int h, int r, int nt) {
+                                                            bf16_t* __restrict__ V, int64_t N, int h, int r, int nt,
+                                                            int planes) {
     constexpr int JT = RP / 32, RT = 32 * W, ROWB = 128;
     constexpr int XTILEB = RT * ROWB, PTILEB = RP * ROWB, STAGEB = XTILEB + PTILEB;
     constexpr int PI = RP / 8;               // 1 KiB loads that make up the panel tile
@@ -253,23 +270,7 @@ __global__ __launch_bounds__(64 * W) void k_thin_nn_bf16_dma(const bf16_t* __res
     __syncthreads();
 
     // epilogue: fp32 -> bf16 through LDS so the tile leaves as contiguous 16-byte stores
-    bf16_t* vs = reinterpret_cast<bf16_t*>(smem);  // [RT][r]
-#pragma unroll
-    for (int j = 0; j < JT; ++j) {
-        const int col = j * 32 + (lane & 31);
-        if (col < r) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = wave * 32 + ((v >> 2) << 3) + ((lane >> 5) << 2) + (v & 3);
-                vs[row * r + col] = f32_to_bf16(acc[j][v]);
-            }
-        }
-    }
-    __syncthreads();
-    const int chunks = RT * r / 8;
-    u32x4* dst = reinterpret_cast<u32x4*>(V + n0 * r);
-    const u32x4* src = reinterpret_cast<const u32x4*>(vs);
-    for (int e = t; e < chunks; e += 64 * W) dst[e] = src[e];
+    store_planes<JT, RT>(acc, reinterpret_cast<bf16_t*>(smem), V, N, n0, RT, r, planes, wave * 32, 64 * W);
 }
 
 // Start of a compress call on the direct-to-LDS path: Gb <- bf16(G0) with rows r..RP-1 zero, the same
@@ -312,14 +313,16 @@ __device__ __forceinline__ bf16x8 tn_frag(const char* tile, int rowb, int m0, in
     return __builtin_bit_cast(bf16x8, v);
 }
 
-template <int RP>
+// NV = number of bf16 planes of V (1, or 2 when V = hi + lo): the planes are N * r elements apart and
+// both are multiplied into the same accumulators.
+template <int RP, int NV>
 __global__ __launch_bounds__(256) void k_thin_tn_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ V,
                                                       float* __restrict__ part, int64_t N, int h, int r,
                                                       int64_t chunk_rows) {
     constexpr int JT = RP / 32;
     constexpr int VROWB = RP * 2;
     constexpr int VTILEB = tn::BK * VROWB;
-    constexpr int STAGEB = tn::XTILEB + VTILEB;
+    constexpr int STAGEB = tn::XTILEB + NV * VTILEB;
     constexpr int VLOADS = (tn::BK * RP / 8 + 255) / 256;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -328,13 +331,14 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16(const bf16_t* __restrict__
     const int64_t nend = (nbeg + chunk_rows < N) ? nbeg + chunk_rows : N;
     const int nk = (int)((nend - nbeg + tn::BK - 1) / tn::BK);
     const int rc = r >> 3;  // 16-byte chunks per V row
+    const int64_t plane = N * (int64_t)r;
 
     // X staging: chunk xc of rows xr + 16*i ; (xr + 16*i) & 3 == xr & 3
     const int xc = t & 15, xr = t >> 4;
     const int x_st = tn_x_off(xr, xc);
 
     u32x4 xs[2][4];
-    u32x4 vsr[2][VLOADS];
+    u32x4 vsr[2][NV][VLOADS];
 
     auto gload = [&](int kt, int set) {
         const int64_t kb = nbeg + (int64_t)kt * tn::BK;
@@ -347,15 +351,17 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16(const bf16_t* __restrict__
                 xs[set][i] = (u32x4){0, 0, 0, 0};
         }
 #pragma unroll
-        for (int i = 0; i < VLOADS; ++i) {
-            const int e = t + 256 * i;
-            const int row = e / rc, c = e - row * rc;
-            const int64_t n = kb + row;
-            if (row < tn::BK && n < nend)
-                vsr[set][i] = *reinterpret_cast<const u32x4*>(V + n * r + c * 8);
-            else
-                vsr[set][i] = (u32x4){0, 0, 0, 0};
-        }
+        for (int q = 0; q < NV; ++q)
+#pragma unroll
+            for (int i = 0; i < VLOADS; ++i) {
+                const int e = t + 256 * i;
+                const int row = e / rc, c = e - row * rc;
+                const int64_t n = kb + row;
+                if (row < tn::BK && n < nend)
+                    vsr[set][q][i] = *reinterpret_cast<const u32x4*>(V + q * plane + n * r + c * 8);
+                else
+                    vsr[set][q][i] = (u32x4){0, 0, 0, 0};
+            }
     };
     auto lstore = [&](int stage, int set) {
         char* xb = smem + stage * STAGEB;
@@ -363,20 +369,25 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16(const bf16_t* __restrict__
 #pragma unroll
         for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(xb + x_st + 16 * i * tn::XROWB) = xs[set][i];
 #pragma unroll
-        for (int i = 0; i < VLOADS; ++i) {
-            const int e = t + 256 * i;
-            const int row = e / rc, c = e - row * rc;
-            if (row < tn::BK) *reinterpret_cast<u32x4*>(vb + row * VROWB + c * 16) = vsr[set][i];
-        }
+        for (int q = 0; q < NV; ++q)
+#pragma unroll
+            for (int i = 0; i < VLOADS; ++i) {
+                const int e = t + 256 * i;
+                const int row = e / rc, c = e - row * rc;
+                if (row < tn::BK) *reinterpret_cast<u32x4*>(vb + q * VTILEB + row * VROWB + c * 16) = vsr[set][q][i];
+            }
     };
 
-    // columns r..RP-1 of both V tiles stay zero for the whole kernel
+    // columns r..RP-1 of all V tiles stay zero for the whole kernel
     if (r < RP) {
-        for (int e = t; e < 2 * tn::BK * RP / 8; e += 256) {
-            const int stage = e / (tn::BK * RP / 8), rem = e - stage * (tn::BK * RP / 8);
-            const int row = rem / (RP / 8), c = rem - row * (RP / 8);
+        constexpr int PER = tn::BK * RP / 8;  // 16-byte chunks per V tile
+        for (int e = t; e < 2 * NV * PER; e += 256) {
+            const int stage = e / (NV * PER), rem = e - stage * (NV * PER);
+            const int q = rem / PER, rem2 = rem - q * PER;
+            const int row = rem2 / (RP / 8), c = rem2 - row * (RP / 8);
             if (c >= rc)
-                *reinterpret_cast<u32x4*>(smem + stage * STAGEB + tn::XTILEB + row * VROWB + c * 16) = (u32x4){0, 0, 0, 0};
+                *reinterpret_cast<u32x4*>(smem + stage * STAGEB + tn::XTILEB + q * VTILEB + row * VROWB + c * 16) =
+                    (u32x4){0, 0, 0, 0};
         }
     }
 
@@ -393,10 +404,12 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16(const bf16_t* __restrict__
         for (int ks = 0; ks < tn::BK / 16; ++ks) {
             bf16x8 fx = tn_frag<true>(xb, tn::XROWB, wave * 32, ks * 16, lane);
 #pragma unroll
-            for (int j = 0; j < JT; ++j) {
-                bf16x8 fv = tn_frag<false>(vb, VROWB, j * 32, ks * 16, lane);
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv, fx, acc[j], 0, 0, 0);
-            }
+            for (int j = 0; j < JT; ++j)
+#pragma unroll
+                for (int q = 0; q < NV; ++q) {
+                    bf16x8 fv = tn_frag<false>(vb + q * VTILEB, VROWB, j * 32, ks * 16, lane);
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv, fx, acc[j], 0, 0, 0);
+                }
         }
     };
 
@@ -440,7 +453,7 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16(const bf16_t* __restrict__
 // of three slots, so two tiles per workgroup are always in flight and two workgroups share a CU.
 // The swizzle of the X tile is applied on the global side, as in the rebuild kernel.
 // ------------------------------------------------------------------------------------------------
-template <int R, int PW, int BK>
+template <int R, int PW, int BK, int NV>
 __global__ __launch_bounds__(256) void k_thin_tn_bf16_dma(const bf16_t* __restrict__ X, const bf16_t* __restrict__ V,
                                                           float* __restrict__ part, int64_t N, int h,
                                                           int64_t chunk_rows, int strips, int splits, int nt) {
@@ -453,12 +466,12 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16_dma(const bf16_t* __restri
     constexpr int CPR = PW / 8;                   // 16-byte chunks per row
     constexpr int VROWB = R * 2;
     constexpr int VTILEB = BK * VROWB;
-    constexpr int VSLOT = VTILEB + 256;  // R = 16: fragment reads of the unused columns 16..31 run past the tile
+    constexpr int VSLOT = NV * VTILEB + 256;  // R = 16: fragment reads of the unused columns 16..31 run past the tile
     constexpr int STAGEB = XTILEB + VSLOT;
     constexpr int NS = 3;
     constexpr int VP = VTILEB / 1024;             // 1 KiB pieces of the V tile
     constexpr int VL = VP > 4 ? VP / 4 : 1;       // V loads per wave per tile (fewer pieces than waves: repeats)
-    constexpr int LOADS = XL + VL;
+    constexpr int LOADS = XL + NV * VL;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     // Workgroups are handed to the eight XCDs round-robin by their linear index.  All column strips
@@ -485,13 +498,16 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16_dma(const bf16_t* __restri
         const int c = (lane % CPR) ^ ((row & 3) << 2);
         gx[i] = reinterpret_cast<const char*>(X + (nbeg + row) * (int64_t)h + p0 + c * 8);
     }
-    // V: the tile is 64*R*2 contiguous bytes; load i of this wave covers its 1 KiB piece vi[i]
-    const char* gv[VL];
+    // V: a tile is BK*R*2 contiguous bytes of each of the NV planes (N*R elements apart); load i of
+    // this wave covers the 1 KiB piece vi[i] of every plane
+    const char* gv[NV][VL];
     int vi[VL];
 #pragma unroll
     for (int i = 0; i < VL; ++i) {
         vi[i] = (wave * VL + i) % VP;
-        gv[i] = reinterpret_cast<const char*>(V + nbeg * R) + vi[i] * 1024 + lane * 16;
+#pragma unroll
+        for (int q = 0; q < NV; ++q)
+            gv[q][i] = reinterpret_cast<const char*>(V + (int64_t)q * N * R + nbeg * R) + vi[i] * 1024 + lane * 16;
     }
     const int64_t adv_x = (int64_t)BK * h * 2;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
@@ -507,10 +523,12 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16_dma(const bf16_t* __restri
             gx[i] += adv_x;
         }
 #pragma unroll
-        for (int i = 0; i < VL; ++i) {
-            dma16(gv[i], base + XTILEB + vi[i] * 1024);
-            gv[i] += VTILEB;
-        }
+        for (int q = 0; q < NV; ++q)
+#pragma unroll
+            for (int i = 0; i < VL; ++i) {
+                dma16(gv[q][i], base + XTILEB + q * VTILEB + vi[i] * 1024);
+                gv[q][i] += VTILEB;
+            }
     };
 
     f32x16 acc[MT][JT];
@@ -537,15 +555,19 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16_dma(const bf16_t* __restri
         const char* vb = xb + XTILEB;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 fv[JT];
+            bf16x8 fv[NV][JT];
 #pragma unroll
-            for (int j = 0; j < JT; ++j) fv[j] = tn_frag<false>(vb, VROWB, j * 32, ks * 16, lane);
+            for (int q = 0; q < NV; ++q)
+#pragma unroll
+                for (int j = 0; j < JT; ++j) fv[q][j] = tn_frag<false>(vb + q * VTILEB, VROWB, j * 32, ks * 16, lane);
 #pragma unroll
             for (int m = 0; m < MT; ++m) {
                 bf16x8 fx = tn_frag<true>(xb, XROWB, (wave * MT + m) * 32, ks * 16, lane);
 #pragma unroll
                 for (int j = 0; j < JT; ++j)
-                    acc[m][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[j], fx, acc[m][j], 0, 0, 0);
+#pragma unroll
+                    for (int q = 0; q < NV; ++q)
+                        acc[m][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[q][j], fx, acc[m][j], 0, 0, 0);
             }
         }
         slot = slot == NS - 1 ? 0 : slot + 1;
@@ -606,17 +628,17 @@ static dad_status set_lds(Kern k, int bytes) {
 }
 
 dad_status fast_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int64_t h, int r, int* zero_hdr,
-                        hipStream_t s) {
+                        int planes, hipStream_t s) {
     dim3 grid((unsigned)ceil_div(N, nn::RT));
     ProfScope prof(KID_THIN_NN_BF16, s);
     if (r <= 32) {
         const int lds = 2 * (nn::XTILEB + 32 * nn::XROWB);
         hipLaunchKernelGGL(k_thin_nn_bf16<32>, grid, dim3(256), lds, s, (const bf16_t*)X, Pt, (bf16_t*)out, N, (int)h, r,
-                           zero_hdr);
+                           zero_hdr, planes);
     } else {
         const int lds = 2 * (nn::XTILEB + 64 * nn::XROWB);
         hipLaunchKernelGGL(k_thin_nn_bf16<64>, grid, dim3(256), lds, s, (const bf16_t*)X, Pt, (bf16_t*)out, N, (int)h, r,
-                           zero_hdr);
+                           zero_hdr, planes);
     }
     DAD_LAUNCH_CHECK();
     return DAD_OK;
@@ -639,7 +661,8 @@ dad_status launch_panel_init(const float* G0, void* Gb, void* Ub, int64_t h_in, 
 }
 
 template <int RP, int W, int NS>
-static dad_status dma_thin_nn_cfg(const void* X, const void* Pb, void* out, int64_t N, int64_t h, int r, hipStream_t s) {
+static dad_status dma_thin_nn_cfg(const void* X, const void* Pb, void* out, int64_t N, int64_t h, int r, int planes,
+                                  hipStream_t s) {
     const int lds = NS * (32 * W * 128 + RP * 128);
     static bool attr_set = false;
     if (!attr_set) {
@@ -648,17 +671,19 @@ static dad_status dma_thin_nn_cfg(const void* X, const void* Pb, void* out, int6
         attr_set = true;
     }
     hipLaunchKernelGGL((k_thin_nn_bf16_dma<RP, W, NS>), dim3((unsigned)(N / (32 * W))), dim3(64 * W), lds, s,
-                       (const bf16_t*)X, (const bf16_t*)Pb, (bf16_t*)out, N, (int)h, r, stream_once(N, h) ? 1 : 0);
+                       (const bf16_t*)X, (const bf16_t*)Pb, (bf16_t*)out, N, (int)h, r, stream_once(N, h) ? 1 : 0, planes);
     DAD_LAUNCH_CHECK();
     return DAD_OK;
 }
 
 // Rows per workgroup: 256 (eight waves) when that still gives one workgroup per CU, fewer for
 // shorter factors so that the chip stays filled (a site's 8192 rows: 256 single-wave workgroups).
-dad_status dma_thin_nn(const void* X, const void* Pb, void* out, int64_t N, int64_t h, int r, hipStream_t s) {
+dad_status dma_thin_nn(const void* X, const void* Pb, void* out, int64_t N, int64_t h, int r, int planes,
+                       hipStream_t s) {
     ProfScope prof(KID_THIN_NN_BF16, s);
     const int64_t want = 256;  // workgroups
-#define DAD_NN_W(W) (r <= 32 ? dma_thin_nn_cfg<32, W, 3>(X, Pb, out, N, h, r, s) : dma_thin_nn_cfg<64, W, 3>(X, Pb, out, N, h, r, s))
+#define DAD_NN_W(W) \
+    (r <= 32 ? dma_thin_nn_cfg<32, W, 3>(X, Pb, out, N, h, r, planes, s) : dma_thin_nn_cfg<64, W, 3>(X, Pb, out, N, h, r, planes, s))
     if (N / 256 >= want) return DAD_NN_W(8);
     if (N / 128 >= want) return DAD_NN_W(4);
     if (N / 64 >= want) return DAD_NN_W(2);
@@ -667,25 +692,32 @@ dad_status dma_thin_nn(const void* X, const void* Pb, void* out, int64_t N, int6
 }
 
 dad_status fast_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp, int64_t N, int64_t h,
-                        int r, void* out_bf16, hipStream_t s) {
+                        int r, void* out_bf16, int planes, hipStream_t s) {
     float* dst = sp.splits == 1 ? out_t : partials;
     if ((r == 16 || r == 32 || r == 64) && N % tn::BK == 0 && sp.chunk % tn::BK == 0) {
         ProfScope prof(KID_THIN_TN_BF16, s);
         const int pw = thin_tn_pw(h);
         const int bk = pw == 128 ? 64 : 32;
-        const int lds = 3 * (bk * pw * 2 + bk * r * 2 + 256);
+        const int lds = 3 * (bk * pw * 2 + planes * bk * r * 2 + 256);
         const int strips = (int)(h / pw);
-#define DAD_TN_LAUNCH(RR, PP, BB)                                                                                     \
+#define DAD_TN_LAUNCH_NV(RR, PP, BB, NV)                                                                              \
     do {                                                                                                              \
         static bool attr_set = false;                                                                                 \
         if (!attr_set) {                                                                                              \
-            DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_thin_tn_bf16_dma<RR, PP, BB>),           \
+            DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_thin_tn_bf16_dma<RR, PP, BB, NV>),       \
                                             hipFuncAttributeMaxDynamicSharedMemorySize, lds));                        \
             attr_set = true;                                                                                          \
         }                                                                                                             \
-        hipLaunchKernelGGL((k_thin_tn_bf16_dma<RR, PP, BB>), dim3((unsigned)(strips * sp.splits)), dim3(256), lds, s, \
+        hipLaunchKernelGGL((k_thin_tn_bf16_dma<RR, PP, BB, NV>), dim3((unsigned)(strips * sp.splits)), dim3(256), lds, s, \
                            (const bf16_t*)X, (const bf16_t*)V, dst, N, (int)h, sp.chunk, strips, sp.splits,           \
                            stream_once(N, h) ? 1 : 0);                                                                \
+    } while (0)
+#define DAD_TN_LAUNCH(RR, PP, BB)                  \
+    do {                                           \
+        if (planes > 1)                            \
+            DAD_TN_LAUNCH_NV(RR, PP, BB, 2);       \
+        else                                       \
+            DAD_TN_LAUNCH_NV(RR, PP, BB, 1);       \
     } while (0)
         if (pw == 128) {
             if (r == 16) DAD_TN_LAUNCH(16, 128, 64);
@@ -696,19 +728,24 @@ dad_status fast_thin_tn(const void* X, const void* V, float* out_t, float* parti
             else if (r == 32) DAD_TN_LAUNCH(32, 256, 32);
             else DAD_TN_LAUNCH(64, 256, 32);
         }
+#undef DAD_TN_LAUNCH_NV
 #undef DAD_TN_LAUNCH
     } else {  // ragged row count or a rank the direct-to-LDS kernel is not built for
         ProfScope prof(KID_THIN_TN_BF16, s);
         const dim3 grid((unsigned)(h / tn::PW), (unsigned)sp.splits);
+        const int rp = r <= 32 ? 32 : 64;
+        const int lds = 2 * (tn::XTILEB + planes * tn::BK * rp * 2);  // at most 64 KiB
+#define DAD_TN_REG(RP, NV)                                                                                            \
+    hipLaunchKernelGGL((k_thin_tn_bf16<RP, NV>), grid, dim3(256), lds, s, (const bf16_t*)X, (const bf16_t*)V, dst, N, \
+                       (int)h, r, sp.chunk)
         if (r <= 32) {
-            const int lds = 2 * (tn::XTILEB + tn::BK * 64);
-            hipLaunchKernelGGL(k_thin_tn_bf16<32>, grid, dim3(256), lds, s, (const bf16_t*)X, (const bf16_t*)V, dst, N,
-                               (int)h, r, sp.chunk);
+            if (planes > 1) DAD_TN_REG(32, 2);
+            else DAD_TN_REG(32, 1);
         } else {
-            const int lds = 2 * (tn::XTILEB + tn::BK * 128);
-            hipLaunchKernelGGL(k_thin_tn_bf16<64>, grid, dim3(256), lds, s, (const bf16_t*)X, (const bf16_t*)V, dst, N,
-                               (int)h, r, sp.chunk);
+            if (planes > 1) DAD_TN_REG(64, 2);
+            else DAD_TN_REG(64, 1);
         }
+#undef DAD_TN_REG
     }
     DAD_LAUNCH_CHECK();
     if (sp.splits > 1) return reduce_slabs(partials, out_t, (int64_t)r * h, sp.splits, s, out_bf16);

@@ -77,7 +77,7 @@ def test_vit_large_layer_shapes_full(gpu, layer):
     run_full_size(w, layer, h_in, h_out, gpu)
 
 
-def run_two_level(w, layer, h_in, h_out, dev, agg=None, site_tol=TOL_BF16):
+def run_two_level(w, layer, h_in, h_out, dev, agg=None):
     """Algorithm 1 at the workload's sizes: every site reduces its own b rows, the S*r-row
     stack of the pairs is reduced again, the estimate is rebuilt; the oracle does the same in
     fp64 from the same factors and start matrices."""
@@ -95,18 +95,18 @@ def run_two_level(w, layer, h_in, h_out, dev, agg=None, site_tol=TOL_BF16):
     Pt_ref, Gt_ref, pairs_ref = O.rank_dad(A_h, D_h, G0s, G0a, n)
     out = {"e_two_level": O.rel_fro(G_hat, O.rank_r_grad(Pt_ref, Gt_ref)),
            "e_site_max": max(O.rel_fro(dad.reconstruct_grad(p, g).cpu().numpy(), O.rank_r_grad(pr, gr))
-                             for (p, g), (pr, gr) in zip(pairs[:2], pairs_ref[:2]))}
+                             for (p, g), (pr, gr) in zip(pairs, pairs_ref))}
     g = Gt.cpu().numpy().astype(np.float64)
     out["orth"] = float(np.abs(g @ g.T - np.eye(r)).max())
     print(w.name, "two-level", layer, h_in, h_out, out)
-    assert out["e_site_max"] <= site_tol, out
+    assert out["e_site_max"] <= TOL_BF16, out
     assert out["e_two_level"] <= TOL_BF16, out
     assert out["orth"] <= 1e-4, out
     del As, Ds
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("widx,layer", [(2, 0), (2, 3), (3, 2), (3, 3), (4, 2)])
+@pytest.mark.parametrize("widx,layer", [(2, 0), (2, 3), (3, 2), (3, 3), (4, 2), (4, 3)])
 def test_two_level_rank_dad_full(gpu, widx, layer):
     """Site-level reduction at b rows per site (bf16 factors), aggregator-level reduction of the
     S*r stacked fp32 rows (64, 256 and 1024 rows for the three transformer workloads)."""
@@ -122,11 +122,4 @@ def test_two_level_rank_dad_full_gram_aggregator(gpu, widx, layer):
     runs it."""
     w = W.WORKLOADS[widx]
     _, h_in, h_out = w.all_layers()[layer]
-    # The result of Algorithm 1 is held to the bf16 bar.  The intermediate per-site pairs of the
-    # ViT-large 5120 -> 1280 layer are only reported against 3e-2: one of its 16384-row sites
-    # measures 2.13e-2 (the others 4e-3 .. 8e-3).  GELU activations have a large common mean, so the
-    # rows of W = A (A^T V) carry a large common component, and rounding W to bf16 for the matrix
-    # instruction costs 7e-3 .. 1.3e-2 there against 1e-3 for each of the other three roundings
-    # (CPU emulation of the roundings one at a time); the residual |M - P G^T| is unaffected.
-    site_tol = 3e-2 if (widx, layer) == (4, 3) else TOL_BF16
-    run_two_level(w, layer, h_in, h_out, gpu, agg=dad.compress_rank_gram, site_tol=site_tol)
+    run_two_level(w, layer, h_in, h_out, gpu, agg=dad.compress_rank_gram)
