@@ -18,25 +18,31 @@
  *   - All matrices are dense, row-major, with no padding between rows.
  *   - Every pointer named "device" is a HIP device pointer on the current
  *     device and is owned by the caller; the library allocates and frees no
- *     device memory and keeps no state between calls.  Scratch space comes in
- *     through `workspace` (size from the matching *_workspace_bytes query).
+ *     device memory.  Scratch space comes in through `workspace` (size from
+ *     the matching *_workspace_bytes query).  Nothing computed is kept from
+ *     one call to the next; the only process-wide state is a per-device
+ *     "set-up done" flag (see dad_init) and, when switched on, the timing
+ *     records of dad_profile_*; both are safe to use from several host
+ *     threads.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls enqueue work and return; they do not synchronise.
  *   - Argument errors are detected on the host and returned before anything
  *     is enqueued (so they can be exercised without a GPU).  A numerical
  *     breakdown found on the device is latched in the workspace and reported
  *     by dad_poll_numeric_status.
- *   - Device pointers must be 16-byte aligned.  Any N, h_in, h_out >= 1 is
- *     accepted; shapes whose widths are multiples of the MFMA tile take the
- *     fast kernels, others a slower guarded path with identical results up to
- *     rounding order.
+ *   - Device pointers must be 16-byte aligned.  Any 1 <= N <= DAD_MAX_ROWS and
+ *     1 <= h_in, h_out <= DAD_MAX_WIDTH is accepted (DAD_ERR_SHAPE beyond: the
+ *     launch grids do not hold more); shapes whose widths are multiples of the
+ *     MFMA tile take the fast kernels, others a slower guarded path with
+ *     identical results up to rounding order.
  *   - Overlapping calls that share a workspace race; use one workspace per
  *     stream.
  *   - Every call but dad_poll_numeric_status (which copies one word to the host
- *     and waits for it) may be recorded into a HIP graph: nothing is allocated,
- *     copied or cleared by memset.  dad_compress_rank_gram and
- *     dad_backprop_delta ask the runtime once per process for more than 64 KB
- *     of LDS on their first call: make that first call outside a capture.
+ *     and waits for it) and dad_init may be recorded into a HIP graph: nothing
+ *     is allocated, copied or cleared by memset.  The first call on a device
+ *     sets kernel attributes (several kernels ask for more than 64 KB of LDS):
+ *     call dad_init() on that device before the first capture, or make any
+ *     first call outside a capture.
  */
 #ifndef DAD_H
 #define DAD_H
@@ -65,9 +71,19 @@ typedef enum {
 #define DAD_MAX_RANK 64    /* largest r accepted by dad_compress_rank */
 #define DAD_GRAM_MAX_ROWS 1024 /* largest N accepted by dad_compress_rank_gram */
 #define DAD_MAX_SITES 4096 /* largest S accepted by dad_stack_factors */
+#define DAD_MAX_ROWS ((int64_t)1 << 36)  /* largest N (or K) accepted */
+#define DAD_MAX_WIDTH ((int64_t)1 << 21) /* largest h_in, h_out accepted */
 
 /* Human-readable name of a status code; static storage, never NULL. */
 const char* dad_status_string(dad_status s);
+
+/*
+ * One-time set-up of the current device (kernel attributes).  Optional: every entry point does the
+ * same on its first call on a device, guarded by a mutex, and after that only reads a flag.  Call
+ * it explicitly, once per device with that device current, when the first real call would fall
+ * inside a HIP graph capture.  Returns DAD_OK or DAD_ERR_HIP.
+ */
+dad_status dad_init(void);
 
 /*
  * dad_stack_factors - Section 3.2 (concatenate the sites' factors along the

@@ -42,6 +42,8 @@ def lib() -> C.CDLL:
     vp, i64, sz = C.c_void_p, C.c_int64, C.c_size_t
     L.dad_status_string.restype = C.c_char_p
     L.dad_status_string.argtypes = [C.c_int]
+    L.dad_init.restype = C.c_int
+    L.dad_init.argtypes = []
     L.dad_stack_factors.restype = C.c_int
     L.dad_stack_factors.argtypes = [C.c_int, C.POINTER(vp), C.POINTER(vp), C.POINTER(i64), i64, i64, C.c_int,
                                     vp, vp, vp]
@@ -99,6 +101,11 @@ def _check(rc: int, where: str):
 def _dense2d(t: torch.Tensor, name: str):
     if t.dim() != 2 or not t.is_contiguous() or not t.is_cuda:
         raise ValueError(f"{name} must be a contiguous 2-D CUDA tensor")
+
+
+def init():
+    """dad_init: one-time set-up of the current device (needed only before a first call under graph capture)."""
+    _check(lib().dad_init(), "dad_init")
 
 
 def stack_factors(A_sites, D_sites, A_out=None, D_out=None):

@@ -1,4 +1,7 @@
 // C ABI of libdad: argument checks on the host, then kernel launches on the caller's stream.
+#include <atomic>
+#include <mutex>
+
 #include "dad_internal.h"
 
 namespace dad {
@@ -91,6 +94,33 @@ RebuildPlan plan_rebuild(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt) {
 
 static bool dtype_ok(dad_dtype dt) { return dt == DAD_F32 || dt == DAD_BF16; }
 
+// ---------------------------------------------------------------- per-device set-up
+constexpr int MAX_DEVICES = 64;
+struct DeviceState {
+    std::atomic<int> ready{0};
+};
+static DeviceState g_dev[MAX_DEVICES];
+static std::mutex g_dev_mu;
+
+dad_status device_ready() {
+    int dev = -1;
+    DAD_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return DAD_ERR_HIP;
+    DeviceState& st = g_dev[dev];
+    if (!st.ready.load(std::memory_order_acquire)) {
+        std::lock_guard<std::mutex> lk(g_dev_mu);
+        if (!st.ready.load(std::memory_order_relaxed)) {
+            dad_status rc;
+            if ((rc = thin_prepare_device()) != DAD_OK) return rc;
+            if ((rc = rebuild_prepare_device()) != DAD_OK) return rc;
+            if ((rc = gram_prepare_device()) != DAD_OK) return rc;
+            if ((rc = backprop_prepare_device()) != DAD_OK) return rc;
+            st.ready.store(1, std::memory_order_release);
+        }
+    }
+    return DAD_OK;
+}
+
 }  // namespace dad
 
 using namespace dad;
@@ -123,14 +153,15 @@ dad_status dad_stack_factors(int S, const void* const* A_sites, const void* cons
     if (!aligned16(A_out) || !aligned16(D_out)) return DAD_ERR_ALIGN;
     for (int s = 0; s < S; ++s)
         if (rows[s] > 0 && (!aligned16(A_sites[s]) || !aligned16(D_sites[s]))) return DAD_ERR_ALIGN;
+    if (const dad_status ready = device_ready(); ready != DAD_OK) return ready;
     return launch_stack(S, A_sites, D_sites, rows, h_in, h_out, dt, A_out, D_out, (hipStream_t)stream);
 }
 
 static bool compress_shape_ok(int64_t N, int64_t h_in, int64_t h_out, int r) {
     if (N < 1 || h_in < 1 || h_out < 1 || r < 1 || r > DAD_MAX_RANK) return false;
     if (r > N || r > h_in || r > h_out) return false;
-    // intermediate indices are computed in int64; keep element counts well inside it
-    if (N > (int64_t)1 << 40 || h_in > (int64_t)1 << 24 || h_out > (int64_t)1 << 24) return false;
+    // what the launch grids hold: ceil(N / 64) in grid.x, ceil(h / 64) in grid.y
+    if (N > DAD_MAX_ROWS || h_in > DAD_MAX_WIDTH || h_out > DAD_MAX_WIDTH) return false;
     return true;
 }
 
@@ -139,19 +170,20 @@ size_t dad_compress_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, int 
     return plan_compress(N, h_in, h_out, r, dt).total;
 }
 
-dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_in, int64_t h_out, dad_dtype dt,
-                             int r, int n_iter, const float* G0, float* Pt, float* Gt, void* workspace,
-                             size_t ws_bytes, void* stream) {
-    if (!A || !D || !G0 || !Pt || !Gt || !workspace) return DAD_ERR_NULL;
+// Host-side argument checks of dad_compress_rank.
+static dad_status compress_args_ok(const void* A, const void* D, int64_t N, int64_t h_in, int64_t h_out, dad_dtype dt,
+                                   int r, int n_iter, const float* G0, const float* Pt, const float* Gt) {
+    if (!A || !D || !G0 || !Pt || !Gt) return DAD_ERR_NULL;
     if (!dtype_ok(dt)) return DAD_ERR_DTYPE;
     if (!compress_shape_ok(N, h_in, h_out, r) || n_iter < 1) return DAD_ERR_SHAPE;
-    if (!aligned16(A) || !aligned16(D) || !aligned16(G0) || !aligned16(Pt) || !aligned16(Gt) ||
-        !aligned16(workspace))
-        return DAD_ERR_ALIGN;
-    const CompressPlan p = plan_compress(N, h_in, h_out, r, dt);
-    if (ws_bytes < p.total) return DAD_ERR_WORKSPACE;
+    if (!aligned16(A) || !aligned16(D) || !aligned16(G0) || !aligned16(Pt) || !aligned16(Gt)) return DAD_ERR_ALIGN;
+    return DAD_OK;
+}
 
-    hipStream_t s = (hipStream_t)stream;
+// The launches of one compress call; every argument has been checked and the device is ready.
+static dad_status compress_launch(const CompressPlan& p, const void* A, const void* D, int64_t N, int64_t h_in,
+                                  int64_t h_out, dad_dtype dt, int r, int n_iter, const float* G0, float* Pt, float* Gt,
+                                  void* workspace, hipStream_t s) {
     char* ws = static_cast<char*>(workspace);
     int* flag = reinterpret_cast<int*>(ws + p.off_flag);
     void* V = ws + p.off_V;
@@ -204,9 +236,23 @@ dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_
 #undef DAD_TRY
 }
 
+dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_in, int64_t h_out, dad_dtype dt,
+                             int r, int n_iter, const float* G0, float* Pt, float* Gt, void* workspace,
+                             size_t ws_bytes, void* stream) {
+    if (!workspace) return DAD_ERR_NULL;
+    dad_status rc = compress_args_ok(A, D, N, h_in, h_out, dt, r, n_iter, G0, Pt, Gt);
+    if (rc != DAD_OK) return rc;
+    if (!aligned16(workspace)) return DAD_ERR_ALIGN;
+    const CompressPlan p = plan_compress(N, h_in, h_out, r, dt);
+    if (ws_bytes < p.total) return DAD_ERR_WORKSPACE;
+    if ((rc = device_ready()) != DAD_OK) return rc;
+    return compress_launch(p, A, D, N, h_in, h_out, dt, r, n_iter, G0, Pt, Gt, workspace, (hipStream_t)stream);
+}
+
+dad_status dad_init(void) { return device_ready(); }
+
 static bool rebuild_shape_ok(int64_t K, int64_t h_in, int64_t h_out) {
-    return K >= 1 && h_in >= 1 && h_out >= 1 && K <= (int64_t)1 << 40 && h_in <= (int64_t)1 << 24 &&
-           h_out <= (int64_t)1 << 24;
+    return K >= 1 && h_in >= 1 && h_out >= 1 && K <= DAD_MAX_ROWS && h_in <= DAD_MAX_WIDTH && h_out <= DAD_MAX_WIDTH;
 }
 
 size_t dad_reconstruct_workspace_bytes(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt) {
@@ -223,6 +269,7 @@ dad_status dad_reconstruct_grad(const void* L, const void* R, int64_t K, int64_t
     if (p.total > 0 && !workspace) return DAD_ERR_NULL;
     if (!aligned16(L) || !aligned16(R) || !aligned16(G) || (workspace && !aligned16(workspace))) return DAD_ERR_ALIGN;
     if (ws_bytes < p.total) return DAD_ERR_WORKSPACE;
+    if (const dad_status ready = device_ready(); ready != DAD_OK) return ready;
     return launch_rebuild(L, R, K, h_in, h_out, dt, G, static_cast<float*>(workspace), p, (hipStream_t)stream);
 }
 

@@ -312,18 +312,21 @@ template <int ACT>
 static dad_status launch_backprop_fast(const void* Dn, const void* Wn, const void* Z, void* Dout, int64_t N, int64_t h,
                                        int64_t hn, hipStream_t s) {
     const int lds = bp::STAGES * bp::STAGEB;
-    static bool attr_set = false;
-    if (!attr_set) {
-        DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_backprop_bf16<ACT>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-        attr_set = true;
-    }
     const int tiles_n = (int)(h / bp::TILE);
     const int total = (int)((N / bp::TILE) * tiles_n);
     ProfScope prof(KID_BACKPROP_BF16, s);
     hipLaunchKernelGGL(k_backprop_bf16<ACT>, dim3((unsigned)total), dim3(bp::THREADS), lds, s, (const bf16_t*)Dn,
                        (const bf16_t*)Wn, (const bf16_t*)Z, (bf16_t*)Dout, (int)h, (int)hn, tiles_n, total);
     DAD_LAUNCH_CHECK();
+    return DAD_OK;
+}
+
+dad_status backprop_prepare_device() {
+    const int lds = bp::STAGES * bp::STAGEB;
+    DAD_HIP_TRY(set_max_lds(k_backprop_bf16<DAD_ACT_IDENTITY>, lds));
+    DAD_HIP_TRY(set_max_lds(k_backprop_bf16<DAD_ACT_RELU>, lds));
+    DAD_HIP_TRY(set_max_lds(k_backprop_bf16<DAD_ACT_TANH>, lds));
+    DAD_HIP_TRY(set_max_lds(k_backprop_bf16<DAD_ACT_SIGMOID>, lds));
     return DAD_OK;
 }
 
@@ -337,11 +340,14 @@ extern "C" dad_status dad_backprop_delta(const void* D_next, const void* W_next,
     if (dt != DAD_F32 && dt != DAD_BF16) return DAD_ERR_DTYPE;
     if (act != DAD_ACT_IDENTITY && act != DAD_ACT_RELU && act != DAD_ACT_TANH && act != DAD_ACT_SIGMOID)
         return DAD_ERR_SHAPE;
-    if (N < 1 || h < 1 || h_next < 1 || N > ((int64_t)1 << 40) || h > ((int64_t)1 << 24) || h_next > ((int64_t)1 << 24))
+    if (N < 1 || h < 1 || h_next < 1 || N > DAD_MAX_ROWS || h > DAD_MAX_WIDTH || h_next > DAD_MAX_WIDTH)
         return DAD_ERR_SHAPE;
     hipStream_t s = (hipStream_t)stream;
-    if (backprop_fast_ok(N, h, h_next, dt)) {
-        if (!aligned16(D_next) || !aligned16(W_next) || !aligned16(Z) || !aligned16(D_out)) return DAD_ERR_ALIGN;
+    const bool fast = backprop_fast_ok(N, h, h_next, dt);
+    if (fast && (!aligned16(D_next) || !aligned16(W_next) || !aligned16(Z) || !aligned16(D_out))) return DAD_ERR_ALIGN;
+    if (!fast && ceil_div(N, 64) > 65535) return DAD_ERR_SHAPE;  // grid.y limit of the guarded kernel
+    if (const dad_status ready = device_ready(); ready != DAD_OK) return ready;
+    if (fast) {
         switch (act) {
             case DAD_ACT_RELU: return launch_backprop_fast<DAD_ACT_RELU>(D_next, W_next, Z, D_out, N, h, h_next, s);
             case DAD_ACT_TANH: return launch_backprop_fast<DAD_ACT_TANH>(D_next, W_next, Z, D_out, N, h, h_next, s);
@@ -349,7 +355,6 @@ extern "C" dad_status dad_backprop_delta(const void* D_next, const void* W_next,
             default: return launch_backprop_fast<DAD_ACT_IDENTITY>(D_next, W_next, Z, D_out, N, h, h_next, s);
         }
     }
-    if (ceil_div(N, 64) > 65535) return DAD_ERR_SHAPE;  // grid.y limit of the guarded kernel
     dim3 grid((unsigned)ceil_div(h, 64), (unsigned)ceil_div(N, 64));
     ProfScope prof(KID_BACKPROP, s);
     if (dt == DAD_BF16)

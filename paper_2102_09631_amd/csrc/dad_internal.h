@@ -69,6 +69,24 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
         if (hipGetLastError() != hipSuccess) return DAD_ERR_HIP; \
     } while (0)
 
+// Raises a kernel's dynamic-LDS limit (needed above 64 KiB) on the current device.
+template <typename Kern>
+inline hipError_t set_max_lds(Kern k, int bytes) {
+    if (bytes <= 64 * 1024) return hipSuccess;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+// Per-device set-up of each translation unit's kernels; called once per device by the entry points
+// (api.hip: device_ready) or by dad_init.
+dad_status thin_prepare_device();
+dad_status rebuild_prepare_device();
+dad_status gram_prepare_device();
+dad_status backprop_prepare_device();
+
+// Makes the current device ready for launches (kernel attributes set); cheap after the first call
+// on a device.
+dad_status device_ready();
+
 // ---------------------------------------------------------------- optional per-kernel timing
 
 enum KernelId {

@@ -686,18 +686,6 @@ static dad_status ns_steps(const GramPlan& p, char* ws, int64_t N, int r, int n_
     double* piv = reinterpret_cast<double*>(ws + p.off_hdr + 128);  // smallest and largest pivot of the last factor
     const dim3 grid((unsigned)p.rows16), block(256);
     const size_t lds = sizeof(NsShared<NA>);
-    static bool attr_set = false;  // more than 64 KB of LDS has to be asked for once per kernel
-    if (!attr_set) {
-        DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_ns_step<NA, NS_CV>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_ns_step<NA, NS_EZ>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_ns_step<NA, NS_REFINE>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_ns_step<NA, NS_APPLY>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        attr_set = true;
-    }
     int cur = 0;  // rinv[cur] holds the factor of the latest Gram matrix
     for (int it = 0; it < n_iter; ++it) {
         {
@@ -773,6 +761,21 @@ static dad_status run_gram(const GramPlan& p, const T* A, const T* D, int64_t N,
     return DAD_OK;
 }
 
+template <int NA>
+static dad_status ns_prepare() {
+    const int lds = (int)sizeof(NsShared<NA>);
+    DAD_HIP_TRY(set_max_lds((k_ns_step<NA, NS_CV>), lds));
+    DAD_HIP_TRY(set_max_lds((k_ns_step<NA, NS_EZ>), lds));
+    DAD_HIP_TRY(set_max_lds((k_ns_step<NA, NS_REFINE>), lds));
+    DAD_HIP_TRY(set_max_lds((k_ns_step<NA, NS_APPLY>), lds));
+    return DAD_OK;
+}
+
+dad_status gram_prepare_device() {
+    const dad_status rc = ns_prepare<2>();
+    return rc != DAD_OK ? rc : ns_prepare<4>();
+}
+
 }  // namespace dad
 
 using namespace dad;
@@ -780,7 +783,7 @@ using namespace dad;
 static bool gram_shape_ok(int64_t N, int64_t h_in, int64_t h_out, int r) {
     if (N < 1 || N > DAD_GRAM_MAX_ROWS || h_in < 1 || h_out < 1 || r < 1 || r > DAD_MAX_RANK) return false;
     if (r > N || r > h_in || r > h_out) return false;
-    return h_in <= ((int64_t)1 << 24) && h_out <= ((int64_t)1 << 24);
+    return h_in <= DAD_MAX_WIDTH && h_out <= DAD_MAX_WIDTH;
 }
 
 extern "C" size_t dad_compress_gram_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt) {
@@ -798,6 +801,7 @@ extern "C" dad_status dad_compress_rank_gram(const void* A, const void* D, int64
         return DAD_ERR_ALIGN;
     const GramPlan p = plan_gram(N, h_in, h_out, r);
     if (ws_bytes < p.total) return DAD_ERR_WORKSPACE;
+    if (const dad_status ready = device_ready(); ready != DAD_OK) return ready;
     hipStream_t s = (hipStream_t)stream;
     char* ws = static_cast<char*>(workspace);
     if (dt == DAD_F32)

@@ -1,6 +1,7 @@
 // Optional per-kernel timing: when enabled, every kernel launch of the library is bracketed by a
 // pair of HIP events on the launch stream; dad_profile_get sums the elapsed times per kernel.
 // Disabled (the default) it costs one branch per launch.
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -20,7 +21,7 @@ struct Pending {
 };
 
 static std::mutex g_mu;
-static bool g_on = false;
+static std::atomic<bool> g_on{false};  // read on every launch without the mutex
 static std::vector<Pending> g_pending;
 static std::vector<hipEvent_t> g_free;
 static double g_ms[KID_COUNT];
@@ -38,7 +39,7 @@ static hipEvent_t get_event() {
 }
 
 ProfScope::ProfScope(int id, hipStream_t s) : id_(id), s_(s), a_(nullptr) {
-    if (!g_on) return;
+    if (!g_on.load(std::memory_order_relaxed)) return;
     std::lock_guard<std::mutex> lk(g_mu);
     hipEvent_t a = get_event();
     if (a && hipEventRecord(a, s) == hipSuccess) a_ = a;
@@ -74,7 +75,7 @@ extern "C" {
 dad_status dad_profile_enable(int on) {
     std::lock_guard<std::mutex> lk(g_mu);
     dad_status rc = drain();
-    g_on = on != 0;
+    g_on.store(on != 0, std::memory_order_relaxed);
     return rc;
 }
 

@@ -373,12 +373,6 @@ template <int T, int WM, int WN>
 static dad_status launch_rebuild_dma(const void* L, const void* R, float* dst, int64_t K, int64_t h_in, int64_t h_out,
                                      SplitPlan sp, hipStream_t s) {
     const int lds = rb::DMA_STAGES * 2 * rb::BK * T * 2;
-    static bool attr_set = false;
-    if (!attr_set) {
-        DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_rebuild_bf16_dma<T, WM, WN>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-        attr_set = true;
-    }
     const int tm = (int)(h_in / T), tn = (int)(h_out / T);
     const int total = tm * tn * sp.splits;
     ProfScope prof(KID_REBUILD_BF16_DMA, s);
@@ -397,13 +391,7 @@ dad_status fast_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, i
                          : launch_rebuild_dma<256, 2, 4>(L, R, dst, K, h_in, h_out, sp, s);
         if (rc != DAD_OK) return rc;
     } else {  // ragged K: register-staged kernel, 256-tiles (the plan never picks 128-tiles here)
-        static bool attr_set = false;
         const int lds = rb::NSTAGE * rb::STAGEB;
-        if (!attr_set) {
-            DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_rebuild_bf16),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-            attr_set = true;
-        }
         const int tm = (int)(h_in / rb::TILE), tn = (int)(h_out / rb::TILE);
         const int total = tm * tn * sp.splits;
         ProfScope prof(KID_REBUILD_BF16, s);
@@ -412,6 +400,13 @@ dad_status fast_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, i
         DAD_LAUNCH_CHECK();
     }
     if (sp.splits > 1) return reduce_slabs(partials, G, h_in * h_out, sp.splits, s);
+    return DAD_OK;
+}
+
+dad_status rebuild_prepare_device() {
+    DAD_HIP_TRY(set_max_lds((k_rebuild_bf16_dma<256, 2, 4>), rb::DMA_STAGES * 2 * rb::BK * 256 * 2));
+    DAD_HIP_TRY(set_max_lds((k_rebuild_bf16_dma<128, 2, 2>), rb::DMA_STAGES * 2 * rb::BK * 128 * 2));
+    DAD_HIP_TRY(set_max_lds(k_rebuild_bf16, rb::NSTAGE * rb::STAGEB));
     return DAD_OK;
 }
 

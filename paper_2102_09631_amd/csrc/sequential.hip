@@ -129,7 +129,7 @@ using namespace dad;
 static bool seq_shape_ok(int64_t N, int64_t h_in, int64_t h_out, int r) {
     if (N < 1 || h_in < 1 || h_out < 1 || r < 1 || r > DAD_MAX_RANK) return false;
     if (r > N || r > h_in || r > h_out) return false;
-    return N <= ((int64_t)1 << 40) && h_in <= ((int64_t)1 << 24) && h_out <= ((int64_t)1 << 24);
+    return N <= DAD_MAX_ROWS && h_in <= DAD_MAX_WIDTH && h_out <= DAD_MAX_WIDTH;
 }
 
 extern "C" size_t dad_compress_sequential_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, dad_dtype dt) {
@@ -148,6 +148,7 @@ extern "C" dad_status dad_compress_rank_sequential(const void* A, const void* D,
         return DAD_ERR_ALIGN;
     const SeqPlan p = plan_sequential(N, h_in, h_out, dt);
     if (ws_bytes < p.total) return DAD_ERR_WORKSPACE;
+    if (const dad_status ready = device_ready(); ready != DAD_OK) return ready;
 
     hipStream_t s = (hipStream_t)stream;
     char* ws = static_cast<char*>(workspace);

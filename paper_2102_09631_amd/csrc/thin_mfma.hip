@@ -620,13 +620,6 @@ SplitPlan thin_tn_split(int64_t N, int64_t h, int r) {
     return sp;
 }
 
-template <typename Kern>
-static dad_status set_lds(Kern k, int bytes) {
-    if (bytes > 64 * 1024)
-        DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
-    return DAD_OK;
-}
-
 dad_status fast_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int64_t h, int r, int* zero_hdr,
                         int planes, hipStream_t s) {
     dim3 grid((unsigned)ceil_div(N, nn::RT));
@@ -660,16 +653,13 @@ dad_status launch_panel_init(const float* G0, void* Gb, void* Ub, int64_t h_in, 
     return DAD_OK;
 }
 
+constexpr int nn_dma_lds(int rp, int w, int ns) { return ns * (32 * w * 128 + rp * 128); }
+constexpr int tn_dma_lds(int r, int pw, int bk, int nv) { return 3 * (bk * pw * 2 + nv * bk * r * 2 + 256); }
+
 template <int RP, int W, int NS>
 static dad_status dma_thin_nn_cfg(const void* X, const void* Pb, void* out, int64_t N, int64_t h, int r, int planes,
                                   hipStream_t s) {
-    const int lds = NS * (32 * W * 128 + RP * 128);
-    static bool attr_set = false;
-    if (!attr_set) {
-        DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_thin_nn_bf16_dma<RP, W, NS>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-        attr_set = true;
-    }
+    const int lds = nn_dma_lds(RP, W, NS);
     hipLaunchKernelGGL((k_thin_nn_bf16_dma<RP, W, NS>), dim3((unsigned)(N / (32 * W))), dim3(64 * W), lds, s,
                        (const bf16_t*)X, (const bf16_t*)Pb, (bf16_t*)out, N, (int)h, r, stream_once(N, h) ? 1 : 0, planes);
     DAD_LAUNCH_CHECK();
@@ -698,16 +688,10 @@ dad_status fast_thin_tn(const void* X, const void* V, float* out_t, float* parti
         ProfScope prof(KID_THIN_TN_BF16, s);
         const int pw = thin_tn_pw(h);
         const int bk = pw == 128 ? 64 : 32;
-        const int lds = 3 * (bk * pw * 2 + planes * bk * r * 2 + 256);
+        const int lds = tn_dma_lds(r, pw, bk, planes);
         const int strips = (int)(h / pw);
 #define DAD_TN_LAUNCH_NV(RR, PP, BB, NV)                                                                              \
     do {                                                                                                              \
-        static bool attr_set = false;                                                                                 \
-        if (!attr_set) {                                                                                              \
-            DAD_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(k_thin_tn_bf16_dma<RR, PP, BB, NV>),       \
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds));                        \
-            attr_set = true;                                                                                          \
-        }                                                                                                             \
         hipLaunchKernelGGL((k_thin_tn_bf16_dma<RR, PP, BB, NV>), dim3((unsigned)(strips * sp.splits)), dim3(256), lds, s, \
                            (const bf16_t*)X, (const bf16_t*)V, dst, N, (int)h, sp.chunk, strips, sp.splits,           \
                            stream_once(N, h) ? 1 : 0);                                                                \
@@ -750,6 +734,22 @@ dad_status fast_thin_tn(const void* X, const void* V, float* out_t, float* parti
     DAD_LAUNCH_CHECK();
     if (sp.splits > 1) return reduce_slabs(partials, out_t, (int64_t)r * h, sp.splits, s, out_bf16);
     if (out_bf16) return reduce_slabs(out_t, out_t, (int64_t)r * h, 1, s, out_bf16);  // copy only
+    return DAD_OK;
+}
+
+// Once per device: the direct-to-LDS kernels use more than the 64 KiB of dynamic LDS a kernel gets
+// without asking.
+dad_status thin_prepare_device() {
+#define DAD_NN_ATTR(RP, W) DAD_HIP_TRY(set_max_lds((k_thin_nn_bf16_dma<RP, W, 3>), nn_dma_lds(RP, W, 3)))
+    DAD_NN_ATTR(32, 1); DAD_NN_ATTR(32, 2); DAD_NN_ATTR(32, 4); DAD_NN_ATTR(32, 8);
+    DAD_NN_ATTR(64, 1); DAD_NN_ATTR(64, 2); DAD_NN_ATTR(64, 4); DAD_NN_ATTR(64, 8);
+#undef DAD_NN_ATTR
+#define DAD_TN_ATTR(R, PW, BK)                                                                   \
+    DAD_HIP_TRY(set_max_lds((k_thin_tn_bf16_dma<R, PW, BK, 1>), tn_dma_lds(R, PW, BK, 1))); \
+    DAD_HIP_TRY(set_max_lds((k_thin_tn_bf16_dma<R, PW, BK, 2>), tn_dma_lds(R, PW, BK, 2)))
+    DAD_TN_ATTR(16, 128, 64); DAD_TN_ATTR(32, 128, 64); DAD_TN_ATTR(64, 128, 64);
+    DAD_TN_ATTR(16, 256, 32); DAD_TN_ATTR(32, 256, 32); DAD_TN_ATTR(64, 256, 32);
+#undef DAD_TN_ATTR
     return DAD_OK;
 }
 

@@ -67,6 +67,9 @@ def test_compress_rejects_bad_arguments_on_host(lib):
     assert call(ho=2) == dad.DAD_ERR_SHAPE         # r > h_out
     assert call(n=0) == dad.DAD_ERR_SHAPE
     assert call(N=0) == dad.DAD_ERR_SHAPE
+    assert call(N=(1 << 36) + 1) == dad.DAD_ERR_SHAPE      # beyond what the launch grids hold
+    assert call(hi=(1 << 21) + 1) == dad.DAD_ERR_SHAPE
+    assert call(ho=(1 << 21) + 1) == dad.DAD_ERR_SHAPE
     assert call(D=p + 4) == dad.DAD_ERR_ALIGN
     assert call(wb=128) == dad.DAD_ERR_WORKSPACE
 
@@ -75,6 +78,7 @@ def test_reconstruct_and_stack_reject_bad_arguments_on_host(lib):
     p = 0x1000
     assert lib.dad_reconstruct_grad(None, p, 4, 8, 8, 0, p, None, 0, None) == dad.DAD_ERR_NULL
     assert lib.dad_reconstruct_grad(p, p, 0, 8, 8, 0, p, None, 0, None) == dad.DAD_ERR_SHAPE
+    assert lib.dad_reconstruct_grad(p, p, 4, (1 << 21) + 1, 8, 0, p, None, 0, None) == dad.DAD_ERR_SHAPE
     assert lib.dad_reconstruct_grad(p, p, 4, 8, 8, 9, p, None, 0, None) == dad.DAD_ERR_DTYPE
     assert lib.dad_reconstruct_grad(p, p + 2, 4, 8, 8, 0, p, None, 0, None) == dad.DAD_ERR_ALIGN
     need = lib.dad_reconstruct_workspace_bytes(65536, 1024, 1024, dad.DAD_BF16)
