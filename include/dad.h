@@ -78,7 +78,7 @@ typedef enum {
 const char* dad_status_string(dad_status s);
 
 /*
- * One-time set-up of the current device (kernel attributes).  Optional: every entry point does the
+ * One-time set-up of the current device (kernel attributes, address of the static scratch).  Optional: every entry point does the
  * same on its first call on a device, guarded by a mutex, and after that only reads a flag.  Call
  * it explicitly, once per device with that device current, when the first real call would fall
  * inside a HIP graph capture.  Returns DAD_OK or DAD_ERR_HIP.
@@ -137,6 +137,28 @@ size_t dad_compress_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, int 
 dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_in, int64_t h_out,
                              dad_dtype dt, int r, int n_iter, const float* G0, float* Pt, float* Gt,
                              void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * dad_compress_rank_noalloc - dad_compress_rank for callers that cannot allocate device memory or
+ * carry a workspace: code recorded into a HIP graph whose owner has no buffer to hand over, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results (bit for bit)
+ * as dad_compress_rank, but the scratch space is a static array of DAD_STATIC_SCRATCH_BYTES that the
+ * library's code object holds on every device it is loaded on until the process ends; the call
+ * allocates and frees nothing.
+ *   numeric_flag  device out, one int (4-byte aligned), or NULL: receives 0, or 1 when the
+ *                 orthonormalisation broke down (what dad_poll_numeric_status reports for the
+ *                 workspace variant); the pointer may also be handed to dad_poll_numeric_status
+ * Sizes whose dad_compress_workspace_bytes exceeds DAD_STATIC_SCRATCH_BYTES are rejected with
+ * DAD_ERR_WORKSPACE before anything is enqueued (every benchmark shape up to N = 65536 rows at
+ * r = 32 and every per-site reduction fits; N = 262144 at r = 64 does not).  All calls on one
+ * device share that device's array: calls that overlap in time on one device (two streams, two
+ * threads) race; calls on one stream, or ordered by events, do not.  The first call on a device
+ * resolves the array's address (see dad_init for calls under capture).
+ */
+#define DAD_STATIC_SCRATCH_BYTES (32u << 20)
+dad_status dad_compress_rank_noalloc(const void* A, const void* D, int64_t N, int64_t h_in, int64_t h_out,
+                                     dad_dtype dt, int r, int n_iter, const float* G0, float* Pt, float* Gt,
+                                     int* numeric_flag, void* stream);
 
 /* Bytes of device workspace dad_compress_rank_gram needs (0 on invalid sizes, N > DAD_GRAM_MAX_ROWS included). */
 size_t dad_compress_gram_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);

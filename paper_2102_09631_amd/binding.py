@@ -51,6 +51,8 @@ def lib() -> C.CDLL:
     L.dad_compress_workspace_bytes.argtypes = [i64, i64, i64, C.c_int, C.c_int]
     L.dad_compress_rank.restype = C.c_int
     L.dad_compress_rank.argtypes = [vp, vp, i64, i64, i64, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, sz, vp]
+    L.dad_compress_rank_noalloc.restype = C.c_int
+    L.dad_compress_rank_noalloc.argtypes = [vp, vp, i64, i64, i64, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp]
     L.dad_reconstruct_workspace_bytes.restype = sz
     L.dad_reconstruct_workspace_bytes.argtypes = [i64, i64, i64, C.c_int]
     L.dad_reconstruct_grad.restype = C.c_int
@@ -169,6 +171,34 @@ def compress_rank(A, D, r, n_iter, G0, Pt=None, Gt=None, workspace=None, check=F
            "dad_compress_rank")
     if check:
         _check(lib().dad_poll_numeric_status(workspace.data_ptr(), _stream()), "dad_poll_numeric_status")
+    return Pt, Gt
+
+
+DAD_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def compress_rank_noalloc(A, D, r, n_iter, G0, Pt, Gt, numeric_flag=None):
+    """dad_compress_rank_noalloc: compress_rank on the library's static scratch.  Every buffer is the
+    caller's (Pt r x h_in, Gt r x h_out fp32; numeric_flag an int32 tensor of one element or None);
+    nothing is allocated here or in the library."""
+    _dense2d(A, "A")
+    _dense2d(D, "Delta")
+    _dense2d(G0, "G0")
+    N, h_in = A.shape
+    h_out = D.shape[1]
+    if D.shape[0] != N or D.dtype != A.dtype:
+        raise ValueError("A and Delta disagree in rows or dtype")
+    if G0.dtype != torch.float32 or tuple(G0.shape) != (r, h_out):
+        raise ValueError("G0 must be float32 of shape (r, h_out)")
+    if tuple(Pt.shape) != (r, h_in) or tuple(Gt.shape) != (r, h_out) or Pt.dtype != torch.float32 \
+            or Gt.dtype != torch.float32:
+        raise ValueError("Pt, Gt must be float32 of shape (r, h_in), (r, h_out)")
+    if numeric_flag is not None and (numeric_flag.dtype != torch.int32 or numeric_flag.numel() != 1):
+        raise ValueError("numeric_flag must be one int32")
+    _check(lib().dad_compress_rank_noalloc(A.data_ptr(), D.data_ptr(), N, h_in, h_out, _dt(A), r, n_iter, G0.data_ptr(),
+                                           Pt.data_ptr(), Gt.data_ptr(),
+                                           numeric_flag.data_ptr() if numeric_flag is not None else None, _stream()),
+           "dad_compress_rank_noalloc")
     return Pt, Gt
 
 

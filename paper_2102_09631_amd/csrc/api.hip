@@ -4,6 +4,12 @@
 
 #include "dad_internal.h"
 
+// Scratch of dad_compress_rank_noalloc: one copy per device, held from the load of the library's
+// code object until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; device_ready() resolves each device's address once and every launch and
+// kernel argument uses that pointer.
+static __device__ __align__(256) unsigned char scratch[DAD_STATIC_SCRATCH_BYTES];
+
 namespace dad {
 
 // implemented in the kernel translation units
@@ -98,11 +104,12 @@ static bool dtype_ok(dad_dtype dt) { return dt == DAD_F32 || dt == DAD_BF16; }
 constexpr int MAX_DEVICES = 64;
 struct DeviceState {
     std::atomic<int> ready{0};
+    void* scratch = nullptr;  // this device's copy of the static scratch array
 };
 static DeviceState g_dev[MAX_DEVICES];
 static std::mutex g_dev_mu;
 
-dad_status device_ready() {
+dad_status device_ready(void** scratch_out) {
     int dev = -1;
     DAD_HIP_TRY(hipGetDevice(&dev));
     if (dev < 0 || dev >= MAX_DEVICES) return DAD_ERR_HIP;
@@ -115,11 +122,19 @@ dad_status device_ready() {
             if ((rc = rebuild_prepare_device()) != DAD_OK) return rc;
             if ((rc = gram_prepare_device()) != DAD_OK) return rc;
             if ((rc = backprop_prepare_device()) != DAD_OK) return rc;
+            void* ptr = nullptr;
+            DAD_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+            if (!ptr) return DAD_ERR_HIP;
+            st.scratch = ptr;
             st.ready.store(1, std::memory_order_release);
         }
     }
+    if (scratch_out) *scratch_out = st.scratch;
     return DAD_OK;
 }
+
+// Copies the flag word of a workspace header to a caller-owned word.
+__global__ void k_copy_flag(const int* __restrict__ hdr, int* __restrict__ out) { *out = *hdr; }
 
 }  // namespace dad
 
@@ -133,7 +148,7 @@ const char* dad_status_string(dad_status s) {
         case DAD_ERR_NULL: return "DAD_ERR_NULL: required pointer is NULL";
         case DAD_ERR_SHAPE: return "DAD_ERR_SHAPE: size out of range";
         case DAD_ERR_ALIGN: return "DAD_ERR_ALIGN: device pointer not 16-byte aligned";
-        case DAD_ERR_WORKSPACE: return "DAD_ERR_WORKSPACE: workspace too small";
+        case DAD_ERR_WORKSPACE: return "DAD_ERR_WORKSPACE: workspace too small (or sizes beyond the static scratch)";
         case DAD_ERR_DTYPE: return "DAD_ERR_DTYPE: unknown element type";
         case DAD_ERR_NUMERIC: return "DAD_ERR_NUMERIC: orthonormalisation broke down (iterate lost rank)";
         case DAD_ERR_HIP: return "DAD_ERR_HIP: HIP runtime call failed";
@@ -170,7 +185,7 @@ size_t dad_compress_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, int 
     return plan_compress(N, h_in, h_out, r, dt).total;
 }
 
-// Host-side argument checks of dad_compress_rank.
+// Host-side argument checks shared by dad_compress_rank and dad_compress_rank_noalloc.
 static dad_status compress_args_ok(const void* A, const void* D, int64_t N, int64_t h_in, int64_t h_out, dad_dtype dt,
                                    int r, int n_iter, const float* G0, const float* Pt, const float* Gt) {
     if (!A || !D || !G0 || !Pt || !Gt) return DAD_ERR_NULL;
@@ -247,6 +262,24 @@ dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_
     if (ws_bytes < p.total) return DAD_ERR_WORKSPACE;
     if ((rc = device_ready()) != DAD_OK) return rc;
     return compress_launch(p, A, D, N, h_in, h_out, dt, r, n_iter, G0, Pt, Gt, workspace, (hipStream_t)stream);
+}
+
+dad_status dad_compress_rank_noalloc(const void* A, const void* D, int64_t N, int64_t h_in, int64_t h_out,
+                                     dad_dtype dt, int r, int n_iter, const float* G0, float* Pt, float* Gt,
+                                     int* numeric_flag, void* stream) {
+    dad_status rc = compress_args_ok(A, D, N, h_in, h_out, dt, r, n_iter, G0, Pt, Gt);
+    if (rc != DAD_OK) return rc;
+    if (numeric_flag && (reinterpret_cast<uintptr_t>(numeric_flag) & 3u)) return DAD_ERR_ALIGN;
+    const CompressPlan p = plan_compress(N, h_in, h_out, r, dt);
+    if (p.total > (size_t)DAD_STATIC_SCRATCH_BYTES) return DAD_ERR_WORKSPACE;
+    void* ws = nullptr;  // the current device's copy of `scratch`
+    if ((rc = device_ready(&ws)) != DAD_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    rc = compress_launch(p, A, D, N, h_in, h_out, dt, r, n_iter, G0, Pt, Gt, ws, s);
+    if (rc != DAD_OK || !numeric_flag) return rc;
+    hipLaunchKernelGGL(k_copy_flag, dim3(1), dim3(1), 0, s, (const int*)ws, numeric_flag);
+    DAD_LAUNCH_CHECK();
+    return DAD_OK;
 }
 
 dad_status dad_init(void) { return device_ready(); }

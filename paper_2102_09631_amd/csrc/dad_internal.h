@@ -83,9 +83,10 @@ dad_status rebuild_prepare_device();
 dad_status gram_prepare_device();
 dad_status backprop_prepare_device();
 
-// Makes the current device ready for launches (kernel attributes set); cheap after the first call
-// on a device.
-dad_status device_ready();
+// Makes the current device ready for launches (kernel attributes set, the address of this device's
+// copy of the static scratch array resolved); cheap after the first call on a device.
+// scratch_out, when not null, receives that address.
+dad_status device_ready(void** scratch_out = nullptr);
 
 // ---------------------------------------------------------------- optional per-kernel timing
 

@@ -74,6 +74,24 @@ def test_compress_rejects_bad_arguments_on_host(lib):
     assert call(wb=128) == dad.DAD_ERR_WORKSPACE
 
 
+def test_noalloc_rejects_bad_arguments_and_oversize_on_host(lib):
+    p = 0x1000  # never dereferenced: every call below must fail before a launch
+
+    def call(A=p, D=p, N=64, hi=784, ho=128, dt=dad.DAD_F32, r=4, n=2, G0=p, Pt=p, Gt=p, flag=None):
+        return lib.dad_compress_rank_noalloc(A, D, N, hi, ho, dt, r, n, G0, Pt, Gt, flag, None)
+
+    assert call(D=None) == dad.DAD_ERR_NULL
+    assert call(dt=3) == dad.DAD_ERR_DTYPE
+    assert call(r=65) == dad.DAD_ERR_SHAPE
+    assert call(Gt=p + 4) == dad.DAD_ERR_ALIGN
+    assert call(flag=p + 2) == dad.DAD_ERR_ALIGN
+    # the static scratch holds DAD_STATIC_SCRATCH_BYTES: the largest benchmark shape does not fit
+    big = dict(N=262144, hi=1280, ho=5120, dt=dad.DAD_BF16, r=64)
+    assert lib.dad_compress_workspace_bytes(262144, 1280, 5120, 64, dad.DAD_BF16) > dad.DAD_STATIC_SCRATCH_BYTES
+    assert call(**big) == dad.DAD_ERR_WORKSPACE
+    assert lib.dad_compress_workspace_bytes(65536, 1024, 4096, 32, dad.DAD_BF16) <= dad.DAD_STATIC_SCRATCH_BYTES
+
+
 def test_reconstruct_and_stack_reject_bad_arguments_on_host(lib):
     p = 0x1000
     assert lib.dad_reconstruct_grad(None, p, 4, 8, 8, 0, p, None, 0, None) == dad.DAD_ERR_NULL
