@@ -120,7 +120,12 @@ __global__ __launch_bounds__(bp::THREADS) void k_backprop_bf16(const bf16_t* __r
     // Each stage is four MFMA K-steps; fragment sets 0 and 1 alternate.  The last step of a stage is
     // multiplied after the next stage's barrier, so the matrix cores have independent MFMAs to chew on
     // while the first fragments of the new stage travel from LDS.
+    // Within a step the six fragment reads are spread between the eight MFMAs of the other set.
     bf16x8 fa0[4], fb0[2], fa1[4], fb1[2];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) fa1[a] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};  // the first stage multiplies zeros
+#pragma unroll
+    for (int b = 0; b < 2; ++b) fb1[b] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
     auto read_frags = [&](bf16x8 (&fa)[4], bf16x8 (&fb)[2], const char* ta, int ks) {
         const char* tb = ta + bp::TILEB;
 #pragma unroll
@@ -141,21 +146,22 @@ __global__ __launch_bounds__(bp::THREADS) void k_backprop_bf16(const bf16_t* __r
         __syncthreads();  // tile kt is complete in LDS, and every wave has its fragments of tile kt-1
         if (kt + 1 < nk) issue((kt + 1) & 1);
         const char* ta = smem + (kt & 1) * bp::STAGEB;
-        read_frags(fa0, fb0, ta, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if (kt > 0) mma(fa1, fb1);
+        read_frags(fa0, fb0, ta, 0);
+        mma(fa1, fb1);
+        interleave_reads_mfma<6, 8, true>();
         __builtin_amdgcn_sched_barrier(0);
         read_frags(fa1, fb1, ta, 1);
-        __builtin_amdgcn_sched_barrier(0);
         mma(fa0, fb0);
+        interleave_reads_mfma<6, 8, false>();
         __builtin_amdgcn_sched_barrier(0);
         read_frags(fa0, fb0, ta, 2);
-        __builtin_amdgcn_sched_barrier(0);
         mma(fa1, fb1);
+        interleave_reads_mfma<6, 8, false>();
         __builtin_amdgcn_sched_barrier(0);
         read_frags(fa1, fb1, ta, 3);
-        __builtin_amdgcn_sched_barrier(0);
         mma(fa0, fb0);
+        interleave_reads_mfma<6, 8, false>();
         __builtin_amdgcn_sched_barrier(0);
     }
     // this wave's 16 pieces of Z (eight lanes per row, 16 bytes each) are requested now, so that

@@ -54,6 +54,26 @@ __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
+// Places NR LDS reads and NM matrix instructions of one scheduling region alternately in the
+// instruction stream (reads first or matrix instructions first), so that a wave's fragment reads are
+// issued in the shadow of its own MFMAs instead of in a block before them.
+template <int NR, int NM, bool READ_FIRST, int I = 0>
+__device__ __forceinline__ void interleave_reads_mfma() {
+    constexpr int N = NR >= NM ? NM : NR;
+    if constexpr (I < N) {
+        constexpr int nr = NR >= NM ? (NR + NM - 1 - I) / NM : 1;
+        constexpr int nm = NR >= NM ? 1 : (NM + NR - 1 - I) / NR;
+        if (READ_FIRST) {
+            __builtin_amdgcn_sched_group_barrier(0x100, nr, 0);  // DS read
+            __builtin_amdgcn_sched_group_barrier(0x008, nm, 0);  // MFMA
+        } else {
+            __builtin_amdgcn_sched_group_barrier(0x008, nm, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, nr, 0);
+        }
+        interleave_reads_mfma<NR, NM, READ_FIRST, I + 1>();
+    }
+}
+
 inline size_t elem_size(dad_dtype dt) { return dt == DAD_BF16 ? 2 : 4; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

@@ -264,8 +264,16 @@ __global__ __launch_bounds__(64 * WM * WN) void k_rebuild_bf16_dma(const bf16_t*
     // Each K tile is two MFMA K-steps (ks = 0, 1) with fragment sets 0 and 1.  The second step of a
     // tile is multiplied after the next tile's barrier, so the matrix cores have independent MFMAs to
     // chew on while the first fragments of the new tile travel from LDS:
-    //   barrier | DMA(kt+3) | read set0(kt,0) | MFMA set1(kt-1,1) | read set1(kt,1) | MFMA set0(kt,0) | ...
+    //   barrier | DMA(kt+3) | read set0(kt,0) x MFMA set1(kt-1,1) | read set1(kt,1) x MFMA set0(kt,0) | ...
+    // where "x" is an instruction-by-instruction interleave: one or two fragment reads between
+    // consecutive MFMAs (measured 6-7 % faster than reads and MFMAs in blocks: 67 % instead of 60 % of
+    // peak on all-zero operands, 49 % instead of 46 % on the benchmark's).
     bf16x8 fa0[FA], fb0[FB], fa1[FA], fb1[FB];
+    // set 1 starts as zeros, so that the first tile's "previous K-step" multiplies into zero accumulators
+#pragma unroll
+    for (int a = 0; a < FA; ++a) fa1[a] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int b = 0; b < FB; ++b) fb1[b] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
     auto read_frags = [&](bf16x8 (&fa)[FA], bf16x8 (&fb)[FB], const char* tl, int ks) {
         const char* tr = tl + TILEB;
 #pragma unroll
@@ -293,13 +301,15 @@ __global__ __launch_bounds__(64 * WM * WN) void k_rebuild_bf16_dma(const bf16_t*
         __syncthreads();  // everyone's part of tile kt is in LDS, and tile kt-1's slot is free
         if (kt + rb::DMA_STAGES - 1 < nk) issue((STAGE + rb::DMA_STAGES - 1) % rb::DMA_STAGES);
         const char* tl = smem + STAGE * STAGEB;
-        read_frags(fa0, fb0, tl, 0);
+        constexpr int NR = 2 * (FA + FB), NM = FA * FB;  // LDS reads and MFMAs per K-step
         __builtin_amdgcn_sched_barrier(0);
-        if (kt > 0) mma(fa1, fb1);
+        read_frags(fa0, fb0, tl, 0);
+        mma(fa1, fb1);
+        interleave_reads_mfma<NR, NM, true>();
         __builtin_amdgcn_sched_barrier(0);
         read_frags(fa1, fb1, tl, 1);
-        __builtin_amdgcn_sched_barrier(0);
         mma(fa0, fb0);
+        interleave_reads_mfma<NR, NM, false>();
         __builtin_amdgcn_sched_barrier(0);
     };
     for (int kt = 0; kt < nk; kt += rb::DMA_STAGES) {
