@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="gpt2_medium_stack")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="default mode: skip the encoder_d768 and vit_large_stack passes that follow the headline workload")
     ap.add_argument("--mode", default="one_level", choices=["one_level", "two_level", "backprop", "sequential"],
                     help="two_level: Algorithm 1 (per-site reduction, stack of the pairs, aggregator reduction, rebuild); "
                          "backprop: the delta recursion of Eq. 3, every site writing its rows into the stacked buffer; "
@@ -527,6 +529,32 @@ def main():
         return backprop(args, w, dad, W, torch, np, dev)
     if args.mode == "sequential":
         return sequential(args, w, dad, W, torch, np, dev)
+    out = one_level(args, w, args.steps, args.warmup, dad, W, torch, np, dev,
+                    cpu_budget_s=None if args.no_cpu_baseline else 10.0, yardsticks=True)
+    # The other transformer workloads in the same process (fewer steps; one block of distinct layer
+    # shapes resident where the stack exceeds HBM), so that one run carries all three.
+    others = {}
+    if args.workload == "gpt2_medium_stack" and not args.no_other_workloads:
+        for name, steps in (("encoder_d768", max(3, args.steps)), ("vit_large_stack", 3)):
+            torch.cuda.empty_cache()
+            o = one_level(args, W.by_name(name), steps, 1, dad, W, torch, np, dev,
+                          cpu_budget_s=None if args.no_cpu_baseline else 0.0, yardsticks=False)
+            others[name] = {k: o[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "dtype", "config",
+                                              "rebuild_frac_of_mfma_peak", "compress_us_per_layer", "compress_GBps",
+                                              "compress_frac_of_hbm_peak", "stack_GBps", "rank_rebuild_us_per_layer",
+                                              "rank_rebuild_GBps", "phase_ms_per_step", "roofline", "kernels")}
+            if o["cpu_baseline"]:
+                others[name]["parity_rel_fro"] = o["cpu_baseline"]["parity_rel_fro"]
+                others[name]["oracle_sample"] = o["cpu_baseline"]["sample"]
+    out["other_workloads"] = others or None
+    print(json.dumps(out))
+
+
+def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yardsticks):
+    """stack -> compress -> full rebuild -> rank-r rebuild over every layer of `w`, timed over `steps`
+    steps after `warmup`; returns the result record.  cpu_budget_s: None = no oracle leg; otherwise
+    the oracle runs on at least one layer of each distinct shape (0.0: exactly one layer, the
+    smallest) and on further layers until that many seconds of oracle time are spent."""
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     es = 2 if w.dtype == "bf16" else 4
     N, r, n_iter, S, b = w.N, w.rank, w.n_iter, w.sites, w.rows_per_site
@@ -559,7 +587,7 @@ def main():
 
     # Timing events are created, and one pair is exercised, before the timed region: the first use of
     # a timing event costs milliseconds of one-off set-up in the runtime.
-    pool = [torch.cuda.Event(enable_timing=True) for _ in range(5 * len(layers) * args.steps)]
+    pool = [torch.cuda.Event(enable_timing=True) for _ in range(5 * len(layers) * steps)]
     pool_next = [0]
     if pool:
         pool[0].record(); pool[1].record(); torch.cuda.synchronize(); pool[0].elapsed_time(pool[1])
@@ -583,18 +611,26 @@ def main():
             if ev: ev[4].record()
             if ev: events.append(ev)
 
-    for _ in range(args.warmup):
+    # Untimed pre-pass: every layer's compress once, with the numeric status polled per layer (the
+    # flag lives in the shared workspace and is cleared by the next call, so one poll after a whole
+    # step would only see the last layer's).
+    for li, hi, ho in layers:
+        s_ = (hi, ho)
+        As, Ds = factors_of(li)
+        dad.stack_factors(As, Ds, A_out=A_st[s_], D_out=D_st[s_])
+        dad.compress_rank(A_st[s_], D_st[s_], r, n_iter, G0[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_c)
+        if dad.poll_numeric_status(ws_c) != dad.DAD_OK:
+            print(f"bench.py: numerical breakdown latched on layer {li} ({hi}x{ho}) of {w.name}", file=sys.stderr)
+            sys.exit(1)
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    if dad.poll_numeric_status(ws_c) != dad.DAD_OK:
-        print("bench.py: numerical breakdown latched during warm-up", file=sys.stderr)
-        sys.exit(1)
 
     # timed region: K steps, phase boundaries marked by events on the launch stream
     events = []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step(events)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -602,18 +638,18 @@ def main():
     # launch cost about 10 us per launch, so they stay out of the region that `value` comes from)
     dad.profile_reset()
     dad.profile_enable(True)
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     dad.profile_enable(False)
     kern = dad.profile_read()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = (t1 - t0) * 1e3 / steps
 
     phase_ms = dict.fromkeys(PH, 0.0)
     for ev in events:
         for i, ph in enumerate(PH):
             phase_ms[ph] += ev[i].elapsed_time(ev[i + 1])
-    phase_ms = {k: v / args.steps for k, v in phase_ms.items()}
+    phase_ms = {k: v / steps for k, v in phase_ms.items()}
     nl = len(layers)
     flops_full = sum(2.0 * N * hi * ho for _, hi, ho in layers)
     bytes_stack = sum(2.0 * N * (hi + ho) * es for _, hi, ho in layers)
@@ -644,11 +680,11 @@ def main():
             per_step_work[name] = (bound, tot)
     roof_all = {}
     for name, (ms, launches) in kern.items():
-        entry = {"ms_per_step": ms / args.steps, "launches_per_step": launches / args.steps,
+        entry = {"ms_per_step": ms / steps, "launches_per_step": launches / steps,
                  "avg_us": ms * 1e3 / launches}
         if name in per_step_work:
             bound, work = per_step_work[name]
-            rate = work * args.steps / (ms * 1e-3)
+            rate = work * steps / (ms * 1e-3)
             if bound == "hbm":
                 entry.update(bound="hbm", achieved=rate / 1e9, peak=PEAK_HBM_GBPS, unit="GB/s",
                              frac=rate / 1e9 / PEAK_HBM_GBPS)
@@ -675,7 +711,7 @@ def main():
     # ---- CPU baseline: the fp64 oracle on the first layers of the stack, at least one of each distinct
     # shape and until about 10 s of oracle time are spent (bounded sample)
     cpu = None
-    if not args.no_cpu_baseline:
+    if cpu_budget_s is not None:
         from oracle import dad_oracle as O
         try:
             from threadpoolctl import threadpool_info
@@ -686,8 +722,12 @@ def main():
         t_full = t_spi = flops = 0.0
         e_full = e_rank = 0.0
         sampled = []
-        for li, hi, ho in layers:   # in stack order: every distinct shape comes up in the first block
-            if len(sampled) >= len(w.shapes) and t_full + t_spi >= 10.0:
+        if cpu_budget_s == 0.0:     # exactly one layer: the one with the smallest gradient
+            order = [min(layers[:len(w.shapes)], key=lambda t: t[1] * t[2])]
+        else:                       # in stack order: every distinct shape comes up in the first block
+            order = layers
+        for li, hi, ho in order:
+            if cpu_budget_s > 0.0 and len(sampled) >= len(w.shapes) and t_full + t_spi >= cpu_budget_s:
                 break
             As, Ds = factors_of(li)
             A64 = torch.cat([a.float().cpu() for a in As]).numpy().astype(np.float64)
@@ -723,11 +763,14 @@ def main():
             print(f"bench.py: parity check failed: {e_full:.3e} {e_rank:.3e}", file=sys.stderr)
             sys.exit(1)
 
-    # ---- in-run yardsticks, outside the timed region: what this box's libraries reach on the same
-    # work (torch's device copy for the stack; its matmul, hipBLASLt, for the full rebuild at the same
-    # shapes and K = N).  Context beside the published peaks, not part of the path.
+    # ---- in-run yardsticks, outside the timed region.  (a) What the chip sustains on this very data:
+    # a bare MFMA loop whose fragments come from the stacked activations (the matrix cores' clock
+    # under load follows the operands' bit toggling), the same loop on zeros, a plain read stream, and
+    # the rebuild call itself on all-zero factors of the same shapes.  (b) What the box's libraries
+    # reach on the same work: torch's device copy and torch.matmul (hipBLASLt) at the same shapes.
+    # Context beside the published peaks; nothing on the path calls any of these.
     yard = None
-    if w.dtype == "bf16":
+    if yardsticks and w.dtype == "bf16":
         def timed(fn, reps):
             fn()
             torch.cuda.synchronize()
@@ -746,7 +789,25 @@ def main():
         for sh in w.shapes:
             t_mm += timed(lambda: torch.matmul(A_st[sh].t(), D_st[sh]), 3)
             fl_mm += 2.0 * N * sh[0] * sh[1]
-        yard = {"torch_copy_GBps": 2.0 * src.numel() * es / t_copy / 1e9,
+        mfma_data = dad.probe_mfma_loop(A_st[s0])
+        zeros = torch.zeros(1 << 22, dtype=tdt, device=dev)
+        mfma_zero = dad.probe_mfma_loop(zeros)
+        read_gbps = dad.probe_read_stream(D_st[s0])
+        # the rebuild call on zero factors: same launches and clocks per stage, no operand toggling
+        t_z = fl_z = 0.0
+        for sh in w.shapes:
+            Az, Dz = torch.zeros_like(A_st[sh]), torch.zeros_like(D_st[sh])
+            t_z += timed(lambda: dad.reconstruct_grad(Az, Dz, G=G_full[sh], workspace=ws_r), 5)
+            fl_z += 2.0 * N * sh[0] * sh[1]
+            del Az, Dz
+        k_reb = roof_all.get("k_rebuild_bf16_dma", {}).get("achieved")
+        yard = {"mfma_loop_TFLOPs_on_stacked_activations": mfma_data,
+                "mfma_loop_TFLOPs_on_zeros": mfma_zero,
+                "read_stream_GBps": read_gbps,
+                "rebuild_call_TFLOPs_on_zero_factors": fl_z / t_z / 1e12,
+                "rebuild_kernel_vs_mfma_loop_same_data": (k_reb / mfma_data) if k_reb else None,
+                "rebuild_phase_vs_mfma_loop_same_data": rebuild_tflops / mfma_data,
+                "torch_copy_GBps": 2.0 * src.numel() * es / t_copy / 1e9,
                 "torch_matmul_same_shapes_TFLOPs": fl_mm / t_mm / 1e12,
                 "stack_vs_torch_copy": (bytes_stack / (phase_ms["stack"] * 1e-3) / 1e9) / (2.0 * src.numel() * es / t_copy / 1e9),
                 "rebuild_vs_torch_matmul": rebuild_tflops / (fl_mm / t_mm / 1e12)}
@@ -756,8 +817,8 @@ def main():
         "value": rebuild_tflops,
         "unit": "TFLOP/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
@@ -780,7 +841,7 @@ def main():
         "in_run_yardsticks": yard,
         "cpu_baseline": cpu,
     }
-    print(json.dumps(out))
+    return out
 
 
 if __name__ == "__main__":

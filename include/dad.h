@@ -274,6 +274,25 @@ int dad_profile_kernel_count(void);
 const char* dad_profile_kernel_name(int id);
 dad_status dad_profile_get(int id, double* total_ms, int64_t* launches);
 
+/*
+ * In-process ceilings (instrumentation, not part of the method; bench.py reports them beside the
+ * published peaks).  Both calls time their own launches with events, synchronise `stream` and
+ * cannot be recorded into a graph.  `sink` is one caller-owned device word (4-byte aligned) that the
+ * kernels may write.
+ *
+ * dad_probe_mfma_loop: one workgroup of eight waves per compute unit; every wave loads 4 + 2 operand
+ * fragments once from `operands` (device, >= 48 KiB of bf16 values, 16-byte aligned; workgroup b
+ * takes the b-th 48 KiB piece, modulo the pieces available) and issues iters * 8 independent
+ * v_mfma_f32_32x32x16_bf16 with no memory access inside the loop.  *tflops = sustained rate.  The
+ * matrix cores' clock under load depends on the operand values, hence real data as input.
+ *
+ * dad_probe_read_stream: one pass over `bytes` bytes of `src` with non-temporal 16-byte loads,
+ * averaged over five launches.  *gbps = bytes / time.
+ */
+dad_status dad_probe_mfma_loop(const void* operands, size_t operand_bytes, int iters, void* sink, void* stream,
+                               double* tflops);
+dad_status dad_probe_read_stream(const void* src, size_t bytes, void* sink, void* stream, double* gbps);
+
 #ifdef __cplusplus
 }
 #endif

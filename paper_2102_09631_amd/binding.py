@@ -79,6 +79,10 @@ def lib() -> C.CDLL:
     L.dad_profile_kernel_name.argtypes = [C.c_int]
     L.dad_profile_get.restype = C.c_int
     L.dad_profile_get.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    L.dad_probe_mfma_loop.restype = C.c_int
+    L.dad_probe_mfma_loop.argtypes = [vp, sz, C.c_int, vp, vp, C.POINTER(C.c_double)]
+    L.dad_probe_read_stream.restype = C.c_int
+    L.dad_probe_read_stream.argtypes = [vp, sz, vp, vp, C.POINTER(C.c_double)]
     _lib = L
     return L
 
@@ -311,6 +315,24 @@ def backprop_delta(D_next, W_next, Z, act, D_out=None):
     _check(lib().dad_backprop_delta(D_next.data_ptr(), W_next.data_ptr(), Z.data_ptr(), N, h, h_next, _dt(Z),
                                     DAD_ACT[act], D_out.data_ptr(), _stream()), "dad_backprop_delta")
     return D_out
+
+
+def probe_mfma_loop(operands: torch.Tensor, iters: int = 20000) -> float:
+    """dad_probe_mfma_loop: sustained TFLOP/s of a bare bf16 MFMA loop whose fragments come from `operands`."""
+    sink = torch.zeros(1, dtype=torch.float32, device=operands.device)
+    out = C.c_double(0.0)
+    _check(lib().dad_probe_mfma_loop(operands.data_ptr(), operands.numel() * operands.element_size(), iters,
+                                     sink.data_ptr(), _stream(), C.byref(out)), "dad_probe_mfma_loop")
+    return out.value
+
+
+def probe_read_stream(src: torch.Tensor) -> float:
+    """dad_probe_read_stream: GB/s of one non-temporal pass over `src`."""
+    sink = torch.zeros(1, dtype=torch.int32, device=src.device)
+    out = C.c_double(0.0)
+    _check(lib().dad_probe_read_stream(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(), _stream(),
+                                       C.byref(out)), "dad_probe_read_stream")
+    return out.value
 
 
 def poll_numeric_status(workspace) -> int:
