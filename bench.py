@@ -71,6 +71,10 @@ def kernel_model(name, N, h_in, h_out, r, es, which, bf16=True):
         if bf16:   # only the rank-r rebuild (K = r, fp32 pairs) runs this kernel: write bound
             return "hbm", 4.0 * h_in * h_out + 4.0 * r * (h_in + h_out)
         return "mfma", 2.0 * N * h_in * h_out + 2.0 * r * h_in * h_out   # full + rank-r launches together
+    if name == "k_rebuild_f32_mfma":
+        if bf16:   # rank-r rebuild only (K = r, fp32 pairs): write bound
+            return "hbm", 4.0 * h_in * h_out + 4.0 * r * (h_in + h_out)
+        return "mfma", 2.0 * N * h_in * h_out + 2.0 * r * h_in * h_out   # full + rank-r launches together
     if name == "k_stack":
         return "hbm", 2.0 * N * (h_in + h_out) * es
     return None, 0.0
@@ -574,7 +578,8 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
     A_st = {s: torch.empty((N, s[0]), dtype=tdt, device=dev) for s in w.shapes}
     D_st = {s: torch.empty((N, s[1]), dtype=tdt, device=dev) for s in w.shapes}
     G_full = {s: torch.empty(s, dtype=torch.float32, device=dev) for s in w.shapes}
-    G_rank = {s: torch.empty(s, dtype=torch.float32, device=dev) for s in w.shapes}
+    # the rank-r gradients of all layers are rebuilt by ONE grouped call at the end of a step
+    G_rank = {li: torch.empty((hi, ho), dtype=torch.float32, device=dev) for li, hi, ho in layers}
     Pt = {li: torch.empty((r, hi), dtype=torch.float32, device=dev) for li, hi, _ in layers}
     Gt = {li: torch.empty((r, ho), dtype=torch.float32, device=dev) for li, _, ho in layers}
     ws_c = torch.zeros(max(dad.compress_workspace_bytes(N, hi, ho, r, tdt) for _, hi, ho in layers),
@@ -583,23 +588,27 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
                        dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
 
+    rank_group = dad.RebuildGroup([(Pt[li], Gt[li]) for li, _, _ in layers], [G_rank[li] for li, _, _ in layers])
+
     PH = ("stack", "compress", "rebuild_full", "rebuild_rank")
 
     # Timing events are created, and one pair is exercised, before the timed region: the first use of
     # a timing event costs milliseconds of one-off set-up in the runtime.
-    pool = [torch.cuda.Event(enable_timing=True) for _ in range(5 * len(layers) * steps)]
+    pool = [torch.cuda.Event(enable_timing=True) for _ in range((4 * len(layers) + 2) * steps)]
     pool_next = [0]
     if pool:
         pool[0].record(); pool[1].record(); torch.cuda.synchronize(); pool[0].elapsed_time(pool[1])
+
+    def take(n):
+        ev = pool[pool_next[0]:pool_next[0] + n]
+        pool_next[0] += n
+        return ev
 
     def step(events=None):
         for li, hi, ho in layers:
             s = (hi, ho)
             As, Ds = factors_of(li)
-            ev = None
-            if events is not None:
-                ev = pool[pool_next[0]:pool_next[0] + 5]
-                pool_next[0] += 5
+            ev = take(4) if events is not None else None
             if ev: ev[0].record()
             dad.stack_factors(As, Ds, A_out=A_st[s], D_out=D_st[s])
             if ev: ev[1].record()
@@ -607,9 +616,12 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
             if ev: ev[2].record()
             dad.reconstruct_grad(A_st[s], D_st[s], G=G_full[s], workspace=ws_r)
             if ev: ev[3].record()
-            dad.reconstruct_grad(Pt[li], Gt[li], G=G_rank[s])
-            if ev: ev[4].record()
-            if ev: events.append(ev)
+            if ev: events.append(("layer", ev))
+        ev = take(2) if events is not None else None
+        if ev: ev[0].record()
+        rank_group.run()          # every layer's rank-r gradient P^T G in one grouped call
+        if ev: ev[1].record()
+        if ev: events.append(("rank", ev))
 
     # Untimed pre-pass: every layer's compress once, with the numeric status polled per layer (the
     # flag lives in the shared workspace and is cleared by the next call, so one poll after a whole
@@ -646,9 +658,12 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
     ms_per_step = (t1 - t0) * 1e3 / steps
 
     phase_ms = dict.fromkeys(PH, 0.0)
-    for ev in events:
-        for i, ph in enumerate(PH):
-            phase_ms[ph] += ev[i].elapsed_time(ev[i + 1])
+    for kind, ev in events:
+        if kind == "rank":
+            phase_ms["rebuild_rank"] += ev[0].elapsed_time(ev[1])
+        else:
+            for i, ph in enumerate(PH[:3]):
+                phase_ms[ph] += ev[i].elapsed_time(ev[i + 1])
     phase_ms = {k: v / steps for k, v in phase_ms.items()}
     nl = len(layers)
     flops_full = sum(2.0 * N * hi * ho for _, hi, ho in layers)
@@ -747,10 +762,10 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
             dad.stack_factors(As, Ds, A_out=A_st[s], D_out=D_st[s])
             dad.compress_rank(A_st[s], D_st[s], r, n_iter, G0[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_c)
             dad.reconstruct_grad(A_st[s], D_st[s], G=G_full[s], workspace=ws_r)
-            dad.reconstruct_grad(Pt[li], Gt[li], G=G_rank[s])
+            dad.reconstruct_grad(Pt[li], Gt[li], G=G_rank[li])
             torch.cuda.synchronize()
             e_full = max(e_full, O.rel_fro(G_full[s].cpu().numpy(), M))
-            e_rank = max(e_rank, O.rel_fro(G_rank[s].cpu().numpy(), O.rank_r_grad(Pt_ref, Gt_ref)))
+            e_rank = max(e_rank, O.rel_fro(G_rank[li].cpu().numpy(), O.rank_r_grad(Pt_ref, Gt_ref)))
             sampled.append(f"{hi}x{ho}")
             del M
         cpu = {"value": flops / t_full / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",

@@ -226,6 +226,29 @@ size_t dad_reconstruct_workspace_bytes(int64_t K, int64_t h_in, int64_t h_out, d
 dad_status dad_reconstruct_grad(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out,
                                 dad_dtype dt, float* G, void* workspace, size_t ws_bytes, void* stream);
 
+/*
+ * dad_reconstruct_grad_grouped - dad_reconstruct_grad for n layers in one call (Algorithm 1 rebuilds
+ * every layer's gradient from its broadcast pair in the same step): G_i = L_i^T R_i.
+ *   descs     HOST array of n jobs, 1 <= n <= DAD_MAX_GROUP; pointers are device pointers with the
+ *             meaning and alignment of dad_reconstruct_grad's
+ *   dt        element type of every L_i, R_i
+ *   workspace device, ws_bytes >= dad_reconstruct_grouped_workspace_bytes(n, descs, dt) (may be NULL
+ *             when that is 0)
+ * Results are bit-identical to n separate dad_reconstruct_grad calls.  fp32 jobs (the rank-r pairs,
+ * K = r) share launches, up to 32 jobs per launch: one layer's rank-r gradient is a few MB and
+ * launch bound on its own.  bf16 jobs are large and run one after the other.
+ */
+typedef struct {
+    const void* L; /* K x h_in  */
+    const void* R; /* K x h_out */
+    float* G;      /* h_in x h_out, overwritten */
+    int64_t K, h_in, h_out;
+} dad_rebuild_desc;
+#define DAD_MAX_GROUP 4096
+size_t dad_reconstruct_grouped_workspace_bytes(int n, const dad_rebuild_desc* descs, dad_dtype dt);
+dad_status dad_reconstruct_grad_grouped(int n, const dad_rebuild_desc* descs, dad_dtype dt, void* workspace,
+                                        size_t ws_bytes, void* stream);
+
 /* Activation functions phi whose derivative dad_backprop_delta applies. */
 typedef enum {
     DAD_ACT_IDENTITY = 0,

@@ -24,6 +24,12 @@ DAD_ACT = {"identity": 0, "relu": 1, "tanh": 2, "sigmoid": 3}
 _lib = None
 
 
+class RebuildDesc(C.Structure):
+    """dad_rebuild_desc"""
+    _fields_ = [("L", C.c_void_p), ("R", C.c_void_p), ("G", C.c_void_p), ("K", C.c_int64), ("h_in", C.c_int64),
+                ("h_out", C.c_int64)]
+
+
 class DadError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -79,6 +85,10 @@ def lib() -> C.CDLL:
     L.dad_profile_kernel_name.argtypes = [C.c_int]
     L.dad_profile_get.restype = C.c_int
     L.dad_profile_get.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    L.dad_reconstruct_grouped_workspace_bytes.restype = sz
+    L.dad_reconstruct_grouped_workspace_bytes.argtypes = [C.c_int, C.POINTER(RebuildDesc), C.c_int]
+    L.dad_reconstruct_grad_grouped.restype = C.c_int
+    L.dad_reconstruct_grad_grouped.argtypes = [C.c_int, C.POINTER(RebuildDesc), C.c_int, vp, sz, vp]
     L.dad_probe_mfma_loop.restype = C.c_int
     L.dad_probe_mfma_loop.argtypes = [vp, sz, C.c_int, vp, vp, C.POINTER(C.c_double)]
     L.dad_probe_read_stream.restype = C.c_int
@@ -291,6 +301,47 @@ def reconstruct_grad(L, R, G=None, workspace=None):
                                       workspace.numel() if workspace is not None else 0, _stream()),
            "dad_reconstruct_grad")
     return G
+
+
+class RebuildGroup:
+    """Arguments of dad_reconstruct_grad_grouped marshalled once: the descriptor table, its workspace
+    and the outputs.  run() is one call of the entry point."""
+
+    def __init__(self, pairs, Gs=None, workspace=None):
+        if not pairs:
+            raise ValueError("need at least one (L, R) pair")
+        dt = _dt(pairs[0][0])
+        self.n = len(pairs)
+        self.dt = dt
+        self.G = []
+        self.descs = (RebuildDesc * self.n)()
+        for i, (L, R) in enumerate(pairs):
+            _dense2d(L, "L")
+            _dense2d(R, "R")
+            if R.shape[0] != L.shape[0] or R.dtype != L.dtype or _dt(L) != dt:
+                raise ValueError("L and R disagree in rows or dtype")
+            G = Gs[i] if Gs is not None else torch.empty((L.shape[1], R.shape[1]), dtype=torch.float32, device=L.device)
+            if tuple(G.shape) != (L.shape[1], R.shape[1]) or G.dtype != torch.float32 or not G.is_contiguous():
+                raise ValueError("G must be contiguous float32 h_in x h_out")
+            self.G.append(G)
+            self.descs[i] = RebuildDesc(L.data_ptr(), R.data_ptr(), G.data_ptr(), L.shape[0], L.shape[1], R.shape[1])
+        self._keep = pairs
+        need = lib().dad_reconstruct_grouped_workspace_bytes(self.n, self.descs, dt)
+        if workspace is None and need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=pairs[0][0].device)
+        self.workspace = workspace
+
+    def run(self):
+        ws = self.workspace
+        _check(lib().dad_reconstruct_grad_grouped(self.n, self.descs, self.dt, ws.data_ptr() if ws is not None else None,
+                                                  ws.numel() if ws is not None else 0, _stream()),
+               "dad_reconstruct_grad_grouped")
+        return self.G
+
+
+def reconstruct_grad_grouped(pairs, Gs=None, workspace=None):
+    """dad_reconstruct_grad_grouped: [G_i = L_i^T R_i] for a list of (L_i, R_i) pairs in one call."""
+    return RebuildGroup(pairs, Gs, workspace).run()
 
 
 def backprop_delta(D_next, W_next, Z, act, D_out=None):

@@ -1,6 +1,7 @@
 // C ABI of libdad: argument checks on the host, then kernel launches on the caller's stream.
 #include <atomic>
 #include <mutex>
+#include <vector>
 
 #include "dad_internal.h"
 
@@ -91,9 +92,11 @@ CompressPlan plan_compress(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dt
 RebuildPlan plan_rebuild(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt) {
     RebuildPlan p;
     p.fast = rebuild_fast_ok(K, h_in, h_out, dt);
+    p.f32 = !p.fast && dt == DAD_F32;
     p.tile = 0;
-    p.split = p.fast ? rebuild_fast_split(K, h_in, h_out, &p.tile)
-                     : split_rows(K, ceil_div(h_in, 64) * ceil_div(h_out, 64), 2048, 512, 16);
+    p.split = p.fast  ? rebuild_fast_split(K, h_in, h_out, &p.tile)
+              : p.f32 ? rebuild_f32_split(K, h_in, h_out)
+                      : split_rows(K, ceil_div(h_in, 64) * ceil_div(h_out, 64), 2048, 512, 16);
     p.total = p.split.splits > 1 ? (size_t)p.split.splits * h_in * h_out * 4 : 0;
     return p;
 }
@@ -306,6 +309,76 @@ dad_status dad_reconstruct_grad(const void* L, const void* R, int64_t K, int64_t
     return launch_rebuild(L, R, K, h_in, h_out, dt, G, static_cast<float*>(workspace), p, (hipStream_t)stream);
 }
 
+// Checks of one job of the grouped rebuild; *plan receives its plan.
+static dad_status rebuild_job_ok(const dad_rebuild_desc& d, dad_dtype dt, RebuildPlan* plan) {
+    if (!d.L || !d.R || !d.G) return DAD_ERR_NULL;
+    if (!rebuild_shape_ok(d.K, d.h_in, d.h_out)) return DAD_ERR_SHAPE;
+    if (!aligned16(d.L) || !aligned16(d.R) || !aligned16(d.G)) return DAD_ERR_ALIGN;
+    *plan = plan_rebuild(d.K, d.h_in, d.h_out, dt);
+    return DAD_OK;
+}
+
+// fp32 jobs run together and need their slabs side by side; the others run one after the other on
+// the stream and share one region.
+static size_t grouped_rebuild_bytes(int n, const dad_rebuild_desc* descs, dad_dtype dt) {
+    size_t total = 0;
+    for (int i = 0; i < n; ++i) {
+        const RebuildPlan p = plan_rebuild(descs[i].K, descs[i].h_in, descs[i].h_out, dt);
+        if (p.f32)
+            total += align_up(p.total, 256);
+        else if (p.total > total)
+            total = p.total;
+    }
+    return total;
+}
+
+size_t dad_reconstruct_grouped_workspace_bytes(int n, const dad_rebuild_desc* descs, dad_dtype dt) {
+    if (n < 1 || n > DAD_MAX_GROUP || !descs || !dtype_ok(dt)) return 0;
+    for (int i = 0; i < n; ++i)
+        if (!rebuild_shape_ok(descs[i].K, descs[i].h_in, descs[i].h_out)) return 0;
+    return grouped_rebuild_bytes(n, descs, dt);
+}
+
+dad_status dad_reconstruct_grad_grouped(int n, const dad_rebuild_desc* descs, dad_dtype dt, void* workspace,
+                                        size_t ws_bytes, void* stream) {
+    if (!descs) return DAD_ERR_NULL;
+    if (!dtype_ok(dt)) return DAD_ERR_DTYPE;
+    if (n < 1 || n > DAD_MAX_GROUP) return DAD_ERR_SHAPE;
+    std::vector<RebuildPlan> plans((size_t)n);
+    for (int i = 0; i < n; ++i) {
+        const dad_status rc = rebuild_job_ok(descs[i], dt, &plans[(size_t)i]);
+        if (rc != DAD_OK) return rc;
+    }
+    const size_t need = grouped_rebuild_bytes(n, descs, dt);
+    if (need > 0 && !workspace) return DAD_ERR_NULL;
+    if (workspace && !aligned16(workspace)) return DAD_ERR_ALIGN;
+    if (ws_bytes < need) return DAD_ERR_WORKSPACE;
+    if (const dad_status ready = device_ready(); ready != DAD_OK) return ready;
+    hipStream_t s = (hipStream_t)stream;
+    if (dt == DAD_F32) {  // every fp32 shape runs on the fp32 MFMA kernel: one job table for all of them
+        std::vector<const void*> L((size_t)n), R((size_t)n);
+        std::vector<float*> G((size_t)n), slabs((size_t)n);
+        std::vector<int64_t> K((size_t)n), hi((size_t)n), ho((size_t)n);
+        std::vector<SplitPlan> sp((size_t)n);
+        size_t off = 0;
+        for (int i = 0; i < n; ++i) {
+            const size_t k = (size_t)i;
+            L[k] = descs[i].L, R[k] = descs[i].R, G[k] = descs[i].G;
+            K[k] = descs[i].K, hi[k] = descs[i].h_in, ho[k] = descs[i].h_out;
+            sp[k] = plans[k].split;
+            slabs[k] = plans[k].total ? reinterpret_cast<float*>(static_cast<char*>(workspace) + off) : nullptr;
+            off += align_up(plans[k].total, 256);
+        }
+        return launch_rebuild_f32(n, L.data(), R.data(), G.data(), K.data(), hi.data(), ho.data(), sp.data(), slabs.data(), s);
+    }
+    for (int i = 0; i < n; ++i) {
+        const dad_status rc = launch_rebuild(descs[i].L, descs[i].R, descs[i].K, descs[i].h_in, descs[i].h_out, dt,
+                                             descs[i].G, static_cast<float*>(workspace), plans[(size_t)i], s);
+        if (rc != DAD_OK) return rc;
+    }
+    return DAD_OK;
+}
+
 dad_status dad_poll_numeric_status(const void* workspace, void* stream) {
     if (!workspace) return DAD_ERR_NULL;
     int flag = 0;
@@ -333,6 +406,7 @@ dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* par
 dad_status launch_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt,
                           float* G, float* partials, const RebuildPlan& plan, hipStream_t s) {
     if (plan.fast) return fast_rebuild(L, R, K, h_in, h_out, G, partials, plan.split, plan.tile, s);
+    if (plan.f32) return launch_rebuild_f32(1, &L, &R, &G, &K, &h_in, &h_out, &plan.split, &partials, s);
     return gen_rebuild(L, R, K, h_in, h_out, dt, G, partials, plan.split, s);
 }
 

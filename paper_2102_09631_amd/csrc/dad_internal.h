@@ -113,7 +113,8 @@ dad_status device_ready(void** scratch_out = nullptr);
 enum KernelId {
     KID_STACK = 0, KID_THIN_NN_BF16, KID_THIN_TN_BF16, KID_REDUCE, KID_GRAM, KID_APPLY, KID_APPLY2, KID_REBUILD_BF16,
     KID_THIN_NN, KID_THIN_TN, KID_REBUILD, KID_PANEL_INIT, KID_REBUILD_BF16_DMA, KID_BACKPROP_BF16, KID_BACKPROP,
-    KID_GRAM_TILES, KID_GRAM_GATHER, KID_NS_STEP, KID_NS_PROJECT, KID_COUNT
+    KID_GRAM_TILES, KID_GRAM_GATHER, KID_NS_STEP, KID_NS_PROJECT, KID_REBUILD_F32, KID_REDUCE_WIDE, KID_SEQ_VECTOR,
+    KID_COUNT
 };
 
 // Brackets the kernel launched inside its scope with two events when timing is enabled.
@@ -168,8 +169,9 @@ bool thin_fast_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
 struct RebuildPlan {
     SplitPlan split;
     size_t total;  // bytes of partials (0 when splits == 1)
-    bool fast;
-    int tile;      // output tile edge of the MFMA kernel (256 or 128)
+    bool fast;     // bf16 MFMA kernels
+    bool f32;      // fp32 MFMA kernel (every fp32 shape)
+    int tile;      // output tile edge of the bf16 MFMA kernel (256 or 128)
 };
 
 RebuildPlan plan_rebuild(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
@@ -203,5 +205,12 @@ dad_status launch_cholqr(const float* Yt, float* Gt, int64_t h, int r, int round
 dad_status launch_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt,
                           float* G, float* partials, const RebuildPlan& plan, hipStream_t s);
 
+
+// G_i = L_i^T R_i for n fp32 jobs in as few launches as possible (csrc/rebuild_f32.hip); a job with
+// sp[i].splits > 1 goes through slabs[i] (splits * h_in * h_out floats) and reduce_slabs.
+SplitPlan rebuild_f32_split(int64_t K, int64_t h_in, int64_t h_out);
+dad_status launch_rebuild_f32(int n, const void* const* L, const void* const* R, float* const* G, const int64_t* K,
+                              const int64_t* h_in, const int64_t* h_out, const SplitPlan* sp, float* const* slabs,
+                              hipStream_t s);
 
 }  // namespace dad

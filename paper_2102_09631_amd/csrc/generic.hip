@@ -328,8 +328,9 @@ dad_status gen_thin_nn(const void* X, const float* Pt, void* out, float* partial
 }
 
 dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s, void* out_bf16) {
-    ProfScope prof(KID_REDUCE, s);
-    if (n >= (1 << 20) && n % 4 == 0 && !out_bf16)
+    const bool wide = n >= (1 << 20) && n % 4 == 0 && !out_bf16;
+    ProfScope prof(wide ? KID_REDUCE_WIDE : KID_REDUCE, s);
+    if (wide)
         hipLaunchKernelGGL(k_reduce_slabs_wide, dim3((unsigned)ceil_div(n / 4, 256)), dim3(256), 0, s,
                            reinterpret_cast<const float4*>(part), reinterpret_cast<float4*>(out), n / 4, splits);
     else

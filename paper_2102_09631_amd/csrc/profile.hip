@@ -12,7 +12,7 @@ namespace dad {
 static const char* const kKernelNames[KID_COUNT] = {
     "k_stack",       "k_thin_nn_bf16", "k_thin_tn_bf16", "k_reduce_slabs", "k_qr_gram", "k_qr_apply<NA,true>",
     "k_qr_apply<NA,false>",  "k_rebuild_bf16", "k_thin_nn",      "k_thin_tn",      "k_rebuild",      "k_panel_init",  "k_rebuild_bf16_dma", "k_backprop_bf16", "k_backprop",
-    "k_gram_tiles", "k_gram_gather", "k_ns_step", "k_ns_project",
+    "k_gram_tiles", "k_gram_gather", "k_ns_step", "k_ns_project", "k_rebuild_f32_mfma", "k_reduce_slabs_wide", "k_seq_vector",
 };
 
 struct Pending {

@@ -173,25 +173,35 @@ extern "C" dad_status dad_compress_rank_sequential(const void* A, const void* D,
     };
     if (rp > 1) {
         const int64_t n = (int64_t)(rp - 1) * h_out;
+        ProfScope prof(KID_SEQ_VECTOR, s);
         hipLaunchKernelGGL(k_seq_zero, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, panel + h_out, n);
         DAD_LAUNCH_CHECK();
     }
     for (int j = 0; j < r; ++j) {
-        hipLaunchKernelGGL(k_seq_start, dim3(1), dim3(1024), 0, s, G0 + (int64_t)j * h_out, panel, h_out, flag,
-                           j == 0 ? flag : (int*)nullptr);
+        {
+            ProfScope prof(KID_SEQ_VECTOR, s);
+            hipLaunchKernelGGL(k_seq_start, dim3(1), dim3(1024), 0, s, G0 + (int64_t)j * h_out, panel, h_out, flag,
+                               j == 0 ? flag : (int*)nullptr);
+        }
         DAD_LAUNCH_CHECK();
         for (int it = 0; it < n_iter; ++it) {
             DAD_TRY(nn(D, panel, h_out, p.c.nn_out, 1));  // v = Delta g
             DAD_TRY(tn(A, Ut, h_in, p.c.tn_in, 1));       // u = A^T v
             DAD_TRY(nn(A, Ut, h_in, p.c.nn_in, 2));       // w = A u
             DAD_TRY(tn(D, Yt, h_out, p.c.tn_out, 2));     // y = Delta^T w = M^T M g
-            hipLaunchKernelGGL(k_seq_update, dim3(1), dim3(1024), 0, s, Yt, sGt, j, panel, h_out, flag);
+            {
+                ProfScope prof(KID_SEQ_VECTOR, s);
+                hipLaunchKernelGGL(k_seq_update, dim3(1), dim3(1024), 0, s, Yt, sGt, j, panel, h_out, flag);
+            }
             DAD_LAUNCH_CHECK();
         }
         DAD_TRY(nn(D, panel, h_out, p.c.nn_out, 1));  // v = Delta g
         DAD_TRY(tn(A, Ut, h_in, p.c.tn_in, 1));       // p = A^T v
-        hipLaunchKernelGGL(k_seq_finish, dim3(1), dim3(1024), 0, s, Ut, panel, Qt + (int64_t)j * h_in,
-                           sGt + (int64_t)j * h_out, sigma ? sigma + j : (float*)nullptr, h_in, h_out, flag);
+        {
+            ProfScope prof(KID_SEQ_VECTOR, s);
+            hipLaunchKernelGGL(k_seq_finish, dim3(1), dim3(1024), 0, s, Ut, panel, Qt + (int64_t)j * h_in,
+                               sGt + (int64_t)j * h_out, sigma ? sigma + j : (float*)nullptr, h_in, h_out, flag);
+        }
         DAD_LAUNCH_CHECK();
     }
 #undef DAD_TRY

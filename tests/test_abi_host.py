@@ -115,6 +115,28 @@ def test_reconstruct_and_stack_reject_bad_arguments_on_host(lib):
     assert lib.dad_stack_factors(2, nullp, ptrs, rows, 8, 8, 0, p, p, None) == dad.DAD_ERR_NULL
 
 
+def test_grouped_rebuild_rejects_bad_arguments_on_host(lib):
+    p = 0x1000
+    D = dad.RebuildDesc
+    good = (D * 2)(D(p, p, p, 4, 8, 8), D(p, p, p, 8, 16, 24))
+    assert lib.dad_reconstruct_grad_grouped(2, None, 0, None, 0, None) == dad.DAD_ERR_NULL
+    assert lib.dad_reconstruct_grad_grouped(0, good, 0, None, 0, None) == dad.DAD_ERR_SHAPE
+    assert lib.dad_reconstruct_grad_grouped(4097, good, 0, None, 0, None) == dad.DAD_ERR_SHAPE
+    assert lib.dad_reconstruct_grad_grouped(2, good, 6, None, 0, None) == dad.DAD_ERR_DTYPE
+    bad = (D * 2)(D(p, p, p, 4, 8, 8), D(p, None, p, 8, 16, 24))
+    assert lib.dad_reconstruct_grad_grouped(2, bad, 0, None, 0, None) == dad.DAD_ERR_NULL
+    bad = (D * 2)(D(p, p, p, 4, 8, 8), D(p, p, p, 0, 16, 24))
+    assert lib.dad_reconstruct_grad_grouped(2, bad, 0, None, 0, None) == dad.DAD_ERR_SHAPE
+    bad = (D * 2)(D(p, p, p + 4, 4, 8, 8), D(p, p, p, 8, 16, 24))
+    assert lib.dad_reconstruct_grad_grouped(2, bad, 0, None, 0, None) == dad.DAD_ERR_ALIGN
+    big = (D * 2)(D(p, p, p, 1024, 1024, 1024), D(p, p, p, 1024, 1024, 1024))
+    need = lib.dad_reconstruct_grouped_workspace_bytes(2, big, dad.DAD_F32)
+    assert need >= 2 * lib.dad_reconstruct_workspace_bytes(1024, 1024, 1024, dad.DAD_F32) > 0
+    assert lib.dad_reconstruct_grad_grouped(2, big, 0, None, 0, None) == dad.DAD_ERR_NULL
+    assert lib.dad_reconstruct_grad_grouped(2, big, 0, p, need - 1, None) == dad.DAD_ERR_WORKSPACE
+    assert lib.dad_reconstruct_grouped_workspace_bytes(2, good, dad.DAD_F32) == 0
+
+
 def test_backprop_rejects_bad_arguments_on_host(lib):
     p = 0x1000  # never dereferenced: every call below must fail before a launch
 
