@@ -39,6 +39,12 @@ def parse():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="gpt2_medium_stack")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--lanes", type=int, default=3,
+                    help="default mode: layers of one block whose compress calls are in flight at once "
+                         "(dad_compress_rank_grouped); 0 = one dad_compress_rank call per layer")
+    ap.add_argument("--group-layers", type=int, default=0,
+                    help="default mode: layers per grouped compress call when every layer has its own stacked "
+                         "buffer (0 = the whole stack)")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="default mode: skip the encoder_d768 and vit_large_stack passes that follow the headline workload")
     ap.add_argument("--mode", default="one_level", choices=["one_level", "two_level", "backprop", "sequential"],
@@ -575,8 +581,17 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
         return sites[li] if li in sites else sites[li % len(w.shapes)]
     G0 = {li: W.device_start_matrix(w, li, ho, device=dev) for li, _, ho in layers}
     shape_ids = {s: i for i, s in enumerate(w.shapes)}
-    A_st = {s: torch.empty((N, s[0]), dtype=tdt, device=dev) for s in w.shapes}
-    D_st = {s: torch.empty((N, s[1]), dtype=tdt, device=dev) for s in w.shapes}
+    # Stacked factors: one buffer per layer when unstacked + stacked copies of the whole stack fit in
+    # HBM (the layers of the whole stack can then be reduced by ONE grouped call), else one per
+    # distinct shape (grouped per block of the model).
+    whole = len(resident) == len(layers) and 2 * total_bytes < 200e9 and args.lanes > 0
+    nb = len(w.shapes)
+    gl = args.group_layers if (whole and args.group_layers > 0) else (len(layers) if whole else nb)
+    scopes = [layers[i:i + gl] for i in range(0, len(layers), gl)]
+    def st_key(li, hi, ho):
+        return li if whole else (hi, ho)
+    A_st = {st_key(li, hi, ho): torch.empty((N, hi), dtype=tdt, device=dev) for li, hi, ho in (layers if whole else layers[:nb])}
+    D_st = {st_key(li, hi, ho): torch.empty((N, ho), dtype=tdt, device=dev) for li, hi, ho in (layers if whole else layers[:nb])}
     G_full = {s: torch.empty(s, dtype=torch.float32, device=dev) for s in w.shapes}
     # the rank-r gradients of all layers are rebuilt by ONE grouped call at the end of a step
     G_rank = {li: torch.empty((hi, ho), dtype=torch.float32, device=dev) for li, hi, ho in layers}
@@ -594,7 +609,7 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
 
     # Timing events are created, and one pair is exercised, before the timed region: the first use of
     # a timing event costs milliseconds of one-off set-up in the runtime.
-    pool = [torch.cuda.Event(enable_timing=True) for _ in range((4 * len(layers) + 2) * steps)]
+    pool = [torch.cuda.Event(enable_timing=True) for _ in range((5 * len(layers) + 2 * len(scopes) + 2) * steps)]
     pool_next = [0]
     if pool:
         pool[0].record(); pool[1].record(); torch.cuda.synchronize(); pool[0].elapsed_time(pool[1])
@@ -604,30 +619,60 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
         pool_next[0] += n
         return ev
 
-    def step(events=None):
-        for li, hi, ho in layers:
-            s = (hi, ho)
-            As, Ds = factors_of(li)
-            ev = take(4) if events is not None else None
-            if ev: ev[0].record()
-            dad.stack_factors(As, Ds, A_out=A_st[s], D_out=D_st[s])
-            if ev: ev[1].record()
-            dad.compress_rank(A_st[s], D_st[s], r, n_iter, G0[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_c)
-            if ev: ev[2].record()
-            dad.reconstruct_grad(A_st[s], D_st[s], G=G_full[s], workspace=ws_r)
-            if ev: ev[3].record()
-            if ev: events.append(("layer", ev))
+    # Per scope (the whole stack, or one block of distinct shapes): stack every layer, reduce all of
+    # them with one grouped call (args.lanes layers in flight at once), rebuild every full gradient.
+    groups_all = None
+    if args.lanes > 0:
+        groups_all = groups = []
+        for sc in scopes:
+            groups.append(dad.CompressGroup([(A_st[st_key(*t)], D_st[st_key(*t)], G0[t[0]]) for t in sc], r, n_iter,
+                                            lanes=min(args.lanes, dad.DAD_MAX_LANES),
+                                            Pts=[Pt[t[0]] for t in sc], Gts=[Gt[t[0]] for t in sc],
+                                            workspace=groups[0].workspace if groups else None))
+
+    def step(events=None, grouped=True):
+        groups = groups_all if grouped else None
+        for si, sc in enumerate(scopes):
+            # stack and full rebuild alternate layer by layer (the MFMA-bound rebuild launches then do
+            # not run back to back: 96 of them in a row clock 5 % lower), then the scope's layers are
+            # reduced by one grouped call
+            for li, hi, ho in sc:
+                k = st_key(li, hi, ho)
+                As, Ds = factors_of(li)
+                ev = take(3) if events is not None else None
+                if ev: ev[0].record()
+                dad.stack_factors(As, Ds, A_out=A_st[k], D_out=D_st[k])
+                if ev: ev[1].record()
+                if groups is None:
+                    dad.compress_rank(A_st[k], D_st[k], r, n_iter, G0[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_c)
+                    if ev: ev[2].record()
+                    if ev: events.append(("stack_compress", ev))
+                    ev = take(2) if events is not None else None
+                    if ev: ev[0].record()
+                    dad.reconstruct_grad(A_st[k], D_st[k], G=G_full[(hi, ho)], workspace=ws_r)
+                    if ev: ev[1].record()
+                    if ev: events.append(("rebuild_full", ev))
+                else:
+                    dad.reconstruct_grad(A_st[k], D_st[k], G=G_full[(hi, ho)], workspace=ws_r)
+                    if ev: ev[2].record()
+                    if ev: events.append(("stack_rebuild", ev))
+            if groups is not None:
+                ev = take(2) if events is not None else None
+                if ev: ev[0].record()
+                groups[si].run()
+                if ev: ev[1].record()
+                if ev: events.append(("compress", ev))
         ev = take(2) if events is not None else None
         if ev: ev[0].record()
         rank_group.run()          # every layer's rank-r gradient P^T G in one grouped call
         if ev: ev[1].record()
-        if ev: events.append(("rank", ev))
+        if ev: events.append(("rebuild_rank", ev))
 
     # Untimed pre-pass: every layer's compress once, with the numeric status polled per layer (the
     # flag lives in the shared workspace and is cleared by the next call, so one poll after a whole
     # step would only see the last layer's).
     for li, hi, ho in layers:
-        s_ = (hi, ho)
+        s_ = st_key(li, hi, ho)
         As, Ds = factors_of(li)
         dad.stack_factors(As, Ds, A_out=A_st[s_], D_out=D_st[s_])
         dad.compress_rank(A_st[s_], D_st[s_], r, n_iter, G0[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_c)
@@ -647,11 +692,13 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     # the same K steps once more with the library's per-kernel events switched on (two events per
-    # launch cost about 10 us per launch, so they stay out of the region that `value` comes from)
+    # launch cost about 10 us per launch, so they stay out of the region that `value` comes from), one
+    # layer's compress at a time: kernels of concurrent lanes would share the chip and their event
+    # brackets would overlap
     dad.profile_reset()
     dad.profile_enable(True)
     for _ in range(steps):
-        step()
+        step(grouped=False)
     torch.cuda.synchronize()
     dad.profile_enable(False)
     kern = dad.profile_read()
@@ -659,11 +706,14 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
 
     phase_ms = dict.fromkeys(PH, 0.0)
     for kind, ev in events:
-        if kind == "rank":
-            phase_ms["rebuild_rank"] += ev[0].elapsed_time(ev[1])
+        if kind == "stack_compress":
+            phase_ms["stack"] += ev[0].elapsed_time(ev[1])
+            phase_ms["compress"] += ev[1].elapsed_time(ev[2])
+        elif kind == "stack_rebuild":
+            phase_ms["stack"] += ev[0].elapsed_time(ev[1])
+            phase_ms["rebuild_full"] += ev[1].elapsed_time(ev[2])
         else:
-            for i, ph in enumerate(PH[:3]):
-                phase_ms[ph] += ev[i].elapsed_time(ev[i + 1])
+            phase_ms[kind] += ev[0].elapsed_time(ev[1])
     phase_ms = {k: v / steps for k, v in phase_ms.items()}
     nl = len(layers)
     flops_full = sum(2.0 * N * hi * ho for _, hi, ho in layers)
@@ -759,9 +809,10 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
             flops += 2.0 * N * hi * ho
             # same layer on the GPU, for an on-the-spot parity figure
             s = (hi, ho)
-            dad.stack_factors(As, Ds, A_out=A_st[s], D_out=D_st[s])
-            dad.compress_rank(A_st[s], D_st[s], r, n_iter, G0[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_c)
-            dad.reconstruct_grad(A_st[s], D_st[s], G=G_full[s], workspace=ws_r)
+            k = st_key(li, hi, ho)
+            dad.stack_factors(As, Ds, A_out=A_st[k], D_out=D_st[k])
+            dad.compress_rank(A_st[k], D_st[k], r, n_iter, G0[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_c)
+            dad.reconstruct_grad(A_st[k], D_st[k], G=G_full[s], workspace=ws_r)
             dad.reconstruct_grad(Pt[li], Gt[li], G=G_rank[li])
             torch.cuda.synchronize()
             e_full = max(e_full, O.rel_fro(G_full[s].cpu().numpy(), M))
@@ -796,22 +847,23 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
             e1.record()
             torch.cuda.synchronize()
             return e0.elapsed_time(e1) * 1e-3 / reps
+        first = {(hi, ho): st_key(li, hi, ho) for li, hi, ho in reversed(layers)}   # a stacked buffer of each shape
         s0 = max(w.shapes, key=lambda t: t[1])
-        src, dst = D_st[s0], torch.empty_like(D_st[s0])
+        src, dst = D_st[first[s0]], torch.empty_like(D_st[first[s0]])
         t_copy = timed(lambda: dst.copy_(src), 10)
         del dst
         t_mm = fl_mm = 0.0
         for sh in w.shapes:
-            t_mm += timed(lambda: torch.matmul(A_st[sh].t(), D_st[sh]), 3)
+            t_mm += timed(lambda: torch.matmul(A_st[first[sh]].t(), D_st[first[sh]]), 3)
             fl_mm += 2.0 * N * sh[0] * sh[1]
-        mfma_data = dad.probe_mfma_loop(A_st[s0])
+        mfma_data = dad.probe_mfma_loop(A_st[first[s0]])
         zeros = torch.zeros(1 << 22, dtype=tdt, device=dev)
         mfma_zero = dad.probe_mfma_loop(zeros)
-        read_gbps = dad.probe_read_stream(D_st[s0])
+        read_gbps = dad.probe_read_stream(D_st[first[s0]])
         # the rebuild call on zero factors: same launches and clocks per stage, no operand toggling
         t_z = fl_z = 0.0
         for sh in w.shapes:
-            Az, Dz = torch.zeros_like(A_st[sh]), torch.zeros_like(D_st[sh])
+            Az, Dz = torch.zeros_like(A_st[first[sh]]), torch.zeros_like(D_st[first[sh]])
             t_z += timed(lambda: dad.reconstruct_grad(Az, Dz, G=G_full[sh], workspace=ws_r), 5)
             fl_z += 2.0 * N * sh[0] * sh[1]
             del Az, Dz
@@ -842,7 +894,8 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
         "data": "synthetic",
         "config": {"workload": w.name, "layers": nl, "shapes": [list(s) for s in w.shapes], "sites": S,
                    "rows_per_site": b, "N": N, "rank": r, "n_iter": n_iter,
-                   "resident_layers": len(resident)},
+                   "resident_layers": len(resident), "compress_lanes": args.lanes,
+                   "compress_group_layers": gl},
         "rebuild_frac_of_mfma_peak": rebuild_tflops / (PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS),
         "compress_us_per_layer": phase_ms["compress"] * 1e3 / nl,
         "compress_GBps": bytes_compress / (phase_ms["compress"] * 1e-3) / 1e9,

@@ -20,10 +20,11 @@
  *     device and is owned by the caller; the library allocates and frees no
  *     device memory.  Scratch space comes in through `workspace` (size from
  *     the matching *_workspace_bytes query).  Nothing computed is kept from
- *     one call to the next; the only process-wide state is a per-device
- *     "set-up done" flag (see dad_init) and, when switched on, the timing
- *     records of dad_profile_*; both are safe to use from several host
- *     threads.
+ *     one call to the next; the only process-wide state is per device: a
+ *     "set-up done" flag (see dad_init), seven side streams and their events
+ *     for dad_compress_rank_grouped, the static scratch array of
+ *     dad_compress_rank_noalloc, and, when switched on, the timing records of
+ *     dad_profile_*; all are safe to use from several host threads.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls enqueue work and return; they do not synchronise.
  *   - Argument errors are detected on the host and returned before anything
@@ -71,6 +72,7 @@ typedef enum {
 #define DAD_MAX_RANK 64    /* largest r accepted by dad_compress_rank */
 #define DAD_GRAM_MAX_ROWS 1024 /* largest N accepted by dad_compress_rank_gram */
 #define DAD_MAX_SITES 4096 /* largest S accepted by dad_stack_factors */
+#define DAD_MAX_GROUP 4096 /* largest n accepted by the *_grouped calls */
 #define DAD_MAX_ROWS ((int64_t)1 << 36)  /* largest N (or K) accepted */
 #define DAD_MAX_WIDTH ((int64_t)1 << 21) /* largest h_in, h_out accepted */
 
@@ -160,6 +162,36 @@ dad_status dad_compress_rank_noalloc(const void* A, const void* D, int64_t N, in
                                      dad_dtype dt, int r, int n_iter, const float* G0, float* Pt, float* Gt,
                                      int* numeric_flag, void* stream);
 
+/*
+ * dad_compress_rank_grouped - dad_compress_rank for n layers in one call (Algorithm 1 reduces every
+ * layer's pair in the same step).  Layer i gets exactly the launches of dad_compress_rank on its own
+ * region of the workspace, so its Pt, Gt are bit-identical to a single call's; up to `lanes` layers
+ * are in flight at once (layer i on lane i mod lanes), so that the short, latency-bound launches of
+ * one layer's orthonormalisation run while another layer streams its factors.
+ *   descs     HOST array of n layers, 1 <= n <= DAD_MAX_GROUP; every pointer is a device pointer with
+ *             the meaning and alignment of dad_compress_rank's
+ *   dt, r, n_iter   common to all layers
+ *   lanes     1 .. DAD_MAX_LANES; lane 0 is `stream` itself, the others are streams of default
+ *             priority that the library keeps per device; they start after the work already enqueued
+ *             on `stream`, and `stream` waits for them before the call's successors (fork and join by
+ *             events, so the call can be recorded into a HIP graph after dad_init)
+ *   workspace device, ws_bytes >= dad_compress_grouped_workspace_bytes(n, descs, dt, r, lanes)
+ * dad_poll_numeric_status(workspace, stream) reports DAD_ERR_NUMERIC if ANY layer of the call broke
+ * down.  Calls on one device are serialised on the host by a mutex while they enqueue.
+ */
+typedef struct {
+    const void* A;   /* N x h_in  */
+    const void* D;   /* N x h_out */
+    const float* G0; /* r x h_out */
+    float* Pt;       /* r x h_in,  out */
+    float* Gt;       /* r x h_out, out */
+    int64_t N, h_in, h_out;
+} dad_compress_desc;
+#define DAD_MAX_LANES 8
+size_t dad_compress_grouped_workspace_bytes(int n, const dad_compress_desc* descs, dad_dtype dt, int r, int lanes);
+dad_status dad_compress_rank_grouped(int n, const dad_compress_desc* descs, dad_dtype dt, int r, int n_iter, int lanes,
+                                     void* workspace, size_t ws_bytes, void* stream);
+
 /* Bytes of device workspace dad_compress_rank_gram needs (0 on invalid sizes, N > DAD_GRAM_MAX_ROWS included). */
 size_t dad_compress_gram_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
 
@@ -244,7 +276,6 @@ typedef struct {
     float* G;      /* h_in x h_out, overwritten */
     int64_t K, h_in, h_out;
 } dad_rebuild_desc;
-#define DAD_MAX_GROUP 4096
 size_t dad_reconstruct_grouped_workspace_bytes(int n, const dad_rebuild_desc* descs, dad_dtype dt);
 dad_status dad_reconstruct_grad_grouped(int n, const dad_rebuild_desc* descs, dad_dtype dt, void* workspace,
                                         size_t ws_bytes, void* stream);

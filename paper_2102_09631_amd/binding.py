@@ -30,6 +30,12 @@ class RebuildDesc(C.Structure):
                 ("h_out", C.c_int64)]
 
 
+class CompressDesc(C.Structure):
+    """dad_compress_desc"""
+    _fields_ = [("A", C.c_void_p), ("D", C.c_void_p), ("G0", C.c_void_p), ("Pt", C.c_void_p), ("Gt", C.c_void_p),
+                ("N", C.c_int64), ("h_in", C.c_int64), ("h_out", C.c_int64)]
+
+
 class DadError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -89,6 +95,10 @@ def lib() -> C.CDLL:
     L.dad_reconstruct_grouped_workspace_bytes.argtypes = [C.c_int, C.POINTER(RebuildDesc), C.c_int]
     L.dad_reconstruct_grad_grouped.restype = C.c_int
     L.dad_reconstruct_grad_grouped.argtypes = [C.c_int, C.POINTER(RebuildDesc), C.c_int, vp, sz, vp]
+    L.dad_compress_grouped_workspace_bytes.restype = sz
+    L.dad_compress_grouped_workspace_bytes.argtypes = [C.c_int, C.POINTER(CompressDesc), C.c_int, C.c_int, C.c_int]
+    L.dad_compress_rank_grouped.restype = C.c_int
+    L.dad_compress_rank_grouped.argtypes = [C.c_int, C.POINTER(CompressDesc), C.c_int, C.c_int, C.c_int, C.c_int, vp, sz, vp]
     L.dad_probe_mfma_loop.restype = C.c_int
     L.dad_probe_mfma_loop.argtypes = [vp, sz, C.c_int, vp, vp, C.POINTER(C.c_double)]
     L.dad_probe_read_stream.restype = C.c_int
@@ -301,6 +311,52 @@ def reconstruct_grad(L, R, G=None, workspace=None):
                                       workspace.numel() if workspace is not None else 0, _stream()),
            "dad_reconstruct_grad")
     return G
+
+
+DAD_MAX_LANES = 8
+
+
+class CompressGroup:
+    """Arguments of dad_compress_rank_grouped marshalled once.  layers: list of (A, D, G0) tensors;
+    outputs Pt, Gt are allocated unless given.  run() is one call of the entry point."""
+
+    def __init__(self, layers, r, n_iter, lanes=2, Pts=None, Gts=None, workspace=None):
+        if not layers:
+            raise ValueError("need at least one layer")
+        self.n, self.r, self.n_iter, self.lanes = len(layers), r, n_iter, lanes
+        self.dt = _dt(layers[0][0])
+        self.descs = (CompressDesc * self.n)()
+        self.Pt, self.Gt = [], []
+        for i, (A, D, G0) in enumerate(layers):
+            _dense2d(A, "A")
+            _dense2d(D, "Delta")
+            _dense2d(G0, "G0")
+            N, h_in = A.shape
+            h_out = D.shape[1]
+            if D.shape[0] != N or D.dtype != A.dtype or _dt(A) != self.dt:
+                raise ValueError("A and Delta disagree in rows or dtype")
+            if G0.dtype != torch.float32 or tuple(G0.shape) != (r, h_out):
+                raise ValueError("G0 must be float32 of shape (r, h_out)")
+            Pt = Pts[i] if Pts is not None else torch.empty((r, h_in), dtype=torch.float32, device=A.device)
+            Gt = Gts[i] if Gts is not None else torch.empty((r, h_out), dtype=torch.float32, device=A.device)
+            self.Pt.append(Pt)
+            self.Gt.append(Gt)
+            self.descs[i] = CompressDesc(A.data_ptr(), D.data_ptr(), G0.data_ptr(), Pt.data_ptr(), Gt.data_ptr(), N, h_in, h_out)
+        self._keep = layers
+        need = lib().dad_compress_grouped_workspace_bytes(self.n, self.descs, self.dt, r, lanes)
+        if need == 0:
+            raise ValueError("invalid sizes for dad_compress_rank_grouped")
+        if workspace is None:
+            workspace = torch.zeros(need, dtype=torch.uint8, device=layers[0][0].device)
+        self.workspace = workspace
+
+    def run(self, check=False):
+        ws = self.workspace
+        _check(lib().dad_compress_rank_grouped(self.n, self.descs, self.dt, self.r, self.n_iter, self.lanes,
+                                               ws.data_ptr(), ws.numel(), _stream()), "dad_compress_rank_grouped")
+        if check:
+            _check(lib().dad_poll_numeric_status(ws.data_ptr(), _stream()), "dad_poll_numeric_status")
+        return self.Pt, self.Gt
 
 
 class RebuildGroup:

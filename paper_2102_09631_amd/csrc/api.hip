@@ -105,9 +105,16 @@ static bool dtype_ok(dad_dtype dt) { return dt == DAD_F32 || dt == DAD_BF16; }
 
 // ---------------------------------------------------------------- per-device set-up
 constexpr int MAX_DEVICES = 64;
+constexpr int SIDE_STREAMS = DAD_MAX_LANES - 1;
 struct DeviceState {
     std::atomic<int> ready{0};
     void* scratch = nullptr;  // this device's copy of the static scratch array
+    // dad_compress_rank_grouped: side streams (default priority) the lanes beyond the first run on,
+    // one fork event and one join event per side stream
+    hipStream_t side[SIDE_STREAMS] = {};
+    hipEvent_t fork = nullptr;
+    hipEvent_t join[SIDE_STREAMS] = {};
+    std::mutex lanes_mu;  // one grouped call at a time enqueues on a device's side streams
 };
 static DeviceState g_dev[MAX_DEVICES];
 static std::mutex g_dev_mu;
@@ -129,6 +136,11 @@ dad_status device_ready(void** scratch_out) {
             DAD_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
             if (!ptr) return DAD_ERR_HIP;
             st.scratch = ptr;
+            DAD_HIP_TRY(hipEventCreateWithFlags(&st.fork, hipEventDisableTiming));
+            for (int i = 0; i < SIDE_STREAMS; ++i) {
+                DAD_HIP_TRY(hipStreamCreateWithFlags(&st.side[i], hipStreamNonBlocking));
+                DAD_HIP_TRY(hipEventCreateWithFlags(&st.join[i], hipEventDisableTiming));
+            }
             st.ready.store(1, std::memory_order_release);
         }
     }
@@ -138,6 +150,13 @@ dad_status device_ready(void** scratch_out) {
 
 // Copies the flag word of a workspace header to a caller-owned word.
 __global__ void k_copy_flag(const int* __restrict__ hdr, int* __restrict__ out) { *out = *hdr; }
+
+// Grouped compress: the group's sticky flag is cleared at the start of the call and set after every
+// layer whose own flag was latched (several lanes may store the same 1).
+__global__ void k_clear_flag(int* __restrict__ flag) { *flag = 0; }
+__global__ void k_latch_flag(const int* __restrict__ hdr, int* __restrict__ group_flag) {
+    if (*hdr) *group_flag = 1;
+}
 
 }  // namespace dad
 
@@ -283,6 +302,79 @@ dad_status dad_compress_rank_noalloc(const void* A, const void* D, int64_t N, in
     hipLaunchKernelGGL(k_copy_flag, dim3(1), dim3(1), 0, s, (const int*)ws, numeric_flag);
     DAD_LAUNCH_CHECK();
     return DAD_OK;
+}
+
+// Layout of the grouped workspace: 256-byte group header (sticky numeric flag at +0), then one region
+// per lane, each large enough for any layer of the group.
+static size_t grouped_lane_bytes(int n, const dad_compress_desc* descs, dad_dtype dt, int r) {
+    size_t lane = 0;
+    for (int i = 0; i < n; ++i) {
+        const size_t b = plan_compress(descs[i].N, descs[i].h_in, descs[i].h_out, r, dt).total;
+        if (b > lane) lane = b;
+    }
+    return align_up(lane, 256);
+}
+
+size_t dad_compress_grouped_workspace_bytes(int n, const dad_compress_desc* descs, dad_dtype dt, int r, int lanes) {
+    if (n < 1 || n > DAD_MAX_GROUP || !descs || !dtype_ok(dt) || lanes < 1 || lanes > DAD_MAX_LANES) return 0;
+    for (int i = 0; i < n; ++i)
+        if (!compress_shape_ok(descs[i].N, descs[i].h_in, descs[i].h_out, r)) return 0;
+    const int used = lanes < n ? lanes : n;
+    return 256 + (size_t)used * grouped_lane_bytes(n, descs, dt, r);
+}
+
+dad_status dad_compress_rank_grouped(int n, const dad_compress_desc* descs, dad_dtype dt, int r, int n_iter, int lanes,
+                                     void* workspace, size_t ws_bytes, void* stream) {
+    if (!descs || !workspace) return DAD_ERR_NULL;
+    if (!dtype_ok(dt)) return DAD_ERR_DTYPE;
+    if (n < 1 || n > DAD_MAX_GROUP || lanes < 1 || lanes > DAD_MAX_LANES) return DAD_ERR_SHAPE;
+    for (int i = 0; i < n; ++i) {
+        const dad_compress_desc& d = descs[i];
+        const dad_status rc = compress_args_ok(d.A, d.D, d.N, d.h_in, d.h_out, dt, r, n_iter, d.G0, d.Pt, d.Gt);
+        if (rc != DAD_OK) return rc;
+    }
+    if (!aligned16(workspace)) return DAD_ERR_ALIGN;
+    const int used = lanes < n ? lanes : n;
+    const size_t lane_bytes = grouped_lane_bytes(n, descs, dt, r);
+    if (ws_bytes < 256 + (size_t)used * lane_bytes) return DAD_ERR_WORKSPACE;
+    dad_status rc = device_ready();
+    if (rc != DAD_OK) return rc;
+    int dev = 0;
+    DAD_HIP_TRY(hipGetDevice(&dev));
+    DeviceState& st = g_dev[dev];
+    hipStream_t main = (hipStream_t)stream;
+    char* ws = static_cast<char*>(workspace);
+    int* group_flag = reinterpret_cast<int*>(ws);
+
+    std::lock_guard<std::mutex> lk(st.lanes_mu);
+    hipLaunchKernelGGL(k_clear_flag, dim3(1), dim3(1), 0, main, group_flag);
+    DAD_LAUNCH_CHECK();
+    // fork: the side streams start after everything already enqueued on the caller's stream
+    if (used > 1) {
+        DAD_HIP_TRY(hipEventRecord(st.fork, main));
+        for (int l = 1; l < used; ++l) DAD_HIP_TRY(hipStreamWaitEvent(st.side[l - 1], st.fork, 0));
+    }
+    for (int i = 0; i < n; ++i) {  // layer i on lane i mod `used`; a lane's layers follow each other on its stream
+        const int l = i % used;
+        hipStream_t s = l == 0 ? main : st.side[l - 1];
+        void* lane_ws = ws + 256 + (size_t)l * lane_bytes;
+        const dad_compress_desc& d = descs[i];
+        const CompressPlan p = plan_compress(d.N, d.h_in, d.h_out, r, dt);
+        rc = compress_launch(p, d.A, d.D, d.N, d.h_in, d.h_out, dt, r, n_iter, d.G0, d.Pt, d.Gt, lane_ws, s);
+        if (rc != DAD_OK) break;
+        hipLaunchKernelGGL(k_latch_flag, dim3(1), dim3(1), 0, s, (const int*)lane_ws, group_flag);
+        if (hipGetLastError() != hipSuccess) {
+            rc = DAD_ERR_HIP;
+            break;
+        }
+    }
+    // join, also after a failed enqueue: the caller's stream must not run ahead of the side streams
+    for (int l = 1; l < used; ++l) {
+        if (hipEventRecord(st.join[l - 1], st.side[l - 1]) != hipSuccess ||
+            hipStreamWaitEvent(main, st.join[l - 1], 0) != hipSuccess)
+            rc = rc == DAD_OK ? DAD_ERR_HIP : rc;
+    }
+    return rc;
 }
 
 dad_status dad_init(void) { return device_ready(); }

@@ -137,6 +137,38 @@ def test_grouped_rebuild_rejects_bad_arguments_on_host(lib):
     assert lib.dad_reconstruct_grouped_workspace_bytes(2, good, dad.DAD_F32) == 0
 
 
+def test_grouped_compress_rejects_bad_arguments_on_host(lib):
+    p = 0x1000
+    D = dad.CompressDesc
+    good = (D * 2)(D(p, p, p, p, p, 64, 784, 128), D(p, p, p, p, p, 256, 128, 96))
+    ws = 1 << 30
+
+    def call(n=2, descs=good, dt=dad.DAD_F32, r=4, it=2, lanes=2, w=p, wb=ws):
+        return lib.dad_compress_rank_grouped(n, descs, dt, r, it, lanes, w, wb, None)
+
+    assert call(descs=None) == dad.DAD_ERR_NULL
+    assert call(w=None) == dad.DAD_ERR_NULL
+    assert call(dt=4) == dad.DAD_ERR_DTYPE
+    assert call(n=0) == dad.DAD_ERR_SHAPE
+    assert call(lanes=0) == dad.DAD_ERR_SHAPE
+    assert call(lanes=9) == dad.DAD_ERR_SHAPE
+    assert call(r=65) == dad.DAD_ERR_SHAPE
+    assert call(it=0) == dad.DAD_ERR_SHAPE
+    bad = (D * 2)(D(p, p, p, p, p, 64, 784, 128), D(p, p, p, None, p, 256, 128, 96))
+    assert call(descs=bad) == dad.DAD_ERR_NULL
+    bad = (D * 2)(D(p, p, p, p, p, 64, 784, 128), D(p, p, p, p, p, 3, 128, 96))      # r > N
+    assert call(descs=bad) == dad.DAD_ERR_SHAPE
+    bad = (D * 2)(D(p, p + 8, p, p, p, 64, 784, 128), D(p, p, p, p, p, 256, 128, 96))
+    assert call(descs=bad) == dad.DAD_ERR_ALIGN
+    need = lib.dad_compress_grouped_workspace_bytes(2, good, dad.DAD_F32, 4, 2)
+    one = max(lib.dad_compress_workspace_bytes(64, 784, 128, 4, dad.DAD_F32),
+              lib.dad_compress_workspace_bytes(256, 128, 96, 4, dad.DAD_F32))
+    assert need >= 256 + 2 * one
+    assert lib.dad_compress_grouped_workspace_bytes(2, good, dad.DAD_F32, 4, 1) < need
+    assert call(wb=need - 1) == dad.DAD_ERR_WORKSPACE
+    assert lib.dad_compress_grouped_workspace_bytes(2, good, dad.DAD_F32, 4, 9) == 0
+
+
 def test_backprop_rejects_bad_arguments_on_host(lib):
     p = 0x1000  # never dereferenced: every call below must fail before a launch
 

@@ -68,3 +68,68 @@ def test_fp32_rebuild_on_the_matrix_instruction_matches_oracle(gpu, K, h_in, h_o
     G = dad.reconstruct_grad(L, R)
     _check_against_oracle(G, L, R, 1e-5)
     assert torch.equal(G, dad.reconstruct_grad(L, R))      # fixed summation order
+
+
+# ---------------------------------------------------------------- grouped compress
+
+def _layer(N, h_in, h_out, r, seed, dev, dtype):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    A = torch.relu(torch.randn(N, h_in, generator=g)).to(dtype).to(dev)
+    D = (0.03 * torch.randn(N, h_out, generator=g)).to(dtype).to(dev)
+    G0 = torch.randn(r, h_out, generator=g).to(dev)
+    return A, D, G0
+
+
+BF16_LAYERS = [(1024, 768, 2304), (1024, 768, 768), (512, 256, 512), (1000, 384, 128), (2048, 1024, 256)]
+F32_LAYERS = [(64, 784, 128), (300, 96, 80), (1024, 1024, 10), (37, 53, 29)]
+
+
+@pytest.mark.parametrize("lanes", [1, 2, 3, 8])
+@pytest.mark.parametrize("kind", ["bf16", "f32"])
+def test_grouped_compress_equals_single_calls(gpu, kind, lanes):
+    dtype, shapes, r, tol = (torch.bfloat16, BF16_LAYERS, 16, 2e-2) if kind == "bf16" else (torch.float32, F32_LAYERS, 4, 1e-5)
+    layers = [_layer(N, hi, ho, r, 40 + i, gpu, dtype) for i, (N, hi, ho) in enumerate(shapes)]
+    single = [dad.compress_rank(A, D, r, 2, G0, check=True) for A, D, G0 in layers]
+    grp = dad.CompressGroup(layers, r, 2, lanes=lanes)
+    Pts, Gts = grp.run(check=True)
+    torch.cuda.synchronize()
+    for (A, D, G0), (p1, g1), p2, g2 in zip(layers, single, Pts, Gts):
+        assert torch.equal(p1, p2) and torch.equal(g1, g2)
+    A, D, G0 = layers[0]
+    ref = O.rank_r_grad(*O.block_spi(A.float().cpu().numpy(), D.float().cpu().numpy(), G0.cpu().numpy(), 2))
+    assert O.rel_fro(dad.reconstruct_grad(Pts[0], Gts[0]).cpu().numpy(), ref) <= tol
+
+
+def test_grouped_compress_reports_a_breakdown_of_any_layer(gpu):
+    layers = [_layer(N, hi, ho, 4, 60 + i, gpu, torch.float32) for i, (N, hi, ho) in enumerate(F32_LAYERS)]
+    broken = list(layers)
+    A, D, G0 = broken[1]
+    broken[1] = (A, torch.zeros_like(D), G0)          # Delta = 0: the first Cholesky pivot of that layer is zero
+    grp = dad.CompressGroup(broken, 4, 2, lanes=2)
+    grp.run()
+    assert dad.poll_numeric_status(grp.workspace) == dad.DAD_ERR_NUMERIC
+    healthy = dad.CompressGroup(layers, 4, 2, lanes=2, workspace=grp.workspace)
+    healthy.run()
+    assert dad.poll_numeric_status(grp.workspace) == dad.DAD_OK
+
+
+def test_grouped_compress_replays_from_a_hip_graph(gpu):
+    dad.init()
+    layers = [_layer(N, hi, ho, 16, 80 + i, gpu, torch.bfloat16) for i, (N, hi, ho) in enumerate(BF16_LAYERS[:4])]
+    grp = dad.CompressGroup(layers, 16, 2, lanes=3)
+    eager = [(p.clone(), g.clone()) for p, g in zip(*grp.run(check=True))]
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        grp.run()
+    for rep in range(3):
+        for p, g in zip(grp.Pt, grp.Gt):
+            p.fill_(float("nan"))
+            g.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for (p1, g1), p2, g2 in zip(eager, grp.Pt, grp.Gt):
+            assert torch.equal(p1, p2) and torch.equal(g1, g2), rep
+        _ = dad.reconstruct_grad(grp.Pt[0], grp.Gt[0])    # eager work between the replays
+        torch.cuda.synchronize()
