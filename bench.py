@@ -39,12 +39,15 @@ def parse():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="gpt2_medium_stack")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--lanes", type=int, default=3,
+    ap.add_argument("--lanes", type=int, default=4,
                     help="default mode: layers of one block whose compress calls are in flight at once "
                          "(dad_compress_rank_grouped); 0 = one dad_compress_rank call per layer")
     ap.add_argument("--group-layers", type=int, default=0,
                     help="default mode: layers per grouped compress call when every layer has its own stacked "
                          "buffer (0 = the whole stack)")
+    ap.add_argument("--graphs", default="off", choices=["auto", "on", "off"],
+                    help="default mode: replay one captured HIP graph per operation of a step (auto: workloads of "
+                         "at most 8 layers, which are bound by launch latency)")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="default mode: skip the encoder_d768 and vit_large_stack passes that follow the headline workload")
     ap.add_argument("--mode", default="one_level", choices=["one_level", "two_level", "backprop", "sequential"],
@@ -607,66 +610,74 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
 
     PH = ("stack", "compress", "rebuild_full", "rebuild_rank")
 
-    # Timing events are created, and one pair is exercised, before the timed region: the first use of
-    # a timing event costs milliseconds of one-off set-up in the runtime.
-    pool = [torch.cuda.Event(enable_timing=True) for _ in range((5 * len(layers) + 2 * len(scopes) + 2) * steps)]
-    pool_next = [0]
-    if pool:
-        pool[0].record(); pool[1].record(); torch.cuda.synchronize(); pool[0].elapsed_time(pool[1])
-
-    def take(n):
-        ev = pool[pool_next[0]:pool_next[0] + n]
-        pool_next[0] += n
-        return ev
-
-    # Per scope (the whole stack, or one block of distinct shapes): stack every layer, reduce all of
-    # them with one grouped call (args.lanes layers in flight at once), rebuild every full gradient.
-    groups_all = None
+    # Per scope (the whole stack, or one block of distinct shapes): stack and full rebuild alternate
+    # layer by layer (the MFMA-bound rebuild launches then do not run back to back: 96 of them in a
+    # row clock 5 % lower), then the scope's layers are reduced by one grouped call (args.lanes layers
+    # in flight at once); the rank-r gradients of all layers close the step with one grouped call.
+    # A step is a list of (phase, call) operations; `ungrouped` is the same work with one
+    # dad_compress_rank call per layer.
+    groups = []
     if args.lanes > 0:
-        groups_all = groups = []
         for sc in scopes:
             groups.append(dad.CompressGroup([(A_st[st_key(*t)], D_st[st_key(*t)], G0[t[0]]) for t in sc], r, n_iter,
                                             lanes=min(args.lanes, dad.DAD_MAX_LANES),
                                             Pts=[Pt[t[0]] for t in sc], Gts=[Gt[t[0]] for t in sc],
                                             workspace=groups[0].workspace if groups else None))
 
-    def step(events=None, grouped=True):
-        groups = groups_all if grouped else None
+    def make_ops(grouped):
+        ops = []
         for si, sc in enumerate(scopes):
-            # stack and full rebuild alternate layer by layer (the MFMA-bound rebuild launches then do
-            # not run back to back: 96 of them in a row clock 5 % lower), then the scope's layers are
-            # reduced by one grouped call
             for li, hi, ho in sc:
                 k = st_key(li, hi, ho)
                 As, Ds = factors_of(li)
-                ev = take(3) if events is not None else None
-                if ev: ev[0].record()
-                dad.stack_factors(As, Ds, A_out=A_st[k], D_out=D_st[k])
-                if ev: ev[1].record()
-                if groups is None:
-                    dad.compress_rank(A_st[k], D_st[k], r, n_iter, G0[li], Pt=Pt[li], Gt=Gt[li], workspace=ws_c)
-                    if ev: ev[2].record()
-                    if ev: events.append(("stack_compress", ev))
-                    ev = take(2) if events is not None else None
-                    if ev: ev[0].record()
-                    dad.reconstruct_grad(A_st[k], D_st[k], G=G_full[(hi, ho)], workspace=ws_r)
-                    if ev: ev[1].record()
-                    if ev: events.append(("rebuild_full", ev))
-                else:
-                    dad.reconstruct_grad(A_st[k], D_st[k], G=G_full[(hi, ho)], workspace=ws_r)
-                    if ev: ev[2].record()
-                    if ev: events.append(("stack_rebuild", ev))
-            if groups is not None:
-                ev = take(2) if events is not None else None
-                if ev: ev[0].record()
-                groups[si].run()
-                if ev: ev[1].record()
-                if ev: events.append(("compress", ev))
-        ev = take(2) if events is not None else None
-        if ev: ev[0].record()
-        rank_group.run()          # every layer's rank-r gradient P^T G in one grouped call
-        if ev: ev[1].record()
-        if ev: events.append(("rebuild_rank", ev))
+                ops.append(("stack", lambda As=As, Ds=Ds, k=k: dad.stack_factors(As, Ds, A_out=A_st[k], D_out=D_st[k])))
+                if not grouped:
+                    ops.append(("compress", lambda k=k, li=li: dad.compress_rank(A_st[k], D_st[k], r, n_iter, G0[li], Pt=Pt[li],
+                                                                                 Gt=Gt[li], workspace=ws_c)))
+                ops.append(("rebuild_full", lambda k=k, s_=(hi, ho): dad.reconstruct_grad(A_st[k], D_st[k], G=G_full[s_],
+                                                                                          workspace=ws_r)))
+            if grouped:
+                ops.append(("compress", groups[si].run))
+        ops.append(("rebuild_rank", rank_group.run))
+        return ops
+
+    ops = make_ops(grouped=bool(groups))
+    ops_ungrouped = ops if not groups else make_ops(grouped=False)
+
+    # Small workloads are bound by launch latency (a step of encoder_d768 is about 130 launches in a
+    # millisecond): there every operation is captured into a HIP graph of its own, and a step replays
+    # the graphs in order with the phase events between them.
+    use_graphs = args.graphs == "on" or (args.graphs == "auto" and len(layers) <= 8)
+
+    # Timing events are created, and one pair is exercised, before the timed region: the first use of
+    # a timing event costs milliseconds of one-off set-up in the runtime.
+    pool = [torch.cuda.Event(enable_timing=True) for _ in range((len(ops) + 1) * steps)]
+    pool_next = [0]
+    if pool:
+        pool[0].record(); pool[1].record(); torch.cuda.synchronize(); pool[0].elapsed_time(pool[1])
+
+    def step(events=None, which=None, graphs=None):
+        """One step.  With `events`, an event is recorded before every operation and after the last,
+        and (phase, start, end) triples are appended."""
+        which = ops if which is None else which
+        marks = []
+        for i, (phase, fn) in enumerate(which):
+            if events is not None:
+                e = pool[pool_next[0]]
+                pool_next[0] += 1
+                e.record()
+                marks.append(e)
+            if graphs is not None:
+                graphs[i].replay()
+            else:
+                fn()
+        if events is not None:
+            e = pool[pool_next[0]]
+            pool_next[0] += 1
+            e.record()
+            marks.append(e)
+            for i, (phase, _) in enumerate(which):
+                events.append((phase, marks[i], marks[i + 1]))
 
     # Untimed pre-pass: every layer's compress once, with the numeric status polled per layer (the
     # flag lives in the shared workspace and is cleared by the next call, so one poll after a whole
@@ -679,16 +690,26 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
         if dad.poll_numeric_status(ws_c) != dad.DAD_OK:
             print(f"bench.py: numerical breakdown latched on layer {li} ({hi}x{ho}) of {w.name}", file=sys.stderr)
             sys.exit(1)
-    for _ in range(warmup):
+    for _ in range(max(warmup, 1) if use_graphs else warmup):
         step()
     torch.cuda.synchronize()
+    op_graphs = None
+    if use_graphs:
+        op_graphs = []
+        for _, fn in ops:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                fn()
+            op_graphs.append(g)
+        step(graphs=op_graphs)
+        torch.cuda.synchronize()
 
     # timed region: K steps, phase boundaries marked by events on the launch stream
     events = []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        step(events)
+        step(events, graphs=op_graphs)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     # the same K steps once more with the library's per-kernel events switched on (two events per
@@ -698,22 +719,15 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
     dad.profile_reset()
     dad.profile_enable(True)
     for _ in range(steps):
-        step(grouped=False)
+        step(which=ops_ungrouped)
     torch.cuda.synchronize()
     dad.profile_enable(False)
     kern = dad.profile_read()
     ms_per_step = (t1 - t0) * 1e3 / steps
 
     phase_ms = dict.fromkeys(PH, 0.0)
-    for kind, ev in events:
-        if kind == "stack_compress":
-            phase_ms["stack"] += ev[0].elapsed_time(ev[1])
-            phase_ms["compress"] += ev[1].elapsed_time(ev[2])
-        elif kind == "stack_rebuild":
-            phase_ms["stack"] += ev[0].elapsed_time(ev[1])
-            phase_ms["rebuild_full"] += ev[1].elapsed_time(ev[2])
-        else:
-            phase_ms[kind] += ev[0].elapsed_time(ev[1])
+    for phase, e0, e1 in events:
+        phase_ms[phase] += e0.elapsed_time(e1)
     phase_ms = {k: v / steps for k, v in phase_ms.items()}
     nl = len(layers)
     flops_full = sum(2.0 * N * hi * ho for _, hi, ho in layers)
@@ -895,7 +909,7 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
         "config": {"workload": w.name, "layers": nl, "shapes": [list(s) for s in w.shapes], "sites": S,
                    "rows_per_site": b, "N": N, "rank": r, "n_iter": n_iter,
                    "resident_layers": len(resident), "compress_lanes": args.lanes,
-                   "compress_group_layers": gl},
+                   "compress_group_layers": gl, "hip_graphs": use_graphs},
         "rebuild_frac_of_mfma_peak": rebuild_tflops / (PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS),
         "compress_us_per_layer": phase_ms["compress"] * 1e3 / nl,
         "compress_GBps": bytes_compress / (phase_ms["compress"] * 1e-3) / 1e9,
