@@ -21,11 +21,17 @@ Pins (see tests/test_oracle_*.py):
   full_grad            brute-force triple loop, N=1 outer product, linearity
   block_spi*           three unrelated routes agree; exact truncated SVD when
                        r >= rank(M); Eckart-Young bound and Pythagoras otherwise
-  sequential_spi       converges to numpy's truncated SVD on a planted spectrum
+  sequential_spi       converges to numpy's truncated SVD on a planted spectrum; the printed
+                       association (sequential_spi_precomputed) gives the same pairs; with theta:
+                       rank = k on planted rank-k gradients, = r on a flat full-rank spectrum, the
+                       product within the convergence tolerance of the truncated SVD, fewer
+                       applications for a larger theta.  What the two stop tests compare is a
+                       reading of an ambiguous listing: beyond those pins, PARITY UNPINNED for the
+                       iteration counts and the rank on spectra without a clear gap
   rank_dad             stacked pairs represent the sum of the sites' estimates (brute
                        force); exact global gradient when its rank fits both budgets;
                        converged aggregator step = truncated SVD of that sum
-No function here is "parity unpinned".
+No other function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -209,17 +215,96 @@ def block_spi_precomputed(A, Delta, G0t, n_iter):
     return P.T.copy(), G.T.copy()
 
 
-def sequential_spi(A, Delta, g0t, n_iter):
-    """Algorithm 2 one vector at a time, with peeling (Eq. 7).
+def sequential_spi(A, Delta, g0t, n_iter, theta=None):
+    """Algorithm 2 one singular pair at a time, with peeling (Eq. 5 and 7), written from the definition:
+    power iteration on T = M^T M, M = A^T Delta, deflated by the pairs already found.
 
-    Readings taken where the listing cannot be executed as printed: exactly r
-    components and n_iter applications each; the iterate is renormalised after
-    every application; the peeled term is sum_{i<j} sigma_i^2 g_i (g_i^T g), the
-    deflation of M^T M by the pairs already found (the printed Q (G^T g) mixes
-    vectors of length h_in and h_out).  sigma_j = sqrt(v^T C v), v = Delta g_j,
-    q_j = A^T v / sigma_j.  Returns (Q r x h_in with unit rows, sG r x h_out with
-    rows sigma_j g_j), so that Q^T sG approximates M.
+    Readings taken where the listing cannot be executed as printed: exactly r components; the
+    iterate is renormalised after every application; the peeled operator is the deflation of T by
+    the pairs found so far (the printed Q (G^T g) mixes vectors of length h_in and h_out);
+    sigma_j = ||M g_j||, q_j = M g_j / sigma_j.
+
+    theta is None: exactly n_iter applications per component, deflation by subtraction as in
+    Eq. 7, T_j = T - sum_{i<j} sigma_i^2 g_i g_i^T.  Returns (Q, sG): Q r x h_in with unit rows,
+    sG r x h_out with rows sigma_j g_j, so that Q^T sG approximates M.
+
+    theta given (the stop tests of Algorithm 2 and of the last paragraph of Section 3.3.1, under the
+    reading stated below): returns (Q, sG, rank, iters).
+      * inner loop: at most n_iter applications; it stops once two successive unit iterates differ
+        by at most theta (sign aligned);
+      * outer loop: component j > 0 is dropped, and the iteration over components ends, when
+        sigma_j < theta * sigma_0, or as soon as an application leaves nothing to normalise,
+        ||P T g|| < (theta * sigma_0)^2 (the same threshold on the scale of sigma^2: for a gradient of
+        exact rank j the projected iterate is pure rounding noise); `rank` is the number of
+        components kept, the rows of Q and sG beyond it are zero, iters[j] counts the applications
+        spent on component j;
+      * the peeled operator is taken in its projector form P T P, P = I - sum_{i<j} g_i g_i^T, i.e.
+        the start vector and every iterate are kept orthogonal to the vectors already found.  For
+        exact singular pairs this is the same operator as the subtraction of Eq. 7.  For pairs that
+        are only converged to theta it is not: the subtraction leaves a residual of FIRST order in
+        their error, whose dominant eigenvector has ||M g|| of the order of sigma_0, so that no
+        threshold on sigma_j / sigma_0 can tell an exhausted gradient from a live component; with
+        the projector ||M g|| is of the order theta * sigma_0 once the rank is exhausted.
     """
+    M = full_grad(A, Delta)
+    T = M.T @ M
+    g0t = np.asarray(g0t, F64)
+    r = g0t.shape[0]
+    Q = np.zeros((r, M.shape[0]))
+    sG = np.zeros((r, M.shape[1]))
+    gs, sig, iters = [], [], []
+    rank = 0
+    exhausted = False
+    for j in range(r):
+        g = g0t[j].copy()
+        if theta is not None:
+            for gi in gs:
+                g = g - gi * (gi @ g)
+        g = g / np.linalg.norm(g)
+        used = 0
+        for _ in range(n_iter):
+            y = T @ g
+            if theta is None:
+                for gi, si in zip(gs, sig):
+                    y = y - (si ** 2) * gi * (gi @ g)
+            else:
+                for gi in gs:
+                    y = y - gi * (gi @ y)
+                if j > 0 and np.linalg.norm(y) < (theta * sig[0]) ** 2:
+                    exhausted = True
+                    used += 1
+                    break
+            g_new = y / np.linalg.norm(y)
+            used += 1
+            if theta is not None:
+                step = np.linalg.norm(g_new * (1.0 if g_new @ g >= 0.0 else -1.0) - g)
+                g = g_new
+                if step <= theta:
+                    break
+            else:
+                g = g_new
+        iters.append(used)
+        if exhausted:
+            break
+        p = M @ g
+        sigma = np.linalg.norm(p)
+        if theta is not None and j > 0 and sigma < theta * sig[0]:
+            break
+        Q[j] = p / sigma
+        sG[j] = sigma * g
+        gs.append(g)
+        sig.append(sigma)
+        rank = j + 1
+    if theta is None:
+        return Q, sG
+    return Q, sG, rank, iters
+
+
+def sequential_spi_precomputed(A, Delta, g0t, n_iter):
+    """The fixed-count recurrence of sequential_spi with the association order Algorithm 2 prints:
+    C = A A^T and B = Delta^T C formed once, g <- B (Delta g) - peel, v = Delta g,
+    sigma = sqrt(v^T C v), q = A^T v / sigma.  A cross-check of sequential_spi(theta=None); only
+    sensible for small N."""
     A = np.asarray(A, F64)
     D = np.asarray(Delta, F64)
     C = A @ A.T

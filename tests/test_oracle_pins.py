@@ -217,6 +217,99 @@ def test_converged_iteration_is_truncated_svd_and_sequential_route_agrees():
     assert np.allclose(np.linalg.norm(sG, axis=1), s[:r], rtol=1e-8)
 
 
+def test_sequential_route_with_the_printed_association_gives_the_same_pairs():
+    """C = A A^T, B = Delta^T C as Algorithm 2 prints them against the iteration on M^T M."""
+    rng = np.random.default_rng(31)
+    A = rng.standard_normal((9, 20))
+    D = rng.standard_normal((9, 14)) * (0.7 ** np.arange(9))[:, None]
+    G0 = rng.standard_normal((3, 14))
+    Q1, sG1 = O.sequential_spi(A, D, G0, 5)
+    Q2, sG2 = O.sequential_spi_precomputed(A, D, G0, 5)
+    assert np.allclose(Q1, Q2, rtol=1e-9, atol=1e-12) and np.allclose(sG1, sG2, rtol=1e-9, atol=1e-12)
+
+
+def _planted(rng, N, h_in, h_out, sigmas):
+    """Factors whose gradient A^T Delta has exactly the given non-zero singular values."""
+    k = len(sigmas)
+    U, _ = np.linalg.qr(rng.standard_normal((h_in, k)))
+    V, _ = np.linalg.qr(rng.standard_normal((h_out, k)))
+    W, _ = np.linalg.qr(rng.standard_normal((N, k)))
+    return W @ (U * np.sqrt(sigmas)).T, W @ (V * np.sqrt(sigmas)).T     # A = W S^1/2 U^T, Delta = W S^1/2 V^T
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 5])
+def test_early_stop_finds_the_rank_of_a_planted_gradient(k):
+    """Effective rank (Section 3.3.1, last paragraph; Algorithm 2's stop test): a gradient of exact
+    rank k < r with a clear spectral gap yields k components, zero rows beyond, and the product
+    equals the gradient to the convergence tolerance."""
+    rng = np.random.default_rng(40 + k)
+    theta, r = 1e-3, 6
+    A, D = _planted(rng, 24, 30, 26, 2.0 * 0.5 ** np.arange(k))
+    M = O.full_grad(A, D)
+    G0 = rng.standard_normal((r, 26))
+    Q, sG, rank, iters = O.sequential_spi(A, D, G0, 200, theta=theta)
+    assert rank == k
+    assert np.all(Q[k:] == 0.0) and np.all(sG[k:] == 0.0)
+    assert O.rel_fro(O.rank_r_grad(Q, sG), M) < 5 * theta
+    s = np.linalg.svd(M, compute_uv=False)
+    assert np.allclose(np.linalg.norm(sG[:k], axis=1), s[:k], rtol=5 * theta)
+    assert all(it < 200 for it in iters[:k])            # every live component stopped on the step test
+
+
+def test_early_stop_keeps_every_component_of_a_flat_full_rank_spectrum():
+    rng = np.random.default_rng(47)
+    A = rng.standard_normal((64, 20))
+    D = rng.standard_normal((64, 18))
+    G0 = rng.standard_normal((5, 18))
+    Q, sG, rank, iters = O.sequential_spi(A, D, G0, 30, theta=1e-3)
+    assert rank == 5 and len(iters) == 5
+    assert np.allclose(np.linalg.norm(Q, axis=1), 1.0, atol=1e-12)
+    # the rows of sG are orthogonal (projector deflation), their norms are the singular-value estimates
+    g = sG / np.linalg.norm(sG, axis=1, keepdims=True)
+    assert np.allclose(g @ g.T, np.eye(5), atol=1e-10)
+
+
+def test_early_stop_converges_to_the_truncated_svd_and_spends_less_for_a_larger_theta():
+    rng = np.random.default_rng(48)
+    A = rng.standard_normal((12, 40))
+    D = rng.standard_normal((12, 30)) * (0.5 ** np.arange(12))[:, None]
+    M = O.full_grad(A, D)
+    G0 = rng.standard_normal((4, 30))
+    Q, sG, rank, it_fine = O.sequential_spi(A, D, G0, 500, theta=1e-12)
+    assert rank == 4 and O.rel_fro(O.rank_r_grad(Q, sG), O.truncated_svd(M, 4)) < 1e-8
+    _, _, _, it_coarse = O.sequential_spi(A, D, G0, 500, theta=1e-3)
+    _, _, _, it_coarser = O.sequential_spi(A, D, G0, 500, theta=1e-1)
+    assert sum(it_coarser) < sum(it_coarse) < sum(it_fine)
+    # with a cap below what theta asks for, the cap decides
+    _, _, _, it_cap = O.sequential_spi(A, D, G0, 3, theta=1e-12)
+    assert it_cap == [3, 3, 3, 3]
+
+
+def test_subtraction_deflation_cannot_detect_an_exhausted_rank():
+    """The finding behind the projector reading: with the subtraction of Eq. 7 and pairs converged
+    only to theta, the next 'component' of an exactly rank-2 gradient has ||M g|| of the order of
+    sigma_0, not of theta * sigma_0."""
+    rng = np.random.default_rng(49)
+    A, D = _planted(rng, 16, 22, 20, np.array([2.0, 1.0]))
+    M = O.full_grad(A, D)
+    T = M.T @ M
+    Q, sG, rank, _ = O.sequential_spi(A, D, rng.standard_normal((2, 20)), 200, theta=1e-3)
+    assert rank == 2
+    sig = np.linalg.norm(sG, axis=1)
+    gs = sG / sig[:, None]
+    Tdef = T - sum(s ** 2 * np.outer(g, g) for s, g in zip(sig, gs))      # Eq. 7 by subtraction
+    g = rng.standard_normal(20)
+    for _ in range(500):
+        g = Tdef @ g
+        g /= np.linalg.norm(g)
+    assert np.linalg.norm(M @ g) > 0.05 * sig[0]          # far above theta * sigma_0 = 2e-3
+    P = np.eye(20) - gs.T @ gs                            # projector form: nothing is left to iterate on
+    g = P @ rng.standard_normal(20)
+    g /= np.linalg.norm(g)
+    assert np.linalg.norm(P @ (T @ g)) < (1e-3 * sig[0]) ** 2
+    assert np.linalg.norm(M @ g) < 1e-3 * sig[0]
+
+
 def test_result_does_not_depend_on_basis_of_start_span():
     """Only span(G0) matters: mixing the start rows by an invertible matrix leaves P G^T unchanged."""
     rng = np.random.default_rng(24)
