@@ -227,8 +227,8 @@ size_t dad_compress_sequential_workspace_bytes(int64_t N, int64_t h_in, int64_t 
  * pair at a time, with peeling.  Component j starts from g = G0[j] / ||G0[j]|| and applies
  *     g <- normalise( M^T M g - sum_{i<j} sigma_i^2 g_i (g_i^T g) )
  * exactly n_iter times (the deflation of M^T M by the pairs already found stands in for the printed
- * Q (G^T g), whose vectors have two different lengths; the threshold theta of the listing is not
- * implemented).  Then v = Delta g, sigma_j = ||A^T v||, q_j = A^T v / sigma_j.
+ * Q (G^T g), whose vectors have two different lengths; for the threshold theta of the listing see
+ * dad_compress_rank_adaptive).  Then v = Delta g, sigma_j = ||A^T v||, q_j = A^T v / sigma_j.
  *
  *   A, D, N, h_in, h_out, dt, r, n_iter, G0   as for dad_compress_rank
  *   Qt        device out, r x h_in fp32: row j = q_j, unit length
@@ -243,6 +243,35 @@ size_t dad_compress_sequential_workspace_bytes(int64_t N, int64_t h_in, int64_t 
 dad_status dad_compress_rank_sequential(const void* A, const void* D, int64_t N, int64_t h_in, int64_t h_out,
                                         dad_dtype dt, int r, int n_iter, const float* G0, float* Qt, float* sGt,
                                         float* sigma, void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * dad_compress_rank_adaptive - dad_compress_rank_sequential with the stop tests of Algorithm 2 and the
+ * effective rank of Section 3.3.1 (last paragraph), under this reading of the ambiguous listing:
+ *   - component j applies M^T M at most max_iter times and stops once two successive unit iterates
+ *     differ by at most theta (sign aligned);
+ *   - component j > 0 is dropped, and no further component is computed, when sigma_j < theta sigma_0
+ *     or when an application leaves nothing to normalise (||y|| < (theta sigma_0)^2 after the found
+ *     vectors are projected out);
+ *   - the peel of Eq. 7 is applied as a projection (the start vector and every iterate are kept
+ *     orthogonal to the vectors already found).  For exact singular pairs that is the printed
+ *     subtraction; for pairs converged only to theta the subtraction leaves a first-order residual
+ *     whose "component" has ||M g|| of the order of sigma_0, and no threshold on sigma_j / sigma_0
+ *     could detect an exhausted gradient.
+ * Everything is decided on the device: the launch sequence is that of r components x max_iter
+ * applications, and the launches of skipped work return at once on a flag in the workspace, so the
+ * call can be recorded into a HIP graph.
+ *   A .. G0, Qt, sGt, sigma, workspace   as for dad_compress_rank_sequential (same workspace size);
+ *             rows of Qt, sGt and entries of sigma beyond the effective rank are zero
+ *   max_iter  >= 1;  theta  0 <= theta < 1 (the paper uses 1e-3)
+ *   effective_rank  device out, one int: number of components kept (1 .. r)
+ *   iterations      device out, r ints, or NULL: applications spent on each component
+ * Near the thresholds fp32 arithmetic may decide differently from exact arithmetic by one
+ * application or one component; both outcomes are valid results of the method.
+ */
+dad_status dad_compress_rank_adaptive(const void* A, const void* D, int64_t N, int64_t h_in, int64_t h_out,
+                                      dad_dtype dt, int r, int max_iter, float theta, const float* G0, float* Qt,
+                                      float* sGt, float* sigma, int* effective_rank, int* iterations,
+                                      void* workspace, size_t ws_bytes, void* stream);
 
 /* Bytes of device workspace dad_reconstruct_grad needs (may be 0 for small K; 0 on invalid sizes). */
 size_t dad_reconstruct_workspace_bytes(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);

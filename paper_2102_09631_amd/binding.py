@@ -77,6 +77,9 @@ def lib() -> C.CDLL:
     L.dad_compress_sequential_workspace_bytes.argtypes = [i64, i64, i64, C.c_int]
     L.dad_compress_rank_sequential.restype = C.c_int
     L.dad_compress_rank_sequential.argtypes = [vp, vp, i64, i64, i64, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, sz, vp]
+    L.dad_compress_rank_adaptive.restype = C.c_int
+    L.dad_compress_rank_adaptive.argtypes = [vp, vp, i64, i64, i64, C.c_int, C.c_int, C.c_int, C.c_float, vp, vp, vp, vp,
+                                             vp, vp, vp, sz, vp]
     L.dad_backprop_delta.restype = C.c_int
     L.dad_backprop_delta.argtypes = [vp, vp, vp, i64, i64, i64, C.c_int, C.c_int, vp, vp]
     L.dad_poll_numeric_status.restype = C.c_int
@@ -286,6 +289,38 @@ def compress_rank_sequential(A, D, r, n_iter, G0, Qt=None, sGt=None, sigma=None,
     if check:
         _check(lib().dad_poll_numeric_status(workspace.data_ptr(), _stream()), "dad_poll_numeric_status")
     return Qt, sGt, sigma
+
+
+def compress_rank_adaptive(A, D, r, max_iter, theta, G0, workspace=None, check=False):
+    """dad_compress_rank_adaptive: the one-vector recurrence with the theta stop tests.
+
+    Returns (Qt, sGt, sigma, effective_rank, iterations): device tensors, the last two int32.
+    """
+    _dense2d(A, "A")
+    _dense2d(D, "D")
+    _dense2d(G0, "G0")
+    N, h_in = A.shape
+    h_out = D.shape[1]
+    if D.shape[0] != N or D.dtype != A.dtype:
+        raise ValueError("A and D disagree in rows or dtype")
+    if tuple(G0.shape) != (r, h_out) or G0.dtype != torch.float32:
+        raise ValueError("G0 must be r x h_out float32")
+    dt, dev = _dt(A), A.device
+    Qt = torch.empty((r, h_in), dtype=torch.float32, device=dev)
+    sGt = torch.empty((r, h_out), dtype=torch.float32, device=dev)
+    sigma = torch.empty((r,), dtype=torch.float32, device=dev)
+    rank = torch.full((1,), -1, dtype=torch.int32, device=dev)
+    iters = torch.full((r,), -1, dtype=torch.int32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(lib().dad_compress_sequential_workspace_bytes(N, h_in, h_out, dt), dtype=torch.uint8,
+                                device=dev)
+    _check(lib().dad_compress_rank_adaptive(A.data_ptr(), D.data_ptr(), N, h_in, h_out, dt, r, max_iter, theta,
+                                            G0.data_ptr(), Qt.data_ptr(), sGt.data_ptr(), sigma.data_ptr(),
+                                            rank.data_ptr(), iters.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                            _stream()), "dad_compress_rank_adaptive")
+    if check:
+        _check(lib().dad_poll_numeric_status(workspace.data_ptr(), _stream()), "dad_poll_numeric_status")
+    return Qt, sGt, sigma, rank, iters
 
 
 def reconstruct_workspace_bytes(K, h_in, h_out, dtype) -> int:

@@ -15,10 +15,10 @@ namespace dad {
 
 // implemented in the kernel translation units
 dad_status gen_thin_nn(const void*, const float*, void*, float*, SplitPlan, int64_t, int64_t, int, dad_dtype, int*,
-                       hipStream_t);
+                       hipStream_t, const int*);
 SplitPlan gen_thin_nn_split(int64_t N, int64_t h);
 dad_status gen_thin_tn(const void*, const void*, float*, float*, SplitPlan, int64_t, int64_t, int, dad_dtype,
-                       hipStream_t);
+                       hipStream_t, const int*);
 dad_status gen_rebuild(const void*, const void*, int64_t, int64_t, int64_t, dad_dtype, float*, float*, SplitPlan,
                        hipStream_t);
 dad_status launch_stack(int, const void* const*, const void* const*, const int64_t*, int64_t, int64_t, dad_dtype,
@@ -26,9 +26,9 @@ dad_status launch_stack(int, const void* const*, const void* const*, const int64
 int gram_blocks_for(int64_t h);
 bool thin_fast_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
 SplitPlan thin_tn_split(int64_t N, int64_t h, int r);
-dad_status fast_thin_nn(const void*, const float*, void*, int64_t, int64_t, int, int*, int, hipStream_t);
+dad_status fast_thin_nn(const void*, const float*, void*, int64_t, int64_t, int, int*, int, hipStream_t, const int*);
 dad_status fast_thin_tn(const void*, const void*, float*, float*, SplitPlan, int64_t, int64_t, int, void*, int,
-                        hipStream_t);
+                        hipStream_t, const int*);
 bool thin_dma_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
 dad_status launch_panel_init(const float*, void*, void*, int64_t, int64_t, int, int*, hipStream_t);
 dad_status dma_thin_nn(const void*, const void*, void*, int64_t, int64_t, int, int, hipStream_t);
@@ -484,15 +484,17 @@ dad_status dad_poll_numeric_status(const void* workspace, void* stream) {
 namespace dad {
 
 dad_status launch_thin_nn(const void* X, const float* Pt, void* out, float* partials, SplitPlan sp, int64_t N,
-                          int64_t h, int r, dad_dtype dt, bool fast, int* zero_hdr, int planes, hipStream_t s) {
-    if (fast) return fast_thin_nn(X, Pt, out, N, h, r, zero_hdr, planes, s);
-    return gen_thin_nn(X, Pt, out, partials, sp, N, h, r, dt, zero_hdr, s);
+                          int64_t h, int r, dad_dtype dt, bool fast, int* zero_hdr, int planes, hipStream_t s,
+                          const int* skip) {
+    if (fast) return fast_thin_nn(X, Pt, out, N, h, r, zero_hdr, planes, s, skip);
+    return gen_thin_nn(X, Pt, out, partials, sp, N, h, r, dt, zero_hdr, s, skip);
 }
 
 dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp, int64_t N,
-                          int64_t h, int r, dad_dtype dt, bool fast, void* out_bf16, int planes, hipStream_t s) {
-    if (fast) return fast_thin_tn(X, V, out_t, partials, sp, N, h, r, out_bf16, planes, s);
-    return gen_thin_tn(X, V, out_t, partials, sp, N, h, r, dt, s);
+                          int64_t h, int r, dad_dtype dt, bool fast, void* out_bf16, int planes, hipStream_t s,
+                          const int* skip) {
+    if (fast) return fast_thin_tn(X, V, out_t, partials, sp, N, h, r, out_bf16, planes, s, skip);
+    return gen_thin_tn(X, V, out_t, partials, sp, N, h, r, dt, s, skip);
 }
 
 dad_status launch_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt,

@@ -179,7 +179,10 @@ RebuildPlan plan_rebuild(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
 // ---------------------------------------------------------------- launchers (host)
 
 // out[i] = sum over s of part[s*n + i] in a fixed order; out_bf16 (optional) gets a bf16 copy.
-dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s, void* out_bf16 = nullptr);
+// skip (optional, everywhere below): a device word; when it is non-zero at run time the kernels
+// return at once (the adaptive one-vector iteration stops on the device with a fixed launch sequence).
+dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s, void* out_bf16 = nullptr,
+                        const int* skip = nullptr);
 
 
 // out[n][j] = sum_k X[n][k] * Pt[j][k];  X is N x h (dt), Pt r x h fp32.  out is N x r: fp32 from the
@@ -188,14 +191,15 @@ dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hi
 // zero_hdr, when not null, is the 256-byte workspace header the launch clears on the side.
 // partials/sp: fp32 slabs and column split of the guarded kernel (ignored by the MFMA kernel).
 dad_status launch_thin_nn(const void* X, const float* Pt, void* out, float* partials, SplitPlan sp, int64_t N,
-                          int64_t h, int r, dad_dtype dt, bool fast, int* zero_hdr, int planes, hipStream_t s);
+                          int64_t h, int r, dad_dtype dt, bool fast, int* zero_hdr, int planes, hipStream_t s,
+                          const int* skip = nullptr);
 
 // out_t[j][p] = sum_n X[n][p] * V[n][j];  X N x h (dt), V N x r as launch_thin_nn wrote it with the
 // same `fast` and `planes` (the planes are summed), out_t r x h fp32.
 // out_bf16 (optional, fast path only) receives a bf16 copy of out_t.
 dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp,
                           int64_t N, int64_t h, int r, dad_dtype dt, bool fast, void* out_bf16, int planes,
-                          hipStream_t s);
+                          hipStream_t s, const int* skip = nullptr);
 
 // Orthonormalisation Yt (r x h) -> Gt (r x h), rows of Gt orthonormal; rounds = 2 is CholeskyQR2.
 // gt_bf16 (optional) receives a bf16 copy of Gt.

@@ -14,7 +14,9 @@ namespace dad {
 template <typename T, int MA>
 __global__ __launch_bounds__(256) void k_thin_nn(const T* __restrict__ X, const float* __restrict__ Pt,
                                                  float* __restrict__ out, float* __restrict__ part, int64_t N, int64_t h,
-                                                 int r, int64_t kchunk, int* __restrict__ zero_hdr) {
+                                                 int r, int64_t kchunk, int* __restrict__ zero_hdr,
+                                                 const int* __restrict__ skip) {
+    if (skip && *skip) return;  // the caller's device-side stop flag is set: nothing to do
     // the first launch of a compress call also clears the workspace header (flag, ticket counter)
     if (zero_hdr && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 64) zero_hdr[threadIdx.x] = 0;
     constexpr int ROWS = 64, KC = 32;
@@ -94,7 +96,8 @@ __global__ __launch_bounds__(256) void k_thin_nn(const T* __restrict__ X, const 
 template <typename T, int MA>
 __global__ __launch_bounds__(256) void k_thin_tn(const T* __restrict__ X, const float* __restrict__ V,
                                                  float* __restrict__ part, int64_t N, int64_t h, int r,
-                                                 int64_t chunk) {
+                                                 int64_t chunk, const int* __restrict__ skip) {
+    if (skip && *skip) return;
     constexpr int PW = 64, RC = 32;
     __shared__ float Xs[RC][PW];
     __shared__ float Vs[RC][DAD_MAX_RANK];
@@ -165,7 +168,8 @@ __global__ __launch_bounds__(256) void k_thin_tn(const T* __restrict__ X, const 
 // element are shared by the four waves of a workgroup (wave g sums s = g, g+4, ... ascending) and
 // the four partial sums are combined in wave order.
 __global__ __launch_bounds__(256) void k_reduce_slabs(const float* part, float* out, int64_t n, int splits,
-                                                      bf16_t* __restrict__ out_bf16) {
+                                                      bf16_t* __restrict__ out_bf16, const int* __restrict__ skip) {
+    if (skip && *skip) return;
     __shared__ float ps[4][64];
     const int e = threadIdx.x & 63, g = threadIdx.x >> 6;
     const int64_t i = (int64_t)blockIdx.x * 64 + e;
@@ -303,7 +307,7 @@ SplitPlan gen_thin_nn_split(int64_t N, int64_t h) {
 }
 
 dad_status gen_thin_nn(const void* X, const float* Pt, void* out, float* partials, SplitPlan sp, int64_t N, int64_t h,
-                       int r, dad_dtype dt, int* zero_hdr, hipStream_t s) {
+                       int r, dad_dtype dt, int* zero_hdr, hipStream_t s, const int* skip) {
     dim3 grid((unsigned)ceil_div(N, 64), (unsigned)sp.splits);
     float* part = sp.splits == 1 ? nullptr : partials;
     {
@@ -312,10 +316,10 @@ dad_status gen_thin_nn(const void* X, const float* Pt, void* out, float* partial
     do {                                                                                                            \
         if (dt == DAD_BF16)                                                                                         \
             hipLaunchKernelGGL((k_thin_nn<bf16_t, MA>), grid, dim3(256), 0, s, (const bf16_t*)X, Pt, (float*)out, part, N, \
-                               h, r, sp.chunk, zero_hdr);                                                           \
+                               h, r, sp.chunk, zero_hdr, skip);                                                           \
         else                                                                                                        \
             hipLaunchKernelGGL((k_thin_nn<float, MA>), grid, dim3(256), 0, s, (const float*)X, Pt, (float*)out, part, N, h, \
-                               r, sp.chunk, zero_hdr);                                                              \
+                               r, sp.chunk, zero_hdr, skip);                                                              \
     } while (0)
         if (r <= 16) DAD_GEN_NN(4);
         else if (r <= 32) DAD_GEN_NN(8);
@@ -324,24 +328,25 @@ dad_status gen_thin_nn(const void* X, const float* Pt, void* out, float* partial
     }
     DAD_LAUNCH_CHECK();
     if (sp.splits == 1) return DAD_OK;
-    return reduce_slabs(part, (float*)out, N * r, sp.splits, s);
+    return reduce_slabs(part, (float*)out, N * r, sp.splits, s, nullptr, skip);
 }
 
-dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s, void* out_bf16) {
-    const bool wide = n >= (1 << 20) && n % 4 == 0 && !out_bf16;
+dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s, void* out_bf16,
+                        const int* skip) {
+    const bool wide = n >= (1 << 20) && n % 4 == 0 && !out_bf16 && !skip;
     ProfScope prof(wide ? KID_REDUCE_WIDE : KID_REDUCE, s);
     if (wide)
         hipLaunchKernelGGL(k_reduce_slabs_wide, dim3((unsigned)ceil_div(n / 4, 256)), dim3(256), 0, s,
                            reinterpret_cast<const float4*>(part), reinterpret_cast<float4*>(out), n / 4, splits);
     else
         hipLaunchKernelGGL(k_reduce_slabs, dim3((unsigned)ceil_div(n, 64)), dim3(256), 0, s, part, out, n, splits,
-                           (bf16_t*)out_bf16);
+                           (bf16_t*)out_bf16, skip);
     DAD_LAUNCH_CHECK();
     return DAD_OK;
 }
 
 dad_status gen_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp, int64_t N,
-                       int64_t h, int r, dad_dtype dt, hipStream_t s) {
+                       int64_t h, int r, dad_dtype dt, hipStream_t s, const int* skip) {
     dim3 grid((unsigned)ceil_div(h, 64), (unsigned)sp.splits);
     float* dst = sp.splits == 1 ? out_t : partials;
     {
@@ -350,10 +355,10 @@ dad_status gen_thin_tn(const void* X, const void* V, float* out_t, float* partia
     do {                                                                                                            \
         if (dt == DAD_BF16)                                                                                         \
             hipLaunchKernelGGL((k_thin_tn<bf16_t, MA>), grid, dim3(256), 0, s, (const bf16_t*)X, (const float*)V, dst, N, \
-                               h, r, sp.chunk);                                                                     \
+                               h, r, sp.chunk, skip);                                                               \
         else                                                                                                        \
             hipLaunchKernelGGL((k_thin_tn<float, MA>), grid, dim3(256), 0, s, (const float*)X, (const float*)V, dst, N, h, \
-                               r, sp.chunk);                                                                        \
+                               r, sp.chunk, skip);                                                                  \
     } while (0)
     if (r <= 16) DAD_GEN_TN(4);
     else if (r <= 32) DAD_GEN_TN(8);
@@ -361,7 +366,7 @@ dad_status gen_thin_tn(const void* X, const void* V, float* out_t, float* partia
 #undef DAD_GEN_TN
     }
     DAD_LAUNCH_CHECK();
-    if (sp.splits > 1) return reduce_slabs(partials, out_t, (int64_t)r * h, sp.splits, s);
+    if (sp.splits > 1) return reduce_slabs(partials, out_t, (int64_t)r * h, sp.splits, s, nullptr, skip);
     return DAD_OK;
 }
 

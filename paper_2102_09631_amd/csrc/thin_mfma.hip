@@ -67,7 +67,9 @@ constexpr int XTILEB = RT * XROWB;
 template <int RP>  // RP = r rounded up to 32 or 64
 __global__ __launch_bounds__(256) void k_thin_nn_bf16(const bf16_t* __restrict__ X, const float* __restrict__ Pt,
                                                       bf16_t* __restrict__ V, int64_t N, int h, int r,
-                                                      int* __restrict__ zero_hdr, int planes) {
+                                                      int* __restrict__ zero_hdr, int planes,
+                                                      const int* __restrict__ skip) {
+    if (skip && *skip) return;  // the caller's device-side stop flag is set: nothing to do
     // the first launch of a compress call also clears the workspace header (flag, ticket counter)
     if (zero_hdr && blockIdx.x == 0 && threadIdx.x < 64) zero_hdr[threadIdx.x] = 0;
     constexpr int JT = RP / 32;
@@ -318,7 +320,8 @@ __device__ __forceinline__ bf16x8 tn_frag(const char* tile, int rowb, int m0, in
 template <int RP, int NV>
 __global__ __launch_bounds__(256) void k_thin_tn_bf16(const bf16_t* __restrict__ X, const bf16_t* __restrict__ V,
                                                       float* __restrict__ part, int64_t N, int h, int r,
-                                                      int64_t chunk_rows) {
+                                                      int64_t chunk_rows, const int* __restrict__ skip) {
+    if (skip && *skip) return;
     constexpr int JT = RP / 32;
     constexpr int VROWB = RP * 2;
     constexpr int VTILEB = tn::BK * VROWB;
@@ -621,17 +624,17 @@ SplitPlan thin_tn_split(int64_t N, int64_t h, int r) {
 }
 
 dad_status fast_thin_nn(const void* X, const float* Pt, void* out, int64_t N, int64_t h, int r, int* zero_hdr,
-                        int planes, hipStream_t s) {
+                        int planes, hipStream_t s, const int* skip) {
     dim3 grid((unsigned)ceil_div(N, nn::RT));
     ProfScope prof(KID_THIN_NN_BF16, s);
     if (r <= 32) {
         const int lds = 2 * (nn::XTILEB + 32 * nn::XROWB);
         hipLaunchKernelGGL(k_thin_nn_bf16<32>, grid, dim3(256), lds, s, (const bf16_t*)X, Pt, (bf16_t*)out, N, (int)h, r,
-                           zero_hdr, planes);
+                           zero_hdr, planes, skip);
     } else {
         const int lds = 2 * (nn::XTILEB + 64 * nn::XROWB);
         hipLaunchKernelGGL(k_thin_nn_bf16<64>, grid, dim3(256), lds, s, (const bf16_t*)X, Pt, (bf16_t*)out, N, (int)h, r,
-                           zero_hdr, planes);
+                           zero_hdr, planes, skip);
     }
     DAD_LAUNCH_CHECK();
     return DAD_OK;
@@ -682,9 +685,9 @@ dad_status dma_thin_nn(const void* X, const void* Pb, void* out, int64_t N, int6
 }
 
 dad_status fast_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp, int64_t N, int64_t h,
-                        int r, void* out_bf16, int planes, hipStream_t s) {
+                        int r, void* out_bf16, int planes, hipStream_t s, const int* skip) {
     float* dst = sp.splits == 1 ? out_t : partials;
-    if ((r == 16 || r == 32 || r == 64) && N % tn::BK == 0 && sp.chunk % tn::BK == 0) {
+    if (!skip && (r == 16 || r == 32 || r == 64) && N % tn::BK == 0 && sp.chunk % tn::BK == 0) {
         ProfScope prof(KID_THIN_TN_BF16, s);
         const int pw = thin_tn_pw(h);
         const int bk = pw == 128 ? 64 : 32;
@@ -721,7 +724,7 @@ dad_status fast_thin_tn(const void* X, const void* V, float* out_t, float* parti
         const int lds = 2 * (tn::XTILEB + planes * tn::BK * rp * 2);  // at most 64 KiB
 #define DAD_TN_REG(RP, NV)                                                                                            \
     hipLaunchKernelGGL((k_thin_tn_bf16<RP, NV>), grid, dim3(256), lds, s, (const bf16_t*)X, (const bf16_t*)V, dst, N, \
-                       (int)h, r, sp.chunk)
+                       (int)h, r, sp.chunk, skip)
         if (r <= 32) {
             if (planes > 1) DAD_TN_REG(32, 2);
             else DAD_TN_REG(32, 1);
@@ -732,8 +735,8 @@ dad_status fast_thin_tn(const void* X, const void* V, float* out_t, float* parti
 #undef DAD_TN_REG
     }
     DAD_LAUNCH_CHECK();
-    if (sp.splits > 1) return reduce_slabs(partials, out_t, (int64_t)r * h, sp.splits, s, out_bf16);
-    if (out_bf16) return reduce_slabs(out_t, out_t, (int64_t)r * h, 1, s, out_bf16);  // copy only
+    if (sp.splits > 1) return reduce_slabs(partials, out_t, (int64_t)r * h, sp.splits, s, out_bf16, skip);
+    if (out_bf16) return reduce_slabs(out_t, out_t, (int64_t)r * h, 1, s, out_bf16, skip);  // copy only
     return DAD_OK;
 }
 

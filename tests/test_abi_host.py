@@ -232,6 +232,27 @@ def test_sequential_rejects_bad_arguments_on_host(lib):
     assert lib.dad_compress_sequential_workspace_bytes(64, 784, 128, 9) == 0
 
 
+def test_adaptive_rejects_bad_arguments_on_host(lib):
+    p = 0x1000  # never dereferenced: every call below must fail before a launch
+    ws = 1 << 30
+
+    def call(A=p, N=64, dt=dad.DAD_F32, r=4, n=20, theta=1e-3, G0=p, rank=p, iters=None, wb=ws):
+        return lib.dad_compress_rank_adaptive(A, p, N, 784, 128, dt, r, n, theta, G0, p, p, p, rank, iters, p, wb, None)
+
+    assert call(A=None) == dad.DAD_ERR_NULL
+    assert call(rank=None) == dad.DAD_ERR_NULL
+    assert call(dt=2) == dad.DAD_ERR_DTYPE
+    assert call(r=65) == dad.DAD_ERR_SHAPE
+    assert call(n=0) == dad.DAD_ERR_SHAPE
+    assert call(theta=-1e-3) == dad.DAD_ERR_SHAPE
+    assert call(theta=1.0) == dad.DAD_ERR_SHAPE
+    assert call(theta=float("nan")) == dad.DAD_ERR_SHAPE
+    assert call(G0=p + 4) == dad.DAD_ERR_ALIGN
+    assert call(rank=p + 2) == dad.DAD_ERR_ALIGN
+    assert call(iters=p + 2) == dad.DAD_ERR_ALIGN
+    assert call(wb=16) == dad.DAD_ERR_WORKSPACE
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(dad, "_lib", None)
     monkeypatch.setattr(dad, "LIB_PATH", str(tmp_path / "libdad.so"))
