@@ -116,7 +116,8 @@ size_t dad_compress_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, int 
  * evaluated right to left so that neither M nor A A^T is formed; the
  * orthonormalisation (Cholesky QR: one round for the intermediate iterates,
  * of which only the span is used; for the last one a second round unless the
- * pivots of the first differ by at most 16x, decided on the device) stands in for
+ * first factor shows cond(Y) <= 4 r through the upper bound ||R||_F ||R^-1||_F,
+ * decided on the device) stands in for
  * the peeling of Eq. 7.  Then the left factor P = A^T (Delta G) is formed with the singular values left
  * inside it (footnote to Section 3.3.1), so that  M ~ P G^T = M G G^T.
  *
@@ -200,7 +201,8 @@ size_t dad_compress_gram_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out,
  * precomputation C = A A^T, Eq. 6; the regime N << h of Section 3.3.1).  C = A A^T, E = D D^T and
  * H0 = D G0^T are formed once in fp64; with every iterate written as G_k = D^T T_k the block power
  * iteration and its Cholesky orthonormalisation (one round per iterate; a second one for the returned
- * iterate when the pivots of the first differ by more than 1e6) run on N x N and N x r fp64 matrices:
+ * iterate unless the first factor shows cond(Y) <= 1e3 r through the bound ||R||_F ||R^-1||_F) run on
+ * N x N and N x r fp64 matrices:
  *     Z_1 = C H0,  Z_k = C (E T_{k-1}),  Z_k^T E Z_k = R^T R,  T_k = Z_k R^-1,
  * and the pair is Gt = T_n^T D, Pt = (E T_n)^T A.  Each factor is read twice instead of
  * 2 n_iter + 1 times and the call is 9 launches for n_iter = 2.

@@ -20,8 +20,13 @@ struct FactorShared {
 //     S[i][j] -= L[i][k] L[j][k],         T[i][j] -= L[i][k] X[k][j]      for i > k.
 // R^{-1} = X^T (upper triangular, row-major r x r) is written in the type RT.  A pivot that is not
 // > 0 (or NaN) latches *flag and is replaced by 1 so the sweep still ends with finite arithmetic.
-// piv_range, when given, receives the smallest and the largest pivot (squares of the diagonal of R):
-// their ratio bounds the squared condition number of the factorised iterate from below.
+// piv_range, when given, receives two doubles:
+//   [0] the smallest pivot (square of a diagonal entry of R), 0 after a breakdown;
+//   [1] trace(S) * ||R^{-1}||_F^2 / r^2 = (||R||_F ||R^{-1}||_F / r)^2, which is 1 for a factorised
+//       iterate with orthogonal columns of equal length and bounds its squared condition number
+//       from ABOVE (cond_2(Y)^2 = cond_2(R)^2 <= ||R||_F^2 ||R^{-1}||_F^2); +inf after a breakdown.
+//       (The ratio of the pivots would only bound it from below: a unit-diagonal R with large
+//       entries above the diagonal has equal pivots and a condition number that grows like 2^r.)
 // Every thread of the workgroup must call it; the caller synchronises before `f` is reused.
 template <int NA, typename RT>
 __device__ __forceinline__ void factor_partials(FactorShared& f, const double* __restrict__ gram_part, int nblocks, int r,
@@ -59,12 +64,14 @@ __device__ __forceinline__ void factor_partials(FactorShared& f, const double* _
                 for (int b = 0; b < NA; ++b) S[a][b] += v[u][a][b];
     }
     // identity beyond r keeps the padded rows and columns inert
+    double tr_part = 0.0, xsq_part = 0.0;  // this thread's share of trace(S) and of ||R^{-1}||_F^2
 #pragma unroll
     for (int a = 0; a < NA; ++a)
 #pragma unroll
         for (int b = 0; b < NA; ++b) {
             const int i = ti + 16 * a, j = tj + 16 * b;
             if (i >= r || j >= r) S[a][b] = (i == j) ? 1.0 : 0.0;
+            else if (i == j) tr_part += S[a][b];
         }
 
     // Two pivots per step: columns k, k+1 of S and rows k, k+1 of T are published together and every
@@ -159,16 +166,38 @@ __device__ __forceinline__ void factor_partials(FactorShared& f, const double* _
                 const int j = tj + 16 * b;
                 if (j < r) {
                     rinv[j * r + k] = (RT)x0[b];
-                    if (k + 1 < r) rinv[j * r + k + 1] = (RT)x1[b];
+                    xsq_part += x0[b] * x0[b];
+                    if (k + 1 < r) {
+                        rinv[j * r + k + 1] = (RT)x1[b];
+                        xsq_part += x1[b] * x1[b];
+                    }
                 }
             }
         }
     }
     if (bad && t == 0) *flag = 1;
-    if (piv_range && t == 0) {
-        piv_range[0] = bad ? 0.0 : pmin;  // a breakdown reads as infinitely ill conditioned
-        piv_range[1] = pmax;
+    if (piv_range) {  // uniform over the workgroup
+        __syncthreads();  // the last step's reads of the published columns and rows are done
+        double* tr_s = &f.colS[0][0][0];  // 256 doubles each
+        double* xs_s = &f.rowT[0][0][0];
+        tr_s[t] = tr_part;
+        xs_s[t] = xsq_part;
+        __syncthreads();
+        if (t < 64) {
+            double tr = (tr_s[t] + tr_s[t + 64]) + (tr_s[t + 128] + tr_s[t + 192]);
+            double xs = (xs_s[t] + xs_s[t + 64]) + (xs_s[t + 128] + xs_s[t + 192]);
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                tr += __shfl_down(tr, o, 64);
+                xs += __shfl_down(xs, o, 64);
+            }
+            if (t == 0) {
+                piv_range[0] = bad ? 0.0 : pmin;  // a breakdown reads as infinitely ill conditioned
+                piv_range[1] = bad ? __builtin_huge_val() : tr * xs / ((double)r * (double)r);
+            }
+        }
     }
+    (void)pmax;
 }
 
 }  // namespace dad

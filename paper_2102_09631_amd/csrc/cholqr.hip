@@ -158,14 +158,14 @@ __global__ __launch_bounds__(256) void k_qr_gram(const float* __restrict__ Yt, i
 }
 
 // One Cholesky round leaves G^T G - I at about eps32 * cond(Y) (the rounding of Y R^-1 in fp32); the
-// second round brings it to eps32.  The pivots of the first factor are the squared diagonal of R,
-// whose ratio bounds cond(Y)^2 from below: when it is at most QR_ONE_ROUND_SPREAD the first round is
-// kept as the result (the flat spectra of dense layers' gradients) and the second is not run.
-constexpr double QR_ONE_ROUND_SPREAD = 16.0;
+// second round brings it to eps32.  The first factorisation reports (||R||_F ||R^-1||_F / r)^2, an
+// upper bound of cond(Y)^2 that is 1 for orthogonal columns of equal length: when it is at most
+// QR_ONE_ROUND_BOUND (cond(Y) <= 4 r) the first round is kept as the result (the flat spectra of dense
+// layers' gradients) and the second is not run.
+constexpr double QR_ONE_ROUND_BOUND = 16.0;
 
 __device__ __forceinline__ bool one_round_enough(const double* __restrict__ piv_first) {
-    const double pmin = piv_first[0], pmax = piv_first[1];
-    return pmin > 0.0 && pmax <= QR_ONE_ROUND_SPREAD * pmin;
+    return piv_first[0] > 0.0 && piv_first[1] <= QR_ONE_ROUND_BOUND;
 }
 
 // Launches 2 and 3: Gt[j][k] = sum_{i<=j} rinv_in[i][j] * Yt[i][k]; Gt may alias Yt (each workgroup

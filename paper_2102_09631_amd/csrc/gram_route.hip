@@ -229,8 +229,8 @@ enum { NS_CV = 0, NS_EZ = 1, NS_REFINE = 2, NS_APPLY = 3 };
 constexpr int NS_ROWS = 16;   // rows of the N x r matrices per workgroup
 constexpr int NS_IN = 8192;   // entries of the right operand per LDS stage (NS_IN / (16 NA) rows)
 constexpr int NS_LD = DAD_MAX_RANK + 1;
-// Largest ratio of Cholesky pivots (squared diagonal of R) up to which one round is taken to be enough:
-// the orthonormality error of one fp64 round is about 1e-16 cond(Y)^2, and cond(Y)^2 is at least this ratio.
+// Largest (||R||_F ||R^-1||_F / r)^2 of the first factor, an upper bound of cond(Y)^2, up to which one
+// round is taken to be enough: the orthonormality error of one fp64 round is about 1e-16 cond(Y)^2.
 constexpr double NS_REFINE_SPREAD = 1e6;
 
 // Lives in dynamic LDS (about 100 KB).  The product phase and the phases after it never overlap in
@@ -303,11 +303,10 @@ __global__ __launch_bounds__(256) void k_ns_step(const double* __restrict__ S, c
     const int64_t g0 = (int64_t)blockIdx.x * NS_ROWS, gi = g0 + row;
     const bool live = gi < N;
     if (MODE == NS_REFINE) {
-        // The pivots of the first round bound the conditioning of the iterate from below; when their
-        // spread is small the first factor already orthonormalises to fp32 accuracy and more, and the
-        // second round reduces to handing that factor on.
-        const double pmin = piv_range[0], pmax = piv_range[1];
-        if (pmin > 0.0 && pmax <= NS_REFINE_SPREAD * pmin) {
+        // The first round reports an upper bound of the iterate's squared condition number; when it is
+        // small the first factor already orthonormalises to fp32 accuracy and more, and the second
+        // round reduces to handing that factor on.
+        if (piv_range[0] > 0.0 && piv_range[1] <= NS_REFINE_SPREAD) {
             if (blockIdx.x == 0)
                 for (int e = t; e < r * r; e += 256) rout[e] = rin[e];
             return;

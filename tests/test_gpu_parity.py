@@ -204,6 +204,29 @@ def test_rank_pairs_restack_and_recompress(gpu):
     assert O.rel_fro(G_hat, ref) <= 1e-5
 
 
+@pytest.mark.parametrize("route", ["block", "gram"])
+def test_equal_pivots_do_not_hide_an_ill_conditioned_iterate(gpu, route):
+    """A = Delta = I make M the identity, so with one application the iterate that is orthonormalised
+    is the start matrix itself: Y = G0^T = Q R with R unit upper triangular and -1 above the diagonal.
+    Every Cholesky pivot of Y^T Y is 1 although cond(R) grows like 2^r (here ~5e3): one fp32 round
+    would leave G^T G - I at ~1e-4, so the decision to skip the second round must not be taken from the
+    pivots.  span(Y) is the whole r-dimensional span of Q, hence P G^T = Q Q^T."""
+    h, r = 64, 12
+    rng = np.random.default_rng(77)
+    Q, _ = np.linalg.qr(rng.standard_normal((h, r)))
+    R = np.eye(r) - np.triu(np.ones((r, r)), 1)
+    G0 = np.ascontiguousarray((Q @ R).T.astype(np.float32))   # r x h_out, row j = column j of Y
+    eye = torch.eye(h, device=gpu)
+    call = dad.compress_rank if route == "block" else dad.compress_rank_gram
+    Pt, Gt = call(eye, eye.clone(), r, 1, torch.from_numpy(G0).to(gpu), check=True)
+    g = Gt.cpu().numpy().astype(np.float64)
+    assert np.abs(g @ g.T - np.eye(r)).max() <= 1e-5
+    ref = O.rank_r_grad(*O.block_spi(np.eye(h), np.eye(h), G0, 1))
+    # Y R^-1 in fp32 resolves the span of Y only to eps32 * cond(Y), as on the steep spectra above
+    tol = 1e-5 + np.finfo(np.float32).eps * np.linalg.cond(R)
+    assert O.rel_fro(dad.reconstruct_grad(Pt, Gt).cpu().numpy(), ref) <= tol
+
+
 def test_zero_deltas_latch_numeric_breakdown(gpu):
     A = torch.ones((16, 32), device=gpu)
     D = torch.zeros((16, 24), device=gpu)
