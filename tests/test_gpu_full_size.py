@@ -1,9 +1,10 @@
 """Parity at the benchmark's full sizes, in the launch configuration bench.py times.
 
 Factors are drawn on the device (as bench.py does) and copied to the host, so the
-oracle sees the very same bf16 values.  The full gradient is compared on sampled
-rows that the oracle computes from the definition; the rank-r gradient is
-compared in full against the oracle's block iteration on the same start matrix.
+oracle sees the very same bf16 values.  The full gradient is compared in full
+against the oracle's Eq. 4 at 1e-5 (bf16 values are exact in fp64 and their
+products exact in fp32, so only the fp32 summation differs); the rank-r gradient
+is compared in full against the oracle's block iteration on the same start matrix.
 """
 import numpy as np
 import pytest
@@ -16,6 +17,7 @@ from paper_2102_09631_amd import workloads as W
 pytestmark = pytest.mark.gpu
 
 TOL_BF16 = 2e-2
+TOL_FULL = 1e-5      # full gradient from bf16 factors: exact inputs and products, fp32 sums
 
 
 def run_full_size(w, layer, h_in, h_out, dev, rank_check=True):
@@ -29,11 +31,18 @@ def run_full_size(w, layer, h_in, h_out, dev, rank_check=True):
     G_full = dad.reconstruct_grad(A, D)
     A_h = A.float().cpu().numpy().astype(np.float64)
     D_h = D.float().cpu().numpy().astype(np.float64)
-    rows = np.random.default_rng(layer).choice(h_in, size=48, replace=False)
-    ref_rows = A_h[:, rows].T @ D_h                                   # Eq. 4 for the sampled rows
-    e_full = O.rel_fro(G_full[torch.from_numpy(rows).to(dev)].cpu().numpy(), ref_rows)
-    out = {"e_full_sampled": e_full}
-    assert e_full <= TOL_BF16, out
+    G_ref = O.full_grad(A_h, D_h)                                     # Eq. 4, every entry
+    G_gpu = G_full.cpu().numpy()
+    e_full = O.rel_fro(G_gpu, G_ref)
+    # no tile or K slab may be off even where the Frobenius norm would hide it: every 256 x 256
+    # block of the gradient is held to the same bar on its own
+    worst = 0.0
+    for p0 in range(0, h_in, 256):
+        for q0 in range(0, h_out, 256):
+            worst = max(worst, O.rel_fro(G_gpu[p0:p0 + 256, q0:q0 + 256], G_ref[p0:p0 + 256, q0:q0 + 256]))
+    out = {"e_full": e_full, "e_full_worst_block": worst}
+    assert e_full <= TOL_FULL and worst <= TOL_FULL, out
+    del G_ref, G_gpu
     if rank_check:
         Pt, Gt = dad.compress_rank(A, D, w.rank, w.n_iter, G0, check=True)
         G_r = dad.reconstruct_grad(Pt, Gt)

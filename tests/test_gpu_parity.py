@@ -124,6 +124,22 @@ def test_stack_with_empty_and_uneven_sites(gpu):
         assert np.array_equal(D.float().cpu().numpy(), D_ref)
 
 
+def test_stack_of_forty_uneven_sites_takes_a_second_launch(gpu):
+    """A copy launch holds 64 segments, i.e. the A and Delta blocks of 32 sites: 40 sites need two."""
+    rng = np.random.default_rng(6)
+    rows = [int(n) for n in rng.integers(0, 40, size=40)]
+    rows[3] = 0
+    for dtype, width in (("bf16", (33, 7)), ("f32", (24, 16))):     # odd bf16 widths: 2-byte tails and offsets
+        A_s = [rng.standard_normal((n, width[0])).astype(np.float32) for n in rows]
+        D_s = [rng.standard_normal((n, width[1])).astype(np.float32) for n in rows]
+        if dtype == "bf16":
+            A_s = [W.bf16_bits_to_f32(W.f32_to_bf16_bits(a)).reshape(a.shape) for a in A_s]
+            D_s = [W.bf16_bits_to_f32(W.f32_to_bf16_bits(d)).reshape(d.shape) for d in D_s]
+        A, D = dad.stack_factors([to_dev(a, dtype, gpu) for a in A_s], [to_dev(d, dtype, gpu) for d in D_s])
+        A_ref, D_ref = O.stack_factors(A_s, D_s)
+        assert np.array_equal(A.float().cpu().numpy(), A_ref) and np.array_equal(D.float().cpu().numpy(), D_ref)
+
+
 def test_rank_budget_at_least_gradient_rank_recovers_gradient(gpu):
     """r = rank(M) = N: the rank-r gradient equals the full gradient and the truncated SVD."""
     w = W.WORKLOADS[0]

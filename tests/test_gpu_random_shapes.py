@@ -51,6 +51,39 @@ def test_random_shapes_block_route_and_rebuild(gpu, N, h_in, h_out, r, n_iter):
     assert np.abs(g @ g.T - np.eye(r)).max() <= 1e-5
 
 
+def flat_shapes(seed, count, n_max, h_max, r_max):
+    """Shapes with enough rows and columns that a Gaussian gradient's spectrum is flat (no direction
+    is weak): N, h >= 4 r."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        r = int(rng.integers(1, r_max + 1))
+        N = int(rng.integers(4 * r, n_max + 1))
+        h_in = int(rng.integers(4 * r, h_max + 1))
+        h_out = int(rng.integers(4 * r, h_max + 1))
+        out.append((N, h_in, h_out, r, int(rng.integers(1, 4))))
+    return out
+
+
+@pytest.mark.parametrize("N,h_in,h_out,r,n_iter", flat_shapes(104, 24, 700, 600, 32))
+def test_random_shapes_flat_spectrum_at_the_strict_bar(gpu, N, h_in, h_out, r, n_iter):
+    """Gaussian factors without any planted decay (the spectra of the benchmark's own layers are flat):
+    full and rank-r gradient at 1e-5 with no conditioning allowance, both compress routes."""
+    rng = np.random.default_rng([4, N, h_in, h_out, r])
+    A = np.maximum(rng.standard_normal((N, h_in)), 0.0).astype(np.float32)
+    D = (0.1 * rng.standard_normal((N, h_out))).astype(np.float32)
+    G0 = rng.standard_normal((r, h_out)).astype(np.float32)
+    a, d, g0 = torch.from_numpy(A).to(gpu), torch.from_numpy(D).to(gpu), torch.from_numpy(G0).to(gpu)
+    assert O.rel_fro(dad.reconstruct_grad(a, d).cpu().numpy(), O.full_grad(A, D)) <= 1e-5
+    ref = O.rank_r_grad(*O.block_spi(A, D, G0, n_iter))
+    Pt, Gt = dad.compress_rank(a, d, r, n_iter, g0, check=True)
+    assert O.rel_fro(dad.reconstruct_grad(Pt, Gt).cpu().numpy(), ref) <= 1e-5
+    g = Gt.cpu().numpy().astype(np.float64)
+    assert np.abs(g @ g.T - np.eye(r)).max() <= 1e-5
+    Pt2, Gt2 = dad.compress_rank_gram(a, d, r, n_iter, g0, check=True)
+    assert O.rel_fro(dad.reconstruct_grad(Pt2, Gt2).cpu().numpy(), ref) <= 1e-5
+
+
 @pytest.mark.parametrize("N,h_in,h_out,r,n_iter", shapes(102, 24, 300, 400, 48))
 def test_random_shapes_gram_route(gpu, N, h_in, h_out, r, n_iter):
     A, D, G0 = factors(N, h_in, h_out, r, 2)
