@@ -170,7 +170,10 @@ dad_status dad_compress_rank_noalloc(const void* A, const void* D, int64_t N, in
  * are in flight at once (layer i on lane i mod lanes), so that the short, latency-bound launches of
  * one layer's orthonormalisation run while another layer streams its factors.
  *   descs     HOST array of n layers, 1 <= n <= DAD_MAX_GROUP; every pointer is a device pointer with
- *             the meaning and alignment of dad_compress_rank's
+ *             the meaning and alignment of dad_compress_rank's.  A layer with S > 0 gives its factors
+ *             as the S site blocks of dad_stack_factors (A_sites, D_sites, rows: HOST arrays read
+ *             during the call; A, D and N are then ignored, N = sum of rows) and is reduced as
+ *             dad_compress_rank_sites reduces it
  *   dt, r, n_iter   common to all layers
  *   lanes     1 .. DAD_MAX_LANES; lane 0 is `stream` itself, the others are streams of default
  *             priority that the library keeps per device; they start after the work already enqueued
@@ -187,11 +190,43 @@ typedef struct {
     float* Pt;       /* r x h_in,  out */
     float* Gt;       /* r x h_out, out */
     int64_t N, h_in, h_out;
+    int S;                       /* 0: stacked factors A, D with N rows; > 0: S site blocks */
+    const void* const* A_sites;  /* S device pointers, rows[s] x h_in  */
+    const void* const* D_sites;  /* S device pointers, rows[s] x h_out */
+    const int64_t* rows;         /* S row counts */
 } dad_compress_desc;
 #define DAD_MAX_LANES 8
 size_t dad_compress_grouped_workspace_bytes(int n, const dad_compress_desc* descs, dad_dtype dt, int r, int lanes);
 dad_status dad_compress_rank_grouped(int n, const dad_compress_desc* descs, dad_dtype dt, int r, int n_iter, int lanes,
                                      void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * dad_compress_rank_sites, dad_reconstruct_grad_sites - dad_compress_rank and the full rebuild
+ * G = A^T D (Eq. 4) on factors that are given as the S site blocks of dad_stack_factors instead of
+ * the stacked matrices (Section 3.2: stacking only orders the rows; Algorithm 1's vertcat).  The
+ * results are bit-identical to dad_stack_factors followed by dad_compress_rank /
+ * dad_reconstruct_grad, because the same kernels do the same work in the same order and only
+ * fetch their rows from the blocks.
+ *   S, A_sites, D_sites, rows   as for dad_stack_factors (HOST arrays of device pointers and row
+ *             counts, read during the call; empty sites allowed); N = sum of rows must satisfy the
+ *             stacked call's limits
+ *   the other arguments as in dad_compress_rank / dad_reconstruct_grad (L = A, R = D, K = N)
+ *   workspace ws_bytes >= dad_compress_sites_workspace_bytes / dad_reconstruct_sites_workspace_bytes
+ * The blocks are read in place, without any copy, when the stacked call would run its
+ * direct-to-LDS bf16 kernels (bf16, N a multiple of 256, widths multiples of 128, for the
+ * reduction r in {16, 32, 64}), there are at most 32 non-empty sites and every site's row count is a
+ * multiple of 256.  Otherwise the call stacks the blocks into its own workspace first (the size
+ * query accounts for that) and proceeds as the stacked call.  dad_poll_numeric_status(workspace,
+ * stream) works as for dad_compress_rank.  Errors as for the stacked calls and dad_stack_factors.
+ */
+size_t dad_compress_sites_workspace_bytes(int S, const int64_t* rows, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
+dad_status dad_compress_rank_sites(int S, const void* const* A_sites, const void* const* D_sites, const int64_t* rows,
+                                   int64_t h_in, int64_t h_out, dad_dtype dt, int r, int n_iter, const float* G0,
+                                   float* Pt, float* Gt, void* workspace, size_t ws_bytes, void* stream);
+size_t dad_reconstruct_sites_workspace_bytes(int S, const int64_t* rows, int64_t h_in, int64_t h_out, dad_dtype dt);
+dad_status dad_reconstruct_grad_sites(int S, const void* const* A_sites, const void* const* D_sites, const int64_t* rows,
+                                      int64_t h_in, int64_t h_out, dad_dtype dt, float* G, void* workspace,
+                                      size_t ws_bytes, void* stream);
 
 /* Bytes of device workspace dad_compress_rank_gram needs (0 on invalid sizes, N > DAD_GRAM_MAX_ROWS included). */
 size_t dad_compress_gram_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);

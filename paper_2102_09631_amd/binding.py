@@ -33,7 +33,9 @@ class RebuildDesc(C.Structure):
 class CompressDesc(C.Structure):
     """dad_compress_desc"""
     _fields_ = [("A", C.c_void_p), ("D", C.c_void_p), ("G0", C.c_void_p), ("Pt", C.c_void_p), ("Gt", C.c_void_p),
-                ("N", C.c_int64), ("h_in", C.c_int64), ("h_out", C.c_int64)]
+                ("N", C.c_int64), ("h_in", C.c_int64), ("h_out", C.c_int64),
+                ("S", C.c_int), ("A_sites", C.POINTER(C.c_void_p)), ("D_sites", C.POINTER(C.c_void_p)),
+                ("rows", C.POINTER(C.c_int64))]
 
 
 class DadError(RuntimeError):
@@ -102,6 +104,16 @@ def lib() -> C.CDLL:
     L.dad_compress_grouped_workspace_bytes.argtypes = [C.c_int, C.POINTER(CompressDesc), C.c_int, C.c_int, C.c_int]
     L.dad_compress_rank_grouped.restype = C.c_int
     L.dad_compress_rank_grouped.argtypes = [C.c_int, C.POINTER(CompressDesc), C.c_int, C.c_int, C.c_int, C.c_int, vp, sz, vp]
+    pvp, pi64 = C.POINTER(vp), C.POINTER(i64)
+    L.dad_compress_sites_workspace_bytes.restype = sz
+    L.dad_compress_sites_workspace_bytes.argtypes = [C.c_int, pi64, i64, i64, C.c_int, C.c_int]
+    L.dad_compress_rank_sites.restype = C.c_int
+    L.dad_compress_rank_sites.argtypes = [C.c_int, pvp, pvp, pi64, i64, i64, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp,
+                                          sz, vp]
+    L.dad_reconstruct_sites_workspace_bytes.restype = sz
+    L.dad_reconstruct_sites_workspace_bytes.argtypes = [C.c_int, pi64, i64, i64, C.c_int]
+    L.dad_reconstruct_grad_sites.restype = C.c_int
+    L.dad_reconstruct_grad_sites.argtypes = [C.c_int, pvp, pvp, pi64, i64, i64, C.c_int, vp, vp, sz, vp]
     L.dad_probe_mfma_loop.restype = C.c_int
     L.dad_probe_mfma_loop.argtypes = [vp, sz, C.c_int, vp, vp, C.POINTER(C.c_double)]
     L.dad_probe_read_stream.restype = C.c_int
@@ -163,6 +175,72 @@ def stack_factors(A_sites, D_sites, A_out=None, D_out=None):
     _check(lib().dad_stack_factors(S, pa, pd, pr, h_in, h_out, _dt(A_sites[0]), A_out.data_ptr(), D_out.data_ptr(),
                                    _stream()), "dad_stack_factors")
     return A_out, D_out
+
+
+def _site_tables(A_sites, D_sites):
+    """Checks a list of site blocks and marshals it: (S, pointer arrays, row array, rows, h_in, h_out, dt)."""
+    S = len(A_sites)
+    if S == 0 or len(D_sites) != S:
+        raise ValueError("need the same non-zero number of A and Delta blocks")
+    h_in, h_out = A_sites[0].shape[1], D_sites[0].shape[1]
+    dt = _dt(A_sites[0])
+    for a, d in zip(A_sites, D_sites):
+        _dense2d(a, "A_s")
+        _dense2d(d, "Delta_s")
+        if a.shape[0] != d.shape[0] or a.dtype != A_sites[0].dtype or d.dtype != a.dtype:
+            raise ValueError("site blocks disagree in rows or dtype")
+        if a.shape[1] != h_in or d.shape[1] != h_out:
+            raise ValueError("site blocks disagree in width")
+    rows = [int(a.shape[0]) for a in A_sites]
+    pa = (C.c_void_p * S)(*[a.data_ptr() for a in A_sites])
+    pd = (C.c_void_p * S)(*[d.data_ptr() for d in D_sites])
+    pr = (C.c_int64 * S)(*rows)
+    return S, pa, pd, pr, rows, h_in, h_out, dt
+
+
+def compress_rank_sites(A_sites, D_sites, r, n_iter, G0, Pt=None, Gt=None, workspace=None, check=False):
+    """dad_compress_rank_sites: compress_rank on the sites' blocks, without the stacked copy where the
+    blocks can be read in place."""
+    S, pa, pd, pr, rows, h_in, h_out, dt = _site_tables(A_sites, D_sites)
+    _dense2d(G0, "G0")
+    if G0.dtype != torch.float32 or tuple(G0.shape) != (r, h_out):
+        raise ValueError("G0 must be float32 of shape (r, h_out)")
+    dev = A_sites[0].device
+    if workspace is None:
+        nbytes = lib().dad_compress_sites_workspace_bytes(S, pr, h_in, h_out, r, dt)
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+    if Pt is None:
+        Pt = torch.empty((r, h_in), dtype=torch.float32, device=dev)
+    if Gt is None:
+        Gt = torch.empty((r, h_out), dtype=torch.float32, device=dev)
+    _check(lib().dad_compress_rank_sites(S, pa, pd, pr, h_in, h_out, dt, r, n_iter, G0.data_ptr(), Pt.data_ptr(),
+                                         Gt.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()),
+           "dad_compress_rank_sites")
+    if check:
+        _check(lib().dad_poll_numeric_status(workspace.data_ptr(), _stream()), "dad_poll_numeric_status")
+    return Pt, Gt
+
+
+def reconstruct_grad_sites(A_sites, D_sites, G=None, workspace=None):
+    """dad_reconstruct_grad_sites: G = A^T Delta (h_in x h_out fp32) from the sites' blocks."""
+    S, pa, pd, pr, rows, h_in, h_out, dt = _site_tables(A_sites, D_sites)
+    dev = A_sites[0].device
+    if workspace is None:
+        nbytes = lib().dad_reconstruct_sites_workspace_bytes(S, pr, h_in, h_out, dt)
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev) if nbytes else None
+    if G is None:
+        G = torch.empty((h_in, h_out), dtype=torch.float32, device=dev)
+    _check(lib().dad_reconstruct_grad_sites(S, pa, pd, pr, h_in, h_out, dt, G.data_ptr(),
+                                            workspace.data_ptr() if workspace is not None else None,
+                                            workspace.numel() if workspace is not None else 0, _stream()),
+           "dad_reconstruct_grad_sites")
+    return G
+
+
+def reconstruct_sites_workspace_bytes(rows, h_in, h_out, dtype) -> int:
+    pr = (C.c_int64 * len(rows))(*rows)
+    return lib().dad_reconstruct_sites_workspace_bytes(len(rows), pr, h_in, h_out,
+                                                       DAD_BF16 if dtype == torch.bfloat16 else DAD_F32)
 
 
 def compress_workspace_bytes(N, h_in, h_out, r, dtype) -> int:
@@ -352,37 +430,51 @@ DAD_MAX_LANES = 8
 
 
 class CompressGroup:
-    """Arguments of dad_compress_rank_grouped marshalled once.  layers: list of (A, D, G0) tensors;
+    """Arguments of dad_compress_rank_grouped marshalled once.  layers: list of (A, D, G0) tensors, or
+    (A_sites, D_sites, G0) with two lists of site blocks for a layer that is not stacked;
     outputs Pt, Gt are allocated unless given.  run() is one call of the entry point."""
 
     def __init__(self, layers, r, n_iter, lanes=2, Pts=None, Gts=None, workspace=None):
         if not layers:
             raise ValueError("need at least one layer")
         self.n, self.r, self.n_iter, self.lanes = len(layers), r, n_iter, lanes
-        self.dt = _dt(layers[0][0])
         self.descs = (CompressDesc * self.n)()
         self.Pt, self.Gt = [], []
+        self._tables = []
+        first = layers[0][0]
+        dev = (first[0] if isinstance(first, (list, tuple)) else first).device
+        self.dt = _dt(first[0] if isinstance(first, (list, tuple)) else first)
         for i, (A, D, G0) in enumerate(layers):
-            _dense2d(A, "A")
-            _dense2d(D, "Delta")
             _dense2d(G0, "G0")
-            N, h_in = A.shape
-            h_out = D.shape[1]
-            if D.shape[0] != N or D.dtype != A.dtype or _dt(A) != self.dt:
-                raise ValueError("A and Delta disagree in rows or dtype")
+            if isinstance(A, (list, tuple)):
+                S, pa, pd, pr, rows, h_in, h_out, dt = _site_tables(A, D)
+                self._tables.append((pa, pd, pr))
+                N, a_ptr, d_ptr = 0, None, None
+            else:
+                _dense2d(A, "A")
+                _dense2d(D, "Delta")
+                N, h_in = A.shape
+                h_out = D.shape[1]
+                if D.shape[0] != N or D.dtype != A.dtype:
+                    raise ValueError("A and Delta disagree in rows or dtype")
+                S, pa, pd, pr, dt = 0, None, None, None, _dt(A)
+                a_ptr, d_ptr = A.data_ptr(), D.data_ptr()
+            if dt != self.dt:
+                raise ValueError("the layers of a group share one dtype")
             if G0.dtype != torch.float32 or tuple(G0.shape) != (r, h_out):
                 raise ValueError("G0 must be float32 of shape (r, h_out)")
-            Pt = Pts[i] if Pts is not None else torch.empty((r, h_in), dtype=torch.float32, device=A.device)
-            Gt = Gts[i] if Gts is not None else torch.empty((r, h_out), dtype=torch.float32, device=A.device)
+            Pt = Pts[i] if Pts is not None else torch.empty((r, h_in), dtype=torch.float32, device=dev)
+            Gt = Gts[i] if Gts is not None else torch.empty((r, h_out), dtype=torch.float32, device=dev)
             self.Pt.append(Pt)
             self.Gt.append(Gt)
-            self.descs[i] = CompressDesc(A.data_ptr(), D.data_ptr(), G0.data_ptr(), Pt.data_ptr(), Gt.data_ptr(), N, h_in, h_out)
+            self.descs[i] = CompressDesc(a_ptr, d_ptr, G0.data_ptr(), Pt.data_ptr(), Gt.data_ptr(), N, h_in, h_out,
+                                         S, pa, pd, pr)
         self._keep = layers
         need = lib().dad_compress_grouped_workspace_bytes(self.n, self.descs, self.dt, r, lanes)
         if need == 0:
             raise ValueError("invalid sizes for dad_compress_rank_grouped")
         if workspace is None:
-            workspace = torch.zeros(need, dtype=torch.uint8, device=layers[0][0].device)
+            workspace = torch.zeros(need, dtype=torch.uint8, device=dev)
         self.workspace = workspace
 
     def run(self, check=False):

@@ -27,14 +27,17 @@ int gram_blocks_for(int64_t h);
 bool thin_fast_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
 SplitPlan thin_tn_split(int64_t N, int64_t h, int r);
 dad_status fast_thin_nn(const void*, const float*, void*, int64_t, int64_t, int, int*, int, hipStream_t, const int*);
-dad_status fast_thin_tn(const void*, const void*, float*, float*, SplitPlan, int64_t, int64_t, int, void*, int,
-                        hipStream_t, const int*);
+dad_status fast_thin_tn(const void*, const RowBlocks*, const void*, float*, float*, SplitPlan, int64_t, int64_t, int,
+                        void*, int, hipStream_t, const int*);
+bool thin_tn_dma_ok(int64_t N, int r, SplitPlan sp);
 bool thin_dma_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
 dad_status launch_panel_init(const float*, void*, void*, int64_t, int64_t, int, int*, hipStream_t);
-dad_status dma_thin_nn(const void*, const void*, void*, int64_t, int64_t, int, int, hipStream_t);
+dad_status dma_thin_nn(const void*, const RowBlocks*, const void*, void*, int64_t, int64_t, int, int, hipStream_t);
 bool rebuild_fast_ok(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
 SplitPlan rebuild_fast_split(int64_t K, int64_t h_in, int64_t h_out, int* tile);
-dad_status fast_rebuild(const void*, const void*, int64_t, int64_t, int64_t, float*, float*, SplitPlan, int, hipStream_t);
+dad_status fast_rebuild(const void*, const void*, const RowBlocks*, const RowBlocks*, int64_t, int64_t, int64_t, float*,
+                        float*, SplitPlan, int, hipStream_t);
+bool rebuild_dma_ok(int64_t K, SplitPlan sp);
 
 static SplitPlan split_rows(int64_t rows, int64_t tiles, int64_t target_blocks, int64_t min_chunk, int64_t quantum) {
     int64_t want = ceil_div(target_blocks, tiles);
@@ -218,9 +221,12 @@ static dad_status compress_args_ok(const void* A, const void* D, int64_t N, int6
 }
 
 // The launches of one compress call; every argument has been checked and the device is ready.
+// Ab / Db, when not null, give the factors as row blocks read in place (A and D are then unused); the
+// caller has checked compress_in_place().
 static dad_status compress_launch(const CompressPlan& p, const void* A, const void* D, int64_t N, int64_t h_in,
                                   int64_t h_out, dad_dtype dt, int r, int n_iter, const float* G0, float* Pt, float* Gt,
-                                  void* workspace, hipStream_t s) {
+                                  void* workspace, hipStream_t s, const RowBlocks* Ab = nullptr,
+                                  const RowBlocks* Db = nullptr) {
     char* ws = static_cast<char*>(workspace);
     int* flag = reinterpret_cast<int*>(ws + p.off_flag);
     void* V = ws + p.off_V;
@@ -237,14 +243,20 @@ static dad_status compress_launch(const CompressPlan& p, const void* A, const vo
     void* Ub = p.dma ? ws + p.off_Ub : nullptr;
 
     // V <- X * panel (N x r); the direct-to-LDS kernel takes the bf16 copy of the panel
-    auto nn = [&](const void* X, const float* panel, const void* panel_bf16, int64_t h, SplitPlan sp, int* hdr,
+    struct Factor {
+        const void* ptr;          // one allocation, or
+        const RowBlocks* blocks;  // row blocks (ptr unused)
+    };
+    const Factor FA = {A, Ab}, FD = {D, Db};
+    auto nn = [&](const Factor& X, const float* panel, const void* panel_bf16, int64_t h, SplitPlan sp, int* hdr,
                   int planes) {
-        if (p.dma) return dma_thin_nn(X, panel_bf16, V, N, h, r, planes, s);
-        return launch_thin_nn(X, panel, V, part, sp, N, h, r, dt, p.fast, hdr, planes, s);
+        if (p.dma) return dma_thin_nn(X.ptr, X.blocks, panel_bf16, V, N, h, r, planes, s);
+        return launch_thin_nn(X.ptr, panel, V, part, sp, N, h, r, dt, p.fast, hdr, planes, s);
     };
     // out (r x h) <- V^T X, with an optional bf16 copy
-    auto tn = [&](const void* X, float* out, int64_t h, SplitPlan sp, void* out_bf16, int planes) {
-        return launch_thin_tn(X, V, out, part, sp, N, h, r, dt, p.fast, out_bf16, planes, s);
+    auto tn = [&](const Factor& X, float* out, int64_t h, SplitPlan sp, void* out_bf16, int planes) {
+        if (X.blocks) return fast_thin_tn(nullptr, X.blocks, V, out, part, sp, N, h, r, out_bf16, planes, s, nullptr);
+        return launch_thin_tn(X.ptr, V, out, part, sp, N, h, r, dt, p.fast, out_bf16, planes, s);
     };
     // On the MFMA path the N x r intermediates are bf16.  V = Delta G goes as one plane.  W = A U goes
     // as two (rounded value + rounded remainder): activations with a non-zero mean (ReLU, GELU) give
@@ -259,18 +271,135 @@ static dad_status compress_launch(const CompressPlan& p, const void* A, const vo
     if (p.dma) DAD_TRY(launch_panel_init(G0, Gb, Ub, h_in, h_out, r, flag, s));
     const float* G = G0;
     for (int it = 0; it < n_iter; ++it) {
-        DAD_TRY(nn(D, G, Gb, h_out, p.nn_out, it == 0 ? flag : nullptr, PV));  // V = Delta G
-        DAD_TRY(tn(A, Ut, h_in, p.tn_in, Ub, PV));                             // U = A^T V
-        DAD_TRY(nn(A, Ut, Ub, h_in, p.nn_in, nullptr, PW));                    // W = A U
-        DAD_TRY(tn(D, Yt, h_out, p.tn_out, nullptr, PW));                      // Y = Delta^T W
+        DAD_TRY(nn(FD, G, Gb, h_out, p.nn_out, it == 0 ? flag : nullptr, PV));  // V = Delta G
+        DAD_TRY(tn(FA, Ut, h_in, p.tn_in, Ub, PV));                             // U = A^T V
+        DAD_TRY(nn(FA, Ut, Ub, h_in, p.nn_in, nullptr, PW));                    // W = A U
+        DAD_TRY(tn(FD, Yt, h_out, p.tn_out, nullptr, PW));                      // Y = Delta^T W
         // G = orth(Y): up to two Cholesky rounds for the iterate that is returned, one for the others
         DAD_TRY(launch_cholqr(Yt, Gt, h_out, r, (it + 1 == n_iter) ? 2 : 1, gram, p.gram_blocks, rinv, counter, flag, Gb,
                               s));
         G = Gt;
     }
-    DAD_TRY(nn(D, Gt, Gb, h_out, p.nn_out, nullptr, PV));  // V = Delta G
-    return tn(A, Pt, h_in, p.tn_in, nullptr, PV);          // P = A^T V
+    DAD_TRY(nn(FD, Gt, Gb, h_out, p.nn_out, nullptr, PV));  // V = Delta G
+    return tn(FA, Pt, h_in, p.tn_in, nullptr, PV);          // P = A^T V
 #undef DAD_TRY
+}
+
+// ---------------------------------------------------------------- factors given as site blocks
+
+// Checks of a site table (the rules of dad_stack_factors); *N receives the total row count.
+// With check_pointers false only S and the row counts are looked at (workspace size queries).
+static dad_status sites_ok(int S, const void* const* A_sites, const void* const* D_sites, const int64_t* rows,
+                           bool check_pointers, int64_t* N) {
+    if (!rows || (check_pointers && (!A_sites || !D_sites))) return DAD_ERR_NULL;
+    if (S < 1 || S > DAD_MAX_SITES) return DAD_ERR_SHAPE;
+    int64_t total = 0;
+    for (int s = 0; s < S; ++s) {
+        if (rows[s] < 0 || rows[s] > DAD_MAX_ROWS) return DAD_ERR_SHAPE;
+        total += rows[s];
+        if (total > DAD_MAX_ROWS) return DAD_ERR_SHAPE;
+    }
+    if (check_pointers)
+        for (int s = 0; s < S; ++s) {
+            if (rows[s] == 0) continue;
+            if (!A_sites[s] || !D_sites[s]) return DAD_ERR_NULL;
+            if (!aligned16(A_sites[s]) || !aligned16(D_sites[s])) return DAD_ERR_ALIGN;
+        }
+    *N = total;
+    return DAD_OK;
+}
+
+// The kernels that read blocks in place walk rows in whole stages of up to 256 rows.
+static bool rows_allow_blocks(int S, const int64_t* rows) {
+    int used = 0;
+    for (int s = 0; s < S; ++s) {
+        if (rows[s] == 0) continue;
+        if (rows[s] % BLOCK_ROW_QUANTUM) return false;
+        if (++used > MAX_ROW_BLOCKS) return false;
+    }
+    return used > 0;
+}
+
+static void fill_blocks(int S, const void* const* sites, const int64_t* rows, RowBlocks* b) {
+    int n = 0;
+    int64_t row = 0;
+    for (int s = 0; s < S; ++s) {
+        if (rows[s] == 0) continue;
+        b->base[n] = static_cast<const char*>(sites[s]);
+        b->first[n] = row;
+        row += rows[s];
+        ++n;
+    }
+    for (int i = n; i <= MAX_ROW_BLOCKS; ++i) b->first[i] = row;
+    for (int i = n; i < MAX_ROW_BLOCKS; ++i) b->base[i] = nullptr;
+    b->n = n;
+}
+
+// One layer of a compress call: stacked factors, or site blocks read in place, or site blocks that
+// the call first stacks behind the layer's plan in its workspace.
+struct LayerPlan {
+    int64_t N;
+    CompressPlan cp;
+    bool sites, in_place;
+    size_t off_A, off_D, total;
+};
+
+static bool compress_in_place(const CompressPlan& p, int64_t N, int r, int S, const int64_t* rows) {
+    return p.dma && thin_tn_dma_ok(N, r, p.tn_in) && thin_tn_dma_ok(N, r, p.tn_out) && rows_allow_blocks(S, rows);
+}
+
+// Shapes only (d.S, d.rows, d.N, widths); DAD_ERR_* on sizes out of range.
+static dad_status plan_layer(const dad_compress_desc& d, dad_dtype dt, int r, LayerPlan* lp) {
+    lp->sites = d.S > 0;
+    lp->N = d.N;
+    if (d.S < 0) return DAD_ERR_SHAPE;
+    if (lp->sites) {
+        const dad_status rc = sites_ok(d.S, nullptr, nullptr, d.rows, false, &lp->N);
+        if (rc != DAD_OK) return rc;
+    }
+    if (!compress_shape_ok(lp->N, d.h_in, d.h_out, r)) return DAD_ERR_SHAPE;
+    lp->cp = plan_compress(lp->N, d.h_in, d.h_out, r, dt);
+    lp->in_place = lp->sites && compress_in_place(lp->cp, lp->N, r, d.S, d.rows);
+    size_t o = align_up(lp->cp.total, 256);
+    lp->off_A = o;
+    if (lp->sites && !lp->in_place) o += align_up((size_t)lp->N * d.h_in * elem_size(dt), 256);
+    lp->off_D = o;
+    if (lp->sites && !lp->in_place) o += align_up((size_t)lp->N * d.h_out * elem_size(dt), 256);
+    lp->total = o;
+    return DAD_OK;
+}
+
+// Pointer checks of one layer (after plan_layer).
+static dad_status layer_args_ok(const dad_compress_desc& d, const LayerPlan& lp, dad_dtype dt, int r, int n_iter) {
+    if (lp.sites) {
+        int64_t N = 0;
+        const dad_status rc = sites_ok(d.S, d.A_sites, d.D_sites, d.rows, true, &N);
+        if (rc != DAD_OK) return rc;
+        if (!d.G0 || !d.Pt || !d.Gt) return DAD_ERR_NULL;
+        if (n_iter < 1) return DAD_ERR_SHAPE;
+        if (!aligned16(d.G0) || !aligned16(d.Pt) || !aligned16(d.Gt)) return DAD_ERR_ALIGN;
+        return DAD_OK;
+    }
+    return compress_args_ok(d.A, d.D, d.N, d.h_in, d.h_out, dt, r, n_iter, d.G0, d.Pt, d.Gt);
+}
+
+// The launches of one layer on stream s; ws is the layer's region (lp.total bytes).
+static dad_status launch_layer(const dad_compress_desc& d, const LayerPlan& lp, dad_dtype dt, int r, int n_iter,
+                               void* ws, hipStream_t s) {
+    if (!lp.sites)
+        return compress_launch(lp.cp, d.A, d.D, lp.N, d.h_in, d.h_out, dt, r, n_iter, d.G0, d.Pt, d.Gt, ws, s);
+    if (lp.in_place) {
+        RowBlocks a, b;
+        fill_blocks(d.S, d.A_sites, d.rows, &a);
+        fill_blocks(d.S, d.D_sites, d.rows, &b);
+        return compress_launch(lp.cp, nullptr, nullptr, lp.N, d.h_in, d.h_out, dt, r, n_iter, d.G0, d.Pt, d.Gt, ws, s, &a,
+                               &b);
+    }
+    void* A = static_cast<char*>(ws) + lp.off_A;
+    void* D = static_cast<char*>(ws) + lp.off_D;
+    const dad_status rc = launch_stack(d.S, d.A_sites, d.D_sites, d.rows, d.h_in, d.h_out, dt, A, D, s);
+    if (rc != DAD_OK) return rc;
+    return compress_launch(lp.cp, A, D, lp.N, d.h_in, d.h_out, dt, r, n_iter, d.G0, d.Pt, d.Gt, ws, s);
 }
 
 dad_status dad_compress_rank(const void* A, const void* D, int64_t N, int64_t h_in, int64_t h_out, dad_dtype dt,
@@ -304,23 +433,55 @@ dad_status dad_compress_rank_noalloc(const void* A, const void* D, int64_t N, in
     return DAD_OK;
 }
 
+size_t dad_compress_sites_workspace_bytes(int S, const int64_t* rows, int64_t h_in, int64_t h_out, int r, dad_dtype dt) {
+    if (!dtype_ok(dt) || S < 1) return 0;
+    dad_compress_desc d = {};
+    d.S = S, d.rows = rows, d.h_in = h_in, d.h_out = h_out;
+    LayerPlan lp;
+    return plan_layer(d, dt, r, &lp) == DAD_OK ? lp.total : 0;
+}
+
+dad_status dad_compress_rank_sites(int S, const void* const* A_sites, const void* const* D_sites, const int64_t* rows,
+                                   int64_t h_in, int64_t h_out, dad_dtype dt, int r, int n_iter, const float* G0,
+                                   float* Pt, float* Gt, void* workspace, size_t ws_bytes, void* stream) {
+    if (!workspace) return DAD_ERR_NULL;
+    if (!dtype_ok(dt)) return DAD_ERR_DTYPE;
+    if (S < 1) return DAD_ERR_SHAPE;
+    dad_compress_desc d = {};
+    d.S = S, d.A_sites = A_sites, d.D_sites = D_sites, d.rows = rows, d.h_in = h_in, d.h_out = h_out;
+    d.G0 = G0, d.Pt = Pt, d.Gt = Gt;
+    LayerPlan lp;
+    dad_status rc = plan_layer(d, dt, r, &lp);
+    if (rc != DAD_OK) return rc;
+    if ((rc = layer_args_ok(d, lp, dt, r, n_iter)) != DAD_OK) return rc;
+    if (!aligned16(workspace)) return DAD_ERR_ALIGN;
+    if (ws_bytes < lp.total) return DAD_ERR_WORKSPACE;
+    if ((rc = device_ready()) != DAD_OK) return rc;
+    return launch_layer(d, lp, dt, r, n_iter, workspace, (hipStream_t)stream);
+}
+
 // Layout of the grouped workspace: 256-byte group header (sticky numeric flag at +0), then one region
 // per lane, each large enough for any layer of the group.
-static size_t grouped_lane_bytes(int n, const dad_compress_desc* descs, dad_dtype dt, int r) {
+static dad_status grouped_plans(int n, const dad_compress_desc* descs, dad_dtype dt, int r, std::vector<LayerPlan>* plans,
+                                size_t* lane_bytes) {
+    plans->resize((size_t)n);
     size_t lane = 0;
     for (int i = 0; i < n; ++i) {
-        const size_t b = plan_compress(descs[i].N, descs[i].h_in, descs[i].h_out, r, dt).total;
-        if (b > lane) lane = b;
+        const dad_status rc = plan_layer(descs[i], dt, r, &(*plans)[(size_t)i]);
+        if (rc != DAD_OK) return rc;
+        if ((*plans)[(size_t)i].total > lane) lane = (*plans)[(size_t)i].total;
     }
-    return align_up(lane, 256);
+    *lane_bytes = align_up(lane, 256);
+    return DAD_OK;
 }
 
 size_t dad_compress_grouped_workspace_bytes(int n, const dad_compress_desc* descs, dad_dtype dt, int r, int lanes) {
     if (n < 1 || n > DAD_MAX_GROUP || !descs || !dtype_ok(dt) || lanes < 1 || lanes > DAD_MAX_LANES) return 0;
-    for (int i = 0; i < n; ++i)
-        if (!compress_shape_ok(descs[i].N, descs[i].h_in, descs[i].h_out, r)) return 0;
+    std::vector<LayerPlan> plans;
+    size_t lane_bytes = 0;
+    if (grouped_plans(n, descs, dt, r, &plans, &lane_bytes) != DAD_OK) return 0;
     const int used = lanes < n ? lanes : n;
-    return 256 + (size_t)used * grouped_lane_bytes(n, descs, dt, r);
+    return 256 + (size_t)used * lane_bytes;
 }
 
 dad_status dad_compress_rank_grouped(int n, const dad_compress_desc* descs, dad_dtype dt, int r, int n_iter, int lanes,
@@ -328,17 +489,16 @@ dad_status dad_compress_rank_grouped(int n, const dad_compress_desc* descs, dad_
     if (!descs || !workspace) return DAD_ERR_NULL;
     if (!dtype_ok(dt)) return DAD_ERR_DTYPE;
     if (n < 1 || n > DAD_MAX_GROUP || lanes < 1 || lanes > DAD_MAX_LANES) return DAD_ERR_SHAPE;
-    for (int i = 0; i < n; ++i) {
-        const dad_compress_desc& d = descs[i];
-        const dad_status rc = compress_args_ok(d.A, d.D, d.N, d.h_in, d.h_out, dt, r, n_iter, d.G0, d.Pt, d.Gt);
-        if (rc != DAD_OK) return rc;
-    }
+    std::vector<LayerPlan> plans;
+    size_t lane_bytes = 0;
+    dad_status rc = grouped_plans(n, descs, dt, r, &plans, &lane_bytes);
+    if (rc != DAD_OK) return rc;
+    for (int i = 0; i < n; ++i)
+        if ((rc = layer_args_ok(descs[i], plans[(size_t)i], dt, r, n_iter)) != DAD_OK) return rc;
     if (!aligned16(workspace)) return DAD_ERR_ALIGN;
     const int used = lanes < n ? lanes : n;
-    const size_t lane_bytes = grouped_lane_bytes(n, descs, dt, r);
     if (ws_bytes < 256 + (size_t)used * lane_bytes) return DAD_ERR_WORKSPACE;
-    dad_status rc = device_ready();
-    if (rc != DAD_OK) return rc;
+    if ((rc = device_ready()) != DAD_OK) return rc;
     int dev = 0;
     DAD_HIP_TRY(hipGetDevice(&dev));
     DeviceState& st = g_dev[dev];
@@ -358,9 +518,7 @@ dad_status dad_compress_rank_grouped(int n, const dad_compress_desc* descs, dad_
         const int l = i % used;
         hipStream_t s = l == 0 ? main : st.side[l - 1];
         void* lane_ws = ws + 256 + (size_t)l * lane_bytes;
-        const dad_compress_desc& d = descs[i];
-        const CompressPlan p = plan_compress(d.N, d.h_in, d.h_out, r, dt);
-        rc = compress_launch(p, d.A, d.D, d.N, d.h_in, d.h_out, dt, r, n_iter, d.G0, d.Pt, d.Gt, lane_ws, s);
+        rc = launch_layer(descs[i], plans[(size_t)i], dt, r, n_iter, lane_ws, s);
         if (rc != DAD_OK) break;
         hipLaunchKernelGGL(k_latch_flag, dim3(1), dim3(1), 0, s, (const int*)lane_ws, group_flag);
         if (hipGetLastError() != hipSuccess) {
@@ -399,6 +557,66 @@ dad_status dad_reconstruct_grad(const void* L, const void* R, int64_t K, int64_t
     if (ws_bytes < p.total) return DAD_ERR_WORKSPACE;
     if (const dad_status ready = device_ready(); ready != DAD_OK) return ready;
     return launch_rebuild(L, R, K, h_in, h_out, dt, G, static_cast<float*>(workspace), p, (hipStream_t)stream);
+}
+
+// Full rebuild on site blocks: in place on the direct-to-LDS bf16 kernel, else stacked into the
+// workspace behind the split slabs first.
+struct RebuildSitesPlan {
+    int64_t N;
+    RebuildPlan rp;
+    bool in_place;
+    size_t off_A, off_D, total;
+};
+
+static dad_status plan_rebuild_sites(int S, const int64_t* rows, int64_t h_in, int64_t h_out, dad_dtype dt,
+                                     RebuildSitesPlan* p) {
+    const dad_status rc = sites_ok(S, nullptr, nullptr, rows, false, &p->N);
+    if (rc != DAD_OK) return rc;
+    if (!rebuild_shape_ok(p->N, h_in, h_out)) return DAD_ERR_SHAPE;
+    p->rp = plan_rebuild(p->N, h_in, h_out, dt);
+    p->in_place = p->rp.fast && rebuild_dma_ok(p->N, p->rp.split) && rows_allow_blocks(S, rows);
+    size_t o = align_up(p->rp.total, 256);
+    p->off_A = o;
+    if (!p->in_place) o += align_up((size_t)p->N * h_in * elem_size(dt), 256);
+    p->off_D = o;
+    if (!p->in_place) o += align_up((size_t)p->N * h_out * elem_size(dt), 256);
+    p->total = o;
+    return DAD_OK;
+}
+
+size_t dad_reconstruct_sites_workspace_bytes(int S, const int64_t* rows, int64_t h_in, int64_t h_out, dad_dtype dt) {
+    if (!dtype_ok(dt)) return 0;
+    RebuildSitesPlan p;
+    return plan_rebuild_sites(S, rows, h_in, h_out, dt, &p) == DAD_OK ? p.total : 0;
+}
+
+dad_status dad_reconstruct_grad_sites(int S, const void* const* A_sites, const void* const* D_sites, const int64_t* rows,
+                                      int64_t h_in, int64_t h_out, dad_dtype dt, float* G, void* workspace,
+                                      size_t ws_bytes, void* stream) {
+    if (!G) return DAD_ERR_NULL;
+    if (!dtype_ok(dt)) return DAD_ERR_DTYPE;
+    RebuildSitesPlan p;
+    dad_status rc = plan_rebuild_sites(S, rows, h_in, h_out, dt, &p);
+    if (rc != DAD_OK) return rc;
+    int64_t N = 0;
+    if ((rc = sites_ok(S, A_sites, D_sites, rows, true, &N)) != DAD_OK) return rc;
+    if (p.total > 0 && !workspace) return DAD_ERR_NULL;
+    if (!aligned16(G) || (workspace && !aligned16(workspace))) return DAD_ERR_ALIGN;
+    if (ws_bytes < p.total) return DAD_ERR_WORKSPACE;
+    if ((rc = device_ready()) != DAD_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    char* ws = static_cast<char*>(workspace);
+    if (p.in_place) {
+        RowBlocks a, b;
+        fill_blocks(S, A_sites, rows, &a);
+        fill_blocks(S, D_sites, rows, &b);
+        return fast_rebuild(nullptr, nullptr, &a, &b, p.N, h_in, h_out, G, reinterpret_cast<float*>(ws), p.rp.split,
+                            p.rp.tile, s);
+    }
+    void* A = ws + p.off_A;
+    void* D = ws + p.off_D;
+    if ((rc = launch_stack(S, A_sites, D_sites, rows, h_in, h_out, dt, A, D, s)) != DAD_OK) return rc;
+    return launch_rebuild(A, D, p.N, h_in, h_out, dt, G, reinterpret_cast<float*>(ws), p.rp, s);
 }
 
 // Checks of one job of the grouped rebuild; *plan receives its plan.
@@ -493,13 +711,13 @@ dad_status launch_thin_nn(const void* X, const float* Pt, void* out, float* part
 dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp, int64_t N,
                           int64_t h, int r, dad_dtype dt, bool fast, void* out_bf16, int planes, hipStream_t s,
                           const int* skip) {
-    if (fast) return fast_thin_tn(X, V, out_t, partials, sp, N, h, r, out_bf16, planes, s, skip);
+    if (fast) return fast_thin_tn(X, nullptr, V, out_t, partials, sp, N, h, r, out_bf16, planes, s, skip);
     return gen_thin_tn(X, V, out_t, partials, sp, N, h, r, dt, s, skip);
 }
 
 dad_status launch_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt,
                           float* G, float* partials, const RebuildPlan& plan, hipStream_t s) {
-    if (plan.fast) return fast_rebuild(L, R, K, h_in, h_out, G, partials, plan.split, plan.tile, s);
+    if (plan.fast) return fast_rebuild(L, R, nullptr, nullptr, K, h_in, h_out, G, partials, plan.split, plan.tile, s);
     if (plan.f32) return launch_rebuild_f32(1, &L, &R, &G, &K, &h_in, &h_out, &plan.split, &partials, s);
     return gen_rebuild(L, R, K, h_in, h_out, dt, G, partials, plan.split, s);
 }

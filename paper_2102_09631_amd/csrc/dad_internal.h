@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "dad.h"
 
 namespace dad {
@@ -72,6 +74,46 @@ __device__ __forceinline__ void interleave_reads_mfma() {
         }
         interleave_reads_mfma<NR, NM, READ_FIRST, I + 1>();
     }
+}
+
+// A row-major matrix given as n contiguous row blocks (the sites' blocks in stacking order) instead
+// of one allocation.  Passed to kernels by value; first[n] is the total row count.  Kernels that take
+// it walk rows in whole stages, so every block's row count must be a multiple of BLOCK_ROW_QUANTUM.
+constexpr int MAX_ROW_BLOCKS = 32;
+constexpr int64_t BLOCK_ROW_QUANTUM = 256;
+struct RowBlocks {
+    const char* base[MAX_ROW_BLOCKS];
+    int64_t first[MAX_ROW_BLOCKS + 1];
+    int n;
+};
+
+// Where a kernel's walk over rows stands: the block it is in and the row at which that block ends.
+struct RowCursor {
+    int blk;
+    int64_t end;
+};
+
+// Address of row `row` (pitch in bytes); sets the cursor.  One allocation: a single endless block.
+__device__ __forceinline__ const char* row_address(const uint16_t* X, int64_t row, int64_t pitch, RowCursor& c) {
+    c.blk = 0;
+    c.end = INT64_MAX;
+    return reinterpret_cast<const char*>(X) + row * pitch;
+}
+__device__ __forceinline__ const char* row_address(const RowBlocks& X, int64_t row, int64_t pitch, RowCursor& c) {
+    int b = 0;
+    while (b + 1 < X.n && X.first[b + 1] <= row) ++b;
+    c.blk = b;
+    c.end = X.first[b + 1];
+    return X.base[b] + (row - X.first[b]) * pitch;
+}
+// A pointer that has walked to the end of block c.blk continues in the next block after adding this.
+__device__ __forceinline__ int64_t block_jump(const uint16_t*, int64_t, RowCursor&) { return 0; }
+__device__ __forceinline__ int64_t block_jump(const RowBlocks& X, int64_t pitch, RowCursor& c) {
+    const int b = c.blk;
+    const int64_t jump = (X.base[b + 1] - X.base[b]) - (X.first[b + 1] - X.first[b]) * pitch;
+    c.blk = b + 1;
+    c.end = X.first[b + 2];
+    return jump;
 }
 
 inline size_t elem_size(dad_dtype dt) { return dt == DAD_BF16 ? 2 : 4; }

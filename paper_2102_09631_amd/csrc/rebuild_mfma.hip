@@ -183,9 +183,11 @@ constexpr int DMA_LOADS = 4;  // 16-byte loads per thread per stage, for both ti
 // kernel for large gradients.  T = 128 with 2 x 2 waves (two workgroups per CU) serves gradients with
 // few 256-tiles, where filling the chip would otherwise take so many K chunks that their fp32
 // partial slabs outweigh the operand reads.
-template <int T, int WM, int WN>
-__global__ __launch_bounds__(64 * WM * WN) void k_rebuild_bf16_dma(const bf16_t* __restrict__ L,
-                                                                  const bf16_t* __restrict__ R,
+// SRC is `const bf16_t*` (operands in one allocation each) or RowBlocks (the sites' blocks in
+// place, the same row split for both operands, every block a multiple of 256 rows): a K chunk may
+// span blocks, and the operand pointers jump at a block's end.
+template <int T, int WM, int WN, typename SRC>
+__global__ __launch_bounds__(64 * WM * WN) void k_rebuild_bf16_dma(const SRC L, const SRC R,
                                                                   float* __restrict__ out, int64_t K, int h_in,
                                                                   int h_out, int64_t chunk, int tiles_m,
                                                                   int tiles_n, int total) {
@@ -222,14 +224,18 @@ __global__ __launch_bounds__(64 * WM * WN) void k_rebuild_bf16_dma(const bf16_t*
     const int nk = (int)((kend - kbeg) / rb::BK);  // host guarantees whole tiles
 
     // this lane's two rows per operand tile: row = 2*RPI*wave + RPI*i + lane/CPR, LDS chunk position lane%CPR
+    RowCursor cur_l, cur_r;
+    const char* l0 = row_address(L, kbeg, (int64_t)h_in * 2, cur_l);
+    const char* r0 = row_address(R, kbeg, (int64_t)h_out * 2, cur_r);
+    int64_t row_next = kbeg;  // first row of the next tile to be issued
     const char* gl[2];
     const char* gr[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int row = 2 * RPI * wave + RPI * i + lane / CPR;
         const int c = (lane % CPR) ^ ((row & 3) << 2);
-        gl[i] = reinterpret_cast<const char*>(L + (kbeg + row) * (int64_t)h_in + p0 + c * 8);
-        gr[i] = reinterpret_cast<const char*>(R + (kbeg + row) * (int64_t)h_out + q0 + c * 8);
+        gl[i] = l0 + (row * (int64_t)h_in + p0 + c * 8) * 2;
+        gr[i] = r0 + (row * (int64_t)h_out + q0 + c * 8) * 2;
     }
     const int64_t adv_l = (int64_t)rb::BK * h_in * 2, adv_r = (int64_t)rb::BK * h_out * 2;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
@@ -237,6 +243,18 @@ __global__ __launch_bounds__(64 * WM * WN) void k_rebuild_bf16_dma(const bf16_t*
     auto issue = [&](int stage) {  // loads the next tile in sequence into ring slot `stage`
         // wave-uniform by construction; readfirstlane lets the compiler keep it in a scalar register
         const uint32_t base = __builtin_amdgcn_readfirstlane(lds0 + stage * STAGEB + (2 * RPI * wave) * ROWB);
+        if constexpr (!std::is_pointer<SRC>::value) {
+            if (row_next == cur_l.end) {
+                const int64_t jl = block_jump(L, (int64_t)h_in * 2, cur_l);
+                const int64_t jr = block_jump(R, (int64_t)h_out * 2, cur_r);
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    gl[i] += jl;
+                    gr[i] += jr;
+                }
+            }
+            row_next += rb::BK;
+        }
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             dma16(gl[i], base + RPI * i * ROWB);
@@ -380,25 +398,35 @@ SplitPlan rebuild_fast_split(int64_t K, int64_t h_in, int64_t h_out, int* tile_o
 }
 
 template <int T, int WM, int WN>
-static dad_status launch_rebuild_dma(const void* L, const void* R, float* dst, int64_t K, int64_t h_in, int64_t h_out,
-                                     SplitPlan sp, hipStream_t s) {
+static dad_status launch_rebuild_dma(const void* L, const void* R, const RowBlocks* lb, const RowBlocks* rbk, float* dst,
+                                     int64_t K, int64_t h_in, int64_t h_out, SplitPlan sp, hipStream_t s) {
     const int lds = rb::DMA_STAGES * 2 * rb::BK * T * 2;
     const int tm = (int)(h_in / T), tn = (int)(h_out / T);
     const int total = tm * tn * sp.splits;
     ProfScope prof(KID_REBUILD_BF16_DMA, s);
-    hipLaunchKernelGGL((k_rebuild_bf16_dma<T, WM, WN>), dim3((unsigned)total), dim3(64 * WM * WN), lds, s, (const bf16_t*)L,
-                       (const bf16_t*)R, dst, K, (int)h_in, (int)h_out, sp.chunk, tm, tn, total);
+    if (lb)
+        hipLaunchKernelGGL((k_rebuild_bf16_dma<T, WM, WN, RowBlocks>), dim3((unsigned)total), dim3(64 * WM * WN), lds, s,
+                           *lb, *rbk, dst, K, (int)h_in, (int)h_out, sp.chunk, tm, tn, total);
+    else
+        hipLaunchKernelGGL((k_rebuild_bf16_dma<T, WM, WN, const bf16_t*>), dim3((unsigned)total), dim3(64 * WM * WN), lds,
+                           s, (const bf16_t*)L, (const bf16_t*)R, dst, K, (int)h_in, (int)h_out, sp.chunk, tm, tn, total);
     DAD_LAUNCH_CHECK();
     return DAD_OK;
 }
 
-dad_status fast_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, float* G, float* partials,
-                        SplitPlan sp, int tile, hipStream_t s) {
+// True when fast_rebuild takes the direct-to-LDS kernel.
+bool rebuild_dma_ok(int64_t K, SplitPlan sp) { return K % rb::BK == 0 && sp.chunk % rb::BK == 0; }
+
+// lb / rbk, when not null, give both operands as row blocks (L and R are then unused); only the
+// direct-to-LDS kernel reads blocks.
+dad_status fast_rebuild(const void* L, const void* R, const RowBlocks* lb, const RowBlocks* rbk, int64_t K, int64_t h_in,
+                        int64_t h_out, float* G, float* partials, SplitPlan sp, int tile, hipStream_t s) {
     float* dst = sp.splits == 1 ? G : partials;
     dad_status rc;
-    if (K % rb::BK == 0 && sp.chunk % rb::BK == 0) {
-        rc = tile == 128 ? launch_rebuild_dma<128, 2, 2>(L, R, dst, K, h_in, h_out, sp, s)
-                         : launch_rebuild_dma<256, 2, 4>(L, R, dst, K, h_in, h_out, sp, s);
+    if ((lb != nullptr) != (rbk != nullptr) || (lb && !rebuild_dma_ok(K, sp))) return DAD_ERR_SHAPE;
+    if (rebuild_dma_ok(K, sp)) {
+        rc = tile == 128 ? launch_rebuild_dma<128, 2, 2>(L, R, lb, rbk, dst, K, h_in, h_out, sp, s)
+                         : launch_rebuild_dma<256, 2, 4>(L, R, lb, rbk, dst, K, h_in, h_out, sp, s);
         if (rc != DAD_OK) return rc;
     } else {  // ragged K: register-staged kernel, 256-tiles (the plan never picks 128-tiles here)
         const int lds = rb::NSTAGE * rb::STAGEB;
@@ -414,8 +442,10 @@ dad_status fast_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, i
 }
 
 dad_status rebuild_prepare_device() {
-    DAD_HIP_TRY(set_max_lds((k_rebuild_bf16_dma<256, 2, 4>), rb::DMA_STAGES * 2 * rb::BK * 256 * 2));
-    DAD_HIP_TRY(set_max_lds((k_rebuild_bf16_dma<128, 2, 2>), rb::DMA_STAGES * 2 * rb::BK * 128 * 2));
+    DAD_HIP_TRY(set_max_lds((k_rebuild_bf16_dma<256, 2, 4, const bf16_t*>), rb::DMA_STAGES * 2 * rb::BK * 256 * 2));
+    DAD_HIP_TRY(set_max_lds((k_rebuild_bf16_dma<128, 2, 2, const bf16_t*>), rb::DMA_STAGES * 2 * rb::BK * 128 * 2));
+    DAD_HIP_TRY(set_max_lds((k_rebuild_bf16_dma<256, 2, 4, RowBlocks>), rb::DMA_STAGES * 2 * rb::BK * 256 * 2));
+    DAD_HIP_TRY(set_max_lds((k_rebuild_bf16_dma<128, 2, 2, RowBlocks>), rb::DMA_STAGES * 2 * rb::BK * 128 * 2));
     DAD_HIP_TRY(set_max_lds(k_rebuild_bf16, rb::NSTAGE * rb::STAGEB));
     return DAD_OK;
 }

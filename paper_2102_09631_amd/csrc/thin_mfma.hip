@@ -187,8 +187,10 @@ __global__ __launch_bounds__(256) void k_thin_nn_bf16(const bf16_t* __restrict__
 // which makes the 16-byte fragment reads of 16 consecutive rows hit 16 distinct bank groups; the
 // XOR is applied on the global side of the load.
 // ------------------------------------------------------------------------------------------------
-template <int RP, int W, int NS>
-__global__ __launch_bounds__(64 * W) void k_thin_nn_bf16_dma(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Pb,
+// SRC is `const bf16_t*` (one allocation) or RowBlocks (the sites' blocks in place; a workgroup's
+// rows lie in one block because every block holds a multiple of 256 rows).
+template <int RP, int W, int NS, typename SRC>
+__global__ __launch_bounds__(64 * W) void k_thin_nn_bf16_dma(const SRC X, const bf16_t* __restrict__ Pb,
                                                             bf16_t* __restrict__ V, int64_t N, int h, int r, int nt,
                                                             int planes) {
     constexpr int JT = RP / 32, RT = 32 * W, ROWB = 128;
@@ -203,12 +205,14 @@ __global__ __launch_bounds__(64 * W) void k_thin_nn_bf16_dma(const bf16_t* __res
     // every workgroup starts its walk over the contraction columns at its own stage (see k_thin_nn_bf16)
     int kidx = (int)((blockIdx.x * 5u) % (unsigned)nk);
 
+    RowCursor cur;
+    const char* x0 = row_address(X, n0, (int64_t)h * 2, cur);
     const char* gx[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int row = 32 * wave + 8 * i + (lane >> 3);
         const int c = (lane & 7) ^ ((row >> 1) & 7);
-        gx[i] = reinterpret_cast<const char*>(X + (n0 + row) * (int64_t)h) + c * 16;
+        gx[i] = x0 + row * (int64_t)h * 2 + c * 16;
     }
     const char* gp[PL];
     int pi[PL];
@@ -456,8 +460,9 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16(const bf16_t* __restrict__
 // of three slots, so two tiles per workgroup are always in flight and two workgroups share a CU.
 // The swizzle of the X tile is applied on the global side, as in the rebuild kernel.
 // ------------------------------------------------------------------------------------------------
-template <int R, int PW, int BK, int NV>
-__global__ __launch_bounds__(256) void k_thin_tn_bf16_dma(const bf16_t* __restrict__ X, const bf16_t* __restrict__ V,
+// SRC as in k_thin_nn_bf16_dma; a row chunk may span several blocks, the walk jumps at their ends.
+template <int R, int PW, int BK, int NV, typename SRC>
+__global__ __launch_bounds__(256) void k_thin_tn_bf16_dma(const SRC X, const bf16_t* __restrict__ V,
                                                           float* __restrict__ part, int64_t N, int h,
                                                           int64_t chunk_rows, int strips, int splits, int nt) {
     constexpr int JT = R > 32 ? 2 : 1;
@@ -494,12 +499,15 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16_dma(const bf16_t* __restri
     const int nk = (int)((nend - nbeg) / BK);
 
     // X: load i of this wave covers tile rows (wave*XL + i)*RPL .. ; lane -> row += lane/CPR, LDS chunk lane%CPR
+    RowCursor cur;
+    const char* x0 = row_address(X, nbeg, (int64_t)h * 2, cur);
+    int64_t row_next = nbeg;  // first row of the next tile to be issued
     const char* gx[XL];
 #pragma unroll
     for (int i = 0; i < XL; ++i) {
         const int row = (wave * XL + i) * RPL + lane / CPR;
         const int c = (lane % CPR) ^ ((row & 3) << 2);
-        gx[i] = reinterpret_cast<const char*>(X + (nbeg + row) * (int64_t)h + p0 + c * 8);
+        gx[i] = x0 + (row * (int64_t)h + p0 + c * 8) * 2;
     }
     // V: a tile is BK*R*2 contiguous bytes of each of the NV planes (N*R elements apart); load i of
     // this wave covers the 1 KiB piece vi[i] of every plane
@@ -517,6 +525,14 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16_dma(const bf16_t* __restri
 
     auto issue = [&](int stage) {
         const uint32_t base = lds0 + stage * STAGEB;
+        if constexpr (!std::is_pointer<SRC>::value) {
+            if (row_next == cur.end) {
+                const int64_t jump = block_jump(X, (int64_t)h * 2, cur);
+#pragma unroll
+                for (int i = 0; i < XL; ++i) gx[i] += jump;
+            }
+            row_next += BK;
+        }
 #pragma unroll
         for (int i = 0; i < XL; ++i) {
             if (nt)
@@ -660,23 +676,31 @@ constexpr int nn_dma_lds(int rp, int w, int ns) { return ns * (32 * w * 128 + rp
 constexpr int tn_dma_lds(int r, int pw, int bk, int nv) { return 3 * (bk * pw * 2 + nv * bk * r * 2 + 256); }
 
 template <int RP, int W, int NS>
-static dad_status dma_thin_nn_cfg(const void* X, const void* Pb, void* out, int64_t N, int64_t h, int r, int planes,
-                                  hipStream_t s) {
+static dad_status dma_thin_nn_cfg(const void* X, const RowBlocks* xb, const void* Pb, void* out, int64_t N, int64_t h,
+                                  int r, int planes, hipStream_t s) {
     const int lds = nn_dma_lds(RP, W, NS);
-    hipLaunchKernelGGL((k_thin_nn_bf16_dma<RP, W, NS>), dim3((unsigned)(N / (32 * W))), dim3(64 * W), lds, s,
-                       (const bf16_t*)X, (const bf16_t*)Pb, (bf16_t*)out, N, (int)h, r, stream_once(N, h) ? 1 : 0, planes);
+    const dim3 grid((unsigned)(N / (32 * W))), block(64 * W);
+    const int nt = stream_once(N, h) ? 1 : 0;
+    if (xb)
+        hipLaunchKernelGGL((k_thin_nn_bf16_dma<RP, W, NS, RowBlocks>), grid, block, lds, s, *xb, (const bf16_t*)Pb,
+                           (bf16_t*)out, N, (int)h, r, nt, planes);
+    else
+        hipLaunchKernelGGL((k_thin_nn_bf16_dma<RP, W, NS, const bf16_t*>), grid, block, lds, s, (const bf16_t*)X,
+                           (const bf16_t*)Pb, (bf16_t*)out, N, (int)h, r, nt, planes);
     DAD_LAUNCH_CHECK();
     return DAD_OK;
 }
 
 // Rows per workgroup: 256 (eight waves) when that still gives one workgroup per CU, fewer for
 // shorter factors so that the chip stays filled (a site's 8192 rows: 256 single-wave workgroups).
-dad_status dma_thin_nn(const void* X, const void* Pb, void* out, int64_t N, int64_t h, int r, int planes,
-                       hipStream_t s) {
+// xb, when not null, gives X as row blocks (X itself is then unused).
+dad_status dma_thin_nn(const void* X, const RowBlocks* xb, const void* Pb, void* out, int64_t N, int64_t h, int r,
+                       int planes, hipStream_t s) {
     ProfScope prof(KID_THIN_NN_BF16, s);
     const int64_t want = 256;  // workgroups
 #define DAD_NN_W(W) \
-    (r <= 32 ? dma_thin_nn_cfg<32, W, 3>(X, Pb, out, N, h, r, planes, s) : dma_thin_nn_cfg<64, W, 3>(X, Pb, out, N, h, r, planes, s))
+    (r <= 32 ? dma_thin_nn_cfg<32, W, 3>(X, xb, Pb, out, N, h, r, planes, s) \
+             : dma_thin_nn_cfg<64, W, 3>(X, xb, Pb, out, N, h, r, planes, s))
     if (N / 256 >= want) return DAD_NN_W(8);
     if (N / 128 >= want) return DAD_NN_W(4);
     if (N / 64 >= want) return DAD_NN_W(2);
@@ -684,20 +708,33 @@ dad_status dma_thin_nn(const void* X, const void* Pb, void* out, int64_t N, int6
 #undef DAD_NN_W
 }
 
-dad_status fast_thin_tn(const void* X, const void* V, float* out_t, float* partials, SplitPlan sp, int64_t N, int64_t h,
-                        int r, void* out_bf16, int planes, hipStream_t s, const int* skip) {
+// True when fast_thin_tn (without a skip word) takes the direct-to-LDS kernel.
+bool thin_tn_dma_ok(int64_t N, int r, SplitPlan sp) {
+    return (r == 16 || r == 32 || r == 64) && N % tn::BK == 0 && sp.chunk % tn::BK == 0;
+}
+
+// xb, when not null, gives X as row blocks (X itself is then unused); only the direct-to-LDS kernel
+// reads blocks, so the caller has checked thin_tn_dma_ok and passes no skip word.
+dad_status fast_thin_tn(const void* X, const RowBlocks* xb, const void* V, float* out_t, float* partials, SplitPlan sp,
+                        int64_t N, int64_t h, int r, void* out_bf16, int planes, hipStream_t s, const int* skip) {
     float* dst = sp.splits == 1 ? out_t : partials;
-    if (!skip && (r == 16 || r == 32 || r == 64) && N % tn::BK == 0 && sp.chunk % tn::BK == 0) {
+    if (xb && (skip || !thin_tn_dma_ok(N, r, sp))) return DAD_ERR_SHAPE;
+    if (!skip && thin_tn_dma_ok(N, r, sp)) {
         ProfScope prof(KID_THIN_TN_BF16, s);
         const int pw = thin_tn_pw(h);
         const int bk = pw == 128 ? 64 : 32;
         const int lds = tn_dma_lds(r, pw, bk, planes);
         const int strips = (int)(h / pw);
-#define DAD_TN_LAUNCH_NV(RR, PP, BB, NV)                                                                              \
-    do {                                                                                                              \
-        hipLaunchKernelGGL((k_thin_tn_bf16_dma<RR, PP, BB, NV>), dim3((unsigned)(strips * sp.splits)), dim3(256), lds, s, \
-                           (const bf16_t*)X, (const bf16_t*)V, dst, N, (int)h, sp.chunk, strips, sp.splits,           \
-                           stream_once(N, h) ? 1 : 0);                                                                \
+#define DAD_TN_LAUNCH_NV(RR, PP, BB, NV)                                                                          \
+    do {                                                                                                          \
+        const dim3 grid((unsigned)(strips * sp.splits));                                                          \
+        const int nt = stream_once(N, h) ? 1 : 0;                                                                 \
+        if (xb)                                                                                                   \
+            hipLaunchKernelGGL((k_thin_tn_bf16_dma<RR, PP, BB, NV, RowBlocks>), grid, dim3(256), lds, s, *xb,     \
+                               (const bf16_t*)V, dst, N, (int)h, sp.chunk, strips, sp.splits, nt);                \
+        else                                                                                                      \
+            hipLaunchKernelGGL((k_thin_tn_bf16_dma<RR, PP, BB, NV, const bf16_t*>), grid, dim3(256), lds, s,      \
+                               (const bf16_t*)X, (const bf16_t*)V, dst, N, (int)h, sp.chunk, strips, sp.splits, nt); \
     } while (0)
 #define DAD_TN_LAUNCH(RR, PP, BB)                  \
     do {                                           \
@@ -743,13 +780,17 @@ dad_status fast_thin_tn(const void* X, const void* V, float* out_t, float* parti
 // Once per device: the direct-to-LDS kernels use more than the 64 KiB of dynamic LDS a kernel gets
 // without asking.
 dad_status thin_prepare_device() {
-#define DAD_NN_ATTR(RP, W) DAD_HIP_TRY(set_max_lds((k_thin_nn_bf16_dma<RP, W, 3>), nn_dma_lds(RP, W, 3)))
+#define DAD_NN_ATTR(RP, W)                                                                             \
+    DAD_HIP_TRY(set_max_lds((k_thin_nn_bf16_dma<RP, W, 3, const bf16_t*>), nn_dma_lds(RP, W, 3))); \
+    DAD_HIP_TRY(set_max_lds((k_thin_nn_bf16_dma<RP, W, 3, RowBlocks>), nn_dma_lds(RP, W, 3)))
     DAD_NN_ATTR(32, 1); DAD_NN_ATTR(32, 2); DAD_NN_ATTR(32, 4); DAD_NN_ATTR(32, 8);
     DAD_NN_ATTR(64, 1); DAD_NN_ATTR(64, 2); DAD_NN_ATTR(64, 4); DAD_NN_ATTR(64, 8);
 #undef DAD_NN_ATTR
-#define DAD_TN_ATTR(R, PW, BK)                                                                   \
-    DAD_HIP_TRY(set_max_lds((k_thin_tn_bf16_dma<R, PW, BK, 1>), tn_dma_lds(R, PW, BK, 1))); \
-    DAD_HIP_TRY(set_max_lds((k_thin_tn_bf16_dma<R, PW, BK, 2>), tn_dma_lds(R, PW, BK, 2)))
+#define DAD_TN_ATTR(R, PW, BK)                                                                              \
+    DAD_HIP_TRY(set_max_lds((k_thin_tn_bf16_dma<R, PW, BK, 1, const bf16_t*>), tn_dma_lds(R, PW, BK, 1))); \
+    DAD_HIP_TRY(set_max_lds((k_thin_tn_bf16_dma<R, PW, BK, 2, const bf16_t*>), tn_dma_lds(R, PW, BK, 2))); \
+    DAD_HIP_TRY(set_max_lds((k_thin_tn_bf16_dma<R, PW, BK, 1, RowBlocks>), tn_dma_lds(R, PW, BK, 1)));     \
+    DAD_HIP_TRY(set_max_lds((k_thin_tn_bf16_dma<R, PW, BK, 2, RowBlocks>), tn_dma_lds(R, PW, BK, 2)))
     DAD_TN_ATTR(16, 128, 64); DAD_TN_ATTR(32, 128, 64); DAD_TN_ATTR(64, 128, 64);
     DAD_TN_ATTR(16, 256, 32); DAD_TN_ATTR(32, 256, 32); DAD_TN_ATTR(64, 256, 32);
 #undef DAD_TN_ATTR

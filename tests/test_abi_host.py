@@ -169,6 +169,80 @@ def test_grouped_compress_rejects_bad_arguments_on_host(lib):
     assert lib.dad_compress_grouped_workspace_bytes(2, good, dad.DAD_F32, 4, 9) == 0
 
 
+def test_site_calls_reject_bad_arguments_and_size_their_workspace_on_host(lib):
+    p = 0x1000
+    vp, i64 = C.c_void_p, C.c_int64
+
+    def tables(rows, ptr=p):
+        S = len(rows)
+        return S, (vp * S)(*[ptr if n else None for n in rows]), (vp * S)(*[ptr if n else None for n in rows]), \
+            (i64 * S)(*rows)
+
+    def compress(rows, hi=256, ho=384, dt=dad.DAD_BF16, r=32, it=2, G0=p, Pt=p, Gt=p, w=p, wb=1 << 40, ptr=p):
+        S, pa, pd, pr = tables(rows, ptr)
+        return lib.dad_compress_rank_sites(S, pa, pd, pr, hi, ho, dt, r, it, G0, Pt, Gt, w, wb, None)
+
+    def rebuild(rows, hi=256, ho=384, dt=dad.DAD_BF16, G=p, w=p, wb=1 << 40, ptr=p):
+        S, pa, pd, pr = tables(rows, ptr)
+        return lib.dad_reconstruct_grad_sites(S, pa, pd, pr, hi, ho, dt, G, w, wb, None)
+
+    rows = [512, 0, 1024]
+    assert compress(rows, w=None) == dad.DAD_ERR_NULL
+    assert compress(rows, G0=None) == dad.DAD_ERR_NULL
+    assert compress(rows, dt=9) == dad.DAD_ERR_DTYPE
+    assert compress(rows, r=65) == dad.DAD_ERR_SHAPE
+    assert compress(rows, it=0) == dad.DAD_ERR_SHAPE
+    assert compress([0, 0]) == dad.DAD_ERR_SHAPE                       # no rows at all
+    assert compress([512, -1]) == dad.DAD_ERR_SHAPE
+    assert compress(rows, ptr=p + 8) == dad.DAD_ERR_ALIGN
+    assert lib.dad_compress_rank_sites(0, None, None, None, 256, 384, dad.DAD_BF16, 32, 2, p, p, p, p, 1 << 40,
+                                       None) == dad.DAD_ERR_SHAPE
+    S, pa, pd, pr = tables(rows)
+    assert lib.dad_compress_rank_sites(S, None, pd, pr, 256, 384, dad.DAD_BF16, 32, 2, p, p, p, p, 1 << 40,
+                                       None) == dad.DAD_ERR_NULL
+    assert rebuild(rows, G=None) == dad.DAD_ERR_NULL
+    assert rebuild(rows, dt=9) == dad.DAD_ERR_DTYPE
+    assert rebuild([0]) == dad.DAD_ERR_SHAPE
+    assert rebuild(rows, ptr=p + 4) == dad.DAD_ERR_ALIGN
+
+    def cbytes(rows, hi=256, ho=384, r=32, dt=dad.DAD_BF16):
+        return lib.dad_compress_sites_workspace_bytes(len(rows), (i64 * len(rows))(*rows), hi, ho, r, dt)
+
+    def rbytes(rows, hi=256, ho=384, dt=dad.DAD_BF16):
+        return lib.dad_reconstruct_sites_workspace_bytes(len(rows), (i64 * len(rows))(*rows), hi, ho, dt)
+
+    def up(x):
+        return (x + 255) // 256 * 256
+
+    # blocks of whole 256-row multiples on the direct-to-LDS path: no room for a stacked copy
+    assert cbytes(rows) == up(lib.dad_compress_workspace_bytes(1536, 256, 384, 32, dad.DAD_BF16))
+    assert rbytes([4096, 4096]) == up(lib.dad_reconstruct_workspace_bytes(8192, 256, 384, dad.DAD_BF16))
+    # a ragged site, a rank the direct-to-LDS kernel is not built for, fp32, or too many sites: stacked copy included
+    stacked = 1536 * (256 + 384) * 2
+    assert cbytes([500, 12, 1024]) == up(lib.dad_compress_workspace_bytes(1536, 256, 384, 32, dad.DAD_BF16)) + stacked
+    assert cbytes(rows, r=24) == up(lib.dad_compress_workspace_bytes(1536, 256, 384, 24, dad.DAD_BF16)) + stacked
+    assert cbytes(rows, dt=dad.DAD_F32) == up(lib.dad_compress_workspace_bytes(1536, 256, 384, 32, dad.DAD_F32)) + 2 * stacked
+    many = [256] * 40
+    assert cbytes(many) == up(lib.dad_compress_workspace_bytes(10240, 256, 384, 32, dad.DAD_BF16)) + 10240 * 640 * 2
+    assert rbytes([4000, 4192]) == up(lib.dad_reconstruct_workspace_bytes(8192, 256, 384, dad.DAD_BF16)) + 8192 * 640 * 2
+    assert cbytes([0, 0]) == 0 and rbytes([0]) == 0 and cbytes(rows, r=0) == 0
+    need = cbytes(rows)
+    assert compress(rows, wb=need - 1) == dad.DAD_ERR_WORKSPACE
+    assert rebuild([4000, 4192], wb=rbytes([4000, 4192]) - 1) == dad.DAD_ERR_WORKSPACE
+
+    # a grouped layer given as sites is checked and sized the same way
+    D = dad.CompressDesc
+    S, pa, pd, pr = tables(rows)
+    descs = (D * 2)(D(p, p, p, p, p, 512, 256, 384), D(None, None, p, p, p, 0, 256, 384, S, pa, pd, pr))
+    need = lib.dad_compress_grouped_workspace_bytes(2, descs, dad.DAD_BF16, 32, 2)
+    assert need == 256 + 2 * cbytes(rows)
+    assert lib.dad_compress_rank_grouped(2, descs, dad.DAD_BF16, 32, 2, 2, p, need - 1, None) == dad.DAD_ERR_WORKSPACE
+    bad = (D * 1)(D(None, None, p, p, p, 0, 256, 384, S, None, pd, pr))
+    assert lib.dad_compress_rank_grouped(1, bad, dad.DAD_BF16, 32, 2, 1, p, 1 << 40, None) == dad.DAD_ERR_NULL
+    bad = (D * 1)(D(p, p, p, p, p, 512, 256, 384, -1, pa, pd, pr))
+    assert lib.dad_compress_rank_grouped(1, bad, dad.DAD_BF16, 32, 2, 1, p, 1 << 40, None) == dad.DAD_ERR_SHAPE
+
+
 def test_backprop_rejects_bad_arguments_on_host(lib):
     p = 0x1000  # never dereferenced: every call below must fail before a launch
 
