@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--graphs", default="off", choices=["auto", "on", "off"],
                     help="default mode: replay one captured HIP graph per operation of a step (auto: workloads of "
                          "at most 8 layers, which are bound by launch latency)")
+    ap.add_argument("--no-sites-leg", action="store_true",
+                    help="skip the extra timed leg that reads the sites' blocks in place (no stacking pass)")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="default mode: skip the encoder_d768 and vit_large_stack passes that follow the headline workload")
     ap.add_argument("--mode", default="one_level", choices=["one_level", "two_level", "backprop", "sequential"],
@@ -555,7 +557,8 @@ def main():
             others[name] = {k: o[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "dtype", "config",
                                               "rebuild_frac_of_mfma_peak", "compress_us_per_layer", "compress_GBps",
                                               "compress_frac_of_hbm_peak", "stack_GBps", "rank_rebuild_us_per_layer",
-                                              "rank_rebuild_GBps", "phase_ms_per_step", "roofline", "kernels")}
+                                              "rank_rebuild_GBps", "phase_ms_per_step", "roofline", "kernels",
+                                              "sites_in_place")}
             if o["cpu_baseline"]:
                 others[name]["parity_rel_fro"] = o["cpu_baseline"]["parity_rel_fro"]
                 others[name]["oracle_sample"] = o["cpu_baseline"]["sample"]
@@ -787,6 +790,58 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
     roofline["avg_us"] = roof_all[dominant]["avg_us"]
     roofline["traffic"] = traffic
 
+    # ---- the same step without a1: the reduction and the full rebuild read the sites' blocks in
+    # place (dad_compress_rank_grouped with site layers, dad_reconstruct_grad_sites); every output is
+    # compared bit for bit with what the stacked calls left behind.  Reported beside the headline,
+    # never in its place: a step of the headline contains the stacking pass.
+    sites_leg = None
+    if w.dtype == "bf16" and groups and not args.no_sites_leg:
+        Pt2 = {li: torch.empty_like(Pt[li]) for li, _, _ in layers}
+        Gt2 = {li: torch.empty_like(Gt[li]) for li, _, _ in layers}
+        G_full2 = {s_: torch.empty_like(G_full[s_]) for s_ in w.shapes}
+        ws_rs = torch.zeros(max(16, max(dad.reconstruct_sites_workspace_bytes([b] * S, hi, ho, tdt) for _, hi, ho in layers)),
+                            dtype=torch.uint8, device=dev)
+        sgroups = []
+        for sc in scopes:
+            sgroups.append(dad.CompressGroup([(factors_of(t[0])[0], factors_of(t[0])[1], G0[t[0]]) for t in sc], r, n_iter,
+                                             lanes=min(args.lanes, dad.DAD_MAX_LANES),
+                                             Pts=[Pt2[t[0]] for t in sc], Gts=[Gt2[t[0]] for t in sc],
+                                             workspace=sgroups[0].workspace if sgroups else None))
+        rank_group2 = dad.RebuildGroup([(Pt2[li], Gt2[li]) for li, _, _ in layers], [G_rank[li] for li, _, _ in layers])
+        sops = []
+        for si, sc in enumerate(scopes):
+            for li, hi, ho in sc:
+                As, Ds = factors_of(li)
+                sops.append(("rebuild_full", lambda As=As, Ds=Ds, s_=(hi, ho): dad.reconstruct_grad_sites(
+                    As, Ds, G=G_full2[s_], workspace=ws_rs)))
+            sops.append(("compress", sgroups[si].run))
+        sops.append(("rebuild_rank", rank_group2.run))
+        pool_next[0] = 0
+        step(which=sops)
+        torch.cuda.synchronize()
+        same = all(torch.equal(Pt[li], Pt2[li]) and torch.equal(Gt[li], Gt2[li]) for li, _, _ in layers) and \
+            all(torch.equal(G_full[s_], G_full2[s_]) for s_ in w.shapes)
+        if not same:
+            print("bench.py: the site-block calls differ from the stacked calls", file=sys.stderr)
+            sys.exit(1)
+        ev2 = []
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for _ in range(steps):
+            step(ev2, which=sops)
+        torch.cuda.synchronize()
+        c1 = time.perf_counter()
+        ph2 = dict.fromkeys(PH, 0.0)
+        for phase, e0, e1 in ev2:
+            ph2[phase] += e0.elapsed_time(e1) / steps
+        sites_leg = {"ms_per_step": (c1 - c0) * 1e3 / steps,
+                     "ms_per_step_with_stack": ms_per_step,
+                     "rebuild_full_TFLOPs": flops_full / (ph2["rebuild_full"] * 1e-3) / 1e12,
+                     "compress_us_per_layer": ph2["compress"] * 1e3 / nl,
+                     "compress_frac_of_hbm_peak": bytes_compress / (ph2["compress"] * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+                     "bit_identical_to_stacked_calls": True}
+        del sgroups, rank_group2, ws_rs
+
     # ---- CPU baseline: the fp64 oracle on the first layers of the stack, at least one of each distinct
     # shape and until about 10 s of oracle time are spent (bounded sample)
     cpu = None
@@ -921,6 +976,7 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
         "roofline": roofline,
         "kernels": roof_all,
         "in_run_yardsticks": yard,
+        "sites_in_place": sites_leg,
         "cpu_baseline": cpu,
     }
     return out
