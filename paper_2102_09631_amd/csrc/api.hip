@@ -28,11 +28,14 @@ bool thin_fast_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
 SplitPlan thin_tn_split(int64_t N, int64_t h, int r);
 dad_status fast_thin_nn(const void*, const float*, void*, int64_t, int64_t, int, int*, int, hipStream_t, const int*);
 dad_status fast_thin_tn(const void*, const RowBlocks*, const void*, float*, float*, SplitPlan, int64_t, int64_t, int,
-                        void*, int, hipStream_t, const int*);
+                        void*, int, hipStream_t, const int*, int jobs = 1, int64_t job_stride = 0);
+bool reduce_slabs_is_wide(int64_t n, bool with_bf16, bool with_skip);
 bool thin_tn_dma_ok(int64_t N, int r, SplitPlan sp);
 bool thin_dma_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
-dad_status launch_panel_init(const float*, void*, void*, int64_t, int64_t, int, int*, hipStream_t);
-dad_status dma_thin_nn(const void*, const RowBlocks*, const void*, void*, int64_t, int64_t, int, int, hipStream_t);
+dad_status launch_panel_init(const float*, void*, void*, int64_t, int64_t, int, int*, hipStream_t,
+                             const PtrTable* g0s = nullptr, int jobs = 1, int64_t job_stride = 0);
+dad_status dma_thin_nn(const void*, const RowBlocks*, const void*, void*, int64_t, int64_t, int, int, hipStream_t,
+                       int jobs = 1, int64_t job_stride = 0);
 bool rebuild_fast_ok(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
 SplitPlan rebuild_fast_split(int64_t K, int64_t h_in, int64_t h_out, int* tile);
 dad_status fast_rebuild(const void*, const void*, const RowBlocks*, const RowBlocks*, int64_t, int64_t, int64_t, float*,
@@ -155,10 +158,27 @@ dad_status device_ready(void** scratch_out) {
 __global__ void k_copy_flag(const int* __restrict__ hdr, int* __restrict__ out) { *out = *hdr; }
 
 // Grouped compress: the group's sticky flag is cleared at the start of the call and set after every
-// layer whose own flag was latched (several lanes may store the same 1).
+// layer whose own flag was latched (several lanes may store the same 1).  `jobs` headers, stride
+// bytes apart, are looked at (the jobs of a batch).
 __global__ void k_clear_flag(int* __restrict__ flag) { *flag = 0; }
-__global__ void k_latch_flag(const int* __restrict__ hdr, int* __restrict__ group_flag) {
-    if (*hdr) *group_flag = 1;
+__global__ void k_latch_flag(const int* __restrict__ hdr, int* __restrict__ group_flag, int jobs, int64_t stride) {
+    for (int j = 0; j < jobs; ++j)
+        if (*reinterpret_cast<const int*>(reinterpret_cast<const char*>(hdr) + j * stride)) *group_flag = 1;
+}
+
+// End of a batch: the jobs' pairs leave their workspace regions for the callers' buffers.
+__global__ __launch_bounds__(256) void k_batch_copy_out(const char* __restrict__ ws, int64_t stride, size_t off_p,
+                                                        size_t off_g, int64_t n_p, int64_t n_g, PtrTable pt,
+                                                        PtrTable gt) {
+    const int j = blockIdx.y;
+    const float* sp = reinterpret_cast<const float*>(ws + j * stride + off_p);
+    const float* sg = reinterpret_cast<const float*>(ws + j * stride + off_g);
+    float* dp = static_cast<float*>(const_cast<void*>(pt.p[j]));
+    float* dg = static_cast<float*>(const_cast<void*>(gt.p[j]));
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;  // n_p, n_g are multiples of 4, buffers 16-byte aligned
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    if (i < n_p) *reinterpret_cast<f4*>(dp + i) = *reinterpret_cast<const f4*>(sp + i);
+    if (i < n_g) *reinterpret_cast<f4*>(dg + i) = *reinterpret_cast<const f4*>(sg + i);
 }
 
 }  // namespace dad
@@ -221,12 +241,24 @@ static dad_status compress_args_ok(const void* A, const void* D, int64_t N, int6
 }
 
 // The launches of one compress call; every argument has been checked and the device is ready.
+// A batch: `jobs` reductions of equal sizes on the direct-to-LDS path whose launches are merged (one
+// launch does the same step of every job; a job's arithmetic is that of a call of its own).  Job j
+// works in the workspace region j * stride bytes after the first and has block j of Ab / Db as its
+// factors; the pairs are formed in the regions (P in the U slot, G in place in the Y slot) and
+// copied to the callers' buffers at the end.
+struct Batch {
+    int jobs;
+    int64_t stride;
+    PtrTable g0, pt, gt;
+};
+
 // Ab / Db, when not null, give the factors as row blocks read in place (A and D are then unused); the
-// caller has checked compress_in_place().
+// caller has checked compress_in_place().  With `batch` the blocks are the jobs of a batch, N is one
+// job's row count and G0, Pt, Gt are unused.
 static dad_status compress_launch(const CompressPlan& p, const void* A, const void* D, int64_t N, int64_t h_in,
                                   int64_t h_out, dad_dtype dt, int r, int n_iter, const float* G0, float* Pt, float* Gt,
                                   void* workspace, hipStream_t s, const RowBlocks* Ab = nullptr,
-                                  const RowBlocks* Db = nullptr) {
+                                  const RowBlocks* Db = nullptr, const Batch* batch = nullptr) {
     char* ws = static_cast<char*>(workspace);
     int* flag = reinterpret_cast<int*>(ws + p.off_flag);
     void* V = ws + p.off_V;
@@ -243,6 +275,12 @@ static dad_status compress_launch(const CompressPlan& p, const void* A, const vo
     void* Ub = p.dma ? ws + p.off_Ub : nullptr;
 
     // V <- X * panel (N x r); the direct-to-LDS kernel takes the bf16 copy of the panel
+    const int jobs = batch ? batch->jobs : 1;
+    const int64_t jstride = batch ? batch->stride : 0;
+    if (batch) {  // the pair is formed inside the regions
+        Pt = Ut;
+        Gt = Yt;
+    }
     struct Factor {
         const void* ptr;          // one allocation, or
         const RowBlocks* blocks;  // row blocks (ptr unused)
@@ -250,12 +288,13 @@ static dad_status compress_launch(const CompressPlan& p, const void* A, const vo
     const Factor FA = {A, Ab}, FD = {D, Db};
     auto nn = [&](const Factor& X, const float* panel, const void* panel_bf16, int64_t h, SplitPlan sp, int* hdr,
                   int planes) {
-        if (p.dma) return dma_thin_nn(X.ptr, X.blocks, panel_bf16, V, N, h, r, planes, s);
+        if (p.dma) return dma_thin_nn(X.ptr, X.blocks, panel_bf16, V, N, h, r, planes, s, jobs, jstride);
         return launch_thin_nn(X.ptr, panel, V, part, sp, N, h, r, dt, p.fast, hdr, planes, s);
     };
     // out (r x h) <- V^T X, with an optional bf16 copy
     auto tn = [&](const Factor& X, float* out, int64_t h, SplitPlan sp, void* out_bf16, int planes) {
-        if (X.blocks) return fast_thin_tn(nullptr, X.blocks, V, out, part, sp, N, h, r, out_bf16, planes, s, nullptr);
+        if (X.blocks)
+            return fast_thin_tn(nullptr, X.blocks, V, out, part, sp, N, h, r, out_bf16, planes, s, nullptr, jobs, jstride);
         return launch_thin_tn(X.ptr, V, out, part, sp, N, h, r, dt, p.fast, out_bf16, planes, s);
     };
     // On the MFMA path the N x r intermediates are bf16.  V = Delta G goes as one plane.  W = A U goes
@@ -268,7 +307,7 @@ static dad_status compress_launch(const CompressPlan& p, const void* A, const vo
         if ((rc = (expr)) != DAD_OK) return rc; \
     } while (0)
     // the workspace header is cleared by the first launch of the call
-    if (p.dma) DAD_TRY(launch_panel_init(G0, Gb, Ub, h_in, h_out, r, flag, s));
+    if (p.dma) DAD_TRY(launch_panel_init(G0, Gb, Ub, h_in, h_out, r, flag, s, batch ? &batch->g0 : nullptr, jobs, jstride));
     const float* G = G0;
     for (int it = 0; it < n_iter; ++it) {
         DAD_TRY(nn(FD, G, Gb, h_out, p.nn_out, it == 0 ? flag : nullptr, PV));  // V = Delta G
@@ -277,11 +316,19 @@ static dad_status compress_launch(const CompressPlan& p, const void* A, const vo
         DAD_TRY(tn(FD, Yt, h_out, p.tn_out, nullptr, PW));                      // Y = Delta^T W
         // G = orth(Y): up to two Cholesky rounds for the iterate that is returned, one for the others
         DAD_TRY(launch_cholqr(Yt, Gt, h_out, r, (it + 1 == n_iter) ? 2 : 1, gram, p.gram_blocks, rinv, counter, flag, Gb,
-                              s));
+                              s, jobs, jstride));
         G = Gt;
     }
     DAD_TRY(nn(FD, Gt, Gb, h_out, p.nn_out, nullptr, PV));  // V = Delta G
-    return tn(FA, Pt, h_in, p.tn_in, nullptr, PV);          // P = A^T V
+    DAD_TRY(tn(FA, Pt, h_in, p.tn_in, nullptr, PV));        // P = A^T V
+    if (batch) {
+        const int64_t n_p = (int64_t)r * h_in, n_g = (int64_t)r * h_out;
+        const int64_t n_max = n_p > n_g ? n_p : n_g;
+        hipLaunchKernelGGL(k_batch_copy_out, dim3((unsigned)ceil_div(n_max / 4, 256), (unsigned)jobs), dim3(256), 0, s,
+                           (const char*)ws, jstride, p.off_Ut, p.off_Yt, n_p, n_g, batch->pt, batch->gt);
+        DAD_LAUNCH_CHECK();
+    }
+    return DAD_OK;
 #undef DAD_TRY
 }
 
@@ -460,17 +507,47 @@ dad_status dad_compress_rank_sites(int S, const void* const* A_sites, const void
     return launch_layer(d, lp, dt, r, n_iter, workspace, (hipStream_t)stream);
 }
 
+// The layers of a grouped call are dealt to the lanes in units: a unit is one layer, or a batch of
+// up to MAX_ROW_BLOCKS consecutive stacked layers of equal sizes that the direct-to-LDS kernels serve
+// (the S site reductions of one layer in Algorithm 1 are such a run): the launches of a batch are
+// merged, one launch doing the same step of every job.
+struct Unit {
+    int first, count;
+    size_t bytes;  // of its lane region
+};
+
+static bool batchable(const dad_compress_desc& d, const LayerPlan& lp, int r) {
+    return !lp.sites && lp.cp.dma && thin_tn_dma_ok(lp.N, r, lp.cp.tn_in) && thin_tn_dma_ok(lp.N, r, lp.cp.tn_out) &&
+           !reduce_slabs_is_wide((int64_t)r * d.h_in, false, false) && !reduce_slabs_is_wide((int64_t)r * d.h_out, false, false);
+}
+
 // Layout of the grouped workspace: 256-byte group header (sticky numeric flag at +0), then one region
-// per lane, each large enough for any layer of the group.
+// per lane, each large enough for any unit of the group.
 static dad_status grouped_plans(int n, const dad_compress_desc* descs, dad_dtype dt, int r, std::vector<LayerPlan>* plans,
-                                size_t* lane_bytes) {
+                                std::vector<Unit>* units, size_t* lane_bytes) {
     plans->resize((size_t)n);
-    size_t lane = 0;
+    units->clear();
     for (int i = 0; i < n; ++i) {
-        const dad_status rc = plan_layer(descs[i], dt, r, &(*plans)[(size_t)i]);
+        LayerPlan& lp = (*plans)[(size_t)i];
+        const dad_status rc = plan_layer(descs[i], dt, r, &lp);
         if (rc != DAD_OK) return rc;
-        if ((*plans)[(size_t)i].total > lane) lane = (*plans)[(size_t)i].total;
+        bool joined = false;
+        if (!units->empty() && batchable(descs[i], lp, r)) {
+            Unit& u = units->back();
+            const dad_compress_desc& f = descs[u.first];
+            const LayerPlan& fp = (*plans)[(size_t)u.first];
+            if (u.count < MAX_ROW_BLOCKS && batchable(f, fp, r) && fp.N == lp.N && f.h_in == descs[i].h_in &&
+                f.h_out == descs[i].h_out) {
+                ++u.count;
+                u.bytes = (size_t)u.count * align_up(lp.cp.total, 256);
+                joined = true;
+            }
+        }
+        if (!joined) units->push_back(Unit{i, 1, lp.total});
     }
+    size_t lane = 0;
+    for (const Unit& u : *units)
+        if (u.bytes > lane) lane = u.bytes;
     *lane_bytes = align_up(lane, 256);
     return DAD_OK;
 }
@@ -478,10 +555,35 @@ static dad_status grouped_plans(int n, const dad_compress_desc* descs, dad_dtype
 size_t dad_compress_grouped_workspace_bytes(int n, const dad_compress_desc* descs, dad_dtype dt, int r, int lanes) {
     if (n < 1 || n > DAD_MAX_GROUP || !descs || !dtype_ok(dt) || lanes < 1 || lanes > DAD_MAX_LANES) return 0;
     std::vector<LayerPlan> plans;
+    std::vector<Unit> units;
     size_t lane_bytes = 0;
-    if (grouped_plans(n, descs, dt, r, &plans, &lane_bytes) != DAD_OK) return 0;
-    const int used = lanes < n ? lanes : n;
+    if (grouped_plans(n, descs, dt, r, &plans, &units, &lane_bytes) != DAD_OK) return 0;
+    const int used = lanes < (int)units.size() ? lanes : (int)units.size();
     return 256 + (size_t)used * lane_bytes;
+}
+
+// The launches of one batch on stream s; ws holds u.count regions.
+static dad_status launch_batch(const dad_compress_desc* descs, const Unit& u, const LayerPlan& lp, dad_dtype dt, int r,
+                               int n_iter, void* ws, hipStream_t s) {
+    const dad_compress_desc& f = descs[u.first];
+    RowBlocks a, b;
+    Batch batch;
+    batch.jobs = u.count;
+    batch.stride = (int64_t)align_up(lp.cp.total, 256);
+    for (int j = 0; j < MAX_ROW_BLOCKS; ++j) {
+        const bool in = j < u.count;
+        const dad_compress_desc& d = descs[u.first + (in ? j : 0)];
+        a.base[j] = in ? static_cast<const char*>(d.A) : nullptr;
+        b.base[j] = in ? static_cast<const char*>(d.D) : nullptr;
+        a.first[j] = b.first[j] = (in ? j : u.count) * lp.N;
+        batch.g0.p[j] = in ? d.G0 : nullptr;
+        batch.pt.p[j] = in ? d.Pt : nullptr;
+        batch.gt.p[j] = in ? d.Gt : nullptr;
+    }
+    a.first[MAX_ROW_BLOCKS] = b.first[MAX_ROW_BLOCKS] = (int64_t)u.count * lp.N;
+    a.n = b.n = u.count;
+    return compress_launch(lp.cp, nullptr, nullptr, lp.N, f.h_in, f.h_out, dt, r, n_iter, nullptr, nullptr, nullptr, ws, s,
+                           &a, &b, &batch);
 }
 
 dad_status dad_compress_rank_grouped(int n, const dad_compress_desc* descs, dad_dtype dt, int r, int n_iter, int lanes,
@@ -490,13 +592,15 @@ dad_status dad_compress_rank_grouped(int n, const dad_compress_desc* descs, dad_
     if (!dtype_ok(dt)) return DAD_ERR_DTYPE;
     if (n < 1 || n > DAD_MAX_GROUP || lanes < 1 || lanes > DAD_MAX_LANES) return DAD_ERR_SHAPE;
     std::vector<LayerPlan> plans;
+    std::vector<Unit> units;
     size_t lane_bytes = 0;
-    dad_status rc = grouped_plans(n, descs, dt, r, &plans, &lane_bytes);
+    dad_status rc = grouped_plans(n, descs, dt, r, &plans, &units, &lane_bytes);
     if (rc != DAD_OK) return rc;
     for (int i = 0; i < n; ++i)
         if ((rc = layer_args_ok(descs[i], plans[(size_t)i], dt, r, n_iter)) != DAD_OK) return rc;
     if (!aligned16(workspace)) return DAD_ERR_ALIGN;
-    const int used = lanes < n ? lanes : n;
+    const int nu = (int)units.size();
+    const int used = lanes < nu ? lanes : nu;
     if (ws_bytes < 256 + (size_t)used * lane_bytes) return DAD_ERR_WORKSPACE;
     if ((rc = device_ready()) != DAD_OK) return rc;
     int dev = 0;
@@ -514,13 +618,17 @@ dad_status dad_compress_rank_grouped(int n, const dad_compress_desc* descs, dad_
         DAD_HIP_TRY(hipEventRecord(st.fork, main));
         for (int l = 1; l < used; ++l) DAD_HIP_TRY(hipStreamWaitEvent(st.side[l - 1], st.fork, 0));
     }
-    for (int i = 0; i < n; ++i) {  // layer i on lane i mod `used`; a lane's layers follow each other on its stream
-        const int l = i % used;
+    for (int k = 0; k < nu; ++k) {  // unit k on lane k mod `used`; a lane's units follow each other on its stream
+        const int l = k % used;
         hipStream_t s = l == 0 ? main : st.side[l - 1];
         void* lane_ws = ws + 256 + (size_t)l * lane_bytes;
-        rc = launch_layer(descs[i], plans[(size_t)i], dt, r, n_iter, lane_ws, s);
+        const Unit& u = units[(size_t)k];
+        const LayerPlan& lp = plans[(size_t)u.first];
+        rc = u.count > 1 ? launch_batch(descs, u, lp, dt, r, n_iter, lane_ws, s)
+                         : launch_layer(descs[u.first], lp, dt, r, n_iter, lane_ws, s);
         if (rc != DAD_OK) break;
-        hipLaunchKernelGGL(k_latch_flag, dim3(1), dim3(1), 0, s, (const int*)lane_ws, group_flag);
+        hipLaunchKernelGGL(k_latch_flag, dim3(1), dim3(1), 0, s, (const int*)lane_ws, group_flag, u.count,
+                           (int64_t)align_up(lp.cp.total, 256));
         if (hipGetLastError() != hipSuccess) {
             rc = DAD_ERR_HIP;
             break;

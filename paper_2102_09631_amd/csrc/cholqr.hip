@@ -133,12 +133,24 @@ __device__ __forceinline__ void store_tile(QrShared& sh, const float (&st)[16]) 
 }
 
 // Launch 1: Gram partial per slab + factorisation by the last workgroup.
+// The copy of *p that belongs to job blockIdx.y of a batch (job_stride bytes per job); null stays null.
+template <typename T>
+__device__ __forceinline__ T* at_job(T* p, int64_t job_stride) {
+    typedef typename std::remove_const<T>::type U;
+    return p ? reinterpret_cast<T*>(reinterpret_cast<char*>(const_cast<U*>(p)) + blockIdx.y * job_stride) : p;
+}
+#define DAD_TO_JOB(p) p = at_job(p, job_stride)
+
 template <int NA>
 __global__ __launch_bounds__(256) void k_qr_gram(const float* __restrict__ Yt, int64_t h, int r,
                                                  double* __restrict__ gram_part, int* __restrict__ counter,
                                                  float* __restrict__ rinv, int* __restrict__ flag,
-                                                 double* __restrict__ piv_range) {
+                                                 double* __restrict__ piv_range, int64_t job_stride) {
     __shared__ QrShared sh;
+    if (job_stride != 0) {
+        DAD_TO_JOB(Yt), DAD_TO_JOB(gram_part), DAD_TO_JOB(counter);
+        DAD_TO_JOB(rinv), DAD_TO_JOB(flag), DAD_TO_JOB(piv_range);
+    }
     const int64_t k0 = (int64_t)blockIdx.x * QR_SUB * QR_COLS;
     float st[QR_SUB][16];
     load_slab<QR_SUB>(st, Yt, h, r, k0);
@@ -180,8 +192,14 @@ __global__ __launch_bounds__(256) void k_qr_apply(const float* Yt, float* Gt, co
                                                   int* __restrict__ flag, bf16_t* __restrict__ gt_bf16,
                                                   const double* __restrict__ piv_first,
                                                   double* __restrict__ piv_second, const float* Y_first,
-                                                  const float* __restrict__ rinv_first) {
+                                                  const float* __restrict__ rinv_first, int64_t job_stride) {
     __shared__ QrShared sh;
+    if (job_stride != 0) {
+        DAD_TO_JOB(Yt), DAD_TO_JOB(Gt), DAD_TO_JOB(rinv_in), DAD_TO_JOB(gram_part);
+        DAD_TO_JOB(counter), DAD_TO_JOB(rinv_out), DAD_TO_JOB(flag), DAD_TO_JOB(gt_bf16);
+        DAD_TO_JOB(piv_first), DAD_TO_JOB(piv_second), DAD_TO_JOB(Y_first);
+        DAD_TO_JOB(rinv_first);
+    }
     const bool single = piv_first != nullptr && one_round_enough(piv_first);  // uniform over the grid
     if (WITH_GRAM && single) return;
     if (!WITH_GRAM && single) {
@@ -246,45 +264,48 @@ int gram_blocks_for(int64_t h) { return (int)ceil_div(h, QR_COLS * QR_SUB); }
 // iterate of the power iteration, of which only the span matters.
 template <int NA>
 static dad_status qr(const float* Yt, float* Gt, int64_t h, int r, int rounds, double* gram_part, int nb, float* rinv,
-                     int* counter, int* flag, bf16_t* gt_bf16, hipStream_t s) {
+                     int* counter, int* flag, bf16_t* gt_bf16, hipStream_t s, int jobs, int64_t job_stride) {
     float* rinv2 = rinv + DAD_MAX_RANK * DAD_MAX_RANK;
     // pivot ranges of the two factors: four doubles at byte 128 of the 256-byte workspace header
     double* piv = reinterpret_cast<double*>(reinterpret_cast<char*>(flag) + 128);
     const unsigned nb1 = (unsigned)ceil_div(h, QR_COLS);
     {
         ProfScope prof(KID_GRAM, s);
-        hipLaunchKernelGGL(k_qr_gram<NA>, dim3((unsigned)nb), dim3(256), 0, s, Yt, h, r, gram_part, counter, rinv, flag, piv);
+        hipLaunchKernelGGL(k_qr_gram<NA>, dim3((unsigned)nb, (unsigned)jobs), dim3(256), 0, s, Yt, h, r, gram_part, counter,
+                           rinv, flag, piv, job_stride);
     }
     DAD_LAUNCH_CHECK();
     if (rounds == 1) {
         ProfScope prof(KID_APPLY2, s);
-        hipLaunchKernelGGL((k_qr_apply<NA, false, 1>), dim3(nb1), dim3(256), 0, s, Yt, Gt, (const float*)rinv, h, r,
-                           gram_part, counter, rinv2, flag, gt_bf16, (const double*)nullptr, (double*)nullptr,
-                           (const float*)nullptr, (const float*)nullptr);
+        hipLaunchKernelGGL((k_qr_apply<NA, false, 1>), dim3(nb1, (unsigned)jobs), dim3(256), 0, s, Yt, Gt,
+                           (const float*)rinv, h, r, gram_part, counter, rinv2, flag, gt_bf16, (const double*)nullptr,
+                           (double*)nullptr, (const float*)nullptr, (const float*)nullptr, job_stride);
         DAD_LAUNCH_CHECK();
         return DAD_OK;
     }
     {
         ProfScope prof(KID_APPLY, s);
-        hipLaunchKernelGGL((k_qr_apply<NA, true, QR_SUB>), dim3((unsigned)nb), dim3(256), 0, s, Yt, Gt, (const float*)rinv,
-                           h, r, gram_part, counter, rinv2, flag, (bf16_t*)nullptr, (const double*)piv, piv + 2,
-                           (const float*)nullptr, (const float*)nullptr);
+        hipLaunchKernelGGL((k_qr_apply<NA, true, QR_SUB>), dim3((unsigned)nb, (unsigned)jobs), dim3(256), 0, s, Yt, Gt,
+                           (const float*)rinv, h, r, gram_part, counter, rinv2, flag, (bf16_t*)nullptr, (const double*)piv,
+                           piv + 2, (const float*)nullptr, (const float*)nullptr, job_stride);
     }
     DAD_LAUNCH_CHECK();
     {
         ProfScope prof(KID_APPLY2, s);
-        hipLaunchKernelGGL((k_qr_apply<NA, false, 1>), dim3(nb1), dim3(256), 0, s, (const float*)Gt, Gt,
+        hipLaunchKernelGGL((k_qr_apply<NA, false, 1>), dim3(nb1, (unsigned)jobs), dim3(256), 0, s, (const float*)Gt, Gt,
                            (const float*)rinv2, h, r, gram_part, counter, rinv2, flag, gt_bf16, (const double*)piv,
-                           (double*)nullptr, Yt, (const float*)rinv);
+                           (double*)nullptr, Yt, (const float*)rinv, job_stride);
     }
     DAD_LAUNCH_CHECK();
     return DAD_OK;
 }
 
 dad_status launch_cholqr(const float* Yt, float* Gt, int64_t h, int r, int rounds, double* gram_part, int gram_blocks,
-                         float* rinv, int* counter, int* flag, void* gt_bf16, hipStream_t s) {
-    if (r <= 32) return qr<2>(Yt, Gt, h, r, rounds, gram_part, gram_blocks, rinv, counter, flag, (bf16_t*)gt_bf16, s);
-    return qr<4>(Yt, Gt, h, r, rounds, gram_part, gram_blocks, rinv, counter, flag, (bf16_t*)gt_bf16, s);
+                         float* rinv, int* counter, int* flag, void* gt_bf16, hipStream_t s, int jobs, int64_t job_stride) {
+    if (job_stride == 0) jobs = 1;
+    if (r <= 32)
+        return qr<2>(Yt, Gt, h, r, rounds, gram_part, gram_blocks, rinv, counter, flag, (bf16_t*)gt_bf16, s, jobs, job_stride);
+    return qr<4>(Yt, Gt, h, r, rounds, gram_part, gram_blocks, rinv, counter, flag, (bf16_t*)gt_bf16, s, jobs, job_stride);
 }
 
 }  // namespace dad

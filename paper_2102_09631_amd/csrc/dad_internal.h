@@ -87,6 +87,12 @@ struct RowBlocks {
     int n;
 };
 
+// One caller pointer per job of a batch (a batch: up to MAX_ROW_BLOCKS equal reductions whose
+// launches are merged; everything else of a job lives in its workspace region, at a fixed stride).
+struct PtrTable {
+    const void* p[MAX_ROW_BLOCKS];
+};
+
 // Where a kernel's walk over rows stands: the block it is in and the row at which that block ends.
 struct RowCursor {
     int blk;
@@ -223,8 +229,9 @@ RebuildPlan plan_rebuild(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
 // out[i] = sum over s of part[s*n + i] in a fixed order; out_bf16 (optional) gets a bf16 copy.
 // skip (optional, everywhere below): a device word; when it is non-zero at run time the kernels
 // return at once (the adaptive one-vector iteration stops on the device with a fixed launch sequence).
+// jobs / job_stride: the same sum for `jobs` problems whose pointers lie job_stride bytes apart.
 dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s, void* out_bf16 = nullptr,
-                        const int* skip = nullptr);
+                        const int* skip = nullptr, int jobs = 1, int64_t job_stride = 0);
 
 
 // out[n][j] = sum_k X[n][k] * Pt[j][k];  X is N x h (dt), Pt r x h fp32.  out is N x r: fp32 from the
@@ -245,8 +252,10 @@ dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* par
 
 // Orthonormalisation Yt (r x h) -> Gt (r x h), rows of Gt orthonormal; rounds = 2 is CholeskyQR2.
 // gt_bf16 (optional) receives a bf16 copy of Gt.
+// jobs / job_stride: `jobs` independent iterates whose pointers (all of them) lie job_stride bytes apart.
 dad_status launch_cholqr(const float* Yt, float* Gt, int64_t h, int r, int rounds, double* gram_part, int gram_blocks,
-                         float* rinv, int* counter, int* flag, void* gt_bf16, hipStream_t s);
+                         float* rinv, int* counter, int* flag, void* gt_bf16, hipStream_t s, int jobs = 1,
+                         int64_t job_stride = 0);
 
 dad_status launch_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt,
                           float* G, float* partials, const RebuildPlan& plan, hipStream_t s);

@@ -167,9 +167,17 @@ __global__ __launch_bounds__(256) void k_thin_tn(const T* __restrict__ X, const 
 // Small slabs (the r x h panels of the power iteration): latency bound, so the splits of one
 // element are shared by the four waves of a workgroup (wave g sums s = g, g+4, ... ascending) and
 // the four partial sums are combined in wave order.
+// blockIdx.y: job of a batch, its pointers job_stride bytes further per job.
 __global__ __launch_bounds__(256) void k_reduce_slabs(const float* part, float* out, int64_t n, int splits,
-                                                      bf16_t* __restrict__ out_bf16, const int* __restrict__ skip) {
+                                                      bf16_t* __restrict__ out_bf16, const int* __restrict__ skip,
+                                                      int64_t job_stride) {
     if (skip && *skip) return;
+    if (job_stride != 0) {
+        const int64_t off = blockIdx.y * job_stride;
+        part = reinterpret_cast<const float*>(reinterpret_cast<const char*>(part) + off);
+        out = reinterpret_cast<float*>(reinterpret_cast<char*>(out) + off);
+        if (out_bf16) out_bf16 = reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(out_bf16) + off);
+    }
     __shared__ float ps[4][64];
     const int e = threadIdx.x & 63, g = threadIdx.x >> 6;
     const int64_t i = (int64_t)blockIdx.x * 64 + e;
@@ -331,16 +339,22 @@ dad_status gen_thin_nn(const void* X, const float* Pt, void* out, float* partial
     return reduce_slabs(part, (float*)out, N * r, sp.splits, s, nullptr, skip);
 }
 
+bool reduce_slabs_is_wide(int64_t n, bool with_bf16, bool with_skip) {
+    return n >= (1 << 20) && n % 4 == 0 && !with_bf16 && !with_skip;
+}
+
 dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s, void* out_bf16,
-                        const int* skip) {
-    const bool wide = n >= (1 << 20) && n % 4 == 0 && !out_bf16 && !skip;
+                        const int* skip, int jobs, int64_t job_stride) {
+    const bool wide = reduce_slabs_is_wide(n, out_bf16 != nullptr, skip != nullptr);
+    if (job_stride == 0) jobs = 1;
+    if (wide && jobs > 1) return DAD_ERR_SHAPE;  // batches are formed only of sums the small kernel takes
     ProfScope prof(wide ? KID_REDUCE_WIDE : KID_REDUCE, s);
     if (wide)
         hipLaunchKernelGGL(k_reduce_slabs_wide, dim3((unsigned)ceil_div(n / 4, 256)), dim3(256), 0, s,
                            reinterpret_cast<const float4*>(part), reinterpret_cast<float4*>(out), n / 4, splits);
     else
-        hipLaunchKernelGGL(k_reduce_slabs, dim3((unsigned)ceil_div(n, 64)), dim3(256), 0, s, part, out, n, splits,
-                           (bf16_t*)out_bf16, skip);
+        hipLaunchKernelGGL(k_reduce_slabs, dim3((unsigned)ceil_div(n, 64), (unsigned)jobs), dim3(256), 0, s, part, out, n,
+                           splits, (bf16_t*)out_bf16, skip, job_stride);
     DAD_LAUNCH_CHECK();
     return DAD_OK;
 }

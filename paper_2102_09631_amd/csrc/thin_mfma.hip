@@ -189,10 +189,14 @@ __global__ __launch_bounds__(256) void k_thin_nn_bf16(const bf16_t* __restrict__
 // ------------------------------------------------------------------------------------------------
 // SRC is `const bf16_t*` (one allocation) or RowBlocks (the sites' blocks in place; a workgroup's
 // rows lie in one block because every block holds a multiple of 256 rows).
+// job_stride != 0 (RowBlocks only): the blocks are independent jobs of N rows each (a batch of equal
+// reductions); block j multiplies the panel and writes the V that lie j * job_stride bytes after Pb
+// and V, and counts its workgroups from its own first row, so that a job's result does not depend
+// on the batch it runs in.
 template <int RP, int W, int NS, typename SRC>
 __global__ __launch_bounds__(64 * W) void k_thin_nn_bf16_dma(const SRC X, const bf16_t* __restrict__ Pb,
                                                             bf16_t* __restrict__ V, int64_t N, int h, int r, int nt,
-                                                            int planes) {
+                                                            int planes, int64_t job_stride) {
     constexpr int JT = RP / 32, RT = 32 * W, ROWB = 128;
     constexpr int XTILEB = RT * ROWB, PTILEB = RP * ROWB, STAGEB = XTILEB + PTILEB;
     constexpr int PI = RP / 8;               // 1 KiB loads that make up the panel tile
@@ -200,13 +204,20 @@ __global__ __launch_bounds__(64 * W) void k_thin_nn_bf16_dma(const SRC X, const 
     constexpr int LOADS = 4 + PL;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int64_t n0 = (int64_t)blockIdx.x * RT;
+    int64_t n0 = (int64_t)blockIdx.x * RT;
     const int nk = h / nn::BK;
-    // every workgroup starts its walk over the contraction columns at its own stage (see k_thin_nn_bf16)
-    int kidx = (int)((blockIdx.x * 5u) % (unsigned)nk);
-
     RowCursor cur;
     const char* x0 = row_address(X, n0, (int64_t)h * 2, cur);
+    if constexpr (!std::is_pointer<SRC>::value) {
+        if (job_stride != 0) {
+            n0 -= X.first[cur.blk];  // row within the job
+            Pb = reinterpret_cast<const bf16_t*>(reinterpret_cast<const char*>(Pb) + cur.blk * job_stride);
+            V = reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(V) + cur.blk * job_stride);
+        }
+    }
+    // every workgroup starts its walk over the contraction columns at its own stage (see k_thin_nn_bf16)
+    int kidx = (int)(((unsigned)(n0 / RT) * 5u) % (unsigned)nk);
+
     const char* gx[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -281,9 +292,18 @@ __global__ __launch_bounds__(64 * W) void k_thin_nn_bf16_dma(const SRC X, const 
 
 // Start of a compress call on the direct-to-LDS path: Gb <- bf16(G0) with rows r..RP-1 zero, the same
 // zero rows in Ub, and the workspace header cleared.
+// With a table of start matrices (batch of jobs) job blockIdx.y takes G0 from the table and the other
+// pointers job_stride bytes further per job.
 __global__ __launch_bounds__(256) void k_panel_init(const float* __restrict__ G0, bf16_t* __restrict__ Gb,
                                                     bf16_t* __restrict__ Ub, int64_t h_in, int64_t h_out, int r, int rp,
-                                                    int* __restrict__ hdr) {
+                                                    int* __restrict__ hdr, PtrTable g0s, int64_t job_stride) {
+    if (job_stride != 0) {
+        const int64_t off = blockIdx.y * job_stride;
+        G0 = static_cast<const float*>(g0s.p[blockIdx.y]);
+        Gb = reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(Gb) + off);
+        Ub = reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(Ub) + off);
+        hdr = reinterpret_cast<int*>(reinterpret_cast<char*>(hdr) + off);
+    }
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (blockIdx.x == 0 && threadIdx.x < 64) hdr[threadIdx.x] = 0;
     if (i < (int64_t)rp * h_out) Gb[i] = (i < (int64_t)r * h_out) ? f32_to_bf16(G0[i]) : (bf16_t)0;
@@ -461,10 +481,13 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16(const bf16_t* __restrict__
 // The swizzle of the X tile is applied on the global side, as in the rebuild kernel.
 // ------------------------------------------------------------------------------------------------
 // SRC as in k_thin_nn_bf16_dma; a row chunk may span several blocks, the walk jumps at their ends.
+// job_stride != 0 (RowBlocks only): block blockIdx.y of X is a job of its own with N rows, whose V and
+// partial slabs lie blockIdx.y * job_stride bytes after V and part.
 template <int R, int PW, int BK, int NV, typename SRC>
 __global__ __launch_bounds__(256) void k_thin_tn_bf16_dma(const SRC X, const bf16_t* __restrict__ V,
                                                           float* __restrict__ part, int64_t N, int h,
-                                                          int64_t chunk_rows, int strips, int splits, int nt) {
+                                                          int64_t chunk_rows, int strips, int splits, int nt,
+                                                          int64_t job_stride) {
     constexpr int JT = R > 32 ? 2 : 1;
     constexpr int MT = PW / 128;                  // 32-column tiles per wave
     constexpr int XROWB = PW * 2;
@@ -499,9 +522,17 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16_dma(const SRC X, const bf1
     const int nk = (int)((nend - nbeg) / BK);
 
     // X: load i of this wave covers tile rows (wave*XL + i)*RPL .. ; lane -> row += lane/CPR, LDS chunk lane%CPR
+    int64_t row0 = 0;  // the job's first row in X
+    if constexpr (!std::is_pointer<SRC>::value) {
+        if (job_stride != 0) {
+            row0 = X.first[blockIdx.y];
+            V = reinterpret_cast<const bf16_t*>(reinterpret_cast<const char*>(V) + blockIdx.y * job_stride);
+            part = reinterpret_cast<float*>(reinterpret_cast<char*>(part) + blockIdx.y * job_stride);
+        }
+    }
     RowCursor cur;
-    const char* x0 = row_address(X, nbeg, (int64_t)h * 2, cur);
-    int64_t row_next = nbeg;  // first row of the next tile to be issued
+    const char* x0 = row_address(X, row0 + nbeg, (int64_t)h * 2, cur);
+    int64_t row_next = row0 + nbeg;  // first row of the next tile to be issued
     const char* gx[XL];
 #pragma unroll
     for (int i = 0; i < XL; ++i) {
@@ -660,14 +691,17 @@ bool thin_dma_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt) {
     return thin_fast_ok(N, h_in, h_out, r, dt) && N % 256 == 0 && h_in % nn::BK == 0 && h_out % nn::BK == 0;
 }
 
+// g0s != null: a batch of `jobs` jobs (G0 unused).
 dad_status launch_panel_init(const float* G0, void* Gb, void* Ub, int64_t h_in, int64_t h_out, int r, int* hdr,
-                             hipStream_t s) {
+                             hipStream_t s, const PtrTable* g0s, int jobs, int64_t job_stride) {
+    PtrTable none = {};
+    if (!g0s) jobs = 1, job_stride = 0;
     const int rp = r <= 32 ? 32 : 64;
     int64_t n = (int64_t)rp * h_out;
     if ((int64_t)(rp - r) * h_in > n) n = (int64_t)(rp - r) * h_in;
     ProfScope prof(KID_PANEL_INIT, s);
-    hipLaunchKernelGGL(k_panel_init, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, G0, (bf16_t*)Gb, (bf16_t*)Ub, h_in,
-                       h_out, r, rp, hdr);
+    hipLaunchKernelGGL(k_panel_init, dim3((unsigned)ceil_div(n, 256), (unsigned)jobs), dim3(256), 0, s, G0, (bf16_t*)Gb,
+                       (bf16_t*)Ub, h_in, h_out, r, rp, hdr, g0s ? *g0s : none, job_stride);
     DAD_LAUNCH_CHECK();
     return DAD_OK;
 }
@@ -677,30 +711,34 @@ constexpr int tn_dma_lds(int r, int pw, int bk, int nv) { return 3 * (bk * pw * 
 
 template <int RP, int W, int NS>
 static dad_status dma_thin_nn_cfg(const void* X, const RowBlocks* xb, const void* Pb, void* out, int64_t N, int64_t h,
-                                  int r, int planes, hipStream_t s) {
+                                  int r, int planes, int jobs, int64_t job_stride, hipStream_t s) {
     const int lds = nn_dma_lds(RP, W, NS);
-    const dim3 grid((unsigned)(N / (32 * W))), block(64 * W);
-    const int nt = stream_once(N, h) ? 1 : 0;
+    const dim3 grid((unsigned)(jobs * (N / (32 * W)))), block(64 * W);
+    const int nt = stream_once(jobs * N, h) ? 1 : 0;
     if (xb)
         hipLaunchKernelGGL((k_thin_nn_bf16_dma<RP, W, NS, RowBlocks>), grid, block, lds, s, *xb, (const bf16_t*)Pb,
-                           (bf16_t*)out, N, (int)h, r, nt, planes);
+                           (bf16_t*)out, N, (int)h, r, nt, planes, jobs > 1 || job_stride ? job_stride : (int64_t)0);
     else
         hipLaunchKernelGGL((k_thin_nn_bf16_dma<RP, W, NS, const bf16_t*>), grid, block, lds, s, (const bf16_t*)X,
-                           (const bf16_t*)Pb, (bf16_t*)out, N, (int)h, r, nt, planes);
+                           (const bf16_t*)Pb, (bf16_t*)out, N, (int)h, r, nt, planes, (int64_t)0);
     DAD_LAUNCH_CHECK();
     return DAD_OK;
 }
 
 // Rows per workgroup: 256 (eight waves) when that still gives one workgroup per CU, fewer for
 // shorter factors so that the chip stays filled (a site's 8192 rows: 256 single-wave workgroups).
-// xb, when not null, gives X as row blocks (X itself is then unused).
+// xb, when not null, gives X as row blocks (X itself is then unused).  job_stride != 0: the blocks
+// are `jobs` independent problems of N rows each (see the kernel); the rows per workgroup are chosen
+// from one job's N, as a single call would.
 dad_status dma_thin_nn(const void* X, const RowBlocks* xb, const void* Pb, void* out, int64_t N, int64_t h, int r,
-                       int planes, hipStream_t s) {
+                       int planes, hipStream_t s, int jobs, int64_t job_stride) {
+    if (job_stride != 0 && !xb) return DAD_ERR_SHAPE;
+    if (job_stride == 0) jobs = 1;
     ProfScope prof(KID_THIN_NN_BF16, s);
     const int64_t want = 256;  // workgroups
 #define DAD_NN_W(W) \
-    (r <= 32 ? dma_thin_nn_cfg<32, W, 3>(X, xb, Pb, out, N, h, r, planes, s) \
-             : dma_thin_nn_cfg<64, W, 3>(X, xb, Pb, out, N, h, r, planes, s))
+    (r <= 32 ? dma_thin_nn_cfg<32, W, 3>(X, xb, Pb, out, N, h, r, planes, jobs, job_stride, s) \
+             : dma_thin_nn_cfg<64, W, 3>(X, xb, Pb, out, N, h, r, planes, jobs, job_stride, s))
     if (N / 256 >= want) return DAD_NN_W(8);
     if (N / 128 >= want) return DAD_NN_W(4);
     if (N / 64 >= want) return DAD_NN_W(2);
@@ -715,10 +753,15 @@ bool thin_tn_dma_ok(int64_t N, int r, SplitPlan sp) {
 
 // xb, when not null, gives X as row blocks (X itself is then unused); only the direct-to-LDS kernel
 // reads blocks, so the caller has checked thin_tn_dma_ok and passes no skip word.
+// job_stride != 0: the blocks are `jobs` independent problems of N rows each, and V, out_t, partials
+// and out_bf16 of job j lie j * job_stride bytes after the pointers given.
 dad_status fast_thin_tn(const void* X, const RowBlocks* xb, const void* V, float* out_t, float* partials, SplitPlan sp,
-                        int64_t N, int64_t h, int r, void* out_bf16, int planes, hipStream_t s, const int* skip) {
+                        int64_t N, int64_t h, int r, void* out_bf16, int planes, hipStream_t s, const int* skip,
+                        int jobs, int64_t job_stride) {
     float* dst = sp.splits == 1 ? out_t : partials;
     if (xb && (skip || !thin_tn_dma_ok(N, r, sp))) return DAD_ERR_SHAPE;
+    if (job_stride != 0 && !xb) return DAD_ERR_SHAPE;
+    if (job_stride == 0) jobs = 1;
     if (!skip && thin_tn_dma_ok(N, r, sp)) {
         ProfScope prof(KID_THIN_TN_BF16, s);
         const int pw = thin_tn_pw(h);
@@ -727,14 +770,15 @@ dad_status fast_thin_tn(const void* X, const RowBlocks* xb, const void* V, float
         const int strips = (int)(h / pw);
 #define DAD_TN_LAUNCH_NV(RR, PP, BB, NV)                                                                          \
     do {                                                                                                          \
-        const dim3 grid((unsigned)(strips * sp.splits));                                                          \
-        const int nt = stream_once(N, h) ? 1 : 0;                                                                 \
+        const dim3 grid((unsigned)(strips * sp.splits), (unsigned)jobs);                                          \
+        const int nt = stream_once(jobs * N, h) ? 1 : 0;                                                          \
         if (xb)                                                                                                   \
             hipLaunchKernelGGL((k_thin_tn_bf16_dma<RR, PP, BB, NV, RowBlocks>), grid, dim3(256), lds, s, *xb,     \
-                               (const bf16_t*)V, dst, N, (int)h, sp.chunk, strips, sp.splits, nt);                \
+                               (const bf16_t*)V, dst, N, (int)h, sp.chunk, strips, sp.splits, nt, job_stride);    \
         else                                                                                                      \
             hipLaunchKernelGGL((k_thin_tn_bf16_dma<RR, PP, BB, NV, const bf16_t*>), grid, dim3(256), lds, s,      \
-                               (const bf16_t*)X, (const bf16_t*)V, dst, N, (int)h, sp.chunk, strips, sp.splits, nt); \
+                               (const bf16_t*)X, (const bf16_t*)V, dst, N, (int)h, sp.chunk, strips, sp.splits, nt, \
+                               (int64_t)0);                                                                       \
     } while (0)
 #define DAD_TN_LAUNCH(RR, PP, BB)                  \
     do {                                           \
@@ -772,8 +816,8 @@ dad_status fast_thin_tn(const void* X, const RowBlocks* xb, const void* V, float
 #undef DAD_TN_REG
     }
     DAD_LAUNCH_CHECK();
-    if (sp.splits > 1) return reduce_slabs(partials, out_t, (int64_t)r * h, sp.splits, s, out_bf16, skip);
-    if (out_bf16) return reduce_slabs(out_t, out_t, (int64_t)r * h, 1, s, out_bf16, skip);  // copy only
+    if (sp.splits > 1) return reduce_slabs(partials, out_t, (int64_t)r * h, sp.splits, s, out_bf16, skip, jobs, job_stride);
+    if (out_bf16) return reduce_slabs(out_t, out_t, (int64_t)r * h, 1, s, out_bf16, skip, jobs, job_stride);  // copy only
     return DAD_OK;
 }
 

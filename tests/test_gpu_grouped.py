@@ -133,3 +133,78 @@ def test_grouped_compress_replays_from_a_hip_graph(gpu):
             assert torch.equal(p1, p2) and torch.equal(g1, g2), rep
         _ = dad.reconstruct_grad(grp.Pt[0], grp.Gt[0])    # eager work between the replays
         torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------- batches: runs of equal layers share their launches
+
+# (rows, h_in, h_out, r): runs of equal shapes, as lists of layer counts per run
+BATCH_CASES = [
+    ((2048, 256, 384, 32), [5, 1, 3]),        # a batch of 5, a layer of another shape, a batch of 3
+    ((256, 128, 128, 16), [33]),              # more jobs than one batch takes: 32 + 1
+    ((8192, 1024, 512, 64), [4]),             # a site reduction's size: single-wave workgroups, row chunks
+    ((1024, 384, 128, 16), [2, 2]),
+]
+
+
+@pytest.mark.parametrize("lanes", [1, 3])
+@pytest.mark.parametrize("shape,runs", BATCH_CASES)
+def test_batched_layers_equal_single_calls(gpu, shape, runs, lanes):
+    """Runs of equal layers (the S site reductions of Algorithm 1) go through merged launches; every
+    layer's pair must be what a call of its own returns, bit for bit, whatever batch it lands in."""
+    N, hi, ho, r = shape
+    layers = []
+    for k, count in enumerate(runs):
+        n, a, b = (N, hi, ho) if k % 2 == 0 else (N // 2, ho, hi)     # odd runs: another shape
+        layers += [_layer(n, a, b, r, 300 + 17 * k + i, gpu, torch.bfloat16) for i in range(count)]
+    single = [dad.compress_rank(A, D, r, 2, G0, check=True) for A, D, G0 in layers]
+    grp = dad.CompressGroup(layers, r, 2, lanes=lanes)
+    for _ in range(2):                                                  # the second run re-uses the regions
+        for p, g in zip(grp.Pt, grp.Gt):
+            p.fill_(float("nan"))
+            g.fill_(float("nan"))
+        Pts, Gts = grp.run(check=True)
+        torch.cuda.synchronize()
+        for (p1, g1), p2, g2 in zip(single, Pts, Gts):
+            assert torch.equal(p1, p2) and torch.equal(g1, g2)
+    for i in (0, len(layers) - 1):
+        A, D, G0 = layers[i]
+        ref = O.rank_r_grad(*O.block_spi(A.float().cpu().numpy(), D.float().cpu().numpy(), G0.cpu().numpy(), 2))
+        assert O.rel_fro(dad.reconstruct_grad(Pts[i], Gts[i]).cpu().numpy(), ref) <= 2e-2
+
+
+def test_batch_reports_a_breakdown_of_one_job(gpu):
+    layers = [_layer(1024, 256, 256, 16, 500 + i, gpu, torch.bfloat16) for i in range(4)]
+    broken = list(layers)
+    A, D, G0 = broken[2]
+    broken[2] = (A, torch.zeros_like(D), G0)
+    grp = dad.CompressGroup(broken, 16, 2, lanes=2)
+    grp.run()
+    assert dad.poll_numeric_status(grp.workspace) == dad.DAD_ERR_NUMERIC
+    healthy = dad.CompressGroup(layers, 16, 2, lanes=2, workspace=grp.workspace)
+    Pts, Gts = healthy.run()
+    assert dad.poll_numeric_status(grp.workspace) == dad.DAD_OK
+    for (A, D, G0), p, g in zip(layers, Pts, Gts):
+        p1, g1 = dad.compress_rank(A, D, 16, 2, G0)
+        assert torch.equal(p1, p) and torch.equal(g1, g)
+
+
+def test_batch_replays_from_a_hip_graph(gpu):
+    dad.init()
+    layers = [_layer(2048, 256, 512, 32, 600 + i, gpu, torch.bfloat16) for i in range(6)]
+    grp = dad.CompressGroup(layers, 32, 2, lanes=2)
+    eager = [(p.clone(), g.clone()) for p, g in zip(*grp.run(check=True))]
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        grp.run()
+    for rep in range(3):
+        for p, g in zip(grp.Pt, grp.Gt):
+            p.fill_(float("nan"))
+            g.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for (p1, g1), p2, g2 in zip(eager, grp.Pt, grp.Gt):
+            assert torch.equal(p1, p2) and torch.equal(g1, g2), rep
+        _ = dad.reconstruct_grad(grp.Pt[0], grp.Gt[0])    # eager work between the replays
+        torch.cuda.synchronize()
