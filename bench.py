@@ -63,6 +63,9 @@ def parse():
     ap.add_argument("--agg-route", default="gram", choices=["gram", "block"],
                     help="two_level: the aggregator's reduction of the S*r stacked rows runs on the Gram matrices "
                          "of the stack (dad_compress_rank_gram, when S*r <= 512) or as the block power iteration")
+    ap.add_argument("--site-route", default="grouped", choices=["grouped", "streams"],
+                    help="two_level: the S site reductions of a layer as one dad_compress_rank_grouped call, or as S "
+                         "dad_compress_rank calls on --site-streams streams")
     ap.add_argument("--site-streams", type=int, default=8,
                     help="two_level: HIP streams (default priority) the independent per-site reductions are spread over")
     return ap.parse_args()
@@ -128,8 +131,27 @@ def two_level(args, w, dad, W, torch, np, dev):
     torch.cuda.synchronize()
     PH = ("site_compress", "stack_pairs", "agg_compress", "rebuild_rank")
 
+    # The S site reductions of a layer as ONE dad_compress_rank_grouped call: equal sites on the
+    # direct-to-LDS path share their launches (a batch), others run on up to n_str lanes.
+    site_groups = {}
+    if args.site_route == "grouped":
+        placeholder = torch.zeros(256, dtype=torch.uint8, device=dev)
+        for li, hi, ho in layers:
+            As, Ds = factors_of(li)
+            site_groups[li] = dad.CompressGroup([(As[s_], Ds[s_], G0s[li][s_]) for s_ in range(S)], r, n_iter,
+                                                lanes=min(n_str, dad.DAD_MAX_LANES), Pts=Ps[(hi, ho)], Gts=Gs[(hi, ho)],
+                                                workspace=placeholder)
+        ws_g = torch.zeros(max(g.need for g in site_groups.values()), dtype=torch.uint8, device=dev)
+        for g in site_groups.values():      # all share one workspace, sized for the largest layer
+            g.workspace = ws_g
+        ws_s = [ws_g]
+
     def site_pass(li, sh, As, Ds):
-        """The S independent site reductions, site s on stream s mod n_str (each with its own workspace)."""
+        """The S independent site reductions: one grouped call, or (--site-route streams) site s on
+        stream s mod n_str, each stream with its own workspace."""
+        if site_groups:
+            site_groups[li].run()
+            return
         if not side:
             for s_ in range(S):
                 dad.compress_rank(As[s_], Ds[s_], r, n_iter, G0s[li][s_], Pt=Ps[sh][s_], Gt=Gs[sh][s_], workspace=ws_s[0])
@@ -300,7 +322,7 @@ def two_level(args, w, dad, W, torch, np, dev):
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name + "/two_level", "layers": nl, "shapes": [list(s_) for s_ in w.shapes],
                    "sites": S, "rows_per_site": b, "aggregator_rows": S * r, "rank": r, "n_iter": n_iter,
-                   "site_streams": n_str, "hip_graphs": use_graphs,
+                   "site_route": args.site_route, "site_streams": n_str, "hip_graphs": use_graphs,
                    "agg_route": "gram" if agg_gram else "block",
                    "resident_layers": len(resident)},
         "site_compress_us_per_layer": phase_ms["site_compress"] * 1e3 / nl,

@@ -473,6 +473,7 @@ class CompressGroup:
         need = lib().dad_compress_grouped_workspace_bytes(self.n, self.descs, self.dt, r, lanes)
         if need == 0:
             raise ValueError("invalid sizes for dad_compress_rank_grouped")
+        self.need = need        # bytes of workspace one run() takes
         if workspace is None:
             workspace = torch.zeros(need, dtype=torch.uint8, device=dev)
         self.workspace = workspace

@@ -215,8 +215,10 @@ __global__ __launch_bounds__(64 * W) void k_thin_nn_bf16_dma(const SRC X, const 
             V = reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(V) + cur.blk * job_stride);
         }
     }
-    // every workgroup starts its walk over the contraction columns at its own stage (see k_thin_nn_bf16)
-    int kidx = (int)(((unsigned)(n0 / RT) * 5u) % (unsigned)nk);
+    // Every group of 256 rows starts its walk over the contraction columns at its own stage (see
+    // k_thin_nn_bf16).  The start depends on the rows, not on the workgroup size, so that a row's sum
+    // is taken in the same order whatever W the launch uses.
+    int kidx = (int)(((unsigned)(n0 / 256) * 5u) % (unsigned)nk);
 
     const char* gx[4];
 #pragma unroll
@@ -735,13 +737,14 @@ dad_status dma_thin_nn(const void* X, const RowBlocks* xb, const void* Pb, void*
     if (job_stride != 0 && !xb) return DAD_ERR_SHAPE;
     if (job_stride == 0) jobs = 1;
     ProfScope prof(KID_THIN_NN_BF16, s);
-    const int64_t want = 256;  // workgroups
+    const int64_t want = 256;          // workgroups
+    const int64_t rows = jobs * N;     // a batch fills the chip with the rows of all its jobs (the result does not depend on W)
 #define DAD_NN_W(W) \
     (r <= 32 ? dma_thin_nn_cfg<32, W, 3>(X, xb, Pb, out, N, h, r, planes, jobs, job_stride, s) \
              : dma_thin_nn_cfg<64, W, 3>(X, xb, Pb, out, N, h, r, planes, jobs, job_stride, s))
-    if (N / 256 >= want) return DAD_NN_W(8);
-    if (N / 128 >= want) return DAD_NN_W(4);
-    if (N / 64 >= want) return DAD_NN_W(2);
+    if (rows / 256 >= want) return DAD_NN_W(8);
+    if (rows / 128 >= want) return DAD_NN_W(4);
+    if (rows / 64 >= want) return DAD_NN_W(2);
     return DAD_NN_W(1);
 #undef DAD_NN_W
 }
