@@ -23,6 +23,7 @@ dad_status gen_rebuild(const void*, const void*, int64_t, int64_t, int64_t, dad_
                        hipStream_t);
 dad_status launch_stack(int, const void* const*, const void* const*, const int64_t*, int64_t, int64_t, dad_dtype,
                         void*, void*, hipStream_t);
+dad_status f32_thin_nn(const float*, const float*, float*, float*, SplitPlan, int64_t, int64_t, int, int*, hipStream_t);
 int gram_blocks_for(int64_t h);
 bool thin_fast_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
 SplitPlan thin_tn_split(int64_t N, int64_t h, int r);
@@ -286,15 +287,24 @@ static dad_status compress_launch(const CompressPlan& p, const void* A, const vo
         const RowBlocks* blocks;  // row blocks (ptr unused)
     };
     const Factor FA = {A, Ab}, FD = {D, Db};
+    // fp32 factors: both thin contractions run on the fp32 matrix instruction
+    const bool f32_mfma = !p.fast && dt == DAD_F32;
     auto nn = [&](const Factor& X, const float* panel, const void* panel_bf16, int64_t h, SplitPlan sp, int* hdr,
                   int planes) {
         if (p.dma) return dma_thin_nn(X.ptr, X.blocks, panel_bf16, V, N, h, r, planes, s, jobs, jstride);
+        if (f32_mfma)
+            return f32_thin_nn(static_cast<const float*>(X.ptr), panel, static_cast<float*>(V), part, sp, N, h, r, hdr, s);
         return launch_thin_nn(X.ptr, panel, V, part, sp, N, h, r, dt, p.fast, hdr, planes, s);
     };
     // out (r x h) <- V^T X, with an optional bf16 copy
     auto tn = [&](const Factor& X, float* out, int64_t h, SplitPlan sp, void* out_bf16, int planes) {
         if (X.blocks)
             return fast_thin_tn(nullptr, X.blocks, V, out, part, sp, N, h, r, out_bf16, planes, s, nullptr, jobs, jstride);
+        if (f32_mfma) {  // V^T X is the rebuild L^T R with L = V (N x r) and R = X
+            const void* L = V;
+            const int64_t r64 = r;
+            return launch_rebuild_f32(1, &L, &X.ptr, &out, &N, &r64, &h, &sp, &part, s, KID_THIN_TN);
+        }
         return launch_thin_tn(X.ptr, V, out, part, sp, N, h, r, dt, p.fast, out_bf16, planes, s);
     };
     // On the MFMA path the N x r intermediates are bf16.  V = Delta G goes as one plane.  W = A U goes

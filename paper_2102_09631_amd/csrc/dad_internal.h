@@ -264,8 +264,9 @@ dad_status launch_rebuild(const void* L, const void* R, int64_t K, int64_t h_in,
 // G_i = L_i^T R_i for n fp32 jobs in as few launches as possible (csrc/rebuild_f32.hip); a job with
 // sp[i].splits > 1 goes through slabs[i] (splits * h_in * h_out floats) and reduce_slabs.
 SplitPlan rebuild_f32_split(int64_t K, int64_t h_in, int64_t h_out);
+// kid: the timing id the launches are booked under.
 dad_status launch_rebuild_f32(int n, const void* const* L, const void* const* R, float* const* G, const int64_t* K,
                               const int64_t* h_in, const int64_t* h_out, const SplitPlan* sp, float* const* slabs,
-                              hipStream_t s);
+                              hipStream_t s, int kid = KID_REBUILD_F32);
 
 }  // namespace dad

@@ -200,7 +200,7 @@ SplitPlan rebuild_f32_split(int64_t K, int64_t h_in, int64_t h_out) {
 // at slabs[i] and is summed by reduce_slabs afterwards) in as few launches as the job table allows.
 dad_status launch_rebuild_f32(int n, const void* const* L, const void* const* R, float* const* G, const int64_t* K,
                               const int64_t* h_in, const int64_t* h_out, const SplitPlan* sp, float* const* slabs,
-                              hipStream_t s) {
+                              hipStream_t s, int kid) {
     // the large tile for the 16-byte jobs when together they fill the chip twice over with it
     int64_t big_total = 0;
     for (int i = 0; i < n; ++i)
@@ -212,7 +212,7 @@ dad_status launch_rebuild_f32(int n, const void* const* L, const void* const* R,
     auto flush = [&]() -> dad_status {
         if (nj == 0) return DAD_OK;
         for (int i = nj; i < rf::MAX_JOBS; ++i) tb.first_block[i] = 0x7fffffff;
-        ProfScope prof(KID_REBUILD_F32, s);
+        ProfScope prof(kid, s);
         if (big)
             hipLaunchKernelGGL((k_rebuild_f32_mfma<2, 4, true>), dim3((unsigned)blocks), dim3(256), 0, s, tb);
         else if (vec)
