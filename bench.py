@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--graphs", default="off", choices=["auto", "on", "off"],
                     help="default mode: replay one captured HIP graph per operation of a step (auto: workloads of "
                          "at most 8 layers, which are bound by launch latency)")
+    ap.add_argument("--rebuild-group", type=int, default=0,
+                    help="layers per full-gradient call (dad_reconstruct_grad_grouped); 1 = one dad_reconstruct_grad per "
+                         "layer; 0 = a block's layers together for the small workloads, few-tile neighbours for the large ones")
     ap.add_argument("--no-sites-leg", action="store_true",
                     help="skip the extra timed leg that reads the sites' blocks in place (no stacking pass)")
     ap.add_argument("--no-other-workloads", action="store_true",
@@ -649,18 +652,54 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
                                             Pts=[Pt[t[0]] for t in sc], Gts=[Gt[t[0]] for t in sc],
                                             workspace=groups[0].workspace if groups else None))
 
+    # Full gradients: `rg` consecutive layers per dad_reconstruct_grad_grouped call (1: one
+    # dad_reconstruct_grad call per layer).  The layers of a call must have distinct shapes here, because
+    # the bench keeps one output buffer per shape.
+    # Automatic: a whole block for the small workloads (their launches are short); for the large ones
+    # consecutive layers are joined only while their 256 x 256 output tiles together stay within 64, i.e.
+    # while the call still splits K at least four ways: that merges the few-tile layers (whose own calls
+    # split K 16 ways and write 16 slabs) and leaves the others alternating with the stacking passes.
+    small = w.N * max(hi * ho for hi, ho in w.shapes) < (1 << 37)
+    rg = max(1, min(args.rebuild_group, nb)) if args.rebuild_group > 0 else (nb if small else 0)
+    tile_budget = 64
+    full_groups = {}
+    def full_group(chunk):
+        key = tuple(t[0] for t in chunk)
+        if key not in full_groups:
+            full_groups[key] = dad.RebuildGroup([(A_st[st_key(*t)], D_st[st_key(*t)]) for t in chunk],
+                                                [G_full[(t[1], t[2])] for t in chunk])
+        return full_groups[key]
+
     def make_ops(grouped):
         ops = []
         for si, sc in enumerate(scopes):
-            for li, hi, ho in sc:
+            pending = []
+            for j, (li, hi, ho) in enumerate(sc):
                 k = st_key(li, hi, ho)
                 As, Ds = factors_of(li)
                 ops.append(("stack", lambda As=As, Ds=Ds, k=k: dad.stack_factors(As, Ds, A_out=A_st[k], D_out=D_st[k])))
                 if not grouped:
                     ops.append(("compress", lambda k=k, li=li: dad.compress_rank(A_st[k], D_st[k], r, n_iter, G0[li], Pt=Pt[li],
                                                                                  Gt=Gt[li], workspace=ws_c)))
-                ops.append(("rebuild_full", lambda k=k, s_=(hi, ho): dad.reconstruct_grad(A_st[k], D_st[k], G=G_full[s_],
-                                                                                          workspace=ws_r)))
+                if rg == 1 or not grouped:
+                    ops.append(("rebuild_full", lambda k=k, s_=(hi, ho): dad.reconstruct_grad(A_st[k], D_st[k], G=G_full[s_],
+                                                                                              workspace=ws_r)))
+                    continue
+                pending.append((li, hi, ho))
+                nxt = sc[j + 1] if j + 1 < len(sc) and (li + 1) % nb != 0 else None
+                if rg > 0:
+                    close = len(pending) == rg or nxt is None
+                else:
+                    tiles = lambda t: -(-t[1] // 256) * -(-t[2] // 256)
+                    close = nxt is None or sum(tiles(t) for t in pending) + tiles(nxt) > tile_budget
+                if close:
+                    if len(pending) == 1:
+                        k1, s1 = st_key(*pending[0]), (pending[0][1], pending[0][2])
+                        ops.append(("rebuild_full", lambda k=k1, s_=s1: dad.reconstruct_grad(A_st[k], D_st[k], G=G_full[s_],
+                                                                                             workspace=ws_r)))
+                    else:
+                        ops.append(("rebuild_full", full_group(pending).run))
+                    pending = []
             if grouped:
                 ops.append(("compress", groups[si].run))
         ops.append(("rebuild_rank", rank_group.run))
@@ -986,7 +1025,7 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
         "config": {"workload": w.name, "layers": nl, "shapes": [list(s) for s in w.shapes], "sites": S,
                    "rows_per_site": b, "N": N, "rank": r, "n_iter": n_iter,
                    "resident_layers": len(resident), "compress_lanes": args.lanes,
-                   "compress_group_layers": gl, "hip_graphs": use_graphs},
+                   "compress_group_layers": gl, "rebuild_group_layers": rg, "hip_graphs": use_graphs},
         "rebuild_frac_of_mfma_peak": rebuild_tflops / (PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS),
         "compress_us_per_layer": phase_ms["compress"] * 1e3 / nl,
         "compress_GBps": bytes_compress / (phase_ms["compress"] * 1e-3) / 1e9,

@@ -332,9 +332,15 @@ dad_status dad_reconstruct_grad(const void* L, const void* R, int64_t K, int64_t
  *   dt        element type of every L_i, R_i
  *   workspace device, ws_bytes >= dad_reconstruct_grouped_workspace_bytes(n, descs, dt) (may be NULL
  *             when that is 0)
- * Results are bit-identical to n separate dad_reconstruct_grad calls.  fp32 jobs (the rank-r pairs,
- * K = r) share launches, up to 32 jobs per launch: one layer's rank-r gradient is a few MB and
- * launch bound on its own.  bf16 jobs are large and run one after the other.
+ * fp32 jobs (the rank-r pairs, K = r) share launches, up to 32 jobs per launch: one layer's rank-r
+ * gradient is a few MB and launch bound on its own; their results are bit-identical to n separate
+ * dad_reconstruct_grad calls.  Runs of consecutive bf16 jobs with K a multiple of 32 and widths
+ * multiples of 256 (the full gradients of a block's layers) share launches too, up to 16 per launch,
+ * with ONE number of K chunks chosen for the run as a whole: gradients with few output tiles then
+ * fill the chip together instead of each splitting K finely.  Such a job is summed in another chunk
+ * order than a call of its own would use: equal to it within fp32 summation error (the parity bar
+ * against the oracle is the same), bit-identical from run to run.  Other bf16 jobs run one after the
+ * other exactly as dad_reconstruct_grad runs them.
  */
 typedef struct {
     const void* L; /* K x h_in  */

@@ -42,6 +42,12 @@ SplitPlan rebuild_fast_split(int64_t K, int64_t h_in, int64_t h_out, int* tile);
 dad_status fast_rebuild(const void*, const void*, const RowBlocks*, const RowBlocks*, int64_t, int64_t, int64_t, float*,
                         float*, SplitPlan, int, hipStream_t);
 bool rebuild_dma_ok(int64_t K, SplitPlan sp);
+bool rebuild_group_ok(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
+int rebuild_group_splits(int n, const int64_t* K, const int64_t* h_in, const int64_t* h_out);
+SplitPlan rebuild_group_plan(int64_t K, int splits);
+dad_status launch_rebuild_group(int n, const void* const* L, const void* const* R, float* const* G, const int64_t* K,
+                                const int64_t* h_in, const int64_t* h_out, const SplitPlan* sp, float* const* slabs,
+                                hipStream_t s);
 
 static SplitPlan split_rows(int64_t rows, int64_t tiles, int64_t target_blocks, int64_t min_chunk, int64_t quantum) {
     int64_t want = ceil_div(target_blocks, tiles);
@@ -746,25 +752,70 @@ static dad_status rebuild_job_ok(const dad_rebuild_desc& d, dad_dtype dt, Rebuil
     return DAD_OK;
 }
 
-// fp32 jobs run together and need their slabs side by side; the others run one after the other on
-// the stream and share one region.
-static size_t grouped_rebuild_bytes(int n, const dad_rebuild_desc* descs, dad_dtype dt) {
-    size_t total = 0;
+// Plan of a grouped rebuild.  fp32 jobs all run together (one job table) with their slabs side by
+// side.  bf16 jobs run unit by unit on the stream and share one region: a unit is a run of up to 16
+// consecutive jobs with whole 256-tiles and K stages, launched together with a common number of K
+// chunks chosen for the run as a whole (few-tile gradients then fill the chip together and write
+// fewer slabs), or a single job planned as dad_reconstruct_grad plans it.
+struct RebuildUnit {
+    int first, count;
+};
+struct GroupedRebuild {
+    std::vector<RebuildPlan> single;  // per job, as a call of its own
+    std::vector<RebuildUnit> units;   // bf16 only
+    std::vector<SplitPlan> split;     // per job: the split it runs with
+    std::vector<size_t> off;          // per job: byte offset of its slabs in the workspace
+    size_t bytes = 0;
+};
+
+static void plan_grouped_rebuild(int n, const dad_rebuild_desc* descs, dad_dtype dt, GroupedRebuild* g) {
+    const size_t N = (size_t)n;
+    g->single.resize(N), g->split.resize(N), g->off.assign(N, 0);
     for (int i = 0; i < n; ++i) {
-        const RebuildPlan p = plan_rebuild(descs[i].K, descs[i].h_in, descs[i].h_out, dt);
-        if (p.f32)
-            total += align_up(p.total, 256);
-        else if (p.total > total)
-            total = p.total;
+        g->single[(size_t)i] = plan_rebuild(descs[i].K, descs[i].h_in, descs[i].h_out, dt);
+        g->split[(size_t)i] = g->single[(size_t)i].split;
     }
-    return total;
+    if (dt == DAD_F32) {
+        size_t off = 0;
+        for (int i = 0; i < n; ++i) {
+            g->off[(size_t)i] = off;
+            off += align_up(g->single[(size_t)i].total, 256);
+        }
+        g->bytes = off;
+        return;
+    }
+    for (int i = 0; i < n;) {
+        int cnt = 1;
+        if (rebuild_group_ok(descs[i].K, descs[i].h_in, descs[i].h_out, dt))
+            while (i + cnt < n && cnt < 16 && rebuild_group_ok(descs[i + cnt].K, descs[i + cnt].h_in, descs[i + cnt].h_out, dt))
+                ++cnt;
+        g->units.push_back(RebuildUnit{i, cnt});
+        size_t need = g->single[(size_t)i].total;
+        if (cnt > 1) {
+            std::vector<int64_t> K((size_t)cnt), hi((size_t)cnt), ho((size_t)cnt);
+            for (int j = 0; j < cnt; ++j) K[(size_t)j] = descs[i + j].K, hi[(size_t)j] = descs[i + j].h_in, ho[(size_t)j] = descs[i + j].h_out;
+            const int splits = rebuild_group_splits(cnt, K.data(), hi.data(), ho.data());
+            need = 0;
+            for (int j = 0; j < cnt; ++j) {
+                const size_t k = (size_t)(i + j);
+                g->split[k] = rebuild_group_plan(descs[i + j].K, splits);
+                g->off[k] = need;
+                if (g->split[k].splits > 1)
+                    need += align_up((size_t)g->split[k].splits * descs[i + j].h_in * descs[i + j].h_out * 4, 256);
+            }
+        }
+        if (need > g->bytes) g->bytes = need;
+        i += cnt;
+    }
 }
 
 size_t dad_reconstruct_grouped_workspace_bytes(int n, const dad_rebuild_desc* descs, dad_dtype dt) {
     if (n < 1 || n > DAD_MAX_GROUP || !descs || !dtype_ok(dt)) return 0;
     for (int i = 0; i < n; ++i)
         if (!rebuild_shape_ok(descs[i].K, descs[i].h_in, descs[i].h_out)) return 0;
-    return grouped_rebuild_bytes(n, descs, dt);
+    GroupedRebuild g;
+    plan_grouped_rebuild(n, descs, dt, &g);
+    return g.bytes;
 }
 
 dad_status dad_reconstruct_grad_grouped(int n, const dad_rebuild_desc* descs, dad_dtype dt, void* workspace,
@@ -777,31 +828,43 @@ dad_status dad_reconstruct_grad_grouped(int n, const dad_rebuild_desc* descs, da
         const dad_status rc = rebuild_job_ok(descs[i], dt, &plans[(size_t)i]);
         if (rc != DAD_OK) return rc;
     }
-    const size_t need = grouped_rebuild_bytes(n, descs, dt);
-    if (need > 0 && !workspace) return DAD_ERR_NULL;
+    GroupedRebuild g;
+    plan_grouped_rebuild(n, descs, dt, &g);
+    if (g.bytes > 0 && !workspace) return DAD_ERR_NULL;
     if (workspace && !aligned16(workspace)) return DAD_ERR_ALIGN;
-    if (ws_bytes < need) return DAD_ERR_WORKSPACE;
+    if (ws_bytes < g.bytes) return DAD_ERR_WORKSPACE;
     if (const dad_status ready = device_ready(); ready != DAD_OK) return ready;
     hipStream_t s = (hipStream_t)stream;
-    if (dt == DAD_F32) {  // every fp32 shape runs on the fp32 MFMA kernel: one job table for all of them
-        std::vector<const void*> L((size_t)n), R((size_t)n);
-        std::vector<float*> G((size_t)n), slabs((size_t)n);
-        std::vector<int64_t> K((size_t)n), hi((size_t)n), ho((size_t)n);
-        std::vector<SplitPlan> sp((size_t)n);
-        size_t off = 0;
-        for (int i = 0; i < n; ++i) {
-            const size_t k = (size_t)i;
-            L[k] = descs[i].L, R[k] = descs[i].R, G[k] = descs[i].G;
-            K[k] = descs[i].K, hi[k] = descs[i].h_in, ho[k] = descs[i].h_out;
-            sp[k] = plans[k].split;
-            slabs[k] = plans[k].total ? reinterpret_cast<float*>(static_cast<char*>(workspace) + off) : nullptr;
-            off += align_up(plans[k].total, 256);
+    char* ws = static_cast<char*>(workspace);
+    // the arguments of jobs first .. first + cnt - 1 as parallel arrays
+    auto run = [&](int first, int cnt, bool f32) -> dad_status {
+        const size_t c = (size_t)cnt;
+        std::vector<const void*> L(c), R(c);
+        std::vector<float*> G(c), slabs(c);
+        std::vector<int64_t> K(c), hi(c), ho(c);
+        std::vector<SplitPlan> sp(c);
+        for (int j = 0; j < cnt; ++j) {
+            const size_t k = (size_t)j, q = (size_t)(first + j);
+            L[k] = descs[first + j].L, R[k] = descs[first + j].R, G[k] = descs[first + j].G;
+            K[k] = descs[first + j].K, hi[k] = descs[first + j].h_in, ho[k] = descs[first + j].h_out;
+            sp[k] = g.split[q];
+            slabs[k] = sp[k].splits > 1 ? reinterpret_cast<float*>(ws + g.off[q]) : nullptr;
         }
-        return launch_rebuild_f32(n, L.data(), R.data(), G.data(), K.data(), hi.data(), ho.data(), sp.data(), slabs.data(), s);
-    }
-    for (int i = 0; i < n; ++i) {
-        const dad_status rc = launch_rebuild(descs[i].L, descs[i].R, descs[i].K, descs[i].h_in, descs[i].h_out, dt,
-                                             descs[i].G, static_cast<float*>(workspace), plans[(size_t)i], s);
+        if (f32)
+            return launch_rebuild_f32(cnt, L.data(), R.data(), G.data(), K.data(), hi.data(), ho.data(), sp.data(),
+                                      slabs.data(), s);
+        return launch_rebuild_group(cnt, L.data(), R.data(), G.data(), K.data(), hi.data(), ho.data(), sp.data(),
+                                    slabs.data(), s);
+    };
+    if (dt == DAD_F32) return run(0, n, true);  // every fp32 shape runs on the fp32 MFMA kernel: one job table
+    for (const RebuildUnit& u : g.units) {
+        dad_status rc;
+        if (u.count > 1)
+            rc = run(u.first, u.count, false);
+        else
+            rc = launch_rebuild(descs[u.first].L, descs[u.first].R, descs[u.first].K, descs[u.first].h_in,
+                                descs[u.first].h_out, dt, descs[u.first].G, reinterpret_cast<float*>(ws),
+                                g.single[(size_t)u.first], s);
         if (rc != DAD_OK) return rc;
     }
     return DAD_OK;

@@ -186,11 +186,17 @@ constexpr int DMA_LOADS = 4;  // 16-byte loads per thread per stage, for both ti
 // SRC is `const bf16_t*` (operands in one allocation each) or RowBlocks (the sites' blocks in
 // place, the same row split for both operands, every block a multiple of 256 rows): a K chunk may
 // span blocks, and the operand pointers jump at a block's end.
+// The XCD-aware order of the workgroups of a launch: ids congruent mod 8 share an XCD and get
+// consecutive logical ids.
+__device__ __forceinline__ int rb_logical_id(int total) {
+    const int per = total >> 3, main = per << 3;
+    return (int)blockIdx.x < main ? (int)((blockIdx.x & 7) * per + (blockIdx.x >> 3)) : (int)blockIdx.x;
+}
+
+// One workgroup's tile: `lid` is its logical index among the tiles_m * tiles_n * splits of this product.
 template <int T, int WM, int WN, typename SRC>
-__global__ __launch_bounds__(64 * WM * WN) void k_rebuild_bf16_dma(const SRC L, const SRC R,
-                                                                  float* __restrict__ out, int64_t K, int h_in,
-                                                                  int h_out, int64_t chunk, int tiles_m,
-                                                                  int tiles_n, int total) {
+__device__ __forceinline__ void rebuild_tile_dma(const SRC& L, const SRC& R, float* __restrict__ out, int64_t K, int h_in,
+                                                 int h_out, int64_t chunk, int tiles_m, int tiles_n, int lid) {
     constexpr int WAVES = WM * WN;
     constexpr int FA = T / (32 * WM), FB = T / (32 * WN);  // 32-wide fragments per wave
     constexpr int ROWB = T * 2;                            // bytes per LDS row
@@ -203,11 +209,6 @@ __global__ __launch_bounds__(64 * WM * WN) void k_rebuild_bf16_dma(const SRC L, 
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave / WN, wn = wave % WN;
 
-    int lid = blockIdx.x;
-    {
-        const int per = total >> 3, main = per << 3;
-        if ((int)blockIdx.x < main) lid = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
-    }
     const int tiles = tiles_m * tiles_n;
     const int split = lid / tiles, tile = lid - split * tiles;
     int pm, qn;
@@ -354,6 +355,45 @@ __global__ __launch_bounds__(64 * WM * WN) void k_rebuild_bf16_dma(const SRC L, 
         }
 }
 
+template <int T, int WM, int WN, typename SRC>
+__global__ __launch_bounds__(64 * WM * WN) void k_rebuild_bf16_dma(const SRC L, const SRC R,
+                                                                  float* __restrict__ out, int64_t K, int h_in,
+                                                                  int h_out, int64_t chunk, int tiles_m,
+                                                                  int tiles_n, int total) {
+    rebuild_tile_dma<T, WM, WN, SRC>(L, R, out, K, h_in, h_out, chunk, tiles_m, tiles_n, rb_logical_id(total));
+}
+
+// Several products in one launch (the full gradients of the layers of a block): gradients with few
+// 256-tiles fill the chip together, so each needs fewer K chunks and writes fewer fp32 slabs.
+namespace rb {
+constexpr int MAX_JOBS = 16;
+}
+struct RebuildJob {
+    const bf16_t* L;
+    const bf16_t* R;
+    float* out;  // G, or the first of its slabs
+    int64_t K, chunk;
+    int h_in, h_out, tiles_m, tiles_n;
+};
+struct RebuildJobs {
+    int first_block[rb::MAX_JOBS];  // first logical id of each job; entries beyond the last job hold INT_MAX
+    RebuildJob j[rb::MAX_JOBS];
+};
+
+template <int T, int WM, int WN>
+__global__ __launch_bounds__(64 * WM * WN) void k_rebuild_bf16_dma_jobs(RebuildJobs tb, int total) {
+    const int lid = rb_logical_id(total);
+    int ji = 0;
+#pragma unroll
+    for (int i = 1; i < rb::MAX_JOBS; ++i) ji += tb.first_block[i] <= lid ? 1 : 0;
+    const RebuildJob& jb = tb.j[ji];
+    const bf16_t* L = jb.L;
+    const bf16_t* R = jb.R;
+    rebuild_tile_dma<T, WM, WN, const bf16_t*>(L, R, jb.out, jb.K, jb.h_in, jb.h_out, jb.chunk, jb.tiles_m, jb.tiles_n,
+                                               lid - tb.first_block[ji]);
+}
+
+
 
 bool rebuild_fast_ok(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt) {
     if (dt != DAD_BF16 || K < 256 || h_in > (1 << 20) || h_out > (1 << 20)) return false;
@@ -441,7 +481,93 @@ dad_status fast_rebuild(const void* L, const void* R, const RowBlocks* lb, const
     return DAD_OK;
 }
 
+// True when a product can join a launch of several: whole 256-tiles and whole K stages.
+bool rebuild_group_ok(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt) {
+    return dt == DAD_BF16 && K >= 256 && K % rb::BK == 0 && h_in % 256 == 0 && h_out % 256 == 0 && h_in <= (1 << 20) &&
+           h_out <= (1 << 20);
+}
+
+// Number of K chunks for n products launched together (the same for all of them): the score of
+// rebuild_fast_split on the totals.
+int rebuild_group_splits(int n, const int64_t* K, const int64_t* h_in, const int64_t* h_out) {
+    int64_t tiles = 0, kmin = K[0];
+    double ops = 0.0, outs = 0.0;
+    for (int i = 0; i < n; ++i) {
+        tiles += (h_in[i] / 256) * (h_out[i] / 256);
+        ops += (double)K[i] * (h_in[i] + h_out[i]) * 2.0;
+        outs += (double)h_in[i] * h_out[i] * 4.0;
+        if (K[i] < kmin) kmin = K[i];
+    }
+    int best = 1;
+    double best_score = -1.0;
+    for (int s = 1; s <= 64; ++s) {
+        if (s > 1 && kmin / s < 1024) break;
+        const int64_t wg = tiles * s;
+        const double eff = (double)wg / (double)(ceil_div(wg, 256) * 256);
+        const double extra = s > 1 ? (2.0 * s + 1.0) * outs : 0.0;
+        const double score = eff / (1.0 + extra / ops);
+        if (score > best_score * 1.02) {
+            best_score = score;
+            best = s;
+        }
+    }
+    return best;
+}
+
+SplitPlan rebuild_group_plan(int64_t K, int splits) {
+    SplitPlan sp;
+    sp.chunk = (int64_t)align_up((size_t)ceil_div(K, splits), rb::BK);
+    sp.splits = (int)ceil_div(K, sp.chunk);
+    return sp;
+}
+
+// n products (every one passes rebuild_group_ok; sp[i] from rebuild_group_plan) in launches of up to
+// rb::MAX_JOBS; a product with sp[i].splits > 1 goes through slabs[i] and reduce_slabs.
+dad_status launch_rebuild_group(int n, const void* const* L, const void* const* R, float* const* G, const int64_t* K,
+                                const int64_t* h_in, const int64_t* h_out, const SplitPlan* sp, float* const* slabs,
+                                hipStream_t s) {
+    const int lds = rb::DMA_STAGES * 2 * rb::BK * 256 * 2;
+    for (int first = 0; first < n; first += rb::MAX_JOBS) {
+        const int cnt = n - first < rb::MAX_JOBS ? n - first : rb::MAX_JOBS;
+        RebuildJobs tb;
+        int64_t blocks = 0;
+        for (int i = 0; i < rb::MAX_JOBS; ++i) {
+            if (i >= cnt) {
+                tb.first_block[i] = 0x7fffffff;
+                tb.j[i] = RebuildJob{};
+                continue;
+            }
+            const int k = first + i;
+            RebuildJob& jb = tb.j[i];
+            jb.L = static_cast<const bf16_t*>(L[k]);
+            jb.R = static_cast<const bf16_t*>(R[k]);
+            jb.out = sp[k].splits == 1 ? G[k] : slabs[k];
+            jb.K = K[k];
+            jb.chunk = sp[k].chunk;
+            jb.h_in = (int)h_in[k];
+            jb.h_out = (int)h_out[k];
+            jb.tiles_m = (int)(h_in[k] / 256);
+            jb.tiles_n = (int)(h_out[k] / 256);
+            tb.first_block[i] = (int)blocks;
+            blocks += (int64_t)jb.tiles_m * jb.tiles_n * sp[k].splits;
+            if (blocks > ((int64_t)1 << 30)) return DAD_ERR_SHAPE;
+        }
+        {
+            ProfScope prof(KID_REBUILD_BF16_DMA, s);
+            hipLaunchKernelGGL((k_rebuild_bf16_dma_jobs<256, 2, 4>), dim3((unsigned)blocks), dim3(512), lds, s, tb, (int)blocks);
+        }
+        DAD_LAUNCH_CHECK();
+    }
+    for (int i = 0; i < n; ++i) {
+        if (sp[i].splits == 1) continue;
+        const dad_status rc = reduce_slabs(slabs[i], G[i], h_in[i] * h_out[i], sp[i].splits, s);
+        if (rc != DAD_OK) return rc;
+    }
+    return DAD_OK;
+}
+
 dad_status rebuild_prepare_device() {
+    DAD_HIP_TRY(set_max_lds((k_rebuild_bf16_dma_jobs<256, 2, 4>), rb::DMA_STAGES * 2 * rb::BK * 256 * 2));
     DAD_HIP_TRY(set_max_lds((k_rebuild_bf16_dma<256, 2, 4, const bf16_t*>), rb::DMA_STAGES * 2 * rb::BK * 256 * 2));
     DAD_HIP_TRY(set_max_lds((k_rebuild_bf16_dma<128, 2, 2, const bf16_t*>), rb::DMA_STAGES * 2 * rb::BK * 128 * 2));
     DAD_HIP_TRY(set_max_lds((k_rebuild_bf16_dma<256, 2, 4, RowBlocks>), rb::DMA_STAGES * 2 * rb::BK * 256 * 2));

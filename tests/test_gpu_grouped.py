@@ -208,3 +208,29 @@ def test_batch_replays_from_a_hip_graph(gpu):
             assert torch.equal(p1, p2) and torch.equal(g1, g2), rep
         _ = dad.reconstruct_grad(grp.Pt[0], grp.Gt[0])    # eager work between the replays
         torch.cuda.synchronize()
+
+
+def test_grouped_rebuild_of_bf16_runs_shares_launches(gpu):
+    """A block's full gradients in one call: the four encoder-sized shapes run as one launch with a
+    common K split, a ragged job in between runs on its own; every result within the a5 bar of the
+    oracle and identical from run to run."""
+    shapes = [(4096, 768, 2304), (4096, 768, 768), (4096, 768, 3072), (4096, 3072, 768), (1000, 256, 264),
+              (2048, 256, 512), (2048, 512, 256)]
+    pairs = [_pair(K, hi, ho, 700 + i, gpu, torch.bfloat16) for i, (K, hi, ho) in enumerate(shapes)]
+    first = [g.clone() for g in dad.reconstruct_grad_grouped(pairs)]
+    again = dad.reconstruct_grad_grouped(pairs)
+    torch.cuda.synchronize()
+    for (L, R), a, b in zip(pairs, first, again):
+        assert torch.equal(a, b)
+        _check_against_oracle(b, L, R, 1e-5)
+    # the ragged job is planned as a call of its own
+    assert torch.equal(first[4], dad.reconstruct_grad(*pairs[4]))
+
+
+def test_grouped_rebuild_of_many_bf16_jobs(gpu):
+    """More jobs than one launch takes (16), at a benchmark K with several chunks."""
+    pairs = [_pair(8192, 256, 256 if i % 2 else 512, 800 + i, gpu, torch.bfloat16) for i in range(19)]
+    got = dad.reconstruct_grad_grouped(pairs)
+    torch.cuda.synchronize()
+    for (L, R), G in zip(pairs, got):
+        _check_against_oracle(G, L, R, 1e-5)
