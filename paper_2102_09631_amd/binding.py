@@ -144,6 +144,21 @@ def _dense2d(t: torch.Tensor, name: str):
         raise ValueError(f"{name} must be a contiguous 2-D CUDA tensor")
 
 
+def _factor_args(A, D, G0, r):
+    """Checks shared by the reductions: A (N x h_in) and Delta (N x h_out) dense CUDA tensors of one dtype,
+    G0 float32 r x h_out.  Returns (N, h_in, h_out, dad_dtype)."""
+    _dense2d(A, "A")
+    _dense2d(D, "Delta")
+    _dense2d(G0, "G0")
+    N, h_in = A.shape
+    h_out = D.shape[1]
+    if D.shape[0] != N or D.dtype != A.dtype:
+        raise ValueError("A and Delta disagree in rows or dtype")
+    if G0.dtype != torch.float32 or tuple(G0.shape) != (r, h_out):
+        raise ValueError("G0 must be float32 of shape (r, h_out)")
+    return N, h_in, h_out, _dt(A)
+
+
 def init():
     """dad_init: one-time set-up of the current device (needed only before a first call under graph capture)."""
     _check(lib().dad_init(), "dad_init")
@@ -254,16 +269,7 @@ def compress_rank(A, D, r, n_iter, G0, Pt=None, Gt=None, workspace=None, check=F
     one is allocated when omitted.  With check=True the stream is synchronised
     and a latched numerical breakdown raises DadError(DAD_ERR_NUMERIC).
     """
-    _dense2d(A, "A")
-    _dense2d(D, "Delta")
-    _dense2d(G0, "G0")
-    N, h_in = A.shape
-    h_out = D.shape[1]
-    if D.shape[0] != N or D.dtype != A.dtype:
-        raise ValueError("A and Delta disagree in rows or dtype")
-    if G0.dtype != torch.float32 or tuple(G0.shape) != (r, h_out):
-        raise ValueError("G0 must be float32 of shape (r, h_out)")
-    dt = _dt(A)
+    N, h_in, h_out, dt = _factor_args(A, D, G0, r)
     if workspace is None:
         nbytes = lib().dad_compress_workspace_bytes(N, h_in, h_out, r, dt)
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=A.device)
@@ -286,15 +292,7 @@ def compress_rank_noalloc(A, D, r, n_iter, G0, Pt, Gt, numeric_flag=None):
     """dad_compress_rank_noalloc: compress_rank on the library's static scratch.  Every buffer is the
     caller's (Pt r x h_in, Gt r x h_out fp32; numeric_flag an int32 tensor of one element or None);
     nothing is allocated here or in the library."""
-    _dense2d(A, "A")
-    _dense2d(D, "Delta")
-    _dense2d(G0, "G0")
-    N, h_in = A.shape
-    h_out = D.shape[1]
-    if D.shape[0] != N or D.dtype != A.dtype:
-        raise ValueError("A and Delta disagree in rows or dtype")
-    if G0.dtype != torch.float32 or tuple(G0.shape) != (r, h_out):
-        raise ValueError("G0 must be float32 of shape (r, h_out)")
+    N, h_in, h_out, dt = _factor_args(A, D, G0, r)
     if tuple(Pt.shape) != (r, h_in) or tuple(Gt.shape) != (r, h_out) or Pt.dtype != torch.float32 \
             or Gt.dtype != torch.float32:
         raise ValueError("Pt, Gt must be float32 of shape (r, h_in), (r, h_out)")
@@ -314,16 +312,7 @@ def compress_gram_workspace_bytes(N, h_in, h_out, r, dtype) -> int:
 def compress_rank_gram(A, D, r, n_iter, G0, Pt=None, Gt=None, workspace=None, check=False):
     """dad_compress_rank_gram: dad_compress_rank for N <= DAD_GRAM_MAX_ROWS rows, iterating on A A^T and
     Delta Delta^T; same arguments and outputs as compress_rank."""
-    _dense2d(A, "A")
-    _dense2d(D, "Delta")
-    _dense2d(G0, "G0")
-    N, h_in = A.shape
-    h_out = D.shape[1]
-    if D.shape[0] != N or D.dtype != A.dtype:
-        raise ValueError("A and Delta disagree in rows or dtype")
-    if G0.dtype != torch.float32 or tuple(G0.shape) != (r, h_out):
-        raise ValueError("G0 must be float32 of shape (r, h_out)")
-    dt = _dt(A)
+    N, h_in, h_out, dt = _factor_args(A, D, G0, r)
     if workspace is None:
         nbytes = lib().dad_compress_gram_workspace_bytes(N, h_in, h_out, r, dt)
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=A.device)
@@ -344,16 +333,7 @@ def compress_rank_sequential(A, D, r, n_iter, G0, Qt=None, sGt=None, sigma=None,
 
     Returns (Qt r x h_in unit rows, sGt r x h_out rows sigma_j g_j, sigma r).
     """
-    _dense2d(A, "A")
-    _dense2d(D, "D")
-    _dense2d(G0, "G0")
-    N, h_in = A.shape
-    h_out = D.shape[1]
-    if D.shape[0] != N or D.dtype != A.dtype:
-        raise ValueError("A and D disagree in rows or dtype")
-    if tuple(G0.shape) != (r, h_out) or G0.dtype != torch.float32:
-        raise ValueError("G0 must be r x h_out float32")
-    dt = _dt(A)
+    N, h_in, h_out, dt = _factor_args(A, D, G0, r)
     dev = A.device
     Qt = torch.empty((r, h_in), dtype=torch.float32, device=dev) if Qt is None else Qt
     sGt = torch.empty((r, h_out), dtype=torch.float32, device=dev) if sGt is None else sGt
@@ -374,16 +354,8 @@ def compress_rank_adaptive(A, D, r, max_iter, theta, G0, workspace=None, check=F
 
     Returns (Qt, sGt, sigma, effective_rank, iterations): device tensors, the last two int32.
     """
-    _dense2d(A, "A")
-    _dense2d(D, "D")
-    _dense2d(G0, "G0")
-    N, h_in = A.shape
-    h_out = D.shape[1]
-    if D.shape[0] != N or D.dtype != A.dtype:
-        raise ValueError("A and D disagree in rows or dtype")
-    if tuple(G0.shape) != (r, h_out) or G0.dtype != torch.float32:
-        raise ValueError("G0 must be r x h_out float32")
-    dt, dev = _dt(A), A.device
+    N, h_in, h_out, dt = _factor_args(A, D, G0, r)
+    dev = A.device
     Qt = torch.empty((r, h_in), dtype=torch.float32, device=dev)
     sGt = torch.empty((r, h_out), dtype=torch.float32, device=dev)
     sigma = torch.empty((r,), dtype=torch.float32, device=dev)
