@@ -681,7 +681,7 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
                 if not grouped:
                     ops.append(("compress", lambda k=k, li=li: dad.compress_rank(A_st[k], D_st[k], r, n_iter, G0[li], Pt=Pt[li],
                                                                                  Gt=Gt[li], workspace=ws_c)))
-                if rg == 1 or not grouped:
+                if rg == 1:
                     ops.append(("rebuild_full", lambda k=k, s_=(hi, ho): dad.reconstruct_grad(A_st[k], D_st[k], G=G_full[s_],
                                                                                               workspace=ws_r)))
                     continue
