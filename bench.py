@@ -51,6 +51,9 @@ def parse():
     ap.add_argument("--rebuild-group", type=int, default=0,
                     help="layers per full-gradient call (dad_reconstruct_grad_grouped); 1 = one dad_reconstruct_grad per "
                          "layer; 0 = a block's layers together for the small workloads, few-tile neighbours for the large ones")
+    ap.add_argument("--rebuild-tile-budget", type=int, default=128,
+                    help="automatic full-gradient grouping of the large workloads: join neighbours while their 256x256 "
+                         "output tiles together stay within this")
     ap.add_argument("--no-sites-leg", action="store_true",
                     help="skip the extra timed leg that reads the sites' blocks in place (no stacking pass)")
     ap.add_argument("--no-other-workloads", action="store_true",
@@ -656,12 +659,12 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
     # dad_reconstruct_grad call per layer).  The layers of a call must have distinct shapes here, because
     # the bench keeps one output buffer per shape.
     # Automatic: a whole block for the small workloads (their launches are short); for the large ones
-    # consecutive layers are joined only while their 256 x 256 output tiles together stay within 64, i.e.
-    # while the call still splits K at least four ways: that merges the few-tile layers (whose own calls
-    # split K 16 ways and write 16 slabs) and leaves the others alternating with the stacking passes.
+    # consecutive layers are joined only while their 256 x 256 output tiles together stay within a budget
+    # (128: the call then still splits K at least two ways).  That halves or quarters the K chunks and
+    # fp32 slabs of the few-tile layers and still leaves rebuild launches alternating with stacking passes.
     small = w.N * max(hi * ho for hi, ho in w.shapes) < (1 << 37)
     rg = max(1, min(args.rebuild_group, nb)) if args.rebuild_group > 0 else (nb if small else 0)
-    tile_budget = 64
+    tile_budget = args.rebuild_tile_budget
     full_groups = {}
     def full_group(chunk):
         key = tuple(t[0] for t in chunk)
