@@ -132,3 +132,35 @@ def test_two_level_rank_dad_full_gram_aggregator(gpu, widx, layer):
     w = W.WORKLOADS[widx]
     _, h_in, h_out = w.all_layers()[layer]
     run_two_level(w, layer, h_in, h_out, gpu, agg=dad.compress_rank_gram)
+
+
+@pytest.mark.parametrize("name", ["gpt2_medium_stack", "encoder_d768"])
+def test_block_through_the_grouped_calls_bench_times(gpu, name):
+    """One block of the stack through the calls of a bench.py step: stack per layer, the full gradients as
+    dad_reconstruct_grad_grouped (a job-table launch for the joined layers), the reductions as one
+    dad_compress_rank_grouped with four lanes, the rank-r gradients as one grouped call.  Every output
+    against the oracle on the same values."""
+    w = W.by_name(name)
+    layers = list(enumerate(w.shapes))
+    stacked, G0s = [], []
+    for li, (hi, ho) in layers:
+        As, Ds = W.device_factors(w, li, hi, ho, device=gpu)
+        stacked.append(dad.stack_factors(As, Ds))
+        G0s.append(W.device_start_matrix(w, li, ho, device=gpu))
+        del As, Ds
+    G_full = dad.reconstruct_grad_grouped(stacked)
+    grp = dad.CompressGroup([(A, D, G0) for (A, D), G0 in zip(stacked, G0s)], w.rank, w.n_iter, lanes=4)
+    Pts, Gts = grp.run(check=True)
+    G_rank = dad.reconstruct_grad_grouped(list(zip(Pts, Gts)))
+    torch.cuda.synchronize()
+    for (li, (hi, ho)), (A, D), G0, Gf, Gr in zip(layers, stacked, G0s, G_full, G_rank):
+        A_h = A.float().cpu().numpy().astype(np.float64)
+        D_h = D.float().cpu().numpy().astype(np.float64)
+        G_ref = O.full_grad(A_h, D_h)
+        G_gpu = Gf.cpu().numpy()
+        worst = max(O.rel_fro(G_gpu[p0:p0 + 256, q0:q0 + 256], G_ref[p0:p0 + 256, q0:q0 + 256])
+                    for p0 in range(0, hi, 256) for q0 in range(0, ho, 256))
+        e_rank = O.rel_fro(Gr.cpu().numpy(), O.rank_r_grad(*O.block_spi(A_h, D_h, G0.cpu().numpy(), w.n_iter)))
+        print(name, li, hi, ho, {"e_full_worst_block": worst, "e_rank": e_rank})
+        assert worst <= TOL_FULL and e_rank <= TOL_BF16
+        del A_h, D_h, G_ref
