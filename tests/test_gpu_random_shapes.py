@@ -84,6 +84,29 @@ def test_random_shapes_flat_spectrum_at_the_strict_bar(gpu, N, h_in, h_out, r, n
     assert O.rel_fro(dad.reconstruct_grad(Pt2, Gt2).cpu().numpy(), ref) <= 1e-5
 
 
+# fp32 shapes with r >= 16, which take the fp32 matrix-instruction thin kernels (narrower panels stay
+# on the guarded kernels; the sweeps above mix both): ragged rows, widths that are not multiples of 4 (one-float staging), r on both sides of 32,
+# column chunks for N << h, many row tiles.
+BIG_F32 = [(1000, 1300, 2052, 33, 2), (777, 4096, 1024, 24, 2), (1024, 1280, 5120, 64, 2), (130, 8200, 9001, 64, 1),
+           (4099, 515, 2049, 16, 3), (20000, 130, 420, 20, 2), (300, 97, 61, 17, 2)]
+
+
+@pytest.mark.parametrize("N,h_in,h_out,r,n_iter", BIG_F32)
+def test_fp32_thin_contractions_on_the_matrix_instruction(gpu, N, h_in, h_out, r, n_iter):
+    rng = np.random.default_rng([5, N, h_in, h_out, r])
+    A = np.maximum(rng.standard_normal((N, h_in)), 0.0).astype(np.float32)
+    D = (0.1 * rng.standard_normal((N, h_out))).astype(np.float32)
+    G0 = rng.standard_normal((r, h_out)).astype(np.float32)
+    a, d, g0 = torch.from_numpy(A).to(gpu), torch.from_numpy(D).to(gpu), torch.from_numpy(G0).to(gpu)
+    ref = O.rank_r_grad(*O.block_spi(A, D, G0, n_iter))
+    Pt, Gt = dad.compress_rank(a, d, r, n_iter, g0, check=True)
+    assert O.rel_fro(dad.reconstruct_grad(Pt, Gt).cpu().numpy(), ref) <= 1e-5
+    g = Gt.cpu().numpy().astype(np.float64)
+    assert np.abs(g @ g.T - np.eye(r)).max() <= 1e-5
+    Pt2, Gt2 = dad.compress_rank(a, d, r, n_iter, g0)
+    assert torch.equal(Pt, Pt2) and torch.equal(Gt, Gt2)            # fixed summation order
+
+
 @pytest.mark.parametrize("N,h_in,h_out,r,n_iter", shapes(102, 24, 300, 400, 48))
 def test_random_shapes_gram_route(gpu, N, h_in, h_out, r, n_iter):
     A, D, G0 = factors(N, h_in, h_out, r, 2)
