@@ -129,11 +129,15 @@ size_t dad_compress_workspace_bytes(int64_t N, int64_t h_in, int64_t h_out, int 
  *   Gt        device out, r x h_out fp32: rows orthonormal
  *   workspace device, ws_bytes >= dad_compress_workspace_bytes(...)
  * Outputs have the factor layout (one row per component), so S such pairs can
- * be stacked and compressed again (Algorithm 1).  For dt = DAD_BF16 the two
- * N x r intermediates are rounded to bf16 between contractions, and on the
- * large aligned shapes the h x r panels enter the next contraction rounded to
- * bf16 as well; the panels themselves, the outputs and everything r x r stay
- * fp32 (Gram matrix and r x r factorisation in fp64).
+ * be stacked and compressed again (Algorithm 1).  For dt = DAD_BF16 on shapes
+ * the MFMA kernels serve (N >= 256, widths multiples of 128, r a multiple of
+ * 8) the two N x r intermediates travel as bf16 between contractions: Delta G
+ * rounded once, A U as two bf16 terms (value and rounding remainder, 16
+ * significand bits: activations with a non-zero mean make one rounding of it
+ * too coarse); with N a multiple of 256 the h x r panels enter the next
+ * contraction rounded to bf16 as well.  On other shapes and for fp32 factors
+ * the intermediates are fp32.  The panels themselves, the outputs and
+ * everything r x r stay fp32 (Gram matrix and r x r factorisation in fp64).
  * If the iterate loses rank (r > rank(M)) the outputs are unspecified and
  * DAD_ERR_NUMERIC is latched for dad_poll_numeric_status.
  */
