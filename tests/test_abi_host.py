@@ -332,3 +332,23 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(dad, "LIB_PATH", str(tmp_path / "libdad.so"))
     with pytest.raises(RuntimeError, match="missing"):
         dad.lib()
+
+
+def test_binding_constants_match_the_header():
+    text = open(os.path.join(ROOT, "include", "dad.h")).read()
+
+    def macro(name):
+        m = re.search(r"#define\s+" + name + r"\s+(.+)", text)
+        assert m, name
+        expr = re.sub(r"/\*.*?\*/", "", m.group(1)).strip()
+        expr = expr.replace("(int64_t)", "").replace("u", "")
+        return int(eval(expr, {"__builtins__": {}}))
+
+    assert macro("DAD_MAX_LANES") == dad.DAD_MAX_LANES
+    assert macro("DAD_STATIC_SCRATCH_BYTES") == dad.DAD_STATIC_SCRATCH_BYTES
+    for name in ("DAD_OK", "DAD_ERR_NULL", "DAD_ERR_SHAPE", "DAD_ERR_ALIGN", "DAD_ERR_WORKSPACE", "DAD_ERR_DTYPE",
+                 "DAD_ERR_NUMERIC", "DAD_ERR_HIP"):
+        m = re.search(name + r"\s*=\s*(\d+)", text)
+        assert m and int(m.group(1)) == getattr(dad, name), name
+    assert re.search(r"DAD_F32\s*=\s*0", text) and dad.DAD_F32 == 0
+    assert re.search(r"DAD_BF16\s*=\s*1", text) and dad.DAD_BF16 == 1

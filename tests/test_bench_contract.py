@@ -17,7 +17,9 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("extra", [["--workload", "encoder_d768"], ["--workload", "mlp_784_1024_1024_10"],
-                                   ["--workload", "encoder_d768", "--mode", "two_level"]])
+                                   ["--workload", "encoder_d768", "--mode", "two_level"],
+                                   ["--workload", "encoder_d768", "--mode", "sequential"],
+                                   ["--workload", "encoder_d768", "--mode", "backprop"]])
 def test_bench_prints_one_json_line_with_the_contract_keys(gpu, extra):
     p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "1", "--steps", "3", "--warmup", "1"] + extra,
                        capture_output=True, text=True, timeout=300, cwd=ROOT)
