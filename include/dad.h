@@ -173,12 +173,14 @@ dad_status dad_compress_rank_noalloc(const void* A, const void* D, int64_t N, in
  * region of the workspace, so its Pt, Gt are bit-identical to a single call's; up to `lanes` layers
  * are in flight at once (layer i on lane i mod lanes), so that the short, latency-bound launches of
  * one layer's orthonormalisation run while another layer streams its factors.  A run of consecutive
- * stacked layers of equal N, h_in, h_out that the bf16 direct-to-LDS kernels serve (N a multiple of
- * 256, widths multiples of 128, r in {16, 32, 64}; typically the S site reductions of one layer in
- * Algorithm 1, each site's block passed as a layer) is executed as a batch of up to 32: every launch
- * does the same step of all its layers, so the run costs the launches of one layer.  A batch takes
- * one lane and as many workspace regions as it has layers (the size query accounts for that); its
- * results are still bit-identical to single calls.
+ * stacked layers of equal N that the bf16 direct-to-LDS kernels serve (N a multiple of 256, widths
+ * multiples of 128, r in {16, 32, 64}) is executed as a batch of up to 32: every launch does the
+ * same step of all its layers, so the run costs the launches of one layer.  Batched are layers of
+ * equal widths with at most 256 MiB of factors each (typically the S site reductions of one layer
+ * in Algorithm 1, each site's block passed as a layer), and layers of unequal widths, all multiples
+ * of 256, with at most 32 MiB each (the layers of a small block).  A batch takes one lane and as
+ * many workspace regions as it has layers (the size query accounts for that); its results are still
+ * bit-identical to single calls.
  *   descs     HOST array of n layers, 1 <= n <= DAD_MAX_GROUP; every pointer is a device pointer with
  *             the meaning and alignment of dad_compress_rank's.  A layer with S > 0 gives its factors
  *             as the S site blocks of dad_stack_factors (A_sites, D_sites, rows: HOST arrays read

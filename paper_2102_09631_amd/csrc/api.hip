@@ -34,7 +34,8 @@ bool reduce_slabs_is_wide(int64_t n, bool with_bf16, bool with_skip);
 bool thin_tn_dma_ok(int64_t N, int r, SplitPlan sp);
 bool thin_dma_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
 dad_status launch_panel_init(const float*, void*, void*, int64_t, int64_t, int, int*, hipStream_t,
-                             const PtrTable* g0s = nullptr, int jobs = 1, int64_t job_stride = 0);
+                             const PtrTable* g0s = nullptr, int jobs = 1, int64_t job_stride = 0,
+                             const BatchInts* dims = nullptr);
 dad_status dma_thin_nn(const void*, const RowBlocks*, const void*, void*, int64_t, int64_t, int, int, hipStream_t,
                        int jobs = 1, int64_t job_stride = 0);
 bool rebuild_fast_ok(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
@@ -61,7 +62,7 @@ static SplitPlan split_rows(int64_t rows, int64_t tiles, int64_t target_blocks, 
     return sp;
 }
 
-CompressPlan plan_compress(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt) {
+CompressPlan plan_compress(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt, size_t part_floor) {
     CompressPlan p;
     p.fast = thin_fast_ok(N, h_in, h_out, r, dt);
     p.tn_in = p.fast ? thin_tn_split(N, h_in, r) : split_rows(N, ceil_div(h_in, 64), 1024, 32, 32);
@@ -77,6 +78,7 @@ CompressPlan plan_compress(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dt
     size_t part_in = (size_t)p.tn_in.splits * r * h_in * 4, part_out = (size_t)p.tn_out.splits * r * h_out * 4;
     p.off_part = o;
     size_t part_max = part_in > part_out ? part_in : part_out;
+    if (part_floor > part_max) part_max = part_floor;  // a batch of jobs of several widths shares one layout
     if (!p.fast) {  // column-split slabs of the guarded thin_nn share the region
         const size_t nn_in = p.nn_in.splits > 1 ? (size_t)p.nn_in.splits * N * r * 4 : 0;
         const size_t nn_out = p.nn_out.splits > 1 ? (size_t)p.nn_out.splits * N * r * 4 : 0;
@@ -176,8 +178,12 @@ __global__ void k_latch_flag(const int* __restrict__ hdr, int* __restrict__ grou
 // End of a batch: the jobs' pairs leave their workspace regions for the callers' buffers.
 __global__ __launch_bounds__(256) void k_batch_copy_out(const char* __restrict__ ws, int64_t stride, size_t off_p,
                                                         size_t off_g, int64_t n_p, int64_t n_g, PtrTable pt,
-                                                        PtrTable gt) {
+                                                        PtrTable gt, BatchInts dims, int use_dims) {
     const int j = blockIdx.y;
+    if (use_dims) {  // this job's own sizes; the grid is sized for the largest
+        n_p = dims.a[j];
+        n_g = dims.b[j];
+    }
     const float* sp = reinterpret_cast<const float*>(ws + j * stride + off_p);
     const float* sg = reinterpret_cast<const float*>(ws + j * stride + off_g);
     float* dp = static_cast<float*>(const_cast<void*>(pt.p[j]));
@@ -253,10 +259,15 @@ static dad_status compress_args_ok(const void* A, const void* D, int64_t N, int6
 // works in the workspace region j * stride bytes after the first and has block j of Ab / Db as its
 // factors; the pairs are formed in the regions (P in the U slot, G in place in the Y slot) and
 // copied to the callers' buffers at the end.
+// per_job: the jobs differ in their widths (equal N and r): h_in/h_out and the row splits of thin_tn
+// are per job (tables inside Ab / Db and `widths`), every buffer of the shared layout is sized for the
+// largest job, and the h_in / h_out arguments of compress_launch are the largest widths.
 struct Batch {
     int jobs;
     int64_t stride;
     PtrTable g0, pt, gt;
+    bool per_job;
+    BatchInts widths;  // a = h_in, b = h_out
 };
 
 // Ab / Db, when not null, give the factors as row blocks read in place (A and D are then unused); the
@@ -326,7 +337,17 @@ static dad_status compress_launch(const CompressPlan& p, const void* A, const vo
         if ((rc = (expr)) != DAD_OK) return rc; \
     } while (0)
     // the workspace header is cleared by the first launch of the call
-    if (p.dma) DAD_TRY(launch_panel_init(G0, Gb, Ub, h_in, h_out, r, flag, s, batch ? &batch->g0 : nullptr, jobs, jstride));
+    const bool per_job = batch && batch->per_job;
+    BatchInts out_w = {}, copy_n = {};  // per job: h_out (orthonormalisation), element counts of the pair
+    if (per_job)
+        for (int j = 0; j < jobs; ++j) {
+            out_w.a[j] = batch->widths.b[j];
+            copy_n.a[j] = r * batch->widths.a[j];
+            copy_n.b[j] = r * batch->widths.b[j];
+        }
+    if (p.dma)
+        DAD_TRY(launch_panel_init(G0, Gb, Ub, h_in, h_out, r, flag, s, batch ? &batch->g0 : nullptr, jobs, jstride,
+                                  per_job ? &batch->widths : nullptr));
     const float* G = G0;
     for (int it = 0; it < n_iter; ++it) {
         DAD_TRY(nn(FD, G, Gb, h_out, p.nn_out, it == 0 ? flag : nullptr, PV));  // V = Delta G
@@ -335,7 +356,7 @@ static dad_status compress_launch(const CompressPlan& p, const void* A, const vo
         DAD_TRY(tn(FD, Yt, h_out, p.tn_out, nullptr, PW));                      // Y = Delta^T W
         // G = orth(Y): up to two Cholesky rounds for the iterate that is returned, one for the others
         DAD_TRY(launch_cholqr(Yt, Gt, h_out, r, (it + 1 == n_iter) ? 2 : 1, gram, p.gram_blocks, rinv, counter, flag, Gb,
-                              s, jobs, jstride));
+                              s, jobs, jstride, per_job ? &out_w : nullptr));
         G = Gt;
     }
     DAD_TRY(nn(FD, Gt, Gb, h_out, p.nn_out, nullptr, PV));  // V = Delta G
@@ -344,7 +365,8 @@ static dad_status compress_launch(const CompressPlan& p, const void* A, const vo
         const int64_t n_p = (int64_t)r * h_in, n_g = (int64_t)r * h_out;
         const int64_t n_max = n_p > n_g ? n_p : n_g;
         hipLaunchKernelGGL(k_batch_copy_out, dim3((unsigned)ceil_div(n_max / 4, 256), (unsigned)jobs), dim3(256), 0, s,
-                           (const char*)ws, jstride, p.off_Ut, p.off_Yt, n_p, n_g, batch->pt, batch->gt);
+                           (const char*)ws, jstride, p.off_Ut, p.off_Yt, n_p, n_g, batch->pt, batch->gt, copy_n,
+                           per_job ? 1 : 0);
         DAD_LAUNCH_CHECK();
     }
     return DAD_OK;
@@ -527,17 +549,39 @@ dad_status dad_compress_rank_sites(int S, const void* const* A_sites, const void
 }
 
 // The layers of a grouped call are dealt to the lanes in units: a unit is one layer, or a batch of
-// up to MAX_ROW_BLOCKS consecutive stacked layers of equal sizes that the direct-to-LDS kernels serve
-// (the S site reductions of one layer in Algorithm 1 are such a run): the launches of a batch are
-// merged, one launch doing the same step of every job.
+// up to MAX_ROW_BLOCKS consecutive stacked layers that the direct-to-LDS kernels serve and whose
+// launches are merged, one launch doing the same step of every job.  The jobs of a batch have equal
+// N (and r); their widths are either all equal (the S site reductions of one layer in Algorithm 1)
+// or all multiples of 256 (the layers of a small block).  Only small layers are batched: their
+// launches are short and bound by latency, while a larger layer keeps the chip busy on its own and
+// gains more from running beside another layer on a second lane.  Jobs of equal widths are balanced,
+// so factors of up to 256 MiB per job are taken (the sites of the benchmark's layers: 1.5 times faster
+// than 8 lanes); with unequal widths every job keeps the decomposition of a call of its own, the
+// workgroups of a launch then differ in length, and only layers of at most 32 MiB are taken (the four
+// layers of encoder_d768, 100-126 MB each, measured 141 us per layer as a batch and 124 on four lanes).
+constexpr double BATCH_MAX_BYTES = 256.0 * 1024 * 1024;
+constexpr double BATCH_MAX_BYTES_MIXED = 32.0 * 1024 * 1024;
+
+static double factor_bytes(const dad_compress_desc& d, int64_t N, dad_dtype dt) {
+    return (double)N * (double)(d.h_in + d.h_out) * (double)elem_size(dt);
+}
+
 struct Unit {
     int first, count;
-    size_t bytes;  // of its lane region
+    bool per_job;         // the jobs differ in their widths
+    CompressPlan layout;  // workspace layout of every job's region (sized for the largest job)
+    size_t bytes;         // of its lane region
 };
 
-static bool batchable(const dad_compress_desc& d, const LayerPlan& lp, int r) {
+static bool batchable(const dad_compress_desc& d, const LayerPlan& lp, int r, dad_dtype dt) {
     return !lp.sites && lp.cp.dma && thin_tn_dma_ok(lp.N, r, lp.cp.tn_in) && thin_tn_dma_ok(lp.N, r, lp.cp.tn_out) &&
-           !reduce_slabs_is_wide((int64_t)r * d.h_in, false, false) && !reduce_slabs_is_wide((int64_t)r * d.h_out, false, false);
+           !reduce_slabs_is_wide((int64_t)r * d.h_in, false, false) && !reduce_slabs_is_wide((int64_t)r * d.h_out, false, false) &&
+           lp.N < ((int64_t)1 << 31) && factor_bytes(d, lp.N, dt) <= BATCH_MAX_BYTES;
+}
+
+// A layer that may share a batch with layers of other widths.
+static bool mixable(const dad_compress_desc& d, int64_t N, dad_dtype dt) {
+    return d.h_in % 256 == 0 && d.h_out % 256 == 0 && factor_bytes(d, N, dt) <= BATCH_MAX_BYTES_MIXED;
 }
 
 // Layout of the grouped workspace: 256-byte group header (sticky numeric flag at +0), then one region
@@ -546,27 +590,50 @@ static dad_status grouped_plans(int n, const dad_compress_desc* descs, dad_dtype
                                 std::vector<Unit>* units, size_t* lane_bytes) {
     plans->resize((size_t)n);
     units->clear();
+    bool open = false, uniform = true, all256 = false;  // state of the last unit while it can still grow
     for (int i = 0; i < n; ++i) {
         LayerPlan& lp = (*plans)[(size_t)i];
         const dad_status rc = plan_layer(descs[i], dt, r, &lp);
         if (rc != DAD_OK) return rc;
+        const bool can = batchable(descs[i], lp, r, dt);
         bool joined = false;
-        if (!units->empty() && batchable(descs[i], lp, r)) {
+        if (open && can) {
             Unit& u = units->back();
             const dad_compress_desc& f = descs[u.first];
-            const LayerPlan& fp = (*plans)[(size_t)u.first];
-            if (u.count < MAX_ROW_BLOCKS && batchable(f, fp, r) && fp.N == lp.N && f.h_in == descs[i].h_in &&
-                f.h_out == descs[i].h_out) {
+            const bool same = f.h_in == descs[i].h_in && f.h_out == descs[i].h_out;
+            if (u.count < MAX_ROW_BLOCKS && (*plans)[(size_t)u.first].N == lp.N &&
+                ((uniform && same) || (all256 && mixable(descs[i], lp.N, dt)))) {
                 ++u.count;
-                u.bytes = (size_t)u.count * align_up(lp.cp.total, 256);
+                uniform = uniform && same;
                 joined = true;
             }
         }
-        if (!joined) units->push_back(Unit{i, 1, lp.total});
+        if (!joined) {
+            units->push_back(Unit{i, 1, false, lp.cp, lp.total});
+            open = can;
+            uniform = true;
+            all256 = can && mixable(descs[i], lp.N, dt);
+        }
+        units->back().per_job = !uniform;
     }
     size_t lane = 0;
-    for (const Unit& u : *units)
+    for (Unit& u : *units) {
+        if (u.count > 1) {  // one layout for all jobs of the batch
+            int64_t hi = 0, ho = 0;
+            size_t part = 0;
+            for (int j = u.first; j < u.first + u.count; ++j) {
+                const CompressPlan& c = (*plans)[(size_t)j].cp;
+                if (descs[j].h_in > hi) hi = descs[j].h_in;
+                if (descs[j].h_out > ho) ho = descs[j].h_out;
+                const size_t pi = (size_t)c.tn_in.splits * r * descs[j].h_in * 4, po = (size_t)c.tn_out.splits * r * descs[j].h_out * 4;
+                if (pi > part) part = pi;
+                if (po > part) part = po;
+            }
+            u.layout = plan_compress((*plans)[(size_t)u.first].N, hi, ho, r, dt, part);
+            u.bytes = (size_t)u.count * align_up(u.layout.total, 256);
+        }
         if (u.bytes > lane) lane = u.bytes;
+    }
     *lane_bytes = align_up(lane, 256);
     return DAD_OK;
 }
@@ -582,27 +649,38 @@ size_t dad_compress_grouped_workspace_bytes(int n, const dad_compress_desc* desc
 }
 
 // The launches of one batch on stream s; ws holds u.count regions.
-static dad_status launch_batch(const dad_compress_desc* descs, const Unit& u, const LayerPlan& lp, dad_dtype dt, int r,
-                               int n_iter, void* ws, hipStream_t s) {
-    const dad_compress_desc& f = descs[u.first];
-    RowBlocks a, b;
-    Batch batch;
+static dad_status launch_batch(const dad_compress_desc* descs, const Unit& u, const std::vector<LayerPlan>& plans,
+                               dad_dtype dt, int r, int n_iter, void* ws, hipStream_t s) {
+    const int64_t N = plans[(size_t)u.first].N;
+    RowBlocks a = {}, b = {};
+    Batch batch = {};
     batch.jobs = u.count;
-    batch.stride = (int64_t)align_up(lp.cp.total, 256);
+    batch.stride = (int64_t)align_up(u.layout.total, 256);
+    batch.per_job = u.per_job;
+    int64_t hi = 0, ho = 0;
     for (int j = 0; j < MAX_ROW_BLOCKS; ++j) {
         const bool in = j < u.count;
         const dad_compress_desc& d = descs[u.first + (in ? j : 0)];
+        const CompressPlan& c = plans[(size_t)(u.first + (in ? j : 0))].cp;
         a.base[j] = in ? static_cast<const char*>(d.A) : nullptr;
         b.base[j] = in ? static_cast<const char*>(d.D) : nullptr;
-        a.first[j] = b.first[j] = (in ? j : u.count) * lp.N;
+        a.first[j] = b.first[j] = (in ? j : u.count) * N;
         batch.g0.p[j] = in ? d.G0 : nullptr;
         batch.pt.p[j] = in ? d.Pt : nullptr;
         batch.gt.p[j] = in ? d.Gt : nullptr;
+        if (in && u.per_job) {
+            a.h[j] = (int)d.h_in, a.splits[j] = c.tn_in.splits, a.chunk[j] = (int)c.tn_in.chunk;
+            b.h[j] = (int)d.h_out, b.splits[j] = c.tn_out.splits, b.chunk[j] = (int)c.tn_out.chunk;
+            batch.widths.a[j] = (int)d.h_in;
+            batch.widths.b[j] = (int)d.h_out;
+        }
+        if (in && d.h_in > hi) hi = d.h_in;
+        if (in && d.h_out > ho) ho = d.h_out;
     }
-    a.first[MAX_ROW_BLOCKS] = b.first[MAX_ROW_BLOCKS] = (int64_t)u.count * lp.N;
+    a.first[MAX_ROW_BLOCKS] = b.first[MAX_ROW_BLOCKS] = (int64_t)u.count * N;
     a.n = b.n = u.count;
-    return compress_launch(lp.cp, nullptr, nullptr, lp.N, f.h_in, f.h_out, dt, r, n_iter, nullptr, nullptr, nullptr, ws, s,
-                           &a, &b, &batch);
+    return compress_launch(u.layout, nullptr, nullptr, N, hi, ho, dt, r, n_iter, nullptr, nullptr, nullptr, ws, s, &a, &b,
+                           &batch);
 }
 
 dad_status dad_compress_rank_grouped(int n, const dad_compress_desc* descs, dad_dtype dt, int r, int n_iter, int lanes,
@@ -643,11 +721,11 @@ dad_status dad_compress_rank_grouped(int n, const dad_compress_desc* descs, dad_
         void* lane_ws = ws + 256 + (size_t)l * lane_bytes;
         const Unit& u = units[(size_t)k];
         const LayerPlan& lp = plans[(size_t)u.first];
-        rc = u.count > 1 ? launch_batch(descs, u, lp, dt, r, n_iter, lane_ws, s)
+        rc = u.count > 1 ? launch_batch(descs, u, plans, dt, r, n_iter, lane_ws, s)
                          : launch_layer(descs[u.first], lp, dt, r, n_iter, lane_ws, s);
         if (rc != DAD_OK) break;
         hipLaunchKernelGGL(k_latch_flag, dim3(1), dim3(1), 0, s, (const int*)lane_ws, group_flag, u.count,
-                           (int64_t)align_up(lp.cp.total, 256));
+                           (int64_t)align_up(u.layout.total, 256));
         if (hipGetLastError() != hipSuccess) {
             rc = DAD_ERR_HIP;
             break;

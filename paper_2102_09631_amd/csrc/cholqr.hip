@@ -145,9 +145,16 @@ template <int NA>
 __global__ __launch_bounds__(256) void k_qr_gram(const float* __restrict__ Yt, int64_t h, int r,
                                                  double* __restrict__ gram_part, int* __restrict__ counter,
                                                  float* __restrict__ rinv, int* __restrict__ flag,
-                                                 double* __restrict__ piv_range, int64_t job_stride) {
+                                                 double* __restrict__ piv_range, int64_t job_stride, BatchInts dims,
+                                                 int use_dims) {
     __shared__ QrShared sh;
+    int nblocks = gridDim.x;
     if (job_stride != 0) {
+        if (use_dims) {  // this job's own width; the grid is sized for the widest job
+            h = dims.a[blockIdx.y];
+            nblocks = (int)((h + QR_SUB * QR_COLS - 1) / (QR_SUB * QR_COLS));
+            if ((int)blockIdx.x >= nblocks) return;
+        }
         DAD_TO_JOB(Yt), DAD_TO_JOB(gram_part), DAD_TO_JOB(counter);
         DAD_TO_JOB(rinv), DAD_TO_JOB(flag), DAD_TO_JOB(piv_range);
     }
@@ -166,7 +173,7 @@ __global__ __launch_bounds__(256) void k_qr_gram(const float* __restrict__ Yt, i
         }
     }
     __syncthreads();
-    last_block_factor<NA>(sh, acc, gram_part, gridDim.x, r, counter, rinv, flag, piv_range);
+    last_block_factor<NA>(sh, acc, gram_part, nblocks, r, counter, rinv, flag, piv_range);
 }
 
 // One Cholesky round leaves G^T G - I at about eps32 * cond(Y) (the rounding of Y R^-1 in fp32); the
@@ -192,9 +199,16 @@ __global__ __launch_bounds__(256) void k_qr_apply(const float* Yt, float* Gt, co
                                                   int* __restrict__ flag, bf16_t* __restrict__ gt_bf16,
                                                   const double* __restrict__ piv_first,
                                                   double* __restrict__ piv_second, const float* Y_first,
-                                                  const float* __restrict__ rinv_first, int64_t job_stride) {
+                                                  const float* __restrict__ rinv_first, int64_t job_stride,
+                                                  BatchInts dims, int use_dims) {
     __shared__ QrShared sh;
+    int nblocks = gridDim.x;
     if (job_stride != 0) {
+        if (use_dims) {
+            h = dims.a[blockIdx.y];
+            nblocks = (int)((h + SUB * QR_COLS - 1) / (SUB * QR_COLS));
+            if ((int)blockIdx.x >= nblocks) return;
+        }
         DAD_TO_JOB(Yt), DAD_TO_JOB(Gt), DAD_TO_JOB(rinv_in), DAD_TO_JOB(gram_part);
         DAD_TO_JOB(counter), DAD_TO_JOB(rinv_out), DAD_TO_JOB(flag), DAD_TO_JOB(gt_bf16);
         DAD_TO_JOB(piv_first), DAD_TO_JOB(piv_second), DAD_TO_JOB(Y_first);
@@ -254,7 +268,7 @@ __global__ __launch_bounds__(256) void k_qr_apply(const float* Yt, float* Gt, co
     }
     if (WITH_GRAM) {
         __syncthreads();
-        last_block_factor<NA>(sh, acc, gram_part, gridDim.x, r, counter, rinv_out, flag, piv_second);
+        last_block_factor<NA>(sh, acc, gram_part, nblocks, r, counter, rinv_out, flag, piv_second);
     }
 }
 
@@ -264,7 +278,10 @@ int gram_blocks_for(int64_t h) { return (int)ceil_div(h, QR_COLS * QR_SUB); }
 // iterate of the power iteration, of which only the span matters.
 template <int NA>
 static dad_status qr(const float* Yt, float* Gt, int64_t h, int r, int rounds, double* gram_part, int nb, float* rinv,
-                     int* counter, int* flag, bf16_t* gt_bf16, hipStream_t s, int jobs, int64_t job_stride) {
+                     int* counter, int* flag, bf16_t* gt_bf16, hipStream_t s, int jobs, int64_t job_stride,
+                     const BatchInts* dims) {
+    const BatchInts bd = dims ? *dims : BatchInts{};
+    const int ud = dims ? 1 : 0;
     float* rinv2 = rinv + DAD_MAX_RANK * DAD_MAX_RANK;
     // pivot ranges of the two factors: four doubles at byte 128 of the 256-byte workspace header
     double* piv = reinterpret_cast<double*>(reinterpret_cast<char*>(flag) + 128);
@@ -272,14 +289,14 @@ static dad_status qr(const float* Yt, float* Gt, int64_t h, int r, int rounds, d
     {
         ProfScope prof(KID_GRAM, s);
         hipLaunchKernelGGL(k_qr_gram<NA>, dim3((unsigned)nb, (unsigned)jobs), dim3(256), 0, s, Yt, h, r, gram_part, counter,
-                           rinv, flag, piv, job_stride);
+                           rinv, flag, piv, job_stride, bd, ud);
     }
     DAD_LAUNCH_CHECK();
     if (rounds == 1) {
         ProfScope prof(KID_APPLY2, s);
         hipLaunchKernelGGL((k_qr_apply<NA, false, 1>), dim3(nb1, (unsigned)jobs), dim3(256), 0, s, Yt, Gt,
                            (const float*)rinv, h, r, gram_part, counter, rinv2, flag, gt_bf16, (const double*)nullptr,
-                           (double*)nullptr, (const float*)nullptr, (const float*)nullptr, job_stride);
+                           (double*)nullptr, (const float*)nullptr, (const float*)nullptr, job_stride, bd, ud);
         DAD_LAUNCH_CHECK();
         return DAD_OK;
     }
@@ -287,25 +304,27 @@ static dad_status qr(const float* Yt, float* Gt, int64_t h, int r, int rounds, d
         ProfScope prof(KID_APPLY, s);
         hipLaunchKernelGGL((k_qr_apply<NA, true, QR_SUB>), dim3((unsigned)nb, (unsigned)jobs), dim3(256), 0, s, Yt, Gt,
                            (const float*)rinv, h, r, gram_part, counter, rinv2, flag, (bf16_t*)nullptr, (const double*)piv,
-                           piv + 2, (const float*)nullptr, (const float*)nullptr, job_stride);
+                           piv + 2, (const float*)nullptr, (const float*)nullptr, job_stride, bd, ud);
     }
     DAD_LAUNCH_CHECK();
     {
         ProfScope prof(KID_APPLY2, s);
         hipLaunchKernelGGL((k_qr_apply<NA, false, 1>), dim3(nb1, (unsigned)jobs), dim3(256), 0, s, (const float*)Gt, Gt,
                            (const float*)rinv2, h, r, gram_part, counter, rinv2, flag, gt_bf16, (const double*)piv,
-                           (double*)nullptr, Yt, (const float*)rinv, job_stride);
+                           (double*)nullptr, Yt, (const float*)rinv, job_stride, bd, ud);
     }
     DAD_LAUNCH_CHECK();
     return DAD_OK;
 }
 
 dad_status launch_cholqr(const float* Yt, float* Gt, int64_t h, int r, int rounds, double* gram_part, int gram_blocks,
-                         float* rinv, int* counter, int* flag, void* gt_bf16, hipStream_t s, int jobs, int64_t job_stride) {
-    if (job_stride == 0) jobs = 1;
+                         float* rinv, int* counter, int* flag, void* gt_bf16, hipStream_t s, int jobs, int64_t job_stride,
+                         const BatchInts* dims) {
+    if (job_stride == 0) jobs = 1, dims = nullptr;
     if (r <= 32)
-        return qr<2>(Yt, Gt, h, r, rounds, gram_part, gram_blocks, rinv, counter, flag, (bf16_t*)gt_bf16, s, jobs, job_stride);
-    return qr<4>(Yt, Gt, h, r, rounds, gram_part, gram_blocks, rinv, counter, flag, (bf16_t*)gt_bf16, s, jobs, job_stride);
+        return qr<2>(Yt, Gt, h, r, rounds, gram_part, gram_blocks, rinv, counter, flag, (bf16_t*)gt_bf16, s, jobs, job_stride,
+                     dims);
+    return qr<4>(Yt, Gt, h, r, rounds, gram_part, gram_blocks, rinv, counter, flag, (bf16_t*)gt_bf16, s, jobs, job_stride, dims);
 }
 
 }  // namespace dad

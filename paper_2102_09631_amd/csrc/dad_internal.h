@@ -85,12 +85,24 @@ struct RowBlocks {
     const char* base[MAX_ROW_BLOCKS];
     int64_t first[MAX_ROW_BLOCKS + 1];
     int n;
+    // Only for the jobs of a batch (kernels launched with job_stride != 0), whose widths may differ:
+    // block j is a matrix of its own with h[j] columns, and thin_tn splits its rows into splits[j]
+    // chunks of chunk[j] rows.
+    int h[MAX_ROW_BLOCKS];
+    int splits[MAX_ROW_BLOCKS];
+    int chunk[MAX_ROW_BLOCKS];
 };
 
 // One caller pointer per job of a batch (a batch: up to MAX_ROW_BLOCKS equal reductions whose
 // launches are merged; everything else of a job lives in its workspace region, at a fixed stride).
 struct PtrTable {
     const void* p[MAX_ROW_BLOCKS];
+};
+
+// Two integers per job of a batch (widths, slab counts, block counts: what a launch needs per job).
+struct BatchInts {
+    int a[MAX_ROW_BLOCKS];
+    int b[MAX_ROW_BLOCKS];
 };
 
 // Where a kernel's walk over rows stands: the block it is in and the row at which that block ends.
@@ -209,7 +221,8 @@ struct CompressPlan {
     bool fast;            // MFMA kernels apply to these sizes
 };
 
-CompressPlan plan_compress(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
+// part_floor: least size of the split-partials region (a batch of jobs of several widths).
+CompressPlan plan_compress(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt, size_t part_floor = 0);
 
 // True when the bf16 MFMA thin kernels serve these sizes (otherwise the guarded kernels do).
 bool thin_fast_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt);
@@ -229,9 +242,10 @@ RebuildPlan plan_rebuild(int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt);
 // out[i] = sum over s of part[s*n + i] in a fixed order; out_bf16 (optional) gets a bf16 copy.
 // skip (optional, everywhere below): a device word; when it is non-zero at run time the kernels
 // return at once (the adaptive one-vector iteration stops on the device with a fixed launch sequence).
-// jobs / job_stride: the same sum for `jobs` problems whose pointers lie job_stride bytes apart.
+// jobs / job_stride: the same sum for `jobs` problems whose pointers lie job_stride bytes apart;
+// dims (optional): job j sums dims->b[j] slabs of dims->a[j] floats (n is then the largest a[j]).
 dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s, void* out_bf16 = nullptr,
-                        const int* skip = nullptr, int jobs = 1, int64_t job_stride = 0);
+                        const int* skip = nullptr, int jobs = 1, int64_t job_stride = 0, const BatchInts* dims = nullptr);
 
 
 // out[n][j] = sum_k X[n][k] * Pt[j][k];  X is N x h (dt), Pt r x h fp32.  out is N x r: fp32 from the
@@ -252,10 +266,11 @@ dad_status launch_thin_tn(const void* X, const void* V, float* out_t, float* par
 
 // Orthonormalisation Yt (r x h) -> Gt (r x h), rows of Gt orthonormal; rounds = 2 is CholeskyQR2.
 // gt_bf16 (optional) receives a bf16 copy of Gt.
-// jobs / job_stride: `jobs` independent iterates whose pointers (all of them) lie job_stride bytes apart.
+// jobs / job_stride: `jobs` independent iterates whose pointers (all of them) lie job_stride bytes apart;
+// dims (optional): iterate j is r x dims->a[j] (h is then the largest of them).
 dad_status launch_cholqr(const float* Yt, float* Gt, int64_t h, int r, int rounds, double* gram_part, int gram_blocks,
                          float* rinv, int* counter, int* flag, void* gt_bf16, hipStream_t s, int jobs = 1,
-                         int64_t job_stride = 0);
+                         int64_t job_stride = 0, const BatchInts* dims = nullptr);
 
 dad_status launch_rebuild(const void* L, const void* R, int64_t K, int64_t h_in, int64_t h_out, dad_dtype dt,
                           float* G, float* partials, const RebuildPlan& plan, hipStream_t s);

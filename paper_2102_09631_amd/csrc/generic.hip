@@ -170,9 +170,14 @@ __global__ __launch_bounds__(256) void k_thin_tn(const T* __restrict__ X, const 
 // blockIdx.y: job of a batch, its pointers job_stride bytes further per job.
 __global__ __launch_bounds__(256) void k_reduce_slabs(const float* part, float* out, int64_t n, int splits,
                                                       bf16_t* __restrict__ out_bf16, const int* __restrict__ skip,
-                                                      int64_t job_stride) {
+                                                      int64_t job_stride, BatchInts dims, int use_dims) {
     if (skip && *skip) return;
     if (job_stride != 0) {
+        if (use_dims) {  // this job's own size and slab count
+            n = dims.a[blockIdx.y];
+            splits = dims.b[blockIdx.y];
+            if ((int64_t)blockIdx.x * 64 >= n) return;
+        }
         const int64_t off = blockIdx.y * job_stride;
         part = reinterpret_cast<const float*>(reinterpret_cast<const char*>(part) + off);
         out = reinterpret_cast<float*>(reinterpret_cast<char*>(out) + off);
@@ -344,7 +349,7 @@ bool reduce_slabs_is_wide(int64_t n, bool with_bf16, bool with_skip) {
 }
 
 dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hipStream_t s, void* out_bf16,
-                        const int* skip, int jobs, int64_t job_stride) {
+                        const int* skip, int jobs, int64_t job_stride, const BatchInts* dims) {
     const bool wide = reduce_slabs_is_wide(n, out_bf16 != nullptr, skip != nullptr);
     if (job_stride == 0) jobs = 1;
     if (wide && jobs > 1) return DAD_ERR_SHAPE;  // batches are formed only of sums the small kernel takes
@@ -354,7 +359,7 @@ dad_status reduce_slabs(const float* part, float* out, int64_t n, int splits, hi
                            reinterpret_cast<const float4*>(part), reinterpret_cast<float4*>(out), n / 4, splits);
     else
         hipLaunchKernelGGL(k_reduce_slabs, dim3((unsigned)ceil_div(n, 64), (unsigned)jobs), dim3(256), 0, s, part, out, n,
-                           splits, (bf16_t*)out_bf16, skip, job_stride);
+                           splits, (bf16_t*)out_bf16, skip, job_stride, dims ? *dims : BatchInts{}, dims ? 1 : 0);
     DAD_LAUNCH_CHECK();
     return DAD_OK;
 }

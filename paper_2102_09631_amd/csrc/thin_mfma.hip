@@ -205,6 +205,13 @@ __global__ __launch_bounds__(64 * W) void k_thin_nn_bf16_dma(const SRC X, const 
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     int64_t n0 = (int64_t)blockIdx.x * RT;
+    if constexpr (!std::is_pointer<SRC>::value) {
+        if (job_stride != 0) {  // the job's own width, if the jobs differ in it
+            int b = 0;
+            while (b + 1 < X.n && X.first[b + 1] <= n0) ++b;
+            if (X.h[b]) h = X.h[b];
+        }
+    }
     const int nk = h / nn::BK;
     RowCursor cur;
     const char* x0 = row_address(X, n0, (int64_t)h * 2, cur);
@@ -298,8 +305,13 @@ __global__ __launch_bounds__(64 * W) void k_thin_nn_bf16_dma(const SRC X, const 
 // pointers job_stride bytes further per job.
 __global__ __launch_bounds__(256) void k_panel_init(const float* __restrict__ G0, bf16_t* __restrict__ Gb,
                                                     bf16_t* __restrict__ Ub, int64_t h_in, int64_t h_out, int r, int rp,
-                                                    int* __restrict__ hdr, PtrTable g0s, int64_t job_stride) {
+                                                    int* __restrict__ hdr, PtrTable g0s, int64_t job_stride,
+                                                    BatchInts dims, int use_dims) {
     if (job_stride != 0) {
+        if (use_dims) {  // a = h_in, b = h_out of this job
+            h_in = dims.a[blockIdx.y];
+            h_out = dims.b[blockIdx.y];
+        }
         const int64_t off = blockIdx.y * job_stride;
         G0 = static_cast<const float*>(g0s.p[blockIdx.y]);
         Gb = reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(Gb) + off);
@@ -507,6 +519,15 @@ __global__ __launch_bounds__(256) void k_thin_tn_bf16_dma(const SRC X, const bf1
     constexpr int LOADS = XL + NV * VL;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    if constexpr (!std::is_pointer<SRC>::value) {
+        if (job_stride != 0 && X.h[blockIdx.y]) {  // the job's own width and row split; the grid is sized for the largest job
+            h = X.h[blockIdx.y];
+            splits = X.splits[blockIdx.y];
+            chunk_rows = X.chunk[blockIdx.y];
+            strips = h / PW;
+            if ((int)blockIdx.x >= strips * splits) return;
+        }
+    }
     // Workgroups are handed to the eight XCDs round-robin by their linear index.  All column strips
     // of one row chunk go to the same XCD, so that the chunk of V they share is fetched into one L2.
     int strip, split;
@@ -694,16 +715,18 @@ bool thin_dma_ok(int64_t N, int64_t h_in, int64_t h_out, int r, dad_dtype dt) {
 }
 
 // g0s != null: a batch of `jobs` jobs (G0 unused).
+// dims (optional): job j has widths dims->a[j] (h_in) and dims->b[j] (h_out); h_in, h_out are then the largest.
 dad_status launch_panel_init(const float* G0, void* Gb, void* Ub, int64_t h_in, int64_t h_out, int r, int* hdr,
-                             hipStream_t s, const PtrTable* g0s, int jobs, int64_t job_stride) {
+                             hipStream_t s, const PtrTable* g0s, int jobs, int64_t job_stride, const BatchInts* dims) {
     PtrTable none = {};
-    if (!g0s) jobs = 1, job_stride = 0;
+    if (!g0s) jobs = 1, job_stride = 0, dims = nullptr;
     const int rp = r <= 32 ? 32 : 64;
     int64_t n = (int64_t)rp * h_out;
     if ((int64_t)(rp - r) * h_in > n) n = (int64_t)(rp - r) * h_in;
     ProfScope prof(KID_PANEL_INIT, s);
     hipLaunchKernelGGL(k_panel_init, dim3((unsigned)ceil_div(n, 256), (unsigned)jobs), dim3(256), 0, s, G0, (bf16_t*)Gb,
-                       (bf16_t*)Ub, h_in, h_out, r, rp, hdr, g0s ? *g0s : none, job_stride);
+                       (bf16_t*)Ub, h_in, h_out, r, rp, hdr, g0s ? *g0s : none, job_stride, dims ? *dims : BatchInts{},
+                       dims ? 1 : 0);
     DAD_LAUNCH_CHECK();
     return DAD_OK;
 }
@@ -765,6 +788,20 @@ dad_status fast_thin_tn(const void* X, const RowBlocks* xb, const void* V, float
     if (xb && (skip || !thin_tn_dma_ok(N, r, sp))) return DAD_ERR_SHAPE;
     if (job_stride != 0 && !xb) return DAD_ERR_SHAPE;
     if (job_stride == 0) jobs = 1;
+    // jobs of different widths (xb->h set): the grid is sized for the job with the most workgroups, every job
+    // writes slabs (also one with a single chunk), and the sum runs with each job's own size and count
+    const bool per_job = job_stride != 0 && xb->h[0] != 0;
+    int64_t max_blocks = 0;
+    BatchInts rd = {};
+    if (per_job) {
+        for (int j = 0; j < jobs; ++j) {
+            const int64_t nb = (int64_t)(xb->h[j] / thin_tn_pw(h)) * xb->splits[j];
+            if (nb > max_blocks) max_blocks = nb;
+            rd.a[j] = r * xb->h[j];
+            rd.b[j] = xb->splits[j];
+        }
+        dst = partials;
+    }
     if (!skip && thin_tn_dma_ok(N, r, sp)) {
         ProfScope prof(KID_THIN_TN_BF16, s);
         const int pw = thin_tn_pw(h);
@@ -773,7 +810,7 @@ dad_status fast_thin_tn(const void* X, const RowBlocks* xb, const void* V, float
         const int strips = (int)(h / pw);
 #define DAD_TN_LAUNCH_NV(RR, PP, BB, NV)                                                                          \
     do {                                                                                                          \
-        const dim3 grid((unsigned)(strips * sp.splits), (unsigned)jobs);                                          \
+        const dim3 grid((unsigned)(per_job ? max_blocks : strips * sp.splits), (unsigned)jobs);                  \
         const int nt = stream_once(jobs * N, h) ? 1 : 0;                                                          \
         if (xb)                                                                                                   \
             hipLaunchKernelGGL((k_thin_tn_bf16_dma<RR, PP, BB, NV, RowBlocks>), grid, dim3(256), lds, s, *xb,     \
@@ -819,6 +856,7 @@ dad_status fast_thin_tn(const void* X, const RowBlocks* xb, const void* V, float
 #undef DAD_TN_REG
     }
     DAD_LAUNCH_CHECK();
+    if (per_job) return reduce_slabs(partials, out_t, (int64_t)r * h, sp.splits, s, out_bf16, skip, jobs, job_stride, &rd);
     if (sp.splits > 1) return reduce_slabs(partials, out_t, (int64_t)r * h, sp.splits, s, out_bf16, skip, jobs, job_stride);
     if (out_bf16) return reduce_slabs(out_t, out_t, (int64_t)r * h, 1, s, out_bf16, skip, jobs, job_stride);  // copy only
     return DAD_OK;

@@ -234,3 +234,60 @@ def test_grouped_rebuild_of_many_bf16_jobs(gpu):
     torch.cuda.synchronize()
     for (L, R), G in zip(pairs, got):
         _check_against_oracle(G, L, R, 1e-5)
+
+
+# layers of equal N whose widths differ (all multiples of 256) share launches too
+MIXED_WIDTH_CASES = [
+    (4096, 16, [(768, 2304), (768, 768), (768, 3072), (3072, 768)]),                    # an encoder block
+    (2048, 32, [(256, 512), (512, 256), (768, 1024), (256, 512), (256, 512)]),          # equal and unequal neighbours
+    (1024, 64, [(1280, 256), (256, 1280), (512, 512)]),
+    (2048, 32, [(256, 512), (384, 128), (256, 256), (512, 256), (256, 384), (512, 512)]),  # 384 / 128 wide layers break the runs
+]
+
+
+@pytest.mark.parametrize("lanes", [1, 2])
+@pytest.mark.parametrize("N,r,widths", MIXED_WIDTH_CASES)
+def test_batched_layers_of_different_widths_equal_single_calls(gpu, N, r, widths, lanes):
+    layers = [_layer(N, hi, ho, r, 900 + 13 * i, gpu, torch.bfloat16) for i, (hi, ho) in enumerate(widths)]
+    single = [dad.compress_rank(A, D, r, 2, G0, check=True) for A, D, G0 in layers]
+    grp = dad.CompressGroup(layers, r, 2, lanes=lanes)
+    for _ in range(2):
+        for p, g in zip(grp.Pt, grp.Gt):
+            p.fill_(float("nan"))
+            g.fill_(float("nan"))
+        Pts, Gts = grp.run(check=True)
+        torch.cuda.synchronize()
+        for i, ((p1, g1), p2, g2) in enumerate(zip(single, Pts, Gts)):
+            assert torch.equal(p1, p2) and torch.equal(g1, g2), i
+    A, D, G0 = layers[-1]
+    ref = O.rank_r_grad(*O.block_spi(A.float().cpu().numpy(), D.float().cpu().numpy(), G0.cpu().numpy(), 2))
+    assert O.rel_fro(dad.reconstruct_grad(Pts[-1], Gts[-1]).cpu().numpy(), ref) <= 2e-2
+
+
+def test_mixed_width_batch_reports_a_breakdown_and_replays_from_a_graph(gpu):
+    dad.init()
+    widths = [(768, 2304), (768, 768), (768, 3072), (3072, 768)]
+    layers = [_layer(4096, hi, ho, 16, 950 + i, gpu, torch.bfloat16) for i, (hi, ho) in enumerate(widths)]
+    broken = list(layers)
+    A, D, G0 = broken[1]
+    broken[1] = (A, torch.zeros_like(D), G0)
+    bad = dad.CompressGroup(broken, 16, 2, lanes=2)
+    bad.run()
+    assert dad.poll_numeric_status(bad.workspace) == dad.DAD_ERR_NUMERIC
+    grp = dad.CompressGroup(layers, 16, 2, lanes=2, workspace=bad.workspace)
+    eager = [(p.clone(), g.clone()) for p, g in zip(*grp.run(check=True))]
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        grp.run()
+    for rep in range(3):
+        for p, g in zip(grp.Pt, grp.Gt):
+            p.fill_(float("nan"))
+            g.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for (p1, g1), p2, g2 in zip(eager, grp.Pt, grp.Gt):
+            assert torch.equal(p1, p2) and torch.equal(g1, g2), rep
+        _ = dad.reconstruct_grad(grp.Pt[0], grp.Gt[0])
+        torch.cuda.synchronize()
