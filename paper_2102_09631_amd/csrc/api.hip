@@ -292,7 +292,6 @@ static dad_status compress_launch(const CompressPlan& p, const void* A, const vo
     void* Gb = p.dma ? ws + p.off_Gb : nullptr;
     void* Ub = p.dma ? ws + p.off_Ub : nullptr;
 
-    // V <- X * panel (N x r); the direct-to-LDS kernel takes the bf16 copy of the panel
     const int jobs = batch ? batch->jobs : 1;
     const int64_t jstride = batch ? batch->stride : 0;
     if (batch) {  // the pair is formed inside the regions
@@ -309,6 +308,7 @@ static dad_status compress_launch(const CompressPlan& p, const void* A, const vo
     // Below r = 16 a 32-wide MFMA block is mostly padding and the guarded kernels, which have an
     // instance for narrow panels, measured 4-10 % faster on the two MLP workloads (r = 4, 8).
     const bool f32_mfma = !p.fast && dt == DAD_F32 && r >= 16;
+    // V <- X * panel (N x r); the direct-to-LDS kernel takes the bf16 copy of the panel
     auto nn = [&](const Factor& X, const float* panel, const void* panel_bf16, int64_t h, SplitPlan sp, int* hdr,
                   int planes) {
         if (p.dma) return dma_thin_nn(X.ptr, X.blocks, panel_bf16, V, N, h, r, planes, s, jobs, jstride);
