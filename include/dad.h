@@ -178,7 +178,7 @@ dad_status dad_compress_rank_noalloc(const void* A, const void* D, int64_t N, in
  * same step of all its layers, so the run costs the launches of one layer.  Batched are layers of
  * equal widths with at most 256 MiB of factors each (typically the S site reductions of one layer
  * in Algorithm 1, each site's block passed as a layer), and layers of unequal widths, all multiples
- * of 256, with at most 32 MiB each (the layers of a small block).  A batch takes one lane and as
+ * of 256, with at most 64 MiB each (the layers of a small block).  A batch takes one lane and as
  * many workspace regions as it has layers (the size query accounts for that); its results are still
  * bit-identical to single calls.
  *   descs     HOST array of n layers, 1 <= n <= DAD_MAX_GROUP; every pointer is a device pointer with

@@ -557,10 +557,11 @@ dad_status dad_compress_rank_sites(int S, const void* const* A_sites, const void
 // gains more from running beside another layer on a second lane.  Jobs of equal widths are balanced,
 // so factors of up to 256 MiB per job are taken (the sites of the benchmark's layers: 1.5 times faster
 // than 8 lanes); with unequal widths every job keeps the decomposition of a call of its own, the
-// workgroups of a launch then differ in length, and only layers of at most 32 MiB are taken (the four
-// layers of encoder_d768, 100-126 MB each, measured 141 us per layer as a batch and 124 on four lanes).
+// workgroups of a launch then differ in length, and only layers of at most 64 MiB are taken (four layers
+// with an encoder block's widths: 57 against 88 us per layer at 15 MiB, 77 against 79 at 60 MiB, 138
+// against 117 at 120 MiB, batch against four lanes).
 constexpr double BATCH_MAX_BYTES = 256.0 * 1024 * 1024;
-constexpr double BATCH_MAX_BYTES_MIXED = 32.0 * 1024 * 1024;
+constexpr double BATCH_MAX_BYTES_MIXED = 64.0 * 1024 * 1024;
 
 static double factor_bytes(const dad_compress_desc& d, int64_t N, dad_dtype dt) {
     return (double)N * (double)(d.h_in + d.h_out) * (double)elem_size(dt);
