@@ -558,8 +558,9 @@ dad_status dad_compress_rank_sites(int S, const void* const* A_sites, const void
 // so factors of up to 256 MiB per job are taken (the sites of the benchmark's layers: 1.5 times faster
 // than 8 lanes); with unequal widths every job keeps the decomposition of a call of its own, the
 // workgroups of a launch then differ in length, and only layers of at most 64 MiB are taken (four layers
-// with an encoder block's widths: 57 against 88 us per layer at 15 MiB, 77 against 79 at 60 MiB, 138
-// against 117 at 120 MiB, batch against four lanes).
+// with an encoder block's widths, batch against four lanes on one box: 57 against 109 us per layer at
+// 15 MiB, 76 against 108 at 60 MiB, 119 against 122 at 120 MiB; on a box with faster launches the lanes
+// won at 120 MiB).
 constexpr double BATCH_MAX_BYTES = 256.0 * 1024 * 1024;
 constexpr double BATCH_MAX_BYTES_MIXED = 64.0 * 1024 * 1024;
 

@@ -761,7 +761,11 @@ dad_status dma_thin_nn(const void* X, const RowBlocks* xb, const void* Pb, void*
     if (job_stride == 0) jobs = 1;
     ProfScope prof(KID_THIN_NN_BF16, s);
     const int64_t want = 256;          // workgroups
-    const int64_t rows = jobs * N;     // a batch fills the chip with the rows of all its jobs (the result does not depend on W)
+    // A batch fills the chip with the rows of all its jobs (the result does not depend on W).  Jobs of
+    // unequal widths: every job gets at least 256 workgroups where its rows allow, so that the units,
+    // which take workgroups round-robin, each receive workgroups of every job and finish together.
+    const bool per_job = job_stride != 0 && xb->h[0] != 0;
+    const int64_t rows = per_job ? N : jobs * N;
 #define DAD_NN_W(W) \
     (r <= 32 ? dma_thin_nn_cfg<32, W, 3>(X, xb, Pb, out, N, h, r, planes, jobs, job_stride, s) \
              : dma_thin_nn_cfg<64, W, 3>(X, xb, Pb, out, N, h, r, planes, jobs, job_stride, s))
