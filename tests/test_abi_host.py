@@ -352,3 +352,45 @@ def test_binding_constants_match_the_header():
         assert m and int(m.group(1)) == getattr(dad, name), name
     assert re.search(r"DAD_F32\s*=\s*0", text) and dad.DAD_F32 == 0
     assert re.search(r"DAD_BF16\s*=\s*1", text) and dad.DAD_BF16 == 1
+
+
+def test_grouped_compress_workspace_reflects_how_layers_are_batched(lib):
+    """The size query shows the units a grouped call forms: a batch needs one region per job on ONE lane,
+    layers that are not batched need one region per lane."""
+    p = 0x1000
+    D = dad.CompressDesc
+
+    def up(x):
+        return (x + 255) // 256 * 256
+
+    def single(N, hi, ho, r):
+        return up(lib.dad_compress_workspace_bytes(N, hi, ho, r, dad.DAD_BF16))
+
+    def grouped(shapes, r, lanes):
+        descs = (D * len(shapes))(*[D(p, p, p, p, p, N, hi, ho) for N, hi, ho in shapes])
+        return lib.dad_compress_grouped_workspace_bytes(len(shapes), descs, dad.DAD_BF16, r, lanes)
+
+    site = (8192, 1024, 512)
+    # eight equal site-sized layers: one batch, one lane, eight regions
+    assert grouped([site] * 8, 32, 4) == 256 + 8 * single(*site, 32)
+    # 33 of them: a batch of 32 and a single layer, two units on two lanes, each lane sized for the batch
+    assert grouped([site] * 33, 32, 4) == 256 + 2 * 32 * single(*site, 32)
+    # a layer of another shape (384 wide: not a multiple of 256) splits the run: units of 5, 1, 3 on three lanes
+    other = (8192, 384, 128)
+    need = grouped([site] * 5 + [other] + [site] * 3, 32, 4)
+    assert need == 256 + 3 * max(5 * single(*site, 32), single(*other, 32))
+    # benchmark-sized layers (537 MB of factors each) are not batched: one region per lane
+    big = (65536, 1024, 3072)
+    assert grouped([big] * 4, 32, 2) == 256 + 2 * single(*big, 32)
+    # small layers of unequal widths (multiples of 256) form one batch whose regions are sized for the widest job
+    mixed = [(4096, 768, 2304), (4096, 768, 768), (4096, 768, 3072), (4096, 3072, 768)]
+    need = grouped(mixed, 16, 4)
+    assert need >= 256 + 4 * max(single(*m, 16) for m in mixed)
+    assert need <= 256 + 4 * (single(4096, 3072, 3072, 16) + (1 << 20))
+    # the same widths at the encoder's own row count (100-126 MB per layer) stay separate layers
+    enc = [(16384, hi, ho) for _, hi, ho in mixed]
+    assert grouped(enc, 16, 4) == 256 + 4 * max(single(*m, 16) for m in enc)
+    # fp32 layers are never batched
+    descs = (D * 3)(*[D(p, p, p, p, p, 1024, 1024, 1024) for _ in range(3)])
+    assert lib.dad_compress_grouped_workspace_bytes(3, descs, dad.DAD_F32, 8, 2) == \
+        256 + 2 * up(lib.dad_compress_workspace_bytes(1024, 1024, 1024, 8, dad.DAD_F32))
