@@ -1,5 +1,4 @@
 """Grouped entry points against the single-layer calls (bit for bit) and against the oracle."""
-import numpy as np
 import pytest
 import torch
 
