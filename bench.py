@@ -614,7 +614,6 @@ def one_level(args, w, steps, warmup, dad, W, torch, np, dev, cpu_budget_s, yard
     def factors_of(li):
         return sites[li] if li in sites else sites[li % len(w.shapes)]
     G0 = {li: W.device_start_matrix(w, li, ho, device=dev) for li, _, ho in layers}
-    shape_ids = {s: i for i, s in enumerate(w.shapes)}
     # Stacked factors: one buffer per layer when unstacked + stacked copies of the whole stack fit in
     # HBM (the layers of the whole stack can then be reduced by ONE grouped call), else one per
     # distinct shape (grouped per block of the model).
