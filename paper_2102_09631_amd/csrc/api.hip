@@ -477,7 +477,7 @@ static dad_status launch_layer(const dad_compress_desc& d, const LayerPlan& lp, 
     if (!lp.sites)
         return compress_launch(lp.cp, d.A, d.D, lp.N, d.h_in, d.h_out, dt, r, n_iter, d.G0, d.Pt, d.Gt, ws, s);
     if (lp.in_place) {
-        RowBlocks a, b;
+        RowBlocks a = {}, b = {};
         fill_blocks(d.S, d.A_sites, d.rows, &a);
         fill_blocks(d.S, d.D_sites, d.rows, &b);
         return compress_launch(lp.cp, nullptr, nullptr, lp.N, d.h_in, d.h_out, dt, r, n_iter, d.G0, d.Pt, d.Gt, ws, s, &a,
@@ -814,7 +814,7 @@ dad_status dad_reconstruct_grad_sites(int S, const void* const* A_sites, const v
     hipStream_t s = (hipStream_t)stream;
     char* ws = static_cast<char*>(workspace);
     if (p.in_place) {
-        RowBlocks a, b;
+        RowBlocks a = {}, b = {};
         fill_blocks(S, A_sites, rows, &a);
         fill_blocks(S, D_sites, rows, &b);
         return fast_rebuild(nullptr, nullptr, &a, &b, p.N, h_in, h_out, G, reinterpret_cast<float*>(ws), p.rp.split,
