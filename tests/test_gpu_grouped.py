@@ -290,3 +290,49 @@ def test_mixed_width_batch_reports_a_breakdown_and_replays_from_a_graph(gpu):
             assert torch.equal(p1, p2) and torch.equal(g1, g2), rep
         _ = dad.reconstruct_grad(grp.Pt[0], grp.Gt[0])
         torch.cuda.synchronize()
+
+
+def test_a_whole_step_replays_from_one_hip_graph(gpu):
+    """stack -> full gradients (one joined launch) -> grouped reduction on four lanes -> grouped rank-r
+    gradients, recorded into ONE graph (the lanes fork and join inside the capture) and replayed with
+    eager work in between; every replay must give the eager bits."""
+    dad.init()
+    r, S, b = 16, 4, 1024
+    widths = [(768, 2304), (768, 768), (768, 3072), (3072, 768)]
+    g = torch.Generator(device="cpu").manual_seed(4242)
+    sites = [([torch.randn(b, hi, generator=g).to(torch.bfloat16).to(gpu) for _ in range(S)],
+              [(0.03 * torch.randn(b, ho, generator=g)).to(torch.bfloat16).to(gpu) for _ in range(S)]) for hi, ho in widths]
+    G0 = [torch.randn(r, ho, generator=g).to(gpu) for _, ho in widths]
+    stacked = [(torch.empty((S * b, hi), dtype=torch.bfloat16, device=gpu), torch.empty((S * b, ho), dtype=torch.bfloat16, device=gpu))
+               for hi, ho in widths]
+    full = dad.RebuildGroup(stacked)
+    comp = dad.CompressGroup([(A, D, g0) for (A, D), g0 in zip(stacked, G0)], r, 2, lanes=4)
+    rank = dad.RebuildGroup(list(zip(comp.Pt, comp.Gt)))
+
+    def step():
+        for (As, Ds), (A, D) in zip(sites, stacked):
+            dad.stack_factors(As, Ds, A_out=A, D_out=D)
+        full.run()
+        comp.run()
+        rank.run()
+
+    step()
+    torch.cuda.synchronize()
+    assert dad.poll_numeric_status(comp.workspace) == dad.DAD_OK
+    outputs = full.G + comp.Pt + comp.Gt + rank.G
+    eager = [t.clone() for t in outputs]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        for t in outputs + [x for pair in stacked for x in pair]:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b_ in zip(eager, outputs):
+            assert torch.equal(a, b_), rep
+        _ = dad.reconstruct_grad(stacked[0][0], stacked[0][1])     # eager work between the replays
+        torch.cuda.synchronize()
+    ref = O.full_grad(stacked[2][0].float().cpu().numpy(), stacked[2][1].float().cpu().numpy())
+    assert O.rel_fro(full.G[2].cpu().numpy(), ref) <= 1e-5
